@@ -1,0 +1,317 @@
+/*
+ * CPU oracle for the separable-footprint projector pair.  TEST INFRASTRUCTURE ONLY.
+ * See sf_oracle.h for the weight definition (steps 1-4) this file writes out, and for
+ * which statements of the paper it serves.  Everything is double precision; inputs are
+ * the same float32 arrays the HIP library receives.  Loops are over views (A) or voxels
+ * (A^T) in the plainest order; OpenMP only splits the outermost loop.
+ */
+#include "sf_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---- coordinates ------------------------------------------------------------------ */
+
+static double vox_x(const sfo_scan *s, int i) { return s->cx + (i - 0.5 * (s->nx - 1)) * s->T; }
+static double vox_y(const sfo_scan *s, int j) { return s->cy + (j - 0.5 * (s->ny - 1)) * s->T; }
+static double vox_z(const sfo_scan *s, int k) { return s->cz + (k - 0.5 * (s->nz - 1)) * s->Tz; }
+static double pix_u(const sfo_scan *s, int c) { return (c - 0.5 * (s->ncols - 1) + s->shift_u) * s->pu; }
+static double pix_v(const sfo_scan *s, int r) { return (r - 0.5 * (s->nrows - 1) + s->shift_v) * s->pv; }
+
+/* detector-u coordinate of the in-plane point (x,y) seen from view angle phi */
+static double project_u(const sfo_scan *s, double cphi, double sphi, double x, double y)
+{
+    double t = -x * sphi + y * cphi;
+    if (s->geom == SFO_PARALLEL) return t;
+    double l = x * cphi + y * sphi;
+    return s->sdd * t / (s->sod - l);
+}
+
+static void sort4(double a[4])
+{
+    for (int p = 1; p < 4; ++p) {
+        double v = a[p];
+        int q = p - 1;
+        while (q >= 0 && a[q] > v) { a[q + 1] = a[q]; --q; }
+        a[q + 1] = v;
+    }
+}
+
+/* ---- step 1: knots ---------------------------------------------------------------- */
+
+static void knots_xy(const sfo_scan *s, double phi, double x, double y, double tau[4], double *mag)
+{
+    double cphi = cos(phi), sphi = sin(phi), h = 0.5 * s->T;
+    tau[0] = project_u(s, cphi, sphi, x - h, y - h);
+    tau[1] = project_u(s, cphi, sphi, x + h, y - h);
+    tau[2] = project_u(s, cphi, sphi, x - h, y + h);
+    tau[3] = project_u(s, cphi, sphi, x + h, y + h);
+    sort4(tau);
+    if (mag) {
+        if (s->geom == SFO_PARALLEL) *mag = 1.0;
+        else *mag = s->sdd / (s->sod - (x * cphi + y * sphi));
+    }
+}
+
+void sfo_knots(const sfo_scan *s, int view, int i, int j, double tau[4], double *mag)
+{
+    knots_xy(s, s->phi[view], vox_x(s, i), vox_y(s, j), tau, mag);
+}
+
+/* ---- step 2: trapezoid and F_u ---------------------------------------------------- */
+
+double sfo_trapezoid_integral(const double tau[4], double u)
+{
+    double total = 0.5 * ((tau[3] - tau[0]) + (tau[2] - tau[1]));
+    if (u <= tau[0]) return 0.0;
+    if (u < tau[1]) return (u - tau[0]) * (u - tau[0]) / (2.0 * (tau[1] - tau[0]));
+    if (u <= tau[2]) return 0.5 * (tau[1] - tau[0]) + (u - tau[1]);
+    if (u < tau[3]) return total - (tau[3] - u) * (tau[3] - u) / (2.0 * (tau[3] - tau[2]));
+    return total;
+}
+
+static double footprint_u(const sfo_scan *s, const double tau[4], int c)
+{
+    double uc = pix_u(s, c);
+    return (sfo_trapezoid_integral(tau, uc + 0.5 * s->pu) - sfo_trapezoid_integral(tau, uc - 0.5 * s->pu)) / s->pu;
+}
+
+/* ---- step 3: F_v ------------------------------------------------------------------ */
+
+static double footprint_v(const sfo_scan *s, double mag, int k, int r)
+{
+    if (s->geom == SFO_FAN) return 1.0;
+    double z = vox_z(s, k);
+    double vlo = mag * (z - 0.5 * s->Tz), vhi = mag * (z + 0.5 * s->Tz);
+    double vr = pix_v(s, r);
+    double lo = fmax(vr - 0.5 * s->pv, vlo), hi = fmin(vr + 0.5 * s->pv, vhi);
+    return fmax(0.0, hi - lo) / s->pv;
+}
+
+/* ---- step 4: amplitude ------------------------------------------------------------ */
+
+static double amplitude(const sfo_scan *s, double phi, int r, int c)
+{
+    double cphi = cos(phi), sphi = sin(phi);
+    if (s->geom == SFO_PARALLEL) return s->T / fmax(fabs(cphi), fabs(sphi));
+    double u = pix_u(s, c);
+    double v = (s->geom == SFO_FAN) ? 0.0 : pix_v(s, r);
+    double dx = -s->sdd * cphi - u * sphi;
+    double dy = -s->sdd * sphi + u * cphi;
+    double len = sqrt(dx * dx + dy * dy + v * v);
+    return s->T * len / fmax(fabs(dx), fabs(dy));
+}
+
+/* ---- one weight ------------------------------------------------------------------- */
+
+double sfo_weight(const sfo_scan *s, int view, int r, int c, int i, int j, int k,
+                  double *Fu, double *Fv, double *amp)
+{
+    double tau[4], mag;
+    sfo_knots(s, view, i, j, tau, &mag);
+    double fu = footprint_u(s, tau, c);
+    double fv = footprint_v(s, mag, k, r);
+    double am = amplitude(s, s->phi[view], r, c);
+    if (Fu) *Fu = fu;
+    if (Fv) *Fv = fv;
+    if (amp) *amp = am;
+    return am * fu * fv;
+}
+
+int sfo_dense_matrix(const sfo_scan *s, double *A)
+{
+    int64_t n = (int64_t)s->nx * s->ny * s->nz;
+    for (int a = 0; a < s->nviews; ++a)
+        for (int r = 0; r < s->nrows; ++r)
+            for (int c = 0; c < s->ncols; ++c) {
+                double *row = A + (((int64_t)a * s->nrows + r) * s->ncols + c) * n;
+                for (int k = 0; k < s->nz; ++k)
+                    for (int j = 0; j < s->ny; ++j)
+                        for (int i = 0; i < s->nx; ++i)
+                            row[((int64_t)k * s->ny + j) * s->nx + i] = sfo_weight(s, a, r, c, i, j, k, 0, 0, 0);
+            }
+    return 0;
+}
+
+/* ---- candidate pixels: a superset of those an interval [lo,hi] (mm) can touch ------ */
+
+static void candidates(double lo, double hi, double pitch, double shift, int n, int *first, int *last)
+{
+    /* pixel m covers index coordinates [m-1/2, m+1/2], index(u) = u/pitch - shift + (n-1)/2 */
+    double ilo = lo / pitch - shift + 0.5 * (n - 1);
+    double ihi = hi / pitch - shift + 0.5 * (n - 1);
+    double f = floor(ilo - 0.5), l = ceil(ihi + 0.5);
+    if (f < 0) f = 0;
+    if (l > n - 1) l = n - 1;
+    *first = (int)f;
+    *last = (int)l;          /* empty when last < first */
+}
+
+/* ---- A ---------------------------------------------------------------------------- */
+
+int sfo_project(const sfo_scan *s, const float *vol, double *sino)
+{
+    int64_t per_view = (int64_t)s->nrows * s->ncols;
+    memset(sino, 0, sizeof(double) * per_view * s->nviews);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int a = 0; a < s->nviews; ++a) {
+        double *y = sino + a * per_view;
+        double *amp = (double *)malloc(sizeof(double) * per_view);   /* amp depends on the ray only */
+        for (int r = 0; r < s->nrows; ++r)
+            for (int c = 0; c < s->ncols; ++c) amp[(int64_t)r * s->ncols + c] = amplitude(s, s->phi[a], r, c);
+        for (int j = 0; j < s->ny; ++j)
+            for (int i = 0; i < s->nx; ++i) {
+                double tau[4], mag;
+                sfo_knots(s, a, i, j, tau, &mag);
+                int c0, c1;
+                candidates(tau[0], tau[3], s->pu, s->shift_u, s->ncols, &c0, &c1);
+                for (int c = c0; c <= c1; ++c) {
+                    double fu = footprint_u(s, tau, c);
+                    if (fu <= 0.0) continue;
+                    for (int k = 0; k < s->nz; ++k) {
+                        double x = vol[((int64_t)k * s->ny + j) * s->nx + i];
+                        int r0 = 0, r1 = 0;
+                        if (s->geom != SFO_FAN) {
+                            double z = vox_z(s, k);
+                            candidates(mag * (z - 0.5 * s->Tz), mag * (z + 0.5 * s->Tz), s->pv, s->shift_v, s->nrows, &r0, &r1);
+                        }
+                        for (int r = r0; r <= r1; ++r) {
+                            double fv = footprint_v(s, mag, k, r);
+                            if (fv <= 0.0) continue;
+                            y[(int64_t)r * s->ncols + c] += amp[(int64_t)r * s->ncols + c] * fu * fv * x;
+                        }
+                    }
+                }
+            }
+        free(amp);
+    }
+    return 0;
+}
+
+int sfo_project_rays(const sfo_scan *s, const float *vol, int64_t n, const int64_t *ray, double *out)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t q = 0; q < n; ++q) {
+        int64_t id = ray[q];
+        int c = (int)(id % s->ncols);
+        int r = (int)((id / s->ncols) % s->nrows);
+        int a = (int)(id / ((int64_t)s->ncols * s->nrows));
+        double am = amplitude(s, s->phi[a], r, c), acc = 0.0;
+        for (int j = 0; j < s->ny; ++j)
+            for (int i = 0; i < s->nx; ++i) {
+                double tau[4], mag;
+                sfo_knots(s, a, i, j, tau, &mag);
+                double fu = footprint_u(s, tau, c);
+                if (fu <= 0.0) continue;
+                for (int k = 0; k < s->nz; ++k) {
+                    double fv = footprint_v(s, mag, k, r);
+                    if (fv > 0.0) acc += am * fu * fv * vol[((int64_t)k * s->ny + j) * s->nx + i];
+                }
+            }
+        out[q] = acc;
+    }
+    return 0;
+}
+
+/* ---- A^T -------------------------------------------------------------------------- */
+
+static double backproject_one(const sfo_scan *s, const float *sino, int i, int j, int k)
+{
+    double acc = 0.0;
+    for (int a = 0; a < s->nviews; ++a) {
+        const float *y = sino + (int64_t)a * s->nrows * s->ncols;
+        double tau[4], mag;
+        sfo_knots(s, a, i, j, tau, &mag);
+        int c0, c1, r0 = 0, r1 = 0;
+        candidates(tau[0], tau[3], s->pu, s->shift_u, s->ncols, &c0, &c1);
+        if (s->geom != SFO_FAN) {
+            double z = vox_z(s, k);
+            candidates(mag * (z - 0.5 * s->Tz), mag * (z + 0.5 * s->Tz), s->pv, s->shift_v, s->nrows, &r0, &r1);
+        }
+        for (int c = c0; c <= c1; ++c) {
+            double fu = footprint_u(s, tau, c);
+            if (fu <= 0.0) continue;
+            for (int r = r0; r <= r1; ++r) {
+                double fv = footprint_v(s, mag, k, r);
+                if (fv <= 0.0) continue;
+                acc += amplitude(s, s->phi[a], r, c) * fu * fv * y[(int64_t)r * s->ncols + c];
+            }
+        }
+    }
+    return acc;
+}
+
+int sfo_backproject(const sfo_scan *s, const float *sino, double *vol)
+{
+#pragma omp parallel for collapse(2) schedule(dynamic, 4)
+    for (int k = 0; k < s->nz; ++k)
+        for (int j = 0; j < s->ny; ++j)
+            for (int i = 0; i < s->nx; ++i)
+                vol[((int64_t)k * s->ny + j) * s->nx + i] = backproject_one(s, sino, i, j, k);
+    return 0;
+}
+
+int sfo_backproject_voxels(const sfo_scan *s, const float *sino, int64_t n, const int64_t *voxel, double *out)
+{
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t q = 0; q < n; ++q) {
+        int64_t id = voxel[q];
+        int i = (int)(id % s->nx);
+        int j = (int)((id / s->nx) % s->ny);
+        int k = (int)(id / ((int64_t)s->nx * s->ny));
+        out[q] = backproject_one(s, sino, i, j, k);
+    }
+    return 0;
+}
+
+/* ---- counting --------------------------------------------------------------------- */
+
+int64_t sfo_nnz(const sfo_scan *s, int view_begin, int view_end)
+{
+    int64_t total = 0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(+ : total)
+    for (int a = view_begin; a < view_end; ++a)
+        for (int j = 0; j < s->ny; ++j)
+            for (int i = 0; i < s->nx; ++i) {
+                double tau[4], mag;
+                sfo_knots(s, a, i, j, tau, &mag);
+                int c0, c1;
+                candidates(tau[0], tau[3], s->pu, s->shift_u, s->ncols, &c0, &c1);
+                int64_t nu = 0;
+                for (int c = c0; c <= c1; ++c) nu += footprint_u(s, tau, c) > 0.0;
+                if (!nu) continue;
+                for (int k = 0; k < s->nz; ++k) {
+                    int r0 = 0, r1 = 0;
+                    if (s->geom != SFO_FAN) {
+                        double z = vox_z(s, k);
+                        candidates(mag * (z - 0.5 * s->Tz), mag * (z + 0.5 * s->Tz), s->pv, s->shift_v, s->nrows, &r0, &r1);
+                    }
+                    int64_t nv = 0;
+                    for (int r = r0; r <= r1; ++r) nv += footprint_v(s, mag, k, r) > 0.0;
+                    total += nu * nv;
+                }
+            }
+    return total;
+}
+
+int sfo_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void sfo_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
