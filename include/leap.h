@@ -1,0 +1,100 @@
+/*
+ * leap.h - C ABI of the MI355X separable-footprint CT projector pair.
+ *
+ * The library computes, on one GPU, the forward projector A (line integrals of a voxel
+ * volume along every source-detector ray) and its exact transpose A^T for parallel-,
+ * fan- and flat-panel cone-beam scanners.  The operator and its transpose are the ones
+ * the paper states in its Method section ("CT Projection Models and Geometries":
+ * y = A x, back projection as the exact transpose, separable-footprint weights that
+ * model finite voxel and detector-pixel width, quantities in mm and 1/mm).  The calling
+ * convention follows "Core CUDA Implementation" (the user hands over pointers to
+ * contiguous 32-bit float arrays) and "PyTorch Interfaces and CT Parameters" (the list
+ * of scanner parameters).
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never
+ *     frees or keeps them.  Host arrays are not staged (the caller copies).
+ *   - volume   : float32 [batch][nz][ny][nx], x fastest.
+ *     sinogram : float32 [batch][nviews][nrows][ncols], column fastest.
+ *   - Outputs are OVERWRITTEN, never accumulated into.
+ *   - Calls are asynchronous on the given HIP stream (hipStream_t passed as void*, NULL =
+ *     the default stream), allocate nothing and use no scratch that grows with the volume
+ *     or the sinogram ("Performance and Memory Usage": one copy of each array is all the
+ *     device memory needed).  Per-view tables are uploaded once, in leap_geometry_create.
+ *   - World frame: voxel centres x_i = center_x + (i-(nx-1)/2) voxel_xy (y, z alike); view
+ *     angle phi counter-clockwise from +x, the source sits at sod*(cos phi, sin phi, 0);
+ *     detector columns grow along (-sin phi, cos phi, 0), rows along +z; pixel centres
+ *     u_c = (c-(ncols-1)/2+shift_u) pixel_u, v_r = (r-(nrows-1)/2+shift_v) pixel_v.
+ *   - Every function returns LEAP_OK (0) or a negative status; nothing throws or aborts.
+ */
+#ifndef LEAP_H
+#define LEAP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Scanner families ("CT Projection Models and Geometries"; fan-beam is the one-row,
+ * one-slice case of the flat-panel cone-beam scanner). */
+enum { LEAP_PARALLEL = 0, LEAP_FAN = 1, LEAP_CONE = 2 };
+
+enum {
+    LEAP_OK = 0,
+    LEAP_INVALID_ARG = -1,   /* null pointer, non-positive size or count, FAN with nrows != 1 or nz != 1 */
+    LEAP_BAD_GEOMETRY = -2,  /* cone/fan: source not strictly outside the volume's bounding circle, or sdd <= 0 */
+    LEAP_HIP_ERROR = -3,     /* a HIP runtime call failed (the message is kept, see leap_last_error) */
+    LEAP_UNSUPPORTED = -4    /* sizes beyond what the index arithmetic of the kernels covers */
+};
+
+/* The CT parameter set of "PyTorch Interfaces and CT Parameters": geometry type, number of
+ * projections, list of projection angles, detector pixel width and height, source-to-detector
+ * and source-to-object distance, horizontal/vertical detector shift, voxel counts, voxel sizes,
+ * volume centre.  Host memory; copied by leap_geometry_create. */
+typedef struct {
+    int32_t type;                 /* LEAP_PARALLEL / LEAP_FAN / LEAP_CONE */
+    int32_t nviews, nrows, ncols; /* projections, detector rows (v), detector columns (u) */
+    int32_t nx, ny, nz;           /* voxels */
+    double  pixel_v, pixel_u;     /* mm: pixel height, pixel width */
+    double  shift_v, shift_u;     /* detector shift in PIXELS; positive moves pixel centres to +v / +u */
+    double  sod, sdd;             /* mm: source to rotation axis, source to detector; ignored for PARALLEL */
+    double  voxel_xy, voxel_z;    /* mm: in-plane voxels are square */
+    double  center_x, center_y, center_z; /* mm: volume centre */
+    const double *angles_rad;     /* nviews view angles, any spacing */
+} leap_geometry_desc;
+
+typedef struct leap_geometry leap_geometry;   /* opaque; owned by the library */
+
+/* Validates `desc`, derives the per-view constant tables in double precision and uploads them to
+ * the current HIP device.  On success *out receives a handle valid on that device until
+ * leap_geometry_destroy.  Blocking (synchronous upload). */
+int leap_geometry_create(const leap_geometry_desc *desc, leap_geometry **out);
+
+/* Frees the handle's host and device tables.  NULL is ignored.  The caller must have
+ * synchronised every stream that still uses the handle. */
+void leap_geometry_destroy(leap_geometry *geom);
+
+/* Forward projection y = A x ("CT Projection Models and Geometries", y = A x), ray-driven gather:
+ * d_sino[b] = A d_vol[b] for b < batch.  d_vol: batch volumes, d_sino: batch sinograms (layouts above),
+ * both device memory, not overlapping.  Asynchronous on hip_stream. */
+int leap_project(const leap_geometry *geom, const float *d_vol, float *d_sino, int32_t batch, void *hip_stream);
+
+/* Back projection x = A^T y, the exact transpose of leap_project ("matched projectors"), voxel-driven
+ * gather without atomics (bitwise reproducible): d_vol[b] = A^T d_sino[b].  Asynchronous on hip_stream. */
+int leap_backproject(const leap_geometry *geom, const float *d_sino, float *d_vol, int32_t batch, void *hip_stream);
+
+/* Static description of a status code. */
+const char *leap_status_string(int status);
+
+/* Message of the most recent failure on the calling thread (empty string if none). */
+const char *leap_last_error(void);
+
+/* Which kernel family the handle dispatches to: writes up to `cap` bytes of a short NUL-terminated
+ * description (for logs and benchmarks).  Returns LEAP_OK or LEAP_INVALID_ARG. */
+int leap_geometry_describe(const leap_geometry *geom, char *buf, int32_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

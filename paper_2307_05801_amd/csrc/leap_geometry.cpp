@@ -1,0 +1,201 @@
+// Host geometry module: validates the CT parameter set ("PyTorch Interfaces and CT Parameters") and turns
+// it into the constant tables the kernels read.  All derivations run in double; the tables are rounded to
+// float once, here.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "leap_internal.h"
+
+static thread_local std::string g_last_error;
+
+void leap_set_error(const std::string &msg) { g_last_error = msg; }
+
+int leap_hip_fail(hipError_t e, const char *what)
+{
+    g_last_error = std::string(what) + ": " + hipGetErrorString(e);
+    return LEAP_HIP_ERROR;
+}
+
+extern "C" const char *leap_last_error(void) { return g_last_error.c_str(); }
+
+extern "C" const char *leap_status_string(int status)
+{
+    switch (status) {
+    case LEAP_OK: return "ok";
+    case LEAP_INVALID_ARG: return "invalid argument";
+    case LEAP_BAD_GEOMETRY: return "geometry not supported: source must lie strictly outside the volume";
+    case LEAP_HIP_ERROR: return "HIP runtime error";
+    case LEAP_UNSUPPORTED: return "size not supported";
+    default: return "unknown status";
+    }
+}
+
+static int invalid(const char *why)
+{
+    leap_set_error(why);
+    return LEAP_INVALID_ARG;
+}
+
+static bool finite_pos(double v) { return std::isfinite(v) && v > 0.0; }
+
+extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry **out)
+{
+    if (out) *out = nullptr;
+    if (!d || !out) return invalid("null descriptor or output pointer");
+    if (d->type != LEAP_PARALLEL && d->type != LEAP_FAN && d->type != LEAP_CONE) return invalid("unknown geometry type");
+    if (d->nviews <= 0 || d->nrows <= 0 || d->ncols <= 0) return invalid("nviews, nrows and ncols must be positive");
+    if (d->nx <= 0 || d->ny <= 0 || d->nz <= 0) return invalid("nx, ny and nz must be positive");
+    if (!finite_pos(d->pixel_u) || !finite_pos(d->pixel_v)) return invalid("pixel sizes must be positive");
+    if (!finite_pos(d->voxel_xy) || !finite_pos(d->voxel_z)) return invalid("voxel sizes must be positive");
+    if (!std::isfinite(d->shift_u) || !std::isfinite(d->shift_v)) return invalid("detector shifts must be finite");
+    if (!std::isfinite(d->center_x) || !std::isfinite(d->center_y) || !std::isfinite(d->center_z))
+        return invalid("volume centre must be finite");
+    if (!d->angles_rad) return invalid("angles_rad is null");
+    for (int a = 0; a < d->nviews; ++a)
+        if (!std::isfinite(d->angles_rad[a])) return invalid("view angles must be finite");
+    if (d->type == LEAP_FAN && (d->nrows != 1 || d->nz != 1)) return invalid("fan-beam needs nrows == 1 and nz == 1");
+    if (d->nviews > 65535) {
+        leap_set_error("more than 65535 views in one geometry");
+        return LEAP_UNSUPPORTED;
+    }
+    if ((double)d->nx * d->ny * d->nz >= 2147483648.0 * 2.0 || (double)d->nviews * d->nrows * d->ncols >= 2147483648.0 * 2.0) {
+        leap_set_error("array of more than 2^32 elements");
+        return LEAP_UNSUPPORTED;
+    }
+
+    const double T = d->voxel_xy, h = 0.5 * T;
+    const double half_x = 0.5 * d->nx * T, half_y = 0.5 * d->ny * T;
+    if (d->type != LEAP_PARALLEL) {
+        if (!finite_pos(d->sdd) || !finite_pos(d->sod)) {
+            leap_set_error("sod and sdd must be positive");
+            return LEAP_BAD_GEOMETRY;
+        }
+        // farthest in-plane corner of the volume from the rotation axis
+        const double rx = std::fabs(d->center_x) + half_x, ry = std::fabs(d->center_y) + half_y;
+        const double reach = std::sqrt(rx * rx + ry * ry);
+        if (!(d->sod > reach)) {
+            leap_set_error("source orbit radius (sod) does not clear the volume's bounding circle");
+            return LEAP_BAD_GEOMETRY;
+        }
+        if (!(d->pixel_u < 0.25 * d->sdd)) {
+            leap_set_error("detector pixel wider than a quarter of sdd");
+            return LEAP_BAD_GEOMETRY;
+        }
+    }
+
+    leap_geometry *G = new (std::nothrow) leap_geometry;
+    if (!G) return invalid("out of host memory");
+    G->desc = *d;
+    G->angles.assign(d->angles_rad, d->angles_rad + d->nviews);
+    G->desc.angles_rad = G->angles.data();
+
+    SfGeom &g = G->g;
+    std::memset(&g, 0, sizeof(g));
+    g.type = d->type;
+    g.nviews = d->nviews; g.nrows = d->nrows; g.ncols = d->ncols;
+    g.nx = d->nx; g.ny = d->ny; g.nz = d->nz;
+    g.T = (float)T; g.Tz = (float)d->voxel_z;
+    g.x0 = (float)(d->center_x - 0.5 * (d->nx - 1) * T);
+    g.y0 = (float)(d->center_y - 0.5 * (d->ny - 1) * T);
+    g.zlo0 = (float)(d->center_z - 0.5 * d->nz * d->voxel_z);
+    g.sod = (float)d->sod; g.sdd = (float)d->sdd;
+    g.pu = (float)d->pixel_u; g.pv = (float)d->pixel_v;
+    const bool par = d->type == LEAP_PARALLEL;
+    g.ku = (float)(par ? 1.0 / d->pixel_u : d->sdd / d->pixel_u);
+    g.kv = (float)(par ? 1.0 / d->pixel_v : d->sdd / d->pixel_v);
+    g.col_off = (float)(0.5 * (d->ncols - 1) - d->shift_u);
+    g.row_off = (float)(0.5 * (d->nrows - 1) - d->shift_v + 0.5);
+    g.v0 = (float)((-0.5 * (d->nrows - 1) + d->shift_v) * d->pixel_v);
+
+    G->views.resize(d->nviews);
+    for (int a = 0; a < d->nviews; ++a) {
+        const double c = std::cos(G->angles[a]), s = std::sin(G->angles[a]);
+        SfView &v = G->views[a];
+        v.c = (float)c; v.s = (float)s;
+        v.p = (float)(h * c); v.q = (float)(h * s);
+        v.par_out = (float)(h * (std::fabs(c) + std::fabs(s)) / d->pixel_u);
+        v.par_in = (float)(h * std::fabs(std::fabs(c) - std::fabs(s)) / d->pixel_u);
+        v.par_amp = (float)(T / std::fmax(std::fabs(c), std::fabs(s)));
+        v.xmajor = std::fabs(c) >= std::fabs(s) ? 1 : 0;
+    }
+
+    // Footprint bounds over the whole volume (double): magnification is extreme at the bounding circle.
+    {
+        const double rx = std::fabs(d->center_x) + half_x, ry = std::fabs(d->center_y) + half_y;
+        const double reach = std::sqrt(rx * rx + ry * ry);
+        const double mag_max = par ? 1.0 : d->sdd / (d->sod - reach);
+        const double mag_min = par ? 1.0 : d->sdd / (d->sod + reach);
+        G->max_cols_per_voxel = mag_max * T * std::sqrt(2.0) / d->pixel_u * (par ? 1.0 : 1.05);
+        G->max_rows_per_voxel = (d->type == LEAP_FAN) ? 1.0 : mag_max * d->voxel_z / d->pixel_v;
+        G->max_voxels_per_row = (d->type == LEAP_FAN) ? 1.0 : d->pixel_v / (mag_min * d->voxel_z);
+        double slope = 1.0;
+        if (!par) {
+            // widest fan half-angle seen by any detector column
+            const double umax = (0.5 * d->ncols + std::fabs(d->shift_u)) * d->pixel_u;
+            const double gam = std::atan(umax / d->sdd);
+            slope = (gam < 0.78) ? std::tan(0.7853981633974483 + gam) : 1e30;
+        }
+        G->max_minor_slope = slope;
+    }
+
+    hipError_t e = hipGetDevice(&G->device);
+    if (e == hipSuccess) e = hipMalloc((void **)&G->d_views, sizeof(SfView) * (size_t)d->nviews);
+    if (e == hipSuccess) e = hipMemcpy(G->d_views, G->views.data(), sizeof(SfView) * (size_t)d->nviews, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        if (G->d_views) (void)hipFree(G->d_views);
+        delete G;
+        return leap_hip_fail(e, "uploading the view table");
+    }
+    *out = G;
+    return LEAP_OK;
+}
+
+extern "C" void leap_geometry_destroy(leap_geometry *G)
+{
+    if (!G) return;
+    if (G->d_views) (void)hipFree(G->d_views);
+    delete G;
+}
+
+extern "C" int leap_geometry_describe(const leap_geometry *G, char *buf, int32_t cap)
+{
+    if (!G || !buf || cap <= 0) return invalid("null handle or buffer");
+    std::snprintf(buf, (size_t)cap, "type=%d kernels=%s cols/voxel<=%.2f rows/voxel<=%.2f voxels/row<=%.2f slope<=%.2f",
+                  G->g.type, G->tiled_ok ? "tiled" : "general", G->max_cols_per_voxel, G->max_rows_per_voxel,
+                  G->max_voxels_per_row, G->max_minor_slope);
+    return LEAP_OK;
+}
+
+static int check_call(const leap_geometry *G, const void *in, const void *out, int32_t batch)
+{
+    if (!G || !in || !out) return invalid("null handle or data pointer");
+    if (batch <= 0) return invalid("batch must be positive");
+    if (in == out) return invalid("input and output must not alias");
+    return LEAP_OK;
+}
+
+extern "C" int leap_project(const leap_geometry *G, const float *d_vol, float *d_sino, int32_t batch, void *hip_stream)
+{
+    int rc = check_call(G, d_vol, d_sino, batch);
+    if (rc != LEAP_OK) return rc;
+    const size_t nvol = (size_t)G->g.nx * G->g.ny * G->g.nz, nsino = (size_t)G->g.nviews * G->g.nrows * G->g.ncols;
+    for (int32_t b = 0; b < batch; ++b) {
+        rc = leap_launch_project(G, d_vol + b * nvol, d_sino + b * nsino, (hipStream_t)hip_stream);
+        if (rc != LEAP_OK) return rc;
+    }
+    return LEAP_OK;
+}
+
+extern "C" int leap_backproject(const leap_geometry *G, const float *d_sino, float *d_vol, int32_t batch, void *hip_stream)
+{
+    int rc = check_call(G, d_sino, d_vol, batch);
+    if (rc != LEAP_OK) return rc;
+    const size_t nvol = (size_t)G->g.nx * G->g.ny * G->g.nz, nsino = (size_t)G->g.nviews * G->g.nrows * G->g.ncols;
+    for (int32_t b = 0; b < batch; ++b) {
+        rc = leap_launch_backproject(G, d_sino + b * nsino, d_vol + b * nvol, (hipStream_t)hip_stream);
+        if (rc != LEAP_OK) return rc;
+    }
+    return LEAP_OK;
+}

@@ -1,0 +1,38 @@
+// Library-private definitions shared by the host geometry module and the kernel launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/leap.h"
+#include "sf_types.h"
+
+struct leap_geometry {
+    leap_geometry_desc desc;            // caller's parameters (angles_rad re-pointed at `angles`)
+    std::vector<double> angles;
+    SfGeom g;                           // float parameter block handed to every kernel by value
+    std::vector<SfView> views;          // host copy of the per-view table
+    SfView *d_views = nullptr;          // device copy
+    int device = -1;
+    // static bounds of the footprints, derived in double at creation; they select the kernel family
+    double max_cols_per_voxel = 0;      // widest transaxial footprint, in detector pixels
+    double max_rows_per_voxel = 0;      // tallest axial footprint, in detector pixels
+    double max_voxels_per_row = 0;      // tallest pixel, in voxels (at the smallest magnification)
+    double max_minor_slope = 0;         // largest |d minor / d major| of any ray in its marching frame
+    bool tiled_ok = false;              // the tiled kernels' static limits hold
+};
+
+void leap_set_error(const std::string &msg);
+int leap_hip_fail(hipError_t e, const char *what);
+
+#define LEAP_HIP_CHECK(expr)                                   \
+    do {                                                       \
+        hipError_t e__ = (expr);                               \
+        if (e__ != hipSuccess) return leap_hip_fail(e__, #expr); \
+    } while (0)
+
+// kernel launchers (leap_kernels.hip); one batch item per call
+int leap_launch_project(const leap_geometry *geom, const float *d_vol, float *d_sino, hipStream_t stream);
+int leap_launch_backproject(const leap_geometry *geom, const float *d_sino, float *d_vol, hipStream_t stream);

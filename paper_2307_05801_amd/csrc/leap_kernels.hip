@@ -1,0 +1,76 @@
+// HIP kernels (gfx950) and launchers of the separable-footprint projector pair.
+#include <hip/hip_runtime.h>
+
+#include "leap_internal.h"
+#include "sf_general.h"
+
+// ------------------------------------------------------------------------------------------------
+// General kernels: plain loop nests over global memory, valid for every validated geometry.
+// ------------------------------------------------------------------------------------------------
+
+constexpr int GEN_ZC = 8;   // voxels along z per back-projection thread
+constexpr int GEN_RC = 8;   // detector rows per forward-projection thread
+
+// grid: x = ceil(nx/64), y = ceil(ny/4), z = ceil(nz/GEN_ZC); block 64x4.
+__global__ __launch_bounds__(256) void sf_backproject_general(SfGeom g, const SfView *__restrict__ views,
+                                                              const float *__restrict__ sino, float *__restrict__ vol)
+{
+    const int i = blockIdx.x * 64 + threadIdx.x;
+    const int j = blockIdx.y * 4 + threadIdx.y;
+    const int k0 = blockIdx.z * GEN_ZC;
+    if (i >= g.nx || j >= g.ny) return;
+    float acc[GEN_ZC];
+#pragma unroll
+    for (int kk = 0; kk < GEN_ZC; ++kk) acc[kk] = 0.0f;
+    sf_backproject_column_chunk<GEN_ZC>(g, views, sino, i, j, k0, acc);
+#pragma unroll
+    for (int kk = 0; kk < GEN_ZC; ++kk)
+        if (k0 + kk < g.nz) vol[((size_t)(k0 + kk) * g.ny + j) * g.nx + i] = acc[kk];
+}
+
+// grid: x = ceil(ncols/64), y = ceil(ceil(nrows/GEN_RC)/4), z = nviews; block 64x4.
+__global__ __launch_bounds__(256) void sf_project_general(SfGeom g, const SfView *__restrict__ views,
+                                                          const float *__restrict__ vol, float *__restrict__ sino)
+{
+    const int c = blockIdx.x * 64 + threadIdx.x;
+    const int r0 = (blockIdx.y * 4 + threadIdx.y) * GEN_RC;
+    const int a = blockIdx.z;
+    if (c >= g.ncols || r0 >= g.nrows) return;
+    const SfView v = views[a];
+    float out[GEN_RC];
+    sf_project_ray_chunk<GEN_RC>(g, v, vol, c, r0, out);
+    float *__restrict__ y = sino + ((size_t)a * g.nrows) * g.ncols + c;
+#pragma unroll
+    for (int rr = 0; rr < GEN_RC; ++rr)
+        if (r0 + rr < g.nrows) y[(size_t)(r0 + rr) * g.ncols] = out[rr];
+}
+
+static inline unsigned cdiv(unsigned a, unsigned b) { return (a + b - 1) / b; }
+
+int leap_launch_project(const leap_geometry *G, const float *d_vol, float *d_sino, hipStream_t stream)
+{
+    const SfGeom &g = G->g;
+    dim3 block(64, 4, 1);
+    dim3 grid(cdiv(g.ncols, 64), cdiv(cdiv(g.nrows, GEN_RC), 4), g.nviews);
+    if (grid.y > 65535u) {
+        leap_set_error("detector has too many rows for one launch");
+        return LEAP_UNSUPPORTED;
+    }
+    hipLaunchKernelGGL(sf_project_general, grid, block, 0, stream, g, G->d_views, d_vol, d_sino);
+    LEAP_HIP_CHECK(hipGetLastError());
+    return LEAP_OK;
+}
+
+int leap_launch_backproject(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
+{
+    const SfGeom &g = G->g;
+    dim3 block(64, 4, 1);
+    dim3 grid(cdiv(g.nx, 64), cdiv(g.ny, 4), cdiv(g.nz, GEN_ZC));
+    if (grid.y > 65535u || grid.z > 65535u) {
+        leap_set_error("volume has too many voxels along y or z for one launch");
+        return LEAP_UNSUPPORTED;
+    }
+    hipLaunchKernelGGL(sf_backproject_general, grid, block, 0, stream, g, G->d_views, d_sino, d_vol);
+    LEAP_HIP_CHECK(hipGetLastError());
+    return LEAP_OK;
+}

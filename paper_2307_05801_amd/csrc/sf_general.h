@@ -1,0 +1,139 @@
+// General-purpose (any footprint size, any fan angle) per-thread bodies of the projector pair.
+//
+// These are the plain loop nests: one thread owns a few outputs and walks every contribution to them,
+// reading the other array straight from global memory.  They accept every geometry the library
+// validates and serve as the fallback when a geometry exceeds the static limits of the tiled kernels.
+// The bodies are host/device functions so that the same source can be stepped on a CPU when a kernel
+// has to be debugged.
+#pragma once
+
+#include "sf_footprint.h"
+
+// Back projection: voxels (i, j, k0 .. k0+ZC-1) of one batch item; acc must be zero-initialised.
+template <int ZC>
+SF_HD void sf_backproject_column_chunk(const SfGeom &g, const SfView *__restrict__ views,
+                                       const float *__restrict__ sino, int i, int j, int k0, float acc[ZC])
+{
+    const float x = fmaf((float)i, g.T, g.x0);
+    const float y = fmaf((float)j, g.T, g.y0);
+    const size_t view_stride = (size_t)g.nrows * g.ncols;
+    for (int a = 0; a < g.nviews; ++a) {
+        const SfView v = views[a];
+        const SfColumn f = sf_column(g, v, x, y);
+        int c0, c1;
+        sf_col_range(f, c0, c1);
+        c0 = c0 < 0 ? 0 : c0;
+        c1 = c1 > g.ncols - 1 ? g.ncols - 1 : c1;
+        if (c0 > c1) continue;
+        const SfAxial ax = sf_axial(g, f.inv);
+        const float *__restrict__ ya = sino + (size_t)a * view_stride;
+        for (int c = c0; c <= c1; ++c) {
+            const float fu = sf_fu(f, c);
+            if (!(fu > 0.0f)) continue;
+            const SfAmpCol ac = sf_amp_col(g, v, c);
+            if (g.type == SF_FAN) {
+                acc[0] = fmaf(fu, sf_amp(g, v, ac, 0) * ya[c], acc[0]);
+                continue;
+            }
+#pragma unroll
+            for (int kk = 0; kk < ZC; ++kk) {
+                const int k = k0 + kk;
+                if (k >= g.nz) break;
+                const float lo = fmaf(ax.av, (float)k, ax.bv);
+                const float hi = fmaf(ax.av, (float)(k + 1), ax.bv);
+                int r0 = (int)floorf(lo), r1 = (int)floorf(hi);
+                r0 = r0 < 0 ? 0 : r0;
+                r1 = r1 > g.nrows - 1 ? g.nrows - 1 : r1;
+                float s = 0.0f;
+                for (int r = r0; r <= r1; ++r) {
+                    const float fv = sf_fv(ax, r, k);
+                    s = fmaf(fv, sf_amp(g, v, ac, r) * ya[(size_t)r * g.ncols + c], s);
+                }
+                acc[kk] = fmaf(fu, s, acc[kk]);
+            }
+        }
+    }
+}
+
+// Forward projection: rays (view, rows r0 .. r0+RC-1, column c) of one batch item; returns the finished
+// line integrals (amplitude applied) in out[].
+template <int RC>
+SF_HD void sf_project_ray_chunk(const SfGeom &g, const SfView &v, const float *__restrict__ vol, int c, int r0,
+                                float out[RC])
+{
+    float acc[RC];
+#pragma unroll
+    for (int rr = 0; rr < RC; ++rr) acc[rr] = 0.0f;
+
+    // In-plane lines through the two u-edges of the pixel, as "minor index = m * major index + b".
+    const float ue[2] = {((float)c - 0.5f - g.col_off) * g.pu, ((float)c + 0.5f - g.col_off) * g.pu};
+    const float uc = ((float)c - g.col_off) * g.pu;
+    bool xmajor;
+    float m[2], b[2];
+    if (g.type == SF_PARALLEL) {
+        xmajor = fabsf(v.c) >= fabsf(v.s);
+        for (int e = 0; e < 2; ++e) {
+            if (xmajor) {   // -x s + y c = u  ->  y = (u + x s)/c
+                m[e] = v.s / v.c;
+                b[e] = (ue[e] / v.c + g.x0 * m[e] - g.y0) / g.T;
+            } else {        // x = (y c - u)/s
+                m[e] = v.c / v.s;
+                b[e] = (-ue[e] / v.s + g.y0 * m[e] - g.x0) / g.T;
+            }
+        }
+    } else {
+        const float sx = g.sod * v.c, sy = g.sod * v.s;
+        const float dxc = fmaf(-g.sdd, v.c, -uc * v.s), dyc = fmaf(-g.sdd, v.s, uc * v.c);
+        xmajor = fabsf(dxc) >= fabsf(dyc);
+        for (int e = 0; e < 2; ++e) {
+            const float dx = fmaf(-g.sdd, v.c, -ue[e] * v.s), dy = fmaf(-g.sdd, v.s, ue[e] * v.c);
+            if (xmajor) {
+                m[e] = dy / dx;
+                b[e] = (sy - g.y0 + (g.x0 - sx) * m[e]) / g.T;
+            } else {
+                m[e] = dx / dy;
+                b[e] = (sx - g.x0 + (g.y0 - sy) * m[e]) / g.T;
+            }
+        }
+    }
+    const float spread = 0.5f * fmaxf(fabsf(m[0]), fabsf(m[1])) + 1e-3f;
+    const int n_major = xmajor ? g.nx : g.ny;
+    const int n_minor = xmajor ? g.ny : g.nx;
+
+    for (int n = 0; n < n_major; ++n) {
+        const float qa = fmaf(m[0], (float)n, b[0]), qb = fmaf(m[1], (float)n, b[1]);
+        int q0 = (int)floorf(fminf(qa, qb) - spread + 0.5f);
+        int q1 = (int)floorf(fmaxf(qa, qb) + spread + 0.5f);
+        q0 = q0 < 0 ? 0 : q0;
+        q1 = q1 > n_minor - 1 ? n_minor - 1 : q1;
+        for (int q = q0; q <= q1; ++q) {
+            const int i = xmajor ? n : q, j = xmajor ? q : n;
+            const SfColumn f = sf_column(g, v, fmaf((float)i, g.T, g.x0), fmaf((float)j, g.T, g.y0));
+            const float fu = sf_fu(f, c);
+            if (!(fu > 0.0f)) continue;
+            const float *__restrict__ col = vol + ((size_t)j * g.nx + i);
+            const size_t kstride = (size_t)g.nx * g.ny;
+            if (g.type == SF_FAN) {
+                acc[0] = fmaf(fu, col[0], acc[0]);
+                continue;
+            }
+            const SfAxial ax = sf_axial(g, f.inv);
+            const float inv_av = 1.0f / ax.av;
+#pragma unroll
+            for (int rr = 0; rr < RC; ++rr) {
+                const int r = r0 + rr;
+                if (r >= g.nrows) break;
+                int k0 = (int)floorf(((float)r - ax.bv) * inv_av - 1e-3f);
+                int k1 = (int)floorf(((float)(r + 1) - ax.bv) * inv_av + 1e-3f);
+                k0 = k0 < 0 ? 0 : k0;
+                k1 = k1 > g.nz - 1 ? g.nz - 1 : k1;
+                float s = 0.0f;
+                for (int k = k0; k <= k1; ++k) s = fmaf(sf_fv(ax, r, k), col[(size_t)k * kstride], s);
+                acc[rr] = fmaf(fu, s, acc[rr]);
+            }
+        }
+    }
+    const SfAmpCol ac = sf_amp_col(g, v, c);
+#pragma unroll
+    for (int rr = 0; rr < RC; ++rr) out[rr] = (r0 + rr < g.nrows) ? sf_amp(g, v, ac, r0 + rr) * acc[rr] : 0.0f;
+}
