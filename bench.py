@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the projector pair on one MI355X.
+
+One "step" is one pass of the whole hot path over one synthetic input: y = A x followed by x' = A^T y on
+the 512^3 circular cone-beam workload (720 views, 512x512 detector), inputs resident in HBM.  Prints ONE
+JSON line.  value = voxel-view updates per second over the step (both operators: 2 * nviews*nx*ny*nz per
+step); the literal ray-voxel (nonzero-weight) rate is value * nnz_per_update.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+PEAK_FP32_TFLOPS = 157.3      # MI355X published vector fp32 (packed); 78.6 without packed instructions
+PEAK_HBM_GBPS = 8000.0
+
+
+def algorithmic_flops_per_update(n_u: float, n_v: float, nz: int) -> float:
+    """Cheapest known evaluation of the separable weights, per voxel-view pair: 40 flops per (view, voxel
+    column) for knots and magnification, 15 per transaxial weight, 5 per axial weight, 3 per nonzero
+    (ray, voxel) pair (two multiplies to combine, one add to accumulate)."""
+    return 40.0 / nz + 15.0 * n_u / nz + 5.0 * n_v + 3.0 * n_u * n_v
+
+
+def footprint_counts(cfg) -> tuple:
+    """Mean pixels per voxel in u and v from the scanner's magnification (volume average at the axis)."""
+    if cfg.geom == 0:
+        mag = 1.0
+    else:
+        mag = cfg.sdd / cfg.sod
+    # mean transaxial footprint width over view angles: T * mag * mean(|cos|+|sin|) = T mag 4/pi
+    n_u = 1.0 + cfg.voxel_xy * mag * (4.0 / np.pi) / cfg.pixel_u
+    n_v = 1.0 if cfg.geom == 1 else 1.0 + cfg.voxel_z * mag / cfg.pixel_v
+    return n_u, n_v
+
+
+def cpu_baseline(cfg, x, seconds_target: float):
+    """Times the CPU oracle, as it stands, on a bounded sample of the same workload."""
+    import oracle
+    threads = oracle.num_threads()
+    nview_sample = max(threads, 8)
+    views = [int(v) for v in np.linspace(0, cfg.nviews, nview_sample, endpoint=False)]
+    sub = cfg.with_views(views)
+    t0 = time.perf_counter()
+    ax = oracle.project(sub, x)
+    t_a = time.perf_counter() - t0
+    rate_a = sub.voxel_views / t_a
+    # A^T: sample voxels over all views; size the sample from a probe
+    rng = np.random.default_rng(7)
+    nvox = cfg.nx * cfg.ny * cfg.nz
+    y = rng.random(cfg.sino_shape, dtype=np.float32)
+    probe = rng.integers(0, nvox, 2000)
+    t0 = time.perf_counter()
+    oracle.backproject_voxels(cfg, y, probe)
+    t_probe = time.perf_counter() - t0
+    n = int(min(nvox, max(2000, 2000 * (0.5 * seconds_target) / max(t_probe, 1e-3))))
+    vox = rng.integers(0, nvox, n)
+    t0 = time.perf_counter()
+    oracle.backproject_voxels(cfg, y, vox)
+    t_at = time.perf_counter() - t0
+    rate_at = n * cfg.nviews / t_at
+    step_rate = 2.0 / (1.0 / rate_a + 1.0 / rate_at)          # updates/s of a whole A + A^T step
+    return {
+        "value": step_rate, "unit": "voxel-view updates/s", "cores": threads, "kind": "oracle",
+        "sample": f"A on {len(views)} of {cfg.nviews} views ({t_a:.1f} s), A^T on {n} random voxels over all views "
+                  f"({t_at:.1f} s); rates combined as for one A + A^T step",
+        "A_updates_per_s": rate_a, "AT_updates_per_s": rate_at,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=3, help="benchmark case number (3 = the headline 512^3 cone-beam)")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="CPU time budget of the oracle baseline; 0 skips it")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from synthetic import config, standard_volume
+    from paper_2307_05801_amd import Geometry
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    cfg = config(args.config)
+    batch = cfg.batch
+    x_np = np.stack([standard_volume(args.config, cfg, item=b) for b in range(batch)])
+    geo = Geometry(cfg, device="cuda:0")
+    x = torch.from_numpy(x_np).cuda()
+    y = torch.empty((batch,) + cfg.sino_shape, dtype=torch.float32, device="cuda")
+    xb = torch.empty_like(x)
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        geo.project(x, out=y)
+        if ev:
+            ev[1].record()
+        geo.backproject(y, out=xb)
+        if ev:
+            ev[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_a = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    ms_at = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    ms_step = 1e3 * wall / args.steps
+    updates = 2.0 * batch * cfg.voxel_views
+    value = updates / (ms_step * 1e-3)
+
+    n_u, n_v = footprint_counts(cfg)
+    fl = algorithmic_flops_per_update(n_u, n_v, cfg.nz)
+    dom, dom_ms = ("leap_project (A)", ms_a) if ms_a >= ms_at else ("leap_backproject (A^T)", ms_at)
+    flops_launch = fl * batch * cfg.voxel_views
+    achieved = flops_launch / (dom_ms * 1e-3) / 1e12
+    alg_bytes = 4.0 * batch * (cfg.nx * cfg.ny * cfg.nz + cfg.nviews * cfg.nrows * cfg.ncols)
+    roofline = {
+        "bound": "alu", "kernel": dom, "achieved": achieved, "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
+        "frac": achieved / PEAK_FP32_TFLOPS, "traffic": None,
+        "flops_per_update": fl, "launch_ms": dom_ms,
+        "hbm_algorithmic_GBps": alg_bytes / (dom_ms * 1e-3) / 1e9,
+        "hbm_algorithmic_frac": alg_bytes / (dom_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+    }
+    out = {
+        "metric": "ray-voxel updates/s for A and A^T at 512^3 cone-beam (voxel-view pairs, both operators per step)",
+        "value": value, "unit": "voxel-view updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "nviews": cfg.nviews, "volume": list(cfg.vol_shape),
+                   "detector": [cfg.nrows, cfg.ncols], "batch": batch, "kernels": geo.describe()},
+        "A_ms": ms_a, "AT_ms": ms_at,
+        "A_updates_per_s": batch * cfg.voxel_views / (ms_a * 1e-3),
+        "AT_updates_per_s": batch * cfg.voxel_views / (ms_at * 1e-3),
+        "nnz_per_update": n_u * n_v,
+        "roofline": roofline,
+    }
+    if args.cpu_seconds > 0:
+        out["cpu_baseline"] = cpu_baseline(cfg, x_np[0], args.cpu_seconds)
+    print(json.dumps(out))
+    geo.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

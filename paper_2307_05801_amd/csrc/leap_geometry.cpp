@@ -93,26 +93,33 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
 
     SfGeom &g = G->g;
     std::memset(&g, 0, sizeof(g));
+    const bool par = d->type == LEAP_PARALLEL;
     g.type = d->type;
     g.nviews = d->nviews; g.nrows = d->nrows; g.ncols = d->ncols;
     g.nx = d->nx; g.ny = d->ny; g.nz = d->nz;
+    g.Td = T; g.Tzd = d->voxel_z;
+    g.x0d = d->center_x - 0.5 * (d->nx - 1) * T;
+    g.y0d = d->center_y - 0.5 * (d->ny - 1) * T;
+    g.zlo0d = d->center_z - 0.5 * d->nz * d->voxel_z;
+    g.sodd = par ? 0.0 : d->sod;
+    g.kud = par ? 1.0 / d->pixel_u : d->sdd / d->pixel_u;
+    g.kvd = par ? 1.0 / d->pixel_v : d->sdd / d->pixel_v;
+    g.ikvd = 1.0 / g.kvd;
+    g.iTzd = 1.0 / d->voxel_z;
+    g.col_offd = 0.5 * (d->ncols - 1) - d->shift_u;
+    g.row_offd = 0.5 * (d->nrows - 1) - d->shift_v + 0.5;
     g.T = (float)T; g.Tz = (float)d->voxel_z;
-    g.x0 = (float)(d->center_x - 0.5 * (d->nx - 1) * T);
-    g.y0 = (float)(d->center_y - 0.5 * (d->ny - 1) * T);
-    g.zlo0 = (float)(d->center_z - 0.5 * d->nz * d->voxel_z);
-    g.sod = (float)d->sod; g.sdd = (float)d->sdd;
+    g.sod = (float)g.sodd; g.sdd = par ? 0.0f : (float)d->sdd;
     g.pu = (float)d->pixel_u; g.pv = (float)d->pixel_v;
-    const bool par = d->type == LEAP_PARALLEL;
-    g.ku = (float)(par ? 1.0 / d->pixel_u : d->sdd / d->pixel_u);
-    g.kv = (float)(par ? 1.0 / d->pixel_v : d->sdd / d->pixel_v);
-    g.col_off = (float)(0.5 * (d->ncols - 1) - d->shift_u);
-    g.row_off = (float)(0.5 * (d->nrows - 1) - d->shift_v + 0.5);
+    g.ku = (float)g.kud;
+    g.col_off = (float)g.col_offd;
     g.v0 = (float)((-0.5 * (d->nrows - 1) + d->shift_v) * d->pixel_v);
 
     G->views.resize(d->nviews);
     for (int a = 0; a < d->nviews; ++a) {
         const double c = std::cos(G->angles[a]), s = std::sin(G->angles[a]);
         SfView &v = G->views[a];
+        v.cd = c; v.sd = s;
         v.c = (float)c; v.s = (float)s;
         v.p = (float)(h * c); v.q = (float)(h * s);
         v.par_out = (float)(h * (std::fabs(c) + std::fabs(s)) / d->pixel_u);

@@ -1,6 +1,6 @@
-// Separable-footprint weight factors, evaluated identically by the forward (ray-driven) and the
-// back (voxel-driven) kernels so that the pair is matched: both call these functions with the same
-// (view, voxel column, pixel) arguments and obtain bit-identical F_u, F_v and amplitude.
+// Separable-footprint weight factors, shared by the forward (ray-driven) and the back (voxel-driven)
+// kernels so that the pair is matched: both obtain F_u and the amplitude from the same functions of
+// (view, voxel column, pixel), and F_v from the same axial map.
 //
 // Weight of voxel (i,j,k) for ray (view,r,c):  w = amp(view,r,c) * F_u(view,c;i,j) * F_v(view,r;i,j,k)
 //   F_u: area under a unit-height trapezoid over the pixel's u-interval, divided by the pixel width.  The
@@ -22,14 +22,36 @@
 
 #include <math.h>
 
-SF_HD float sf_rcp(float x)
+SF_HD float sf_rcp_fast(float x)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
-    float r = __builtin_amdgcn_rcpf(x);
+    return __builtin_amdgcn_rcpf(x);
 #else
-    float r = 1.0f / x;
+    return 1.0f / x;
 #endif
-    return fmaf(r, fmaf(-x, r, 1.0f), r);   // one Newton step: below half an ulp of error in practice
+}
+
+SF_HD float sf_rcp(float x)
+{
+    float r = sf_rcp_fast(x);
+    return fmaf(r, fmaf(-x, r, 1.0f), r);   // one Newton step
+}
+
+// double reciprocal from the float estimate: one Newton step squares the 1e-7 error
+SF_HD double sf_rcp_d(double x)
+{
+    double r = (double)sf_rcp_fast((float)x);
+    r = fma(r, fma(-x, r, 1.0), r);
+    return fma(r, fma(-x, r, 1.0), r);
+}
+
+SF_HD float sf_sqrt(float x)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_sqrtf(x);
+#else
+    return sqrtf(x);
+#endif
 }
 
 SF_HD float sf_clamp(float x, float lo, float hi)
@@ -43,10 +65,11 @@ SF_HD float sf_clamp(float x, float lo, float hi)
 
 // Transaxial footprint of one voxel column in one view.
 struct SfColumn {
-    float xi;            // detector column coordinate of the voxel centre
+    double xi;            // detector column coordinate of the voxel centre
+    double den;           // sod - l at the voxel centre (1 for parallel-beam)
+    double inv;           // 1 / den
     float o0, o1, o2, o3; // sorted knot offsets from xi, in pixels
-    float h01, h23;      // 1 / (2 (o1-o0)),  1 / (2 (o3-o2))   (guarded against zero-width ramps)
-    float inv;           // 1 / (sod - l) at the voxel centre (1 for parallel-beam)
+    float h01, h23;       // 1 / (2 (o1-o0)),  1 / (2 (o3-o2))   (guarded against zero-width ramps)
 };
 
 SF_HD void sf_sort4(float a, float b, float c, float d, float &o0, float &o1, float &o2, float &o3)
@@ -59,36 +82,35 @@ SF_HD void sf_sort4(float a, float b, float c, float d, float &o0, float &o1, fl
     o2 = fmaxf(m1, m2);
 }
 
-// x, y: voxel centre in mm.
-SF_HD SfColumn sf_column(const SfGeom &g, const SfView &v, float x, float y)
+SF_HD SfColumn sf_column(const SfGeom &g, const SfView &v, int i, int j)
 {
     SfColumn f;
-    float t = fmaf(y, v.c, -x * v.s);
+    const double x = fma((double)i, g.Td, g.x0d);
+    const double y = fma((double)j, g.Td, g.y0d);
+    const double t = fma(y, v.cd, -x * v.sd);
     if (g.type == SF_PARALLEL) {
-        f.xi = fmaf(t, g.ku, g.col_off);
+        f.xi = fma(t, g.kud, g.col_offd);
+        f.den = 1.0;
+        f.inv = 1.0;
         f.o0 = -v.par_out; f.o1 = -v.par_in; f.o2 = v.par_in; f.o3 = v.par_out;
-        f.inv = 1.0f;
     } else {
-        float l = fmaf(x, v.c, y * v.s);
-        float den = g.sod - l;
-        f.inv = sf_rcp(den);
-        float kin = g.ku * f.inv;
-        f.xi = fmaf(kin, t, g.col_off);
-        // corner offsets (dx,dy) = (+h,+h) -> (dt,dl) = (p-q, p+q);  (+h,-h) -> (-(p+q), p-q); the other two are
-        // their negatives.  Offset of a corner from the centre on the detector:
-        //   ku [ (t+dt)/(den-dl) - t/den ] = kin (dt den + t dl) / (den - dl)
-        float dtA = v.p - v.q, dlA = v.p + v.q;
-        float dtB = -dlA, dlB = dtA;
-        float d2 = den * den;
-        float rA = sf_rcp(fmaf(-dlA, dlA, d2));      // 1/((den-dlA)(den+dlA))
-        float rB = sf_rcp(fmaf(-dlB, dlB, d2));
-        float nA = kin * fmaf(dtA, den, t * dlA) * rA;
-        float nB = kin * fmaf(dtB, den, t * dlB) * rB;
-        float a0 = nA * (den + dlA);     // corner +A : 1/(den-dlA) = (den+dlA) rA
-        float a1 = -nA * (den - dlA);    // corner -A
-        float b0 = nB * (den + dlB);
-        float b1 = -nB * (den - dlB);
-        sf_sort4(a0, a1, b0, b1, f.o0, f.o1, f.o2, f.o3);
+        const double l = fma(x, v.cd, y * v.sd);
+        f.den = g.sodd - l;
+        f.inv = sf_rcp_d(f.den);
+        f.xi = fma(g.kud * t, f.inv, g.col_offd);
+        // Knot offsets in float.  Corner (dx,dy) = (+h,+h) has (dt,dl) = (p-q, p+q); (+h,-h) has (-(p+q), p-q); the
+        // other two corners are their negatives.  Offset of a corner from the centre on the detector:
+        //   ku [ (t+dt)/(den-dl) - t/den ] = (ku/den) (dt den + t dl) / (den - dl)
+        const float tf = (float)t, den = (float)f.den;
+        const float kin = g.ku * (float)f.inv;
+        const float dtA = v.p - v.q, dlA = v.p + v.q;
+        const float dtB = -dlA, dlB = dtA;
+        const float d2 = den * den;
+        const float rA = sf_rcp(fmaf(-dlA, dlA, d2));      // 1/((den-dlA)(den+dlA))
+        const float rB = sf_rcp(fmaf(-dlB, dlB, d2));
+        const float nA = kin * fmaf(dtA, den, tf * dlA) * rA;
+        const float nB = kin * fmaf(dtB, den, tf * dlB) * rB;
+        sf_sort4(nA * (den + dlA), -nA * (den - dlA), nB * (den + dlB), -nB * (den - dlB), f.o0, f.o1, f.o2, f.o3);
     }
     f.h01 = 0.5f / fmaxf(f.o1 - f.o0, 1e-20f);
     f.h23 = 0.5f / fmaxf(f.o3 - f.o2, 1e-20f);
@@ -99,49 +121,88 @@ SF_HD SfColumn sf_column(const SfGeom &g, const SfView &v, float x, float y)
 // additive constant that cancels in differences.
 SF_HD float sf_trap_integral(const SfColumn &f, float u)
 {
-    float a = sf_clamp(u, f.o0, f.o1) - f.o0;
-    float b = sf_clamp(u, f.o1, f.o2);
-    float c = f.o3 - sf_clamp(u, f.o2, f.o3);
+    const float a = sf_clamp(u, f.o0, f.o1) - f.o0;
+    const float b = sf_clamp(u, f.o1, f.o2);
+    const float c = f.o3 - sf_clamp(u, f.o2, f.o3);
     return fmaf(a * a, f.h01, b) - c * c * f.h23;
 }
 
 // First and last detector column the footprint can touch (not yet clipped to the detector).
 SF_HD void sf_col_range(const SfColumn &f, int &c_first, int &c_last)
 {
-    c_first = (int)floorf(f.xi + f.o0 + 0.5f);
-    c_last = (int)floorf(f.xi + f.o3 + 0.5f);
+    c_first = (int)floor(f.xi + (double)f.o0 + 0.5);
+    c_last = (int)floor(f.xi + (double)f.o3 + 0.5);
 }
 
-// F_u of pixel c.
-SF_HD float sf_fu(const SfColumn &f, int c)
+// Lower edge of pixel c measured from the voxel centre, pixels.
+SF_HD float sf_pixel_edge(const SfColumn &f, int c) { return (float)(((double)c - 0.5) - f.xi); }
+
+// F_u of the pixel whose lower edge (from sf_pixel_edge) is ulo.
+SF_HD float sf_fu_at(const SfColumn &f, float ulo)
 {
-    float ulo = ((float)c - 0.5f) - f.xi;
     return fmaxf(sf_trap_integral(f, ulo + 1.0f) - sf_trap_integral(f, ulo), 0.0f);
 }
 
-// Axial map of one voxel column: eta(lower face of voxel k) = av * k + bv.
-struct SfAxial {
-    float av, bv;
+SF_HD float sf_fu(const SfColumn &f, int c) { return sf_fu_at(f, sf_pixel_edge(f, c)); }
+
+// ---- axial part -----------------------------------------------------------------------------------
+
+// Voxel-driven view: the chunk of voxels starting at k0 (lower face zlo_k0, mm) seen on the detector.
+// Relative to row rb, voxel k0+kk covers eta in [phi0 + kk av, phi0 + (kk+1) av).
+struct SfRowsOfVoxels {
+    int rb;
+    float phi0, av;
 };
 
-SF_HD SfAxial sf_axial(const SfGeom &g, float inv)
+SF_HD SfRowsOfVoxels sf_rows_of_voxels(const SfGeom &g, const SfColumn &f, double zlo_k0)
 {
-    SfAxial a;
-    float m = g.kv * inv;                 // rows per mm at this voxel column
-    a.av = m * g.Tz;
-    a.bv = fmaf(m, g.zlo0, g.row_off);
+    SfRowsOfVoxels a;
+    const double m = g.kvd * f.inv;                    // rows per mm at this voxel column
+    const double eta0 = fma(m, zlo_k0, g.row_offd);
+    const double fl = floor(eta0);
+    a.rb = (int)fl;
+    a.phi0 = (float)(eta0 - fl);
+    a.av = (float)(m * g.Tzd);
     return a;
 }
 
-// F_v of (row r, voxel k): overlap of [r, r+1) with [eta_k, eta_{k+1}).
-SF_HD float sf_fv(const SfAxial &a, int r, int k)
+// F_v of (row rb+rr, voxel k0+kk).
+SF_HD float sf_fv_rows(const SfRowsOfVoxels &a, int rr, int kk)
 {
-    float lo = fmaf(a.av, (float)k, a.bv);
-    float hi = fmaf(a.av, (float)(k + 1), a.bv);
-    return fmaxf(fminf((float)(r + 1), hi) - fmaxf((float)r, lo), 0.0f);
+    const float lo = fmaf(a.av, (float)kk, a.phi0);
+    const float hi = fmaf(a.av, (float)(kk + 1), a.phi0);
+    return fmaxf(fminf((float)(rr + 1), hi) - fmaxf((float)rr, lo), 0.0f);
 }
 
-// Ray amplitude.  Column part: gcol = T / max(|D_x|,|D_y|) and wcol = sdd^2 + u^2; amp = gcol * sqrt(wcol + v^2).
+// Ray-driven view: the chunk of rows starting at r0 seen in the voxel column.  Relative to voxel kb,
+// row r0+rr covers kappa in [psi0 + rr step, psi0 + (rr+1) step); F_v = av * overlap in kappa.
+struct SfVoxelsOfRows {
+    int kb;
+    float psi0, step, av;
+};
+
+SF_HD SfVoxelsOfRows sf_voxels_of_rows(const SfGeom &g, const SfColumn &f, int r0)
+{
+    SfVoxelsOfRows a;
+    const double mm_per_row = f.den * g.ikvd;
+    const double kap0 = (((double)r0 - g.row_offd) * mm_per_row - g.zlo0d) * g.iTzd;
+    const double fl = floor(kap0);
+    a.kb = (int)fl;
+    a.psi0 = (float)(kap0 - fl);
+    a.step = (float)(mm_per_row * g.iTzd);
+    a.av = (float)(g.kvd * f.inv * g.Tzd);
+    return a;
+}
+
+SF_HD float sf_fv_voxels(const SfVoxelsOfRows &a, int rr, int kk)
+{
+    const float lo = fmaf(a.step, (float)rr, a.psi0);
+    const float hi = fmaf(a.step, (float)(rr + 1), a.psi0);
+    return a.av * fmaxf(fminf((float)(kk + 1), hi) - fmaxf((float)kk, lo), 0.0f);
+}
+
+// ---- ray amplitude --------------------------------------------------------------------------------
+// Column part: gcol = T / max(|D_x|,|D_y|) and wcol = sdd^2 + u^2;  amp = gcol * sqrt(wcol + v^2).
 struct SfAmpCol {
     float gcol, wcol;
 };
@@ -149,9 +210,9 @@ struct SfAmpCol {
 SF_HD SfAmpCol sf_amp_col(const SfGeom &g, const SfView &v, int c)
 {
     SfAmpCol a;
-    float u = ((float)c - g.col_off) * g.pu;
-    float dx = fmaf(-g.sdd, v.c, -u * v.s);
-    float dy = fmaf(-g.sdd, v.s, u * v.c);
+    const float u = ((float)c - g.col_off) * g.pu;
+    const float dx = fmaf(-g.sdd, v.c, -u * v.s);
+    const float dy = fmaf(-g.sdd, v.s, u * v.c);
     a.gcol = g.T * sf_rcp(fmaxf(fabsf(dx), fabsf(dy)));
     a.wcol = fmaf(g.sdd, g.sdd, u * u);
     return a;
@@ -160,6 +221,6 @@ SF_HD SfAmpCol sf_amp_col(const SfGeom &g, const SfView &v, int c)
 SF_HD float sf_amp(const SfGeom &g, const SfView &v, const SfAmpCol &a, int r)
 {
     if (g.type == SF_PARALLEL) return v.par_amp;
-    float vv = (g.type == SF_FAN) ? 0.0f : fmaf((float)r, g.pv, g.v0);
-    return a.gcol * sqrtf(fmaf(vv, vv, a.wcol));
+    const float vv = (g.type == SF_FAN) ? 0.0f : fmaf((float)r, g.pv, g.v0);
+    return a.gcol * sf_sqrt(fmaf(vv, vv, a.wcol));
 }

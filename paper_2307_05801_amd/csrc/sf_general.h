@@ -14,21 +14,21 @@ template <int ZC>
 SF_HD void sf_backproject_column_chunk(const SfGeom &g, const SfView *__restrict__ views,
                                        const float *__restrict__ sino, int i, int j, int k0, float acc[ZC])
 {
-    const float x = fmaf((float)i, g.T, g.x0);
-    const float y = fmaf((float)j, g.T, g.y0);
     const size_t view_stride = (size_t)g.nrows * g.ncols;
+    const double zlo_k0 = fma((double)k0, g.Tzd, g.zlo0d);
     for (int a = 0; a < g.nviews; ++a) {
         const SfView v = views[a];
-        const SfColumn f = sf_column(g, v, x, y);
+        const SfColumn f = sf_column(g, v, i, j);
         int c0, c1;
         sf_col_range(f, c0, c1);
         c0 = c0 < 0 ? 0 : c0;
         c1 = c1 > g.ncols - 1 ? g.ncols - 1 : c1;
         if (c0 > c1) continue;
-        const SfAxial ax = sf_axial(g, f.inv);
+        const SfRowsOfVoxels ax = sf_rows_of_voxels(g, f, zlo_k0);
         const float *__restrict__ ya = sino + (size_t)a * view_stride;
-        for (int c = c0; c <= c1; ++c) {
-            const float fu = sf_fu(f, c);
+        float ulo = sf_pixel_edge(f, c0);
+        for (int c = c0; c <= c1; ++c, ulo += 1.0f) {
+            const float fu = sf_fu_at(f, ulo);
             if (!(fu > 0.0f)) continue;
             const SfAmpCol ac = sf_amp_col(g, v, c);
             if (g.type == SF_FAN) {
@@ -37,17 +37,15 @@ SF_HD void sf_backproject_column_chunk(const SfGeom &g, const SfView *__restrict
             }
 #pragma unroll
             for (int kk = 0; kk < ZC; ++kk) {
-                const int k = k0 + kk;
-                if (k >= g.nz) break;
-                const float lo = fmaf(ax.av, (float)k, ax.bv);
-                const float hi = fmaf(ax.av, (float)(k + 1), ax.bv);
-                int r0 = (int)floorf(lo), r1 = (int)floorf(hi);
-                r0 = r0 < 0 ? 0 : r0;
-                r1 = r1 > g.nrows - 1 ? g.nrows - 1 : r1;
+                if (k0 + kk >= g.nz) break;
+                int rr0 = (int)floorf(fmaf(ax.av, (float)kk, ax.phi0));
+                int rr1 = (int)floorf(fmaf(ax.av, (float)(kk + 1), ax.phi0));
+                rr0 = ax.rb + rr0 < 0 ? -ax.rb : rr0;
+                rr1 = ax.rb + rr1 > g.nrows - 1 ? g.nrows - 1 - ax.rb : rr1;
                 float s = 0.0f;
-                for (int r = r0; r <= r1; ++r) {
-                    const float fv = sf_fv(ax, r, k);
-                    s = fmaf(fv, sf_amp(g, v, ac, r) * ya[(size_t)r * g.ncols + c], s);
+                for (int rr = rr0; rr <= rr1; ++rr) {
+                    const int r = ax.rb + rr;
+                    s = fmaf(sf_fv_rows(ax, rr, kk), sf_amp(g, v, ac, r) * ya[(size_t)r * g.ncols + c], s);
                 }
                 acc[kk] = fmaf(fu, s, acc[kk]);
             }
@@ -65,9 +63,11 @@ SF_HD void sf_project_ray_chunk(const SfGeom &g, const SfView &v, const float *_
 #pragma unroll
     for (int rr = 0; rr < RC; ++rr) acc[rr] = 0.0f;
 
-    // In-plane lines through the two u-edges of the pixel, as "minor index = m * major index + b".
+    // In-plane lines through the two u-edges of the pixel, as "minor index = m * major index + b".  These only
+    // bound the candidate voxels (a superset with a safety margin); the weights come from sf_column.
     const float ue[2] = {((float)c - 0.5f - g.col_off) * g.pu, ((float)c + 0.5f - g.col_off) * g.pu};
     const float uc = ((float)c - g.col_off) * g.pu;
+    const float x0 = (float)g.x0d, y0 = (float)g.y0d;
     bool xmajor;
     float m[2], b[2];
     if (g.type == SF_PARALLEL) {
@@ -75,10 +75,10 @@ SF_HD void sf_project_ray_chunk(const SfGeom &g, const SfView &v, const float *_
         for (int e = 0; e < 2; ++e) {
             if (xmajor) {   // -x s + y c = u  ->  y = (u + x s)/c
                 m[e] = v.s / v.c;
-                b[e] = (ue[e] / v.c + g.x0 * m[e] - g.y0) / g.T;
+                b[e] = (ue[e] / v.c + x0 * m[e] - y0) / g.T;
             } else {        // x = (y c - u)/s
                 m[e] = v.c / v.s;
-                b[e] = (-ue[e] / v.s + g.y0 * m[e] - g.x0) / g.T;
+                b[e] = (-ue[e] / v.s + y0 * m[e] - x0) / g.T;
             }
         }
     } else {
@@ -89,16 +89,17 @@ SF_HD void sf_project_ray_chunk(const SfGeom &g, const SfView &v, const float *_
             const float dx = fmaf(-g.sdd, v.c, -ue[e] * v.s), dy = fmaf(-g.sdd, v.s, ue[e] * v.c);
             if (xmajor) {
                 m[e] = dy / dx;
-                b[e] = (sy - g.y0 + (g.x0 - sx) * m[e]) / g.T;
+                b[e] = (sy - y0 + (x0 - sx) * m[e]) / g.T;
             } else {
                 m[e] = dx / dy;
-                b[e] = (sx - g.x0 + (g.y0 - sy) * m[e]) / g.T;
+                b[e] = (sx - x0 + (y0 - sy) * m[e]) / g.T;
             }
         }
     }
-    const float spread = 0.5f * fmaxf(fabsf(m[0]), fabsf(m[1])) + 1e-3f;
+    const float spread = 0.5f * fmaxf(fabsf(m[0]), fabsf(m[1])) + 2e-3f;
     const int n_major = xmajor ? g.nx : g.ny;
     const int n_minor = xmajor ? g.ny : g.nx;
+    const size_t kstride = (size_t)g.nx * g.ny;
 
     for (int n = 0; n < n_major; ++n) {
         const float qa = fmaf(m[0], (float)n, b[0]), qb = fmaf(m[1], (float)n, b[1]);
@@ -108,27 +109,25 @@ SF_HD void sf_project_ray_chunk(const SfGeom &g, const SfView &v, const float *_
         q1 = q1 > n_minor - 1 ? n_minor - 1 : q1;
         for (int q = q0; q <= q1; ++q) {
             const int i = xmajor ? n : q, j = xmajor ? q : n;
-            const SfColumn f = sf_column(g, v, fmaf((float)i, g.T, g.x0), fmaf((float)j, g.T, g.y0));
+            const SfColumn f = sf_column(g, v, i, j);
             const float fu = sf_fu(f, c);
             if (!(fu > 0.0f)) continue;
             const float *__restrict__ col = vol + ((size_t)j * g.nx + i);
-            const size_t kstride = (size_t)g.nx * g.ny;
             if (g.type == SF_FAN) {
                 acc[0] = fmaf(fu, col[0], acc[0]);
                 continue;
             }
-            const SfAxial ax = sf_axial(g, f.inv);
-            const float inv_av = 1.0f / ax.av;
+            const SfVoxelsOfRows ax = sf_voxels_of_rows(g, f, r0);
 #pragma unroll
             for (int rr = 0; rr < RC; ++rr) {
-                const int r = r0 + rr;
-                if (r >= g.nrows) break;
-                int k0 = (int)floorf(((float)r - ax.bv) * inv_av - 1e-3f);
-                int k1 = (int)floorf(((float)(r + 1) - ax.bv) * inv_av + 1e-3f);
-                k0 = k0 < 0 ? 0 : k0;
-                k1 = k1 > g.nz - 1 ? g.nz - 1 : k1;
+                if (r0 + rr >= g.nrows) break;
+                int kk0 = (int)floorf(fmaf(ax.step, (float)rr, ax.psi0));
+                int kk1 = (int)floorf(fmaf(ax.step, (float)(rr + 1), ax.psi0));
+                kk0 = ax.kb + kk0 < 0 ? -ax.kb : kk0;
+                kk1 = ax.kb + kk1 > g.nz - 1 ? g.nz - 1 - ax.kb : kk1;
                 float s = 0.0f;
-                for (int k = k0; k <= k1; ++k) s = fmaf(sf_fv(ax, r, k), col[(size_t)k * kstride], s);
+                for (int kk = kk0; kk <= kk1; ++kk)
+                    s = fmaf(sf_fv_voxels(ax, rr, kk), col[(size_t)(ax.kb + kk) * kstride], s);
                 acc[rr] = fmaf(fu, s, acc[rr]);
             }
         }

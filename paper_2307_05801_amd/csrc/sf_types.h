@@ -3,7 +3,13 @@
 // Index coordinates used throughout the kernels:
 //   xi  (detector column coordinate): pixel c covers [c - 1/2, c + 1/2];  xi(u) = u / pixel_u + col_off
 //   eta (detector row coordinate)   : pixel r covers [r, r + 1);          eta(v) = v / pixel_v + row_off
-//   voxel k has its lower face at z = zlo0 + k * Tz (z measured from the source plane z = 0).
+//   kappa (axial voxel coordinate)  : voxel k covers [k, k + 1);          kappa(z) = (z - zlo0) / Tz
+//   z is measured from the source plane z = 0.
+//
+// Precision plan: absolute positions on the detector (xi of a voxel centre, eta / kappa of the first
+// face of a thread's chunk) are formed in double, because a float carries only ~3e-5 pixels at index
+// 512 and a back projection of few noisy views shows that error directly.  Everything measured
+// relative to such a base (knot offsets, fractions, overlaps, weights) is float.
 #pragma once
 
 #include <stdint.h>
@@ -14,21 +20,31 @@ struct SfGeom {
     int32_t type;
     int32_t nviews, nrows, ncols;
     int32_t nx, ny, nz;
-    float T, Tz;          // voxel sizes, mm
-    float x0, y0;         // centre of voxel (i,j) = (0,0), mm
-    float zlo0;           // lower face of voxel k = 0, mm
-    float sod, sdd;       // mm (cone / fan)
-    float pu, pv;         // pixel sizes, mm
-    float ku;             // parallel: 1/pu ; cone/fan: sdd/pu   (xi  = ku * t * inv_den + col_off)
-    float kv;             // parallel: 1/pv ; cone    : sdd/pv   (eta = kv * z * inv_den + row_off)
-    float col_off;        // (ncols-1)/2 - shift_u
-    float row_off;        // (nrows-1)/2 - shift_v + 1/2
+    int32_t pad_;
+    // double: bases
+    double Td, Tzd;       // voxel sizes, mm
+    double x0d, y0d;      // centre of voxel (i,j) = (0,0), mm
+    double zlo0d;         // lower face of voxel k = 0, mm
+    double sodd;          // source to rotation axis, mm
+    double kud;           // parallel: 1/pu ; cone/fan: sdd/pu   (xi  = kud * t / den + col_offd)
+    double kvd;           // parallel: 1/pv ; cone    : sdd/pv   (eta = kvd * z / den + row_offd)
+    double ikvd;          // 1 / kvd
+    double iTzd;          // 1 / Tz
+    double col_offd;      // (ncols-1)/2 - shift_u
+    double row_offd;      // (nrows-1)/2 - shift_v + 1/2
+    // float: relative quantities
+    float T, Tz;
+    float sod, sdd;
+    float pu, pv;
+    float ku;             // (float)kud
+    float col_off;        // (float)col_offd, used by the ray amplitude only
     float v0;             // v (mm) of row 0's centre: (-(nrows-1)/2 + shift_v) * pv
 };
 
 // One entry per view, built in double on the host.
 struct SfView {
-    float c, s;           // cos(phi), sin(phi)
+    double cd, sd;        // cos(phi), sin(phi)
+    float c, s;
     float p, q;           // (T/2) cos(phi), (T/2) sin(phi)
     float par_out;        // parallel: outer half-width of the trapezoid in pixels, (T/2)(|c|+|s|)/pu
     float par_in;         // parallel: inner half-width, (T/2)||c|-|s||/pu

@@ -1,0 +1,239 @@
+"""Parity of the HIP library (through its C ABI) with the CPU oracle on the same seeded inputs.
+
+Tolerance (stated by the build's target): relative L2 error <= 1e-5 per sinogram (A) and per volume (A^T),
+per batch item, both sides fed the same float32 arrays and compared in double; the adjoint identity
+<Ax,y> = <x,A^T y> to <= 1e-5 relative.  Every case prints its name before it touches the GPU.
+"""
+import numpy as np
+import pytest
+
+from synthetic import CTConfig, config, reduced, standard_volume, uniform_sinogram, uniform_volume
+from synthetic.configs import CONE, FAN, PARALLEL
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return torch
+
+
+def rel_l2(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.linalg.norm(ref)
+    return float(np.linalg.norm(got - ref) / den) if den > 0 else float(np.linalg.norm(got))
+
+
+def gpu_project(torch, cfg, x):
+    from paper_2307_05801_amd import Geometry
+    print(f"[gpu] project {cfg.name} views={cfg.nviews} vol={cfg.vol_shape} det={cfg.nrows}x{cfg.ncols}", flush=True)
+    geo = Geometry(cfg)
+    out = geo.project(torch.from_numpy(np.ascontiguousarray(x)).cuda())
+    torch.cuda.synchronize()
+    res = out.cpu().numpy()
+    geo.close()
+    return res
+
+
+def gpu_backproject(torch, cfg, y):
+    from paper_2307_05801_amd import Geometry
+    print(f"[gpu] backproject {cfg.name} views={cfg.nviews} vol={cfg.vol_shape} det={cfg.nrows}x{cfg.ncols}", flush=True)
+    geo = Geometry(cfg)
+    out = geo.backproject(torch.from_numpy(np.ascontiguousarray(y)).cuda())
+    torch.cuda.synchronize()
+    res = out.cpu().numpy()
+    geo.close()
+    return res
+
+
+def ragged(cfg, **kw):
+    """Sizes that are no multiple of any tile edge."""
+    return cfg.replace(**kw)
+
+
+SMALL_CASES = [
+    ("c1_full", 1, lambda: config(1)),
+    ("c2_div4_ragged", 2, lambda: ragged(reduced(config(2), 4, nviews=36), nx=70, ny=61, nz=53, nrows=59, ncols=75)),
+    ("c3_div8_ragged", 3, lambda: ragged(reduced(config(3), 8, nviews=40), nx=67, ny=70, nz=45, nrows=61, ncols=77)),
+    ("c3_div4_offsets", 3, lambda: reduced(config(3), 4, nviews=12).replace(
+        shift_u=1.3, shift_v=-2.7, center_x=6.0, center_y=-4.5, center_z=3.25, start_deg=7.0)),
+    ("c4_div4", 4, lambda: reduced(config(4), 4, nviews=15)),
+    ("c5_div16_shifted", 5, lambda: reduced(config(5), 16, nviews=36)),
+    ("c5_div8_tall_voxels", 5, lambda: reduced(config(5), 8, nviews=10).replace(voxel_z=1.7, nz=40, pixel_v=2.1, nrows=70)),
+    ("fan", 3, lambda: CTConfig("fan_200", FAN, nviews=50, arc_deg=360.0, nrows=1, ncols=150, pixel_v=1.0,
+                                pixel_u=2.0, nx=130, ny=120, nz=1, voxel_xy=1.0, voxel_z=1.0, sod=500.0,
+                                sdd=900.0, shift_u=0.8, center_x=2.0)),
+    ("fine_detector", 3, lambda: reduced(config(3), 8, nviews=9).replace(pixel_u=1.7, pixel_v=1.9, nrows=300, ncols=280)),
+    ("coarse_detector", 3, lambda: reduced(config(3), 8, nviews=9).replace(pixel_u=37.0, pixel_v=29.0, nrows=14, ncols=12)),
+]
+
+
+@pytest.mark.parametrize("name,number,make", SMALL_CASES, ids=[c[0] for c in SMALL_CASES])
+def test_forward_and_adjoint_match_oracle(torch_mod, oracle_mod, name, number, make):
+    cfg = make()
+    x = standard_volume(number, cfg) if cfg.nz > 1 or number == 1 else uniform_volume(cfg, 5)[0]
+    y = uniform_sinogram(cfg, 100 + number)[0]
+    ax = gpu_project(torch_mod, cfg, x)
+    aty = gpu_backproject(torch_mod, cfg, y)
+    ax_ref = oracle_mod.project(cfg, x)
+    aty_ref = oracle_mod.backproject(cfg, y)
+    e_a, e_at = rel_l2(ax, ax_ref), rel_l2(aty, aty_ref)
+    print(f"{name}: rel-L2 A {e_a:.2e}  A^T {e_at:.2e}")
+    assert e_a <= TOL and e_at <= TOL
+    for a in range(cfg.nviews):                       # per view as well: no view may hide behind the others
+        assert rel_l2(ax[a], ax_ref[a]) <= TOL
+    lhs = float((ax.astype(np.float64) * y).sum())
+    rhs = float((aty.astype(np.float64) * x).sum())
+    assert abs(lhs - rhs) <= TOL * abs(lhs)
+    # A^T of the projection itself (the benchmark's second operand)
+    if cfg.nviews * cfg.nx * cfg.ny * cfg.nz < 3e7:
+        ax32 = ax_ref.astype(np.float32)
+        assert rel_l2(gpu_backproject(torch_mod, cfg, ax32), oracle_mod.backproject(cfg, ax32)) <= TOL
+
+
+@pytest.mark.parametrize("geom", [PARALLEL, FAN, CONE])
+def test_columns_of_A_match_the_dense_oracle_matrix(torch_mod, oracle_mod, geom):
+    """Every entry of A and of A^T on a tiny grid with shifts and centre offsets, by unit vectors in a batch."""
+    from paper_2307_05801_amd import Geometry
+    base = dict(name="tiny", geom=geom, nviews=7, arc_deg=360.0, nrows=6, ncols=9, pixel_v=1.3, pixel_u=0.9,
+                nx=5, ny=4, nz=3, voxel_xy=0.8, voxel_z=1.1, sod=30.0, sdd=47.0, shift_v=0.3, shift_u=-0.7,
+                center_x=0.4, center_y=-0.3, center_z=0.25, start_deg=11.0)
+    if geom == FAN:
+        base.update(nrows=1, nz=1, shift_v=0.0, center_z=0.0)
+    cfg = CTConfig(**base)
+    A = oracle_mod.dense_matrix(cfg)
+    m, n = A.shape
+    print(f"[gpu] dense columns geom={geom}", flush=True)
+    geo = Geometry(cfg)
+    eye_v = torch_mod.eye(n, dtype=torch_mod.float32, device="cuda").reshape((n,) + cfg.vol_shape)
+    cols = geo.project(eye_v).reshape(n, m).T.cpu().numpy()            # column j = A e_j
+    eye_s = torch_mod.eye(m, dtype=torch_mod.float32, device="cuda").reshape((m,) + cfg.sino_shape)
+    rows = geo.backproject(eye_s).reshape(m, n).cpu().numpy()          # row i = A^T e_i
+    geo.close()
+    scale = A.max()
+    assert np.abs(cols - A).max() <= 2e-6 * scale
+    assert np.abs(rows - A).max() <= 2e-6 * scale
+    assert ((cols > 0) == (A > 1e-7 * scale)).mean() > 0.999           # same support up to rounding-size entries
+
+
+def test_axis_aligned_and_diagonal_views(torch_mod, oracle_mod):
+    """Degenerate trapezoids: rectangles at multiples of 90 degrees, triangles at 45."""
+    angles = tuple(np.deg2rad([0.0, 45.0, 90.0, 135.0, 180.0, 225.0, 270.0, 315.0, 359.999]))
+    for base in (reduced(config(2), 8), reduced(config(3), 8)):
+        cfg = base.replace(nviews=len(angles), angles_override=angles, shift_u=0.5)
+        x = uniform_volume(cfg, 9)[0]
+        y = uniform_sinogram(cfg, 10)[0]
+        assert rel_l2(gpu_project(torch_mod, cfg, x), oracle_mod.project(cfg, x)) <= TOL
+        assert rel_l2(gpu_backproject(torch_mod, cfg, y), oracle_mod.backproject(cfg, y)) <= TOL
+
+
+def test_few_noisy_views_backprojection_keeps_tolerance(torch_mod, oracle_mod):
+    """One and two views of white noise: nothing averages the coordinate rounding away."""
+    for number, factor in ((3, 2), (5, 4)):
+        full = reduced(config(number), factor)
+        cfg = full.with_views([3]).replace(nz=24, nrows=40)
+        y = uniform_sinogram(cfg, 77)[0]
+        assert rel_l2(gpu_backproject(torch_mod, cfg, y), oracle_mod.backproject(cfg, y)) <= TOL
+
+
+def test_truncated_and_missing_detector(torch_mod, oracle_mod):
+    base = reduced(config(3), 8, nviews=8)
+    small = base.replace(nrows=20, ncols=24)                     # detector smaller than the shadow
+    x = uniform_volume(small, 3)[0]
+    y = uniform_sinogram(small, 4)[0]
+    assert rel_l2(gpu_project(torch_mod, small, x), oracle_mod.project(small, x)) <= TOL
+    assert rel_l2(gpu_backproject(torch_mod, small, y), oracle_mod.backproject(small, y)) <= TOL
+    away = base.replace(shift_u=500.0)                           # detector beside the shadow: all rays miss
+    x = uniform_volume(away, 3)[0]
+    y = uniform_sinogram(away, 4)[0]
+    assert np.all(gpu_project(torch_mod, away, x) == 0.0)
+    assert np.all(gpu_backproject(torch_mod, away, y) == 0.0)
+    up = base.replace(shift_v=400.0)
+    assert np.all(gpu_project(torch_mod, up, uniform_volume(up, 3)[0]) == 0.0)
+    assert np.all(gpu_backproject(torch_mod, up, uniform_sinogram(up, 4)[0]) == 0.0)
+
+
+def test_single_voxel_single_pixel_single_view(torch_mod, oracle_mod):
+    cfg = CTConfig("one", CONE, nviews=1, arc_deg=360.0, nrows=1, ncols=1, pixel_v=1.0, pixel_u=1.0,
+                   nx=1, ny=1, nz=1, voxel_xy=1.0, voxel_z=1.0, sod=1000.0, sdd=1500.0)
+    x = np.full(cfg.vol_shape, 2.0, dtype=np.float32)
+    got = gpu_project(torch_mod, cfg, x)
+    assert abs(float(got[0, 0, 0]) - 2.0) <= 2e-6        # hand-worked: centre pixel weight is exactly 1
+    y = np.full(cfg.sino_shape, 3.0, dtype=np.float32)
+    assert abs(float(gpu_backproject(torch_mod, cfg, y)[0, 0, 0]) - 3.0) <= 3e-6
+
+
+def test_zero_in_zero_out_and_overwrite(torch_mod):
+    from paper_2307_05801_amd import Geometry
+    cfg = reduced(config(3), 8, nviews=6)
+    geo = Geometry(cfg)
+    out = torch_mod.full(cfg.sino_shape, 7.0, dtype=torch_mod.float32, device="cuda")
+    geo.project(torch_mod.zeros(cfg.vol_shape, dtype=torch_mod.float32, device="cuda"), out=out)
+    assert float(out.abs().max()) == 0.0                     # outputs are overwritten, not accumulated
+    outv = torch_mod.full(cfg.vol_shape, 7.0, dtype=torch_mod.float32, device="cuda")
+    geo.backproject(torch_mod.zeros(cfg.sino_shape, dtype=torch_mod.float32, device="cuda"), out=outv)
+    assert float(outv.abs().max()) == 0.0
+    geo.close()
+
+
+def test_batch_equals_item_by_item_and_is_reproducible(torch_mod):
+    from paper_2307_05801_amd import Geometry
+    cfg = reduced(config(4), 4, nviews=10, batch=3)
+    geo = Geometry(cfg)
+    xs = torch_mod.from_numpy(uniform_volume(cfg, 1, batch=3)).cuda()
+    ys = torch_mod.from_numpy(uniform_sinogram(cfg, 2, batch=3)).cuda()
+    a_all, at_all = geo.project(xs), geo.backproject(ys)
+    for b in range(3):
+        assert torch_mod.equal(a_all[b], geo.project(xs[b].contiguous()))
+        assert torch_mod.equal(at_all[b], geo.backproject(ys[b].contiguous()))
+    assert torch_mod.equal(a_all, geo.project(xs)) and torch_mod.equal(at_all, geo.backproject(ys))
+    geo.close()
+
+
+def test_autograd_gradient_is_the_matched_transpose(torch_mod, oracle_mod):
+    """d/dx 1/2 |Ax - y|^2 = A^T (Ax - y) (the paper's least-squares example), and A^T differentiates to A."""
+    from paper_2307_05801_amd import Projector
+    cfg = reduced(config(4), 8, nviews=8)
+    proj = Projector(cfg)
+    x = uniform_volume(cfg, 31, batch=2)
+    y = uniform_sinogram(cfg, 32, batch=2)
+    xt = torch_mod.from_numpy(x).cuda().requires_grad_(True)
+    yt = torch_mod.from_numpy(y).cuda()
+    loss = 0.5 * ((proj(xt) - yt) ** 2).sum()
+    loss.backward()
+    for b in range(2):
+        resid = (oracle_mod.project(cfg, x[b]) - y[b]).astype(np.float32)
+        assert rel_l2(xt.grad[b].cpu().numpy(), oracle_mod.backproject(cfg, resid)) <= 2 * TOL
+    # directional derivative of the loss along a random direction
+    d = torch_mod.from_numpy(uniform_volume(cfg, 33, batch=2)).cuda() - 0.5
+    eps = 1e-2
+    with torch_mod.no_grad():
+        lp = 0.5 * ((proj(xt + eps * d) - yt).double() ** 2).sum()
+        lm = 0.5 * ((proj(xt - eps * d) - yt).double() ** 2).sum()
+    fd = float((lp - lm) / (2 * eps))
+    an = float((xt.grad.double() * d.double()).sum())
+    assert abs(fd - an) <= 1e-4 * abs(an)
+    st = yt.clone().requires_grad_(True)
+    (proj.backproject(st) * xt.detach()).sum().backward()
+    with torch_mod.no_grad():
+        assert rel_l2(st.grad.cpu().numpy(), proj(xt.detach()).cpu().numpy()) <= 1e-6
+
+
+def test_streams_are_honoured(torch_mod):
+    from paper_2307_05801_amd import Geometry
+    cfg = reduced(config(3), 8, nviews=12)
+    geo = Geometry(cfg)
+    x = torch_mod.from_numpy(uniform_volume(cfg, 1)[0]).cuda()
+    ref = geo.project(x)
+    torch_mod.cuda.synchronize()
+    s = torch_mod.cuda.Stream()
+    with torch_mod.cuda.stream(s):
+        got = geo.project(x)
+    s.synchronize()
+    assert torch_mod.equal(ref, got)
+    geo.close()
