@@ -3,10 +3,12 @@
 // float once, here.
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
 #include "leap_internal.h"
+#include "sf_backproject_tiled.h"
 
 static thread_local std::string g_last_error;
 
@@ -128,24 +130,64 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         v.xmajor = std::fabs(c) >= std::fabs(s) ? 1 : 0;
     }
 
-    // Footprint bounds over the whole volume (double): magnification is extreme at the bounding circle.
+    // Footprint bounds over the whole volume (double).  Magnification is extreme at the corner of the volume's
+    // bounding circle; a flat detector stretches a footprint seen at fan angle gamma by 1/cos(gamma).
     {
         const double rx = std::fabs(d->center_x) + half_x, ry = std::fabs(d->center_y) + half_y;
-        const double reach = std::sqrt(rx * rx + ry * ry);
-        const double mag_max = par ? 1.0 : d->sdd / (d->sod - reach);
-        const double mag_min = par ? 1.0 : d->sdd / (d->sod + reach);
-        G->max_cols_per_voxel = mag_max * T * std::sqrt(2.0) / d->pixel_u * (par ? 1.0 : 1.05);
-        G->max_rows_per_voxel = (d->type == LEAP_FAN) ? 1.0 : mag_max * d->voxel_z / d->pixel_v;
-        G->max_voxels_per_row = (d->type == LEAP_FAN) ? 1.0 : d->pixel_v / (mag_min * d->voxel_z);
-        double slope = 1.0;
+        const double reach = std::sqrt(rx * rx + ry * ry) + T;
+        double mag_max = 1.0, mag_min = 1.0, stretch = 1.0, slope = 1.0;
         if (!par) {
-            // widest fan half-angle seen by any detector column
-            const double umax = (0.5 * d->ncols + std::fabs(d->shift_u)) * d->pixel_u;
+            mag_max = d->sdd / std::fmax(d->sod - reach, 1e-9 * d->sod);
+            mag_min = d->sdd / (d->sod + reach);
+            const double umax = (0.5 * d->ncols + std::fabs(d->shift_u) + 2.0) * d->pixel_u;
             const double gam = std::atan(umax / d->sdd);
+            stretch = 1.02 / std::cos(gam);
             slope = (gam < 0.78) ? std::tan(0.7853981633974483 + gam) : 1e30;
         }
+        G->max_cols_per_voxel = mag_max * T * std::sqrt(2.0) / d->pixel_u * stretch;
+        G->max_rows_per_voxel = (d->type == LEAP_FAN) ? 1.0 : mag_max * d->voxel_z / d->pixel_v;
+        G->max_voxels_per_row = (d->type == LEAP_FAN) ? 1.0 : d->pixel_v / (mag_min * d->voxel_z);
         G->max_minor_slope = slope;
     }
+
+    // Tiled back projection: pick the template instance and verify its staged window against every
+    // (view, tile, z-chunk) with the very function the kernel evaluates.
+    if (d->type != LEAP_FAN && d->nz >= 8 && std::isfinite(G->max_cols_per_voxel) && G->max_cols_per_voxel <= 3.0 &&
+        G->max_rows_per_voxel <= 2.0) {
+        G->bp_nc = (int)std::ceil(G->max_cols_per_voxel) + 1;
+        if (G->bp_nc < 2) G->bp_nc = 2;
+        G->bp_nv = (int)std::ceil(G->max_rows_per_voxel - 1e-6) + 1;
+        if (G->bp_nv < 2) G->bp_nv = 2;
+        G->bp_wh = (float)(0.5 * G->max_cols_per_voxel);
+        const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T;
+        const float hx = 0.5f * (float)(BP_T - 1) * g.T;
+        for (int sh = 0; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
+            const int zc = BP_SHAPES[sh].zc;
+            const int chunks = (d->nz + zc - 1) / zc;
+            int need_w = 0, need_h = 0;
+            for (int a = 0; a < d->nviews; ++a)
+                for (int ty = 0; ty < tiles_y; ++ty)
+                    for (int tx = 0; tx < tiles_x; ++tx) {
+                        const float xc = (float)(g.x0d + ((double)(tx * BP_T) + 0.5 * (BP_T - 1)) * g.Td);
+                        const float yc = (float)(g.y0d + ((double)(ty * BP_T) + 0.5 * (BP_T - 1)) * g.Td);
+                        for (int ch = 0; ch < chunks; ch += (chunks > 1 ? chunks - 1 : 1)) {   // extremes: first and last chunk
+                            const float z0 = (float)(g.zlo0d + (double)(ch * zc) * g.Tzd), z1 = z0 + (float)zc * g.Tz;
+                            const SfWindow w = sf_bp_window(g, G->views[a], xc, yc, hx, z0, z1, G->bp_wh, G->bp_nc, G->bp_nv);
+                            need_w = w.need_w > need_w ? w.need_w : need_w;
+                            need_h = w.need_h > need_h ? w.need_h : need_h;
+                        }
+                    }
+            G->bp_need_w = need_w;
+            G->bp_need_h = need_h;
+            G->bp_shape = sh;
+            // one spare row and column: host and device floats may round apart
+            G->bp_tiled = need_w <= BP_SHAPES[sh].pw - 1 && need_h <= BP_SHAPES[sh].ph - 1;
+        }
+    }
+
+    // Testing aid: LEAP_FORCE_GENERAL=1 keeps every call on the general kernels.
+    if (const char *env = std::getenv("LEAP_FORCE_GENERAL"))
+        if (env[0] == '1') G->bp_tiled = false;
 
     hipError_t e = hipGetDevice(&G->device);
     if (e == hipSuccess) e = hipMalloc((void **)&G->d_views, sizeof(SfView) * (size_t)d->nviews);
@@ -169,9 +211,10 @@ extern "C" void leap_geometry_destroy(leap_geometry *G)
 extern "C" int leap_geometry_describe(const leap_geometry *G, char *buf, int32_t cap)
 {
     if (!G || !buf || cap <= 0) return invalid("null handle or buffer");
-    std::snprintf(buf, (size_t)cap, "type=%d kernels=%s cols/voxel<=%.2f rows/voxel<=%.2f voxels/row<=%.2f slope<=%.2f",
-                  G->g.type, G->tiled_ok ? "tiled" : "general", G->max_cols_per_voxel, G->max_rows_per_voxel,
-                  G->max_voxels_per_row, G->max_minor_slope);
+    std::snprintf(buf, (size_t)cap,
+                  "type=%d A=%s AT=%s(nc=%d,nv=%d,zc=%d,window=%dx%d) cols/voxel<=%.2f rows/voxel<=%.2f voxels/row<=%.2f slope<=%.2f",
+                  G->g.type, "general", G->bp_tiled ? "tiled" : "general", G->bp_nc, G->bp_nv, BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h,
+                  G->max_cols_per_voxel, G->max_rows_per_voxel, G->max_voxels_per_row, G->max_minor_slope);
     return LEAP_OK;
 }
 

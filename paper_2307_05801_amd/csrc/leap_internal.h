@@ -21,7 +21,11 @@ struct leap_geometry {
     double max_rows_per_voxel = 0;      // tallest axial footprint, in detector pixels
     double max_voxels_per_row = 0;      // tallest pixel, in voxels (at the smallest magnification)
     double max_minor_slope = 0;         // largest |d minor / d major| of any ray in its marching frame
-    bool tiled_ok = false;              // the tiled kernels' static limits hold
+    // tiled back projection: columns / rows read per voxel, half footprint width, and whether its limits hold
+    int bp_nc = 0, bp_nv = 0, bp_shape = 0;   // bp_shape indexes BP_SHAPES
+    float bp_wh = 0.f;
+    bool bp_tiled = false;
+    int bp_need_w = 0, bp_need_h = 0;   // largest staged window any (view, tile, chunk) asks for
 };
 
 void leap_set_error(const std::string &msg);

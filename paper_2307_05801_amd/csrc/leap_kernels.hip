@@ -3,6 +3,7 @@
 
 #include "leap_internal.h"
 #include "sf_general.h"
+#include "sf_backproject_tiled.h"
 
 // ------------------------------------------------------------------------------------------------
 // General kernels: plain loop nests over global memory, valid for every validated geometry.
@@ -61,9 +62,49 @@ int leap_launch_project(const leap_geometry *G, const float *d_vol, float *d_sin
     return LEAP_OK;
 }
 
+template <int NC, int NV, int SH>
+static void launch_bp_tiled(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
+{
+    constexpr SfBpShape S = BP_SHAPES[SH];
+    const SfGeom &g = G->g;
+    const unsigned tiles_x = cdiv(g.nx, BP_T), tiles_y = cdiv(g.ny, BP_T);
+    dim3 grid(tiles_x * tiles_y, cdiv(g.nz, S.zc), 1);
+    hipLaunchKernelGGL((sf_backproject_tiled<NC, NV, S.zc, S.pw, S.ph>), grid, dim3(256, 1, 1), 0, stream, g, G->d_views,
+                       d_sino, d_vol, (int)tiles_x, G->bp_wh);
+}
+
+template <int NC, int NV>
+static bool launch_bp_shape(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
+{
+    switch (G->bp_shape) {
+    case 0: launch_bp_tiled<NC, NV, 0>(G, d_sino, d_vol, stream); return true;
+    case 1: launch_bp_tiled<NC, NV, 1>(G, d_sino, d_vol, stream); return true;
+    case 2: launch_bp_tiled<NC, NV, 2>(G, d_sino, d_vol, stream); return true;
+    default: return false;
+    }
+}
+
 int leap_launch_backproject(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
 {
     const SfGeom &g = G->g;
+    if (G->bp_tiled) {
+        bool ok = false;
+        switch (G->bp_nc * 10 + G->bp_nv) {
+        case 22: ok = launch_bp_shape<2, 2>(G, d_sino, d_vol, stream); break;
+        case 23: ok = launch_bp_shape<2, 3>(G, d_sino, d_vol, stream); break;
+        case 32: ok = launch_bp_shape<3, 2>(G, d_sino, d_vol, stream); break;
+        case 33: ok = launch_bp_shape<3, 3>(G, d_sino, d_vol, stream); break;
+        case 42: ok = launch_bp_shape<4, 2>(G, d_sino, d_vol, stream); break;
+        case 43: ok = launch_bp_shape<4, 3>(G, d_sino, d_vol, stream); break;
+        default: break;
+        }
+        if (!ok) {
+            leap_set_error("internal: no tiled back-projection instance for this footprint");
+            return LEAP_UNSUPPORTED;
+        }
+        LEAP_HIP_CHECK(hipGetLastError());
+        return LEAP_OK;
+    }
     dim3 block(64, 4, 1);
     dim3 grid(cdiv(g.nx, 64), cdiv(g.ny, 4), cdiv(g.nz, GEN_ZC));
     if (grid.y > 65535u || grid.z > 65535u) {

@@ -1,0 +1,196 @@
+// Tiled back projection (A^T): voxel-driven gather, no atomics, bitwise reproducible.
+//
+// A workgroup of 256 threads owns a 16 x 16 tile of voxel columns and BP_ZC voxels along z; a thread
+// owns one column of BP_ZC voxels and keeps their sums in registers while the workgroup walks all views.
+// Per view the workgroup stages the detector window its tile can touch into LDS, already multiplied by
+// the ray amplitude (so the weight left per sample is F_u * F_v), double-buffered: the loads of view
+// a+1 are in flight while view a is gathered.  Everything outside the detector is staged as zero, which
+// is the truncation rule for footprints that leave the detector.
+//
+// Static limits (checked on the host before this kernel is chosen): a voxel touches at most NC detector
+// columns and NV detector rows; the window of any (view, tile, chunk) fits BP_PW x BP_PH.
+#pragma once
+
+#include "sf_footprint.h"
+
+constexpr int BP_T = 16;        // tile edge in voxels (x and y)
+
+// Shapes the kernel is instantiated for: voxels along z per thread, staged window columns x rows.
+struct SfBpShape {
+    int zc, pw, ph;
+};
+constexpr SfBpShape BP_SHAPES[] = {{32, 32, 44}, {16, 32, 44}, {16, 64, 48}};
+constexpr int BP_NSHAPES = 3;
+
+// Window of the detector that one (view, tile, z-chunk) can touch.  Evaluated identically on the host
+// (limit check) and in the kernel; everything here is uniform over the workgroup.
+struct SfWindow {
+    int c0, r0;       // first staged column / row
+    int need_w, need_h;
+};
+
+// xc, yc: tile centre (mm); hx: half extent of the voxel centres in x and y (mm); z0, z1: lower / upper face
+// of the chunk (mm); wh: half of the widest transaxial footprint (pixels); nc, nv: columns / rows a thread reads
+// per voxel (starting at the first one its footprint touches).
+SF_HD SfWindow sf_bp_window(const SfGeom &g, const SfView &v, float xc, float yc, float hx, float z0, float z1, float wh,
+                            int nc, int nv)
+{
+    SfWindow w;
+    const float tc = fmaf(yc, v.c, -xc * v.s);
+    const float rho = hx * (fabsf(v.c) + fabsf(v.s));
+    const float tlo = tc - rho, thi = tc + rho;
+    float ilo = 1.0f, ihi = 1.0f;       // smallest / largest 1/den over the tile
+    if (g.type != SF_PARALLEL) {
+        const float lc = fmaf(xc, v.c, yc * v.s);
+        ilo = sf_rcp(g.sod - lc + rho);
+        ihi = sf_rcp(g.sod - lc - rho);
+    }
+    const float kv = (float)g.kvd, row_off = (float)g.row_offd;
+    const float xi_lo = fmaf(g.ku * tlo, tlo >= 0.0f ? ilo : ihi, g.col_off);
+    const float xi_hi = fmaf(g.ku * thi, thi >= 0.0f ? ihi : ilo, g.col_off);
+    const float eta_lo = fmaf(kv * z0, z0 >= 0.0f ? ilo : ihi, row_off);
+    const float eta_hi = fmaf(kv * z1, z1 >= 0.0f ? ihi : ilo, row_off);
+    w.c0 = (int)floorf(xi_lo - wh + 0.48f);
+    w.r0 = (int)floorf(eta_lo - 0.02f);
+    w.need_w = (int)floorf(xi_hi + 0.52f) + nc - w.c0;       // a thread reads nc columns from its first one
+    w.need_h = (int)floorf(eta_hi + 0.02f) + nv - w.r0;      // and nv rows from the first row of each voxel
+    return w;
+}
+
+#if defined(__HIPCC__)
+
+// Staging, first half: fetch this thread's share of the window of one view into registers.  ya points at the view.
+template <int NC, int NV, int PW, int PH, int NSTAGE>
+__device__ __forceinline__ void bp_load_view(const SfGeom &g, const SfView v, const float *__restrict__ ya, float xc, float yc,
+                                             float hx, float z0, float z1, float wh, int sc, int sr, SfWindow &w,
+                                             float (&stage)[NSTAGE])
+{
+    constexpr int RSTEP = 256 / PW;
+    w = sf_bp_window(g, v, xc, yc, hx, z0, z1, wh, NC, NV);
+    const int c = w.c0 + sc;
+    const bool cin = c >= 0 && c < g.ncols;
+    ya += cin ? c : 0;
+#pragma unroll
+    for (int s = 0; s < NSTAGE; ++s) {
+        const int r = w.r0 + sr + RSTEP * s;
+        const bool in = cin && r >= 0 && r < g.nrows && (sr + RSTEP * s) < PH;
+        stage[s] = in ? ya[(size_t)r * g.ncols] : 0.0f;
+    }
+}
+
+// Staging, second half: scale by the ray amplitude and write to LDS.
+template <int PW, int PH, int NSTAGE>
+__device__ __forceinline__ void bp_store_view(const SfGeom &g, const SfView v, int sc, int sr, const SfWindow &w,
+                                              const float (&stage)[NSTAGE], float *__restrict__ buf)
+{
+    constexpr int RSTEP = 256 / PW, PS = PW + 1;
+    const SfAmpCol ac = sf_amp_col(g, v, w.c0 + sc);
+#pragma unroll
+    for (int s = 0; s < NSTAGE; ++s) {
+        const int row = sr + RSTEP * s;
+        if (row < PH) buf[row * PS + sc] = stage[s] * sf_amp(g, v, ac, w.r0 + row);
+    }
+}
+
+template <int NC, int NV, int BP_ZC, int BP_PW, int BP_PH>
+__global__ __launch_bounds__(256, 4) void sf_backproject_tiled(SfGeom g, const SfView *__restrict__ views,
+                                                            const float *__restrict__ sino, float *__restrict__ vol,
+                                                            int tiles_x, float wh)
+{
+    constexpr int BP_PS = BP_PW + 1;      // LDS row stride (floats)
+    __shared__ float patch[2][BP_PH * BP_PS];
+
+    const int tid = threadIdx.x;
+    const int ti = tid & (BP_T - 1), tj = tid >> 4;
+    const int tx = blockIdx.x % tiles_x, ty = blockIdx.x / tiles_x;
+    const int i0 = tx * BP_T, j0 = ty * BP_T;
+    const int k0 = blockIdx.y * BP_ZC;
+    const int i = i0 + ti, j = j0 + tj;
+    const int ic = i < g.nx ? i : g.nx - 1, jc = j < g.ny ? j : g.ny - 1;   // out-of-volume threads shadow the edge
+
+    const double zlo_k0 = fma((double)k0, g.Tzd, g.zlo0d);
+    const float z0 = (float)zlo_k0, z1 = z0 + (float)BP_ZC * g.Tz;
+    const float hx = 0.5f * (float)(BP_T - 1) * g.T;
+    const float xc = (float)(g.x0d + ((double)i0 + 0.5 * (BP_T - 1)) * g.Td);
+    const float yc = (float)(g.y0d + ((double)j0 + 0.5 * (BP_T - 1)) * g.Td);
+
+    // staging role: element e = tid + 256 s  ->  window column tid % PW, window row tid / PW + RSTEP s
+    const int sc = tid & (BP_PW - 1), sr = tid / BP_PW;
+    constexpr int NSTAGE = (BP_PH * BP_PW + 255) / 256;
+    const size_t view_stride = (size_t)g.nrows * g.ncols;
+
+    float acc[BP_ZC];
+#pragma unroll
+    for (int kk = 0; kk < BP_ZC; ++kk) acc[kk] = 0.0f;
+
+    float stage[NSTAGE];
+    SfWindow win_next;
+
+    SfWindow win;
+    bp_load_view<NC, NV, BP_PW, BP_PH, NSTAGE>(g, views[0], sino, xc, yc, hx, z0, z1, wh, sc, sr, win, stage);
+    win_next = win;
+    bp_store_view<BP_PW, BP_PH, NSTAGE>(g, views[0], sc, sr, win, stage, patch[0]);
+    __syncthreads();
+
+    for (int a = 0; a < g.nviews; ++a) {
+        const float *buf = patch[a & 1];
+        if (a + 1 < g.nviews)      // global loads in flight during the gather
+            bp_load_view<NC, NV, BP_PW, BP_PH, NSTAGE>(g, views[a + 1], sino + (size_t)(a + 1) * view_stride, xc, yc, hx, z0, z1, wh, sc,
+                                                       sr, win_next, stage);
+
+        const SfView v = views[a];
+        const SfColumn f = sf_column(g, v, ic, jc);
+        int cf, cl;
+        sf_col_range(f, cf, cl);
+        float fu[NC];
+        {
+            float e = sf_pixel_edge(f, cf);
+            float g0 = sf_trap_integral(f, e);
+#pragma unroll
+            for (int m = 0; m < NC; ++m) {
+                e += 1.0f;
+                const float g1 = sf_trap_integral(f, e);
+                fu[m] = fmaxf(g1 - g0, 0.0f);
+                g0 = g1;
+            }
+        }
+        const SfRowsOfVoxels ax = sf_rows_of_voxels(g, f, zlo_k0);
+        int ofs = (ax.rb - win.r0) * BP_PS + (cf - win.c0);
+
+#pragma unroll
+        for (int kk = 0; kk < BP_ZC; ++kk) {
+            const float lo = fmaf(ax.av, (float)kk, ax.phi0);
+            const float hi = fmaf(ax.av, (float)(kk + 1), ax.phi0);
+            const float fl = floorf(lo);
+            const float *q = buf + (ofs + (int)fl * BP_PS);
+            float sum = 0.0f;
+#pragma unroll
+            for (int jj = 0; jj < NV; ++jj) {
+                const float top = fl + (float)(jj + 1);
+                const float w = (jj == 0) ? fminf(top, hi) - lo : sf_clamp(hi - (top - 1.0f), 0.0f, 1.0f);
+                float s = 0.0f;
+#pragma unroll
+                for (int m = 0; m < NC; ++m) s = fmaf(fu[m], q[jj * BP_PS + m], s);
+                sum = fmaf(w, s, sum);
+            }
+            acc[kk] += sum;
+            // An opaque dependency every few voxels: the LDS reads of the next group need `ofs`, which is only
+            // available once this group's sums exist.  Without it the compiler issues all reads of the unrolled
+            // loop first and spills them.
+            if ((kk & 3) == 3)
+                asm volatile("" : "+v"(ofs), "+v"(acc[kk - 3]), "+v"(acc[kk - 2]), "+v"(acc[kk - 1]), "+v"(acc[kk]));
+        }
+
+        if (a + 1 < g.nviews) bp_store_view<BP_PW, BP_PH, NSTAGE>(g, views[a + 1], sc, sr, win_next, stage, patch[(a + 1) & 1]);
+        win = win_next;
+        __syncthreads();
+    }
+
+    if (i < g.nx && j < g.ny) {
+#pragma unroll
+        for (int kk = 0; kk < BP_ZC; ++kk)
+            if (k0 + kk < g.nz) vol[((size_t)(k0 + kk) * g.ny + j) * g.nx + i] = acc[kk];
+    }
+}
+
+#endif

@@ -112,8 +112,8 @@ SF_HD SfColumn sf_column(const SfGeom &g, const SfView &v, int i, int j)
         const float nB = kin * fmaf(dtB, den, tf * dlB) * rB;
         sf_sort4(nA * (den + dlA), -nA * (den - dlA), nB * (den + dlB), -nB * (den - dlB), f.o0, f.o1, f.o2, f.o3);
     }
-    f.h01 = 0.5f / fmaxf(f.o1 - f.o0, 1e-20f);
-    f.h23 = 0.5f / fmaxf(f.o3 - f.o2, 1e-20f);
+    f.h01 = 0.5f * sf_rcp(fmaxf(f.o1 - f.o0, 1e-20f));
+    f.h23 = 0.5f * sf_rcp(fmaxf(f.o3 - f.o2, 1e-20f));
     return f;
 }
 
