@@ -8,7 +8,9 @@
 #include <new>
 
 #include "leap_internal.h"
+#define SF_NO_KERNELS   // this file needs the kernels' host-side limit functions only
 #include "sf_backproject_tiled.h"
+#include "sf_project_columns.h"
 
 static thread_local std::string g_last_error;
 
@@ -152,8 +154,8 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
 
     // Tiled back projection: pick the template instance and verify its staged window against every
     // (view, tile, z-chunk) with the very function the kernel evaluates.
-    if (d->type != LEAP_FAN && d->nz >= 8 && std::isfinite(G->max_cols_per_voxel) && G->max_cols_per_voxel <= 3.0 &&
-        G->max_rows_per_voxel <= 2.0) {
+    if (d->type != LEAP_FAN && d->nz >= 8 && std::isfinite(G->max_cols_per_voxel) && G->max_cols_per_voxel <= 4.0 &&
+        G->max_rows_per_voxel <= 3.0) {
         G->bp_nc = (int)std::ceil(G->max_cols_per_voxel) + 1;
         if (G->bp_nc < 2) G->bp_nc = 2;
         G->bp_nv = (int)std::ceil(G->max_rows_per_voxel - 1e-6) + 1;
@@ -185,13 +187,50 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         }
     }
 
+    // Column-wise forward projection: static limits, then its scratch copy of the volume.
+    if (d->type != LEAP_FAN && d->nrows >= 32 && std::isfinite(G->max_voxels_per_row) && G->max_voxels_per_row <= 3.0 &&
+        (double)d->nx * d->ny * (d->nz + 2.0 * FP_PAD) < 4294967296.0 && d->ny <= 65535) {
+        int need = 0;
+        for (int a = 0; a < d->nviews; ++a)
+            for (int c = 0; c < d->ncols; ++c) {
+                const SfRayLines L = sf_ray_lines(g, G->views[a], c);
+                const int n_major = L.xmajor ? d->nx : d->ny;
+                const float d0 = std::fabs(L.b0 - L.b1);
+                const float d1 = std::fabs(fmaf(L.m0 - L.m1, (float)(n_major - 1), L.b0 - L.b1));
+                const float dm = d0 > d1 ? d0 : d1;
+                if (!(dm < 1e6f)) { need = 1 << 20; break; }
+                const int cnt = (int)std::floor(dm + 2.0f * L.spread + 1e-3f) + 2;
+                need = cnt > need ? cnt : need;
+            }
+        G->fp_need_q = need;
+        G->fp_nq = need <= 4 ? 4 : (need <= 8 ? 8 : 16);
+        G->fp_nk = (int)std::ceil(G->max_voxels_per_row - 1e-6) + 1;
+        if (G->fp_nk < 2) G->fp_nk = 2;
+        const int groups = (d->nrows + 63) / 64;
+        G->fp_rg = groups >= 8 ? 8 : (groups >= 4 ? 4 : (groups >= 2 ? 2 : 1));
+        G->fp_columns = need <= 16 && G->fp_nk <= 4;
+    }
+
     // Testing aid: LEAP_FORCE_GENERAL=1 keeps every call on the general kernels.
     if (const char *env = std::getenv("LEAP_FORCE_GENERAL"))
-        if (env[0] == '1') G->bp_tiled = false;
+        if (env[0] == '1') G->bp_tiled = G->fp_columns = false;
 
     hipError_t e = hipGetDevice(&G->device);
     if (e == hipSuccess) e = hipMalloc((void **)&G->d_views, sizeof(SfView) * (size_t)d->nviews);
     if (e == hipSuccess) e = hipMemcpy(G->d_views, G->views.data(), sizeof(SfView) * (size_t)d->nviews, hipMemcpyHostToDevice);
+    if (e == hipSuccess && G->fp_columns) {
+        G->nzp = d->nz + 2 * FP_PAD;
+        const size_t bytes = sizeof(float) * (size_t)d->nx * d->ny * G->nzp;
+        hipError_t es = hipMalloc((void **)&G->d_volz, bytes);
+        if (es == hipSuccess) es = hipMemset(G->d_volz, 0, bytes);       // the pads stay zero for the handle's life
+        if (es == hipSuccess) es = hipDeviceSynchronize();
+        if (es != hipSuccess) {                                           // no room for the copy: use the general kernel
+            if (G->d_volz) (void)hipFree(G->d_volz);
+            G->d_volz = nullptr;
+            G->fp_columns = false;
+            (void)hipGetLastError();
+        }
+    }
     if (e != hipSuccess) {
         if (G->d_views) (void)hipFree(G->d_views);
         delete G;
@@ -205,6 +244,7 @@ extern "C" void leap_geometry_destroy(leap_geometry *G)
 {
     if (!G) return;
     if (G->d_views) (void)hipFree(G->d_views);
+    if (G->d_volz) (void)hipFree(G->d_volz);
     delete G;
 }
 
@@ -212,8 +252,9 @@ extern "C" int leap_geometry_describe(const leap_geometry *G, char *buf, int32_t
 {
     if (!G || !buf || cap <= 0) return invalid("null handle or buffer");
     std::snprintf(buf, (size_t)cap,
-                  "type=%d A=%s AT=%s(nc=%d,nv=%d,zc=%d,window=%dx%d) cols/voxel<=%.2f rows/voxel<=%.2f voxels/row<=%.2f slope<=%.2f",
-                  G->g.type, "general", G->bp_tiled ? "tiled" : "general", G->bp_nc, G->bp_nv, BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h,
+                  "type=%d A=%s(nq=%d/%d,nk=%d,rg=%d) AT=%s(nc=%d,nv=%d,zc=%d,window=%dx%d) cols/voxel<=%.2f rows/voxel<=%.2f "
+                  "voxels/row<=%.2f slope<=%.2f",
+                  G->g.type, G->fp_columns ? "columns" : "general", G->fp_need_q, G->fp_nq, G->fp_nk, G->fp_rg, G->bp_tiled ? "tiled" : "general", G->bp_nc, G->bp_nv, BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h,
                   G->max_cols_per_voxel, G->max_rows_per_voxel, G->max_voxels_per_row, G->max_minor_slope);
     return LEAP_OK;
 }

@@ -4,6 +4,7 @@
 #include "leap_internal.h"
 #include "sf_general.h"
 #include "sf_backproject_tiled.h"
+#include "sf_project_columns.h"
 
 // ------------------------------------------------------------------------------------------------
 // General kernels: plain loop nests over global memory, valid for every validated geometry.
@@ -48,9 +49,59 @@ __global__ __launch_bounds__(256) void sf_project_general(SfGeom g, const SfView
 
 static inline unsigned cdiv(unsigned a, unsigned b) { return (a + b - 1) / b; }
 
+template <int NQ, int NK, int RG>
+static void launch_fp_columns(const leap_geometry *G, float *d_sino, hipStream_t stream)
+{
+    const SfGeom &g = G->g;
+    const int col_tiles = (int)cdiv(g.ncols, FP_WAVES), bands = (int)cdiv(g.nrows, RG * 64);
+    dim3 grid((unsigned)col_tiles * bands * g.nviews, 1, 1);
+    hipLaunchKernelGGL((sf_project_columns<NQ, NK, RG>), grid, dim3(FP_WAVES * 64, 1, 1), 0, stream, g, G->d_views, G->d_volz,
+                       d_sino, G->nzp, col_tiles, bands);
+}
+
+template <int NQ, int NK>
+static bool launch_fp_rg(const leap_geometry *G, float *d_sino, hipStream_t stream)
+{
+    switch (G->fp_rg) {
+    case 1: launch_fp_columns<NQ, NK, 1>(G, d_sino, stream); return true;
+    case 2: launch_fp_columns<NQ, NK, 2>(G, d_sino, stream); return true;
+    case 4: launch_fp_columns<NQ, NK, 4>(G, d_sino, stream); return true;
+    case 8: launch_fp_columns<NQ, NK, 8>(G, d_sino, stream); return true;
+    default: return false;
+    }
+}
+
+template <int NQ>
+static bool launch_fp_nk(const leap_geometry *G, float *d_sino, hipStream_t stream)
+{
+    switch (G->fp_nk) {
+    case 2: return launch_fp_rg<NQ, 2>(G, d_sino, stream);
+    case 3: return launch_fp_rg<NQ, 3>(G, d_sino, stream);
+    case 4: return launch_fp_rg<NQ, 4>(G, d_sino, stream);
+    default: return false;
+    }
+}
+
 int leap_launch_project(const leap_geometry *G, const float *d_vol, float *d_sino, hipStream_t stream)
 {
     const SfGeom &g = G->g;
+    if (G->fp_columns) {
+        dim3 tgrid(cdiv(g.nx, 32), cdiv(g.nz, 32), g.ny);
+        hipLaunchKernelGGL(sf_volume_to_columns, tgrid, dim3(32, 8, 1), 0, stream, d_vol, G->d_volz, g.nx, g.ny, g.nz, G->nzp);
+        bool ok = false;
+        switch (G->fp_nq) {
+        case 4: ok = launch_fp_nk<4>(G, d_sino, stream); break;
+        case 8: ok = launch_fp_nk<8>(G, d_sino, stream); break;
+        case 16: ok = launch_fp_nk<16>(G, d_sino, stream); break;
+        default: break;
+        }
+        if (!ok) {
+            leap_set_error("internal: no column-wise forward instance for this footprint");
+            return LEAP_UNSUPPORTED;
+        }
+        LEAP_HIP_CHECK(hipGetLastError());
+        return LEAP_OK;
+    }
     dim3 block(64, 4, 1);
     dim3 grid(cdiv(g.ncols, 64), cdiv(cdiv(g.nrows, GEN_RC), 4), g.nviews);
     if (grid.y > 65535u) {
@@ -94,8 +145,14 @@ int leap_launch_backproject(const leap_geometry *G, const float *d_sino, float *
         case 23: ok = launch_bp_shape<2, 3>(G, d_sino, d_vol, stream); break;
         case 32: ok = launch_bp_shape<3, 2>(G, d_sino, d_vol, stream); break;
         case 33: ok = launch_bp_shape<3, 3>(G, d_sino, d_vol, stream); break;
+        case 24: ok = launch_bp_shape<2, 4>(G, d_sino, d_vol, stream); break;
+        case 34: ok = launch_bp_shape<3, 4>(G, d_sino, d_vol, stream); break;
         case 42: ok = launch_bp_shape<4, 2>(G, d_sino, d_vol, stream); break;
         case 43: ok = launch_bp_shape<4, 3>(G, d_sino, d_vol, stream); break;
+        case 44: ok = launch_bp_shape<4, 4>(G, d_sino, d_vol, stream); break;
+        case 52: ok = launch_bp_shape<5, 2>(G, d_sino, d_vol, stream); break;
+        case 53: ok = launch_bp_shape<5, 3>(G, d_sino, d_vol, stream); break;
+        case 54: ok = launch_bp_shape<5, 4>(G, d_sino, d_vol, stream); break;
         default: break;
         }
         if (!ok) {

@@ -57,7 +57,7 @@ SF_HD SfWindow sf_bp_window(const SfGeom &g, const SfView &v, float xc, float yc
     return w;
 }
 
-#if defined(__HIPCC__)
+#if defined(__HIPCC__) && !defined(SF_NO_KERNELS)
 
 // Staging, first half: fetch this thread's share of the window of one view into registers.  ya points at the view.
 template <int NC, int NV, int PW, int PH, int NSTAGE>

@@ -1,0 +1,208 @@
+// Forward projection (A), ray-driven gather with wave-uniform footprints.
+//
+// Data layout.  The volume [z][y][x] is first copied into a z-fastest, zero-padded scratch array
+//   volz[(j * nx + i) * nzp + FP_PAD + k],   nzp = nz + 2 FP_PAD,
+// so that the voxels one ray bundle needs from a voxel column (i,j) are contiguous whatever the view
+// angle.  This copy is the only scratch of the library that grows with the volume.
+//
+// Work split.  One 64-lane wavefront owns one detector column c of one view and a band of FP_RG * 64
+// detector rows: lane l owns rows band0 + 64 g + l, g < FP_RG.  Because all lanes share (view, c), the
+// whole transaxial part of the weight (which voxel columns the pixel sees, F_u, magnification) is the
+// same for the 64 lanes.  The wave therefore computes it lane-parallel: per block of 64 / NQ slabs along
+// the marching axis, lane (slab, slot) evaluates one candidate voxel column; a ballot picks the candidates
+// with F_u > 0 and the wave then walks them one by one, broadcasting their few parameters through
+// v_readlane, while each lane accumulates its own rows' axial overlaps from coalesced loads of volz.
+// Sixteen waves (sixteen adjacent columns) form a workgroup so that neighbouring columns, which see the
+// same voxel columns, share them in L1, and so that the final stores are 64-byte row segments.
+#pragma once
+
+#include "sf_footprint.h"
+
+constexpr int FP_PAD = 4;        // zero voxels before and after every z-column of the scratch copy
+constexpr int FP_WAVES = 16;     // detector columns per workgroup
+
+// Candidate voxel columns of pixel column c in slab n: in-plane lines through the pixel's two u-edges, written
+// as "minor index = m * major index + b".  Wave-uniform.
+struct SfRayLines {
+    float m0, b0, m1, b1, spread;
+    int xmajor;
+};
+
+SF_HD SfRayLines sf_ray_lines(const SfGeom &g, const SfView &v, int c)
+{
+    SfRayLines L;
+    const float ue0 = ((float)c - 0.5f - g.col_off) * g.pu, ue1 = ((float)c + 0.5f - g.col_off) * g.pu;
+    const float x0 = (float)g.x0d, y0 = (float)g.y0d;
+    const float iT = 1.0f / g.T;
+    if (g.type == SF_PARALLEL) {
+        L.xmajor = fabsf(v.c) >= fabsf(v.s);
+        if (L.xmajor) {            // -x s + y c = u  ->  y = (u + x s)/c
+            L.m0 = L.m1 = v.s / v.c;
+            L.b0 = (ue0 / v.c + x0 * L.m0 - y0) * iT;
+            L.b1 = (ue1 / v.c + x0 * L.m1 - y0) * iT;
+        } else {                   // x = (y c - u)/s
+            L.m0 = L.m1 = v.c / v.s;
+            L.b0 = (-ue0 / v.s + y0 * L.m0 - x0) * iT;
+            L.b1 = (-ue1 / v.s + y0 * L.m1 - x0) * iT;
+        }
+    } else {
+        const float uc = ((float)c - g.col_off) * g.pu;
+        const float sx = g.sod * v.c, sy = g.sod * v.s;
+        const float dxc = fmaf(-g.sdd, v.c, -uc * v.s), dyc = fmaf(-g.sdd, v.s, uc * v.c);
+        L.xmajor = fabsf(dxc) >= fabsf(dyc);
+        const float dx0 = fmaf(-g.sdd, v.c, -ue0 * v.s), dy0 = fmaf(-g.sdd, v.s, ue0 * v.c);
+        const float dx1 = fmaf(-g.sdd, v.c, -ue1 * v.s), dy1 = fmaf(-g.sdd, v.s, ue1 * v.c);
+        if (L.xmajor) {
+            L.m0 = dy0 / dx0;
+            L.m1 = dy1 / dx1;
+            L.b0 = (sy - y0 + (x0 - sx) * L.m0) * iT;
+            L.b1 = (sy - y0 + (x0 - sx) * L.m1) * iT;
+        } else {
+            L.m0 = dx0 / dy0;
+            L.m1 = dx1 / dy1;
+            L.b0 = (sx - x0 + (y0 - sy) * L.m0) * iT;
+            L.b1 = (sx - x0 + (y0 - sy) * L.m1) * iT;
+        }
+    }
+    L.spread = 0.5f * fmaxf(fabsf(L.m0), fabsf(L.m1)) + 2e-3f;
+    return L;
+}
+
+// First and last candidate (minor index, unclipped) in slab n.
+SF_HD void sf_candidates(const SfRayLines &L, int n, int &q_first, int &q_last)
+{
+    const float qa = fmaf(L.m0, (float)n, L.b0), qb = fmaf(L.m1, (float)n, L.b1);
+    q_first = (int)floorf(fminf(qa, qb) - L.spread + 0.5f);
+    q_last = (int)floorf(fmaxf(qa, qb) + L.spread + 0.5f);
+}
+
+#if defined(__HIPCC__) && !defined(SF_NO_KERNELS)
+
+// vol [nz][ny][nx]  ->  volz [(j nx + i) nzp + FP_PAD + k].  Block 32 x 8 threads, tile 32 (i) x 32 (k) of one j.
+__global__ __launch_bounds__(256) void sf_volume_to_columns(const float *__restrict__ vol, float *__restrict__ volz, int nx,
+                                                            int ny, int nz, int nzp)
+{
+    __shared__ float tile[32][33];
+    const int j = blockIdx.z;
+    const int i0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+    const int tx = threadIdx.x, ty = threadIdx.y;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int k = k0 + ty + 8 * s, i = i0 + tx;
+        tile[ty + 8 * s][tx] = (k < nz && i < nx) ? vol[((size_t)k * ny + j) * nx + i] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int i = i0 + ty + 8 * s, k = k0 + tx;
+        if (i < nx && k < nz) volz[((size_t)j * nx + i) * nzp + FP_PAD + k] = tile[tx][ty + 8 * s];
+    }
+}
+
+// NQ: candidate slots per slab (power of two <= 64); NK: voxels a detector row can overlap; RG: row groups per wave.
+template <int NQ, int NK, int RG>
+__global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, const SfView *__restrict__ views,
+                                                                    const float *__restrict__ volz, float *__restrict__ sino,
+                                                                    int nzp, int col_tiles, int bands)
+{
+    constexpr int SB = 64 / NQ;                       // slabs per record block
+    __shared__ float out_tile[RG * 64][FP_WAVES + 1];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // block -> (view, band, column tile), column tile fastest
+    const int ct = blockIdx.x % col_tiles;
+    const int band = (blockIdx.x / col_tiles) % bands;
+    const int a = blockIdx.x / (col_tiles * bands);
+    const int c = ct * FP_WAVES + wave;
+    const int band0 = band * (RG * 64);
+    const bool col_ok = c < g.ncols;
+    const int cc = col_ok ? c : g.ncols - 1;
+
+    const SfView v = views[a];
+    const SfRayLines L = sf_ray_lines(g, v, cc);
+    const int n_major = L.xmajor ? g.nx : g.ny;
+    const int n_minor = L.xmajor ? g.ny : g.nx;
+
+    // this lane's rows as doubles relative to the detector's eta origin, and the constant of the kappa map
+    double rd[RG];
+#pragma unroll
+    for (int gq = 0; gq < RG; ++gq) rd[gq] = (double)(band0 + 64 * gq + lane) - g.row_offd;
+    const double zk = -g.zlo0d * g.iTzd;
+    const double mu_scale = g.ikvd * g.iTzd;          // kappa(r) = (r - row_off) * den * mu_scale + zk
+
+    float acc[RG];
+#pragma unroll
+    for (int gq = 0; gq < RG; ++gq) acc[gq] = 0.0f;
+
+    const int slot = lane & (NQ - 1), nrel = lane / NQ;
+    const bool fan = g.type == SF_FAN;
+
+    for (int nb = 0; nb < n_major; nb += SB) {
+        // ---- lane-parallel: one candidate voxel column per lane
+        const int n = nb + nrel;
+        int qf, ql;
+        sf_candidates(L, n, qf, ql);
+        const int q = qf + slot;
+        const bool valid = n < n_major && q >= 0 && q < n_minor && q <= ql;
+        const int i = L.xmajor ? n : q, j = L.xmajor ? q : n;
+        const int ic = valid ? i : 0, jc = valid ? j : 0;
+        const SfColumn f = sf_column(g, v, ic, jc);
+        float fu = sf_fu(f, cc);
+        fu = valid ? fu : 0.0f;
+        const double mu = f.den * mu_scale;                       // voxels per detector row at this column
+        const float fa = fan ? fu : fu * (float)(g.kvd * f.inv * g.Tzd);   // F_u times rows per voxel
+        const unsigned colbase = (unsigned)(jc * g.nx + ic) * (unsigned)nzp;   // start of the padded column
+        const int mu_lo = __double2loint(mu), mu_hi = __double2hiint(mu);
+
+        unsigned long long mask = __ballot(fu > 0.0f);
+        // ---- wave-uniform walk over the candidates that matter
+        while (mask) {
+            const int e = __builtin_ctzll(mask);
+            mask &= mask - 1;
+            const float s_fa = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, fa), e));
+            const unsigned s_base = (unsigned)__builtin_amdgcn_readlane((int)colbase, e);
+            const double s_mu = __hiloint2double(__builtin_amdgcn_readlane(mu_hi, e), __builtin_amdgcn_readlane(mu_lo, e));
+            const float step = (float)s_mu;
+            const float *__restrict__ col = volz + s_base;
+            if (fan) {
+                acc[0] = fmaf(s_fa, col[FP_PAD], acc[0]);
+                continue;
+            }
+#pragma unroll
+            for (int gq = 0; gq < RG; ++gq) {
+                const double kap = fma(rd[gq], s_mu, zk);
+                const double fl = floor(kap);
+                const float fr = (float)(kap - fl);
+                int kf = (int)fl + FP_PAD;                        // index into the padded column
+                kf = kf < 0 ? 0 : (kf > g.nz + FP_PAD ? g.nz + FP_PAD : kf);
+                // overlaps of [kap, kap + step) with voxels kf, kf+1, ...
+                float rem = step, s = 0.0f, w = fminf(1.0f - fr, step);
+#pragma unroll
+                for (int t = 0; t < NK; ++t) {
+                    s = fmaf(w, col[kf + t], s);
+                    rem -= w;
+                    w = (t == NK - 2) ? rem : fminf(rem, 1.0f);
+                }
+                acc[gq] = fmaf(s_fa, s, acc[gq]);
+            }
+        }
+    }
+
+    // ---- amplitude, then transpose through LDS so that stores are row segments of FP_WAVES columns
+    const SfAmpCol ac = sf_amp_col(g, v, cc);
+#pragma unroll
+    for (int gq = 0; gq < RG; ++gq) {
+        const int r = band0 + 64 * gq + lane;
+        out_tile[64 * gq + lane][wave] = sf_amp(g, v, ac, r < g.nrows ? r : 0) * acc[gq];
+    }
+    __syncthreads();
+    float *__restrict__ ya = sino + (size_t)a * g.nrows * g.ncols;
+    for (int e = threadIdx.x; e < RG * 64 * FP_WAVES; e += FP_WAVES * 64) {
+        const int row = e / FP_WAVES, w = e % FP_WAVES;
+        const int r = band0 + row, cw = ct * FP_WAVES + w;
+        if (r < g.nrows && cw < g.ncols) ya[(size_t)r * g.ncols + cw] = out_tile[row][w];
+    }
+}
+
+#endif
