@@ -10,7 +10,7 @@ import os
 from typing import Optional, Sequence
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libleap_hip.so")
+LIB_PATH = os.environ.get("LEAP_LIB_PATH") or os.path.join(HERE, "libleap_hip.so")   # override: testing a variant build
 
 LEAP_PARALLEL, LEAP_FAN, LEAP_CONE = 0, 1, 2
 LEAP_OK, LEAP_INVALID_ARG, LEAP_BAD_GEOMETRY, LEAP_HIP_ERROR, LEAP_UNSUPPORTED = 0, -1, -2, -3, -4

@@ -19,13 +19,14 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build_library(verbose: bool = False) -> str:
+def build_library(verbose: bool = False, out: str = LIB, extra_flags=()) -> str:
     """Compiles every source for gfx950 and links the shared library.  Always recompiles."""
     cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
            # packed FP32 instructions are kept out of the generated code on purpose
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-ffp-contract=fast", "-Wall", "-Wno-unused-command-line-argument",
-           "-I", os.path.join(HERE, "..", "include"), "-o", LIB]
+           "-I", os.path.join(HERE, "..", "include"), "-o", out]
+    cmd += list(extra_flags)
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
@@ -36,7 +37,7 @@ def build_library(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

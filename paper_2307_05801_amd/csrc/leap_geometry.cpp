@@ -209,6 +209,15 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         const int groups = (d->nrows + 63) / 64;
         G->fp_rg = groups >= 8 ? 8 : (groups >= 4 ? 4 : (groups >= 2 ? 2 : 1));
         G->fp_columns = need <= 16 && G->fp_nk <= 4;
+        // tuning aids (read once per handle)
+        if (const char *env = std::getenv("LEAP_FP_RG")) {
+            const int v = std::atoi(env);
+            if (v == 1 || v == 2 || v == 4 || v == 8) G->fp_rg = v;
+        }
+        if (const char *env = std::getenv("LEAP_FP_WAVES")) {
+            const int v = std::atoi(env);
+            if (v == 4 || v == 8 || v == 16) G->fp_waves = v;
+        }
     }
 
     // Testing aid: LEAP_FORCE_GENERAL=1 keeps every call on the general kernels.
@@ -252,9 +261,9 @@ extern "C" int leap_geometry_describe(const leap_geometry *G, char *buf, int32_t
 {
     if (!G || !buf || cap <= 0) return invalid("null handle or buffer");
     std::snprintf(buf, (size_t)cap,
-                  "type=%d A=%s(nq=%d/%d,nk=%d,rg=%d) AT=%s(nc=%d,nv=%d,zc=%d,window=%dx%d) cols/voxel<=%.2f rows/voxel<=%.2f "
+                  "type=%d A=%s(nq=%d/%d,nk=%d,rg=%d,w=%d) AT=%s(nc=%d,nv=%d,zc=%d,window=%dx%d) cols/voxel<=%.2f rows/voxel<=%.2f "
                   "voxels/row<=%.2f slope<=%.2f",
-                  G->g.type, G->fp_columns ? "columns" : "general", G->fp_need_q, G->fp_nq, G->fp_nk, G->fp_rg, G->bp_tiled ? "tiled" : "general", G->bp_nc, G->bp_nv, BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h,
+                  G->g.type, G->fp_columns ? "columns" : "general", G->fp_need_q, G->fp_nq, G->fp_nk, G->fp_rg, G->fp_waves, G->bp_tiled ? "tiled" : "general", G->bp_nc, G->bp_nv, BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h,
                   G->max_cols_per_voxel, G->max_rows_per_voxel, G->max_voxels_per_row, G->max_minor_slope);
     return LEAP_OK;
 }

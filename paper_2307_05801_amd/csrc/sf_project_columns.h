@@ -19,7 +19,6 @@
 #include "sf_footprint.h"
 
 constexpr int FP_PAD = 4;        // zero voxels before and after every z-column of the scratch copy
-constexpr int FP_WAVES = 16;     // detector columns per workgroup
 
 // Candidate voxel columns of pixel column c in slab n: in-plane lines through the pixel's two u-edges, written
 // as "minor index = m * major index + b".  Wave-uniform.
@@ -99,8 +98,9 @@ __global__ __launch_bounds__(256) void sf_volume_to_columns(const float *__restr
     }
 }
 
-// NQ: candidate slots per slab (power of two <= 64); NK: voxels a detector row can overlap; RG: row groups per wave.
-template <int NQ, int NK, int RG>
+// NQ: candidate slots per slab (power of two <= 64); NK: voxels a detector row can overlap; RG: row groups per wave;
+// FP_WAVES: waves (adjacent detector columns) per workgroup.
+template <int NQ, int NK, int RG, int FP_WAVES>
 __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, const SfView *__restrict__ views,
                                                                     const float *__restrict__ volz, float *__restrict__ sino,
                                                                     int nzp, int col_tiles, int bands)
@@ -128,8 +128,9 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, co
     double rd[RG];
 #pragma unroll
     for (int gq = 0; gq < RG; ++gq) rd[gq] = (double)(band0 + 64 * gq + lane) - g.row_offd;
-    const double zk = -g.zlo0d * g.iTzd;
-    const double mu_scale = g.ikvd * g.iTzd;          // kappa(r) = (r - row_off) * den * mu_scale + zk
+    const double zkp = -g.zlo0d * g.iTzd + (double)FP_PAD;   // kappa + pad offset
+    const int kmax = g.nz + FP_PAD;
+    const double mu_scale = g.ikvd * g.iTzd;          // kappa(r) = (r - row_off) * den * mu_scale - zlo0 / Tz
 
     float acc[RG];
 #pragma unroll
@@ -164,23 +165,24 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, co
             const unsigned s_base = (unsigned)__builtin_amdgcn_readlane((int)colbase, e);
             const double s_mu = __hiloint2double(__builtin_amdgcn_readlane(mu_hi, e), __builtin_amdgcn_readlane(mu_lo, e));
             const float step = (float)s_mu;
-            const float *__restrict__ col = volz + s_base;
+            const char *__restrict__ col = reinterpret_cast<const char *>(volz + s_base);   // wave-uniform base address
             if (fan) {
-                acc[0] = fmaf(s_fa, col[FP_PAD], acc[0]);
+                acc[0] = fmaf(s_fa, volz[s_base + FP_PAD], acc[0]);
                 continue;
             }
 #pragma unroll
             for (int gq = 0; gq < RG; ++gq) {
-                const double kap = fma(rd[gq], s_mu, zk);
-                const double fl = floor(kap);
-                const float fr = (float)(kap - fl);
-                int kf = (int)fl + FP_PAD;                        // index into the padded column
-                kf = kf < 0 ? 0 : (kf > g.nz + FP_PAD ? g.nz + FP_PAD : kf);
+                // kappa measured from the start of the padded column; negative values only occur inside the pad
+                const double kap = fma(rd[gq], s_mu, zkp);
+                const float fr = (float)__builtin_amdgcn_fract(kap);
+                int kf = (int)kap;                                 // truncation = floor wherever the clamp leaves it alone
+                kf = max(0, min(kf, kmax));
+                const float *__restrict__ x = reinterpret_cast<const float *>(col + ((unsigned)kf << 2));
                 // overlaps of [kap, kap + step) with voxels kf, kf+1, ...
                 float rem = step, s = 0.0f, w = fminf(1.0f - fr, step);
 #pragma unroll
                 for (int t = 0; t < NK; ++t) {
-                    s = fmaf(w, col[kf + t], s);
+                    s = fmaf(w, x[t], s);
                     rem -= w;
                     w = (t == NK - 2) ? rem : fminf(rem, 1.0f);
                 }
