@@ -163,6 +163,37 @@ __global__ __launch_bounds__(256, 4) void sf_backproject_tiled(SfGeom g, const S
         const SfRowsOfVoxels ax = sf_rows_of_voxels(g, f, zlo_k0);
         unsigned ofs = (unsigned)((ax.rb - win.r0) * BP_PS + (cf - win.c0));
 
+        if constexpr (NV == 2) {
+            // A voxel is at most one row tall, so consecutive voxels share a row: keep the u-combined samples of the
+            // current and the next row in registers and fetch one new row per voxel (half the LDS traffic).
+            auto row_sum = [&](const float *q) {
+                float s = fu[0] * q[0];
+#pragma unroll
+                for (int m = 1; m < NC; ++m) s = fmaf(fu[m], q[m], s);
+                return s;
+            };
+            float lo = ax.phi0, fl = 0.0f;                       // phi0 is in [0,1)
+            float s_cur = row_sum(buf + ofs), s_next = row_sum(buf + ofs + BP_PS);
+#pragma unroll
+            for (int kk = 0; kk < BP_ZC; ++kk) {
+                const float hi = fmaf(ax.av, (float)(kk + 1), ax.phi0);
+                const float edge = fl + 1.0f;
+                const float w0 = fminf(edge, hi) - lo;
+                const float w1 = sf_clamp(hi - edge, 0.0f, 1.0f);
+                acc[kk] = fmaf(w1, s_next, fmaf(w0, s_cur, acc[kk]));
+                if (kk + 1 < BP_ZC) {
+                    const float fl_next = floorf(hi);                 // fl or fl + 1
+                    const float *q = buf + (ofs + __umul24((unsigned)(int)fl_next, (unsigned)BP_PS) + BP_PS);
+                    const float s_new = row_sum(q);                   // row fl_next + 1 (equals s_next when no row was crossed)
+                    s_cur = fl_next > fl ? s_next : s_cur;
+                    s_next = s_new;
+                    fl = fl_next;
+                    lo = hi;
+                }
+                if ((kk & 3) == 3)
+                    asm volatile("" : "+v"(ofs), "+v"(acc[kk - 3]), "+v"(acc[kk - 2]), "+v"(acc[kk - 1]), "+v"(acc[kk]));
+            }
+        } else {
         float lo = ax.phi0;
 #pragma unroll
         for (int kk = 0; kk < BP_ZC; ++kk) {
@@ -188,6 +219,8 @@ __global__ __launch_bounds__(256, 4) void sf_backproject_tiled(SfGeom g, const S
             // loop first and spills them.
             if ((kk & 3) == 3)
                 asm volatile("" : "+v"(ofs), "+v"(acc[kk - 3]), "+v"(acc[kk - 2]), "+v"(acc[kk - 1]), "+v"(acc[kk]));
+        }
+
         }
 
         if (a + 1 < g.nviews) bp_store_view<BP_PW, BP_PH, NSTAGE>(g, views[a + 1], sc, sr, win_next, stage, patch[(a + 1) & 1]);
