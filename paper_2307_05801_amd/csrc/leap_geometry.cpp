@@ -190,18 +190,37 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
     // Column-wise forward projection: static limits, then its scratch copy of the volume.
     if (d->type != LEAP_FAN && d->nrows >= 32 && std::isfinite(G->max_voxels_per_row) && G->max_voxels_per_row <= 3.0 &&
         (double)d->nx * d->ny * (d->nz + 2.0 * FP_PAD) < 4294967296.0 && d->ny <= 65535) {
-        int need = 0;
-        for (int a = 0; a < d->nviews; ++a)
-            for (int c = 0; c < d->ncols; ++c) {
-                const SfRayLines L = sf_ray_lines(g, G->views[a], c);
-                const int n_major = L.xmajor ? d->nx : d->ny;
-                const float d0 = std::fabs(L.b0 - L.b1);
-                const float d1 = std::fabs(fmaf(L.m0 - L.m1, (float)(n_major - 1), L.b0 - L.b1));
-                const float dm = d0 > d1 ? d0 : d1;
-                if (!(dm < 1e6f)) { need = 1 << 20; break; }
-                const int cnt = (int)std::floor(dm + 2.0f * L.spread + 1e-3f) + 2;
-                need = cnt > need ? cnt : need;
-            }
+        // tuning aids (read once per handle)
+        if (const char *env = std::getenv("LEAP_FP_CW")) {
+            const int v = std::atoi(env);
+            if (v == 1 || v == 2 || v == 4) G->fp_cw = v;
+        }
+        if (const char *env = std::getenv("LEAP_FP_WAVES")) {
+            const int v = std::atoi(env);
+            if (v == 4 || v == 8) G->fp_waves = v;
+        }
+        if (G->fp_waves == 8 && G->fp_cw == 4) G->fp_cw = 2;
+        // candidate slots per slab: widest range of voxel columns any bundle of cw detector columns can see
+        auto slots_needed = [&](int cw) {
+            int need = 0;
+            for (int a = 0; a < d->nviews; ++a)
+                for (int c = 0; c < d->ncols; c += cw) {
+                    const SfRayLines L = sf_ray_lines(g, G->views[a], c, cw);
+                    const int n_major = L.xmajor ? d->nx : d->ny;
+                    const float d0 = std::fabs(L.b0 - L.b1);
+                    const float d1 = std::fabs(fmaf(L.m0 - L.m1, (float)(n_major - 1), L.b0 - L.b1));
+                    const float dm = d0 > d1 ? d0 : d1;
+                    if (!(dm < 1e6f)) return 1 << 20;
+                    const int cnt = (int)std::floor(dm + 2.0f * L.spread + 1e-3f) + 2;
+                    need = cnt > need ? cnt : need;
+                }
+            return need;
+        };
+        int need = slots_needed(G->fp_cw);
+        while (need > 16 && G->fp_cw > 1) {
+            G->fp_cw /= 2;
+            need = slots_needed(G->fp_cw);
+        }
         G->fp_need_q = need;
         G->fp_nq = need <= 4 ? 4 : (need <= 8 ? 8 : 16);
         G->fp_nk = (int)std::ceil(G->max_voxels_per_row - 1e-6) + 1;
@@ -209,14 +228,9 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         const int groups = (d->nrows + 63) / 64;
         G->fp_rg = groups >= 8 ? 8 : (groups >= 4 ? 4 : (groups >= 2 ? 2 : 1));
         G->fp_columns = need <= 16 && G->fp_nk <= 4;
-        // tuning aids (read once per handle)
         if (const char *env = std::getenv("LEAP_FP_RG")) {
             const int v = std::atoi(env);
             if (v == 1 || v == 2 || v == 4 || v == 8) G->fp_rg = v;
-        }
-        if (const char *env = std::getenv("LEAP_FP_WAVES")) {
-            const int v = std::atoi(env);
-            if (v == 4 || v == 8 || v == 16) G->fp_waves = v;
         }
     }
 
@@ -261,9 +275,9 @@ extern "C" int leap_geometry_describe(const leap_geometry *G, char *buf, int32_t
 {
     if (!G || !buf || cap <= 0) return invalid("null handle or buffer");
     std::snprintf(buf, (size_t)cap,
-                  "type=%d A=%s(nq=%d/%d,nk=%d,rg=%d,w=%d) AT=%s(nc=%d,nv=%d,zc=%d,window=%dx%d) cols/voxel<=%.2f rows/voxel<=%.2f "
+                  "type=%d A=%s(nq=%d/%d,nk=%d,rg=%d,w=%d,cw=%d) AT=%s(nc=%d,nv=%d,zc=%d,window=%dx%d) cols/voxel<=%.2f rows/voxel<=%.2f "
                   "voxels/row<=%.2f slope<=%.2f",
-                  G->g.type, G->fp_columns ? "columns" : "general", G->fp_need_q, G->fp_nq, G->fp_nk, G->fp_rg, G->fp_waves, G->bp_tiled ? "tiled" : "general", G->bp_nc, G->bp_nv, BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h,
+                  G->g.type, G->fp_columns ? "columns" : "general", G->fp_need_q, G->fp_nq, G->fp_nk, G->fp_rg, G->fp_waves, G->fp_cw, G->bp_tiled ? "tiled" : "general", G->bp_nc, G->bp_nv, BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h,
                   G->max_cols_per_voxel, G->max_rows_per_voxel, G->max_voxels_per_row, G->max_minor_slope);
     return LEAP_OK;
 }

@@ -49,23 +49,25 @@ __global__ __launch_bounds__(256) void sf_project_general(SfGeom g, const SfView
 
 static inline unsigned cdiv(unsigned a, unsigned b) { return (a + b - 1) / b; }
 
-template <int NQ, int NK, int RG, int W>
+template <int NQ, int NK, int RG, int W, int CW>
 static void launch_fp_columns(const leap_geometry *G, float *d_sino, hipStream_t stream)
 {
     const SfGeom &g = G->g;
-    const int col_tiles = (int)cdiv(g.ncols, W), bands = (int)cdiv(g.nrows, RG * 64);
+    const int col_tiles = (int)cdiv(g.ncols, W * CW), bands = (int)cdiv(g.nrows, RG * 64);
     dim3 grid((unsigned)col_tiles * bands * g.nviews, 1, 1);
-    hipLaunchKernelGGL((sf_project_columns<NQ, NK, RG, W>), grid, dim3(W * 64, 1, 1), 0, stream, g, G->d_views, G->d_volz,
+    hipLaunchKernelGGL((sf_project_columns<NQ, NK, RG, W, CW>), grid, dim3(W * 64, 1, 1), 0, stream, g, G->d_views, G->d_volz,
                        d_sino, G->nzp, col_tiles, bands);
 }
 
 template <int NQ, int NK, int RG>
 static bool launch_fp_w(const leap_geometry *G, float *d_sino, hipStream_t stream)
 {
-    switch (G->fp_waves) {
-    case 4: launch_fp_columns<NQ, NK, RG, 4>(G, d_sino, stream); return true;
-    case 8: launch_fp_columns<NQ, NK, RG, 8>(G, d_sino, stream); return true;
-    case 16: launch_fp_columns<NQ, NK, RG, 16>(G, d_sino, stream); return true;
+    switch (G->fp_waves * 10 + G->fp_cw) {
+    case 41: launch_fp_columns<NQ, NK, RG, 4, 1>(G, d_sino, stream); return true;
+    case 42: launch_fp_columns<NQ, NK, RG, 4, 2>(G, d_sino, stream); return true;
+    case 44: launch_fp_columns<NQ, NK, RG, 4, 4>(G, d_sino, stream); return true;
+    case 81: launch_fp_columns<NQ, NK, RG, 8, 1>(G, d_sino, stream); return true;
+    case 82: launch_fp_columns<NQ, NK, RG, 8, 2>(G, d_sino, stream); return true;
     default: return false;
     }
 }

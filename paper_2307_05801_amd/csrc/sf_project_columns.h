@@ -5,32 +5,33 @@
 // so that the voxels one ray bundle needs from a voxel column (i,j) are contiguous whatever the view
 // angle.  This copy is the only scratch of the library that grows with the volume.
 //
-// Work split.  One 64-lane wavefront owns one detector column c of one view and a band of FP_RG * 64
-// detector rows: lane l owns rows band0 + 64 g + l, g < FP_RG.  Because all lanes share (view, c), the
-// whole transaxial part of the weight (which voxel columns the pixel sees, F_u, magnification) is the
-// same for the 64 lanes.  The wave therefore computes it lane-parallel: per block of 64 / NQ slabs along
+// Work split.  One 64-lane wavefront owns CW adjacent detector columns of one view and a band of RG * 64
+// detector rows: lane l owns rows band0 + 64 g + l, g < RG, of each of its columns.  Because all lanes
+// share (view, columns), the whole transaxial part of the weight (which voxel columns the pixels see, F_u,
+// magnification) is the same for the 64 lanes, and the axial part (a row's overlaps with the voxels of a
+// voxel column) is the same for the CW pixel columns: it is computed once and applied CW times.  The wave therefore computes it lane-parallel: per block of 64 / NQ slabs along
 // the marching axis, lane (slab, slot) evaluates one candidate voxel column; a ballot picks the candidates
 // with F_u > 0 and the wave then walks them one by one, broadcasting their few parameters through
 // v_readlane, while each lane accumulates its own rows' axial overlaps from coalesced loads of volz.
-// Sixteen waves (sixteen adjacent columns) form a workgroup so that neighbouring columns, which see the
-// same voxel columns, share them in L1, and so that the final stores are 64-byte row segments.
+// A few waves (adjacent column groups) form a workgroup so that neighbours, which see the same voxel columns,
+// share them in L1, and so that the final stores are row segments of W * CW columns.
 #pragma once
 
 #include "sf_footprint.h"
 
 constexpr int FP_PAD = 4;        // zero voxels before and after every z-column of the scratch copy
 
-// Candidate voxel columns of pixel column c in slab n: in-plane lines through the pixel's two u-edges, written
-// as "minor index = m * major index + b".  Wave-uniform.
+// Candidate voxel columns of pixel columns c .. c+cw-1 in slab n: in-plane lines through the two outer u-edges of
+// the bundle, written as "minor index = m * major index + b".  Wave-uniform.
 struct SfRayLines {
     float m0, b0, m1, b1, spread;
     int xmajor;
 };
 
-SF_HD SfRayLines sf_ray_lines(const SfGeom &g, const SfView &v, int c)
+SF_HD SfRayLines sf_ray_lines(const SfGeom &g, const SfView &v, int c, int cw)
 {
     SfRayLines L;
-    const float ue0 = ((float)c - 0.5f - g.col_off) * g.pu, ue1 = ((float)c + 0.5f - g.col_off) * g.pu;
+    const float ue0 = ((float)c - 0.5f - g.col_off) * g.pu, ue1 = ((float)(c + cw) - 0.5f - g.col_off) * g.pu;
     const float x0 = (float)g.x0d, y0 = (float)g.y0d;
     const float iT = 1.0f / g.T;
     if (g.type == SF_PARALLEL) {
@@ -45,7 +46,7 @@ SF_HD SfRayLines sf_ray_lines(const SfGeom &g, const SfView &v, int c)
             L.b1 = (-ue1 / v.s + y0 * L.m1 - x0) * iT;
         }
     } else {
-        const float uc = ((float)c - g.col_off) * g.pu;
+        const float uc = 0.5f * (ue0 + ue1);
         const float sx = g.sod * v.c, sy = g.sod * v.s;
         const float dxc = fmaf(-g.sdd, v.c, -uc * v.s), dyc = fmaf(-g.sdd, v.s, uc * v.c);
         L.xmajor = fabsf(dxc) >= fabsf(dyc);
@@ -99,14 +100,14 @@ __global__ __launch_bounds__(256) void sf_volume_to_columns(const float *__restr
 }
 
 // NQ: candidate slots per slab (power of two <= 64); NK: voxels a detector row can overlap; RG: row groups per wave;
-// FP_WAVES: waves (adjacent detector columns) per workgroup.
-template <int NQ, int NK, int RG, int FP_WAVES>
+// FP_WAVES: waves per workgroup; CW: adjacent detector columns per wave.
+template <int NQ, int NK, int RG, int FP_WAVES, int CW>
 __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, const SfView *__restrict__ views,
                                                                     const float *__restrict__ volz, float *__restrict__ sino,
                                                                     int nzp, int col_tiles, int bands)
 {
     constexpr int SB = 64 / NQ;                       // slabs per record block
-    __shared__ float out_tile[RG * 64][FP_WAVES + 1];
+    __shared__ float out_tile[RG * 64][FP_WAVES * CW + 1];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -114,13 +115,11 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, co
     const int ct = blockIdx.x % col_tiles;
     const int band = (blockIdx.x / col_tiles) % bands;
     const int a = blockIdx.x / (col_tiles * bands);
-    const int c = ct * FP_WAVES + wave;
+    const int c0 = (ct * FP_WAVES + wave) * CW;          // first detector column of this wave
     const int band0 = band * (RG * 64);
-    const bool col_ok = c < g.ncols;
-    const int cc = col_ok ? c : g.ncols - 1;
 
     const SfView v = views[a];
-    const SfRayLines L = sf_ray_lines(g, v, cc);
+    const SfRayLines L = sf_ray_lines(g, v, c0, CW);
     const int n_major = L.xmajor ? g.nx : g.ny;
     const int n_minor = L.xmajor ? g.ny : g.nx;
 
@@ -132,9 +131,11 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, co
     const int kmax = g.nz + FP_PAD;
     const double mu_scale = g.ikvd * g.iTzd;          // kappa(r) = (r - row_off) * den * mu_scale - zlo0 / Tz
 
-    float acc[RG];
+    float acc[CW][RG];
 #pragma unroll
-    for (int gq = 0; gq < RG; ++gq) acc[gq] = 0.0f;
+    for (int cw = 0; cw < CW; ++cw)
+#pragma unroll
+        for (int gq = 0; gq < RG; ++gq) acc[cw][gq] = 0.0f;
 
     const int slot = lane & (NQ - 1), nrel = lane / NQ;
     const bool fan = g.type == SF_FAN;
@@ -149,25 +150,42 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, co
         const int i = L.xmajor ? n : q, j = L.xmajor ? q : n;
         const int ic = valid ? i : 0, jc = valid ? j : 0;
         const SfColumn f = sf_column(g, v, ic, jc);
-        float fu = sf_fu(f, cc);
-        fu = valid ? fu : 0.0f;
         const double mu = f.den * mu_scale;                       // voxels per detector row at this column
-        const float fa = fan ? fu : fu * (float)(g.kvd * f.inv * g.Tzd);   // F_u times rows per voxel
+        const float rows_per_voxel = fan ? 1.0f : (float)(g.kvd * f.inv * g.Tzd);
+        float fa[CW];                                              // F_u times rows per voxel, per detector column
+        bool any = false;
+        {
+            float e = sf_pixel_edge(f, c0);
+            float g0 = sf_trap_integral(f, e);
+#pragma unroll
+            for (int cw = 0; cw < CW; ++cw) {
+                e += 1.0f;
+                const float g1 = sf_trap_integral(f, e);
+                const float fu = (valid && c0 + cw < g.ncols) ? fmaxf(g1 - g0, 0.0f) : 0.0f;
+                fa[cw] = fu * rows_per_voxel;
+                any = any || fu > 0.0f;
+                g0 = g1;
+            }
+        }
         const unsigned colbase = (unsigned)(jc * g.nx + ic) * (unsigned)nzp;   // start of the padded column
         const int mu_lo = __double2loint(mu), mu_hi = __double2hiint(mu);
 
-        unsigned long long mask = __ballot(fu > 0.0f);
+        unsigned long long mask = __ballot(any);
         // ---- wave-uniform walk over the candidates that matter
         while (mask) {
             const int e = __builtin_ctzll(mask);
             mask &= mask - 1;
-            const float s_fa = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, fa), e));
+            float s_fa[CW];
+#pragma unroll
+            for (int cw = 0; cw < CW; ++cw)
+                s_fa[cw] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, fa[cw]), e));
             const unsigned s_base = (unsigned)__builtin_amdgcn_readlane((int)colbase, e);
             const double s_mu = __hiloint2double(__builtin_amdgcn_readlane(mu_hi, e), __builtin_amdgcn_readlane(mu_lo, e));
             const float step = (float)s_mu;
             const char *__restrict__ col = reinterpret_cast<const char *>(volz + s_base);   // wave-uniform base address
             if (fan) {
-                acc[0] = fmaf(s_fa, volz[s_base + FP_PAD], acc[0]);
+#pragma unroll
+                for (int cw = 0; cw < CW; ++cw) acc[cw][0] = fmaf(s_fa[cw], volz[s_base + FP_PAD], acc[cw][0]);
                 continue;
             }
 #pragma unroll
@@ -186,23 +204,29 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, co
                     rem -= w;
                     w = (t == NK - 2) ? rem : fminf(rem, 1.0f);
                 }
-                acc[gq] = fmaf(s_fa, s, acc[gq]);
+#pragma unroll
+                for (int cw = 0; cw < CW; ++cw) acc[cw][gq] = fmaf(s_fa[cw], s, acc[cw][gq]);
             }
         }
     }
 
-    // ---- amplitude, then transpose through LDS so that stores are row segments of FP_WAVES columns
-    const SfAmpCol ac = sf_amp_col(g, v, cc);
+    // ---- amplitude, then transpose through LDS so that stores are row segments of FP_WAVES * CW columns
 #pragma unroll
-    for (int gq = 0; gq < RG; ++gq) {
-        const int r = band0 + 64 * gq + lane;
-        out_tile[64 * gq + lane][wave] = sf_amp(g, v, ac, r < g.nrows ? r : 0) * acc[gq];
+    for (int cw = 0; cw < CW; ++cw) {
+        const int c = c0 + cw;
+        const SfAmpCol ac = sf_amp_col(g, v, c);
+#pragma unroll
+        for (int gq = 0; gq < RG; ++gq) {
+            const int r = band0 + 64 * gq + lane;
+            out_tile[64 * gq + lane][wave * CW + cw] = sf_amp(g, v, ac, r < g.nrows ? r : 0) * acc[cw][gq];
+        }
     }
     __syncthreads();
+    constexpr int TW = FP_WAVES * CW;
     float *__restrict__ ya = sino + (size_t)a * g.nrows * g.ncols;
-    for (int e = threadIdx.x; e < RG * 64 * FP_WAVES; e += FP_WAVES * 64) {
-        const int row = e / FP_WAVES, w = e % FP_WAVES;
-        const int r = band0 + row, cw = ct * FP_WAVES + w;
+    for (int e = threadIdx.x; e < RG * 64 * TW; e += FP_WAVES * 64) {
+        const int row = e / TW, w = e % TW;
+        const int r = band0 + row, cw = ct * TW + w;
         if (r < g.nrows && cw < g.ncols) ya[(size_t)r * g.ncols + cw] = out_tile[row][w];
     }
 }
