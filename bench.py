@@ -84,6 +84,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=3, help="benchmark case number (3 = the headline 512^3 cone-beam)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="CPU time budget of the oracle baseline; 0 skips it")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after the timed region, run one device-to-device copy of the volume (a plain copy kernel of "
+                         "known size) so that a rocprofv3 --pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -157,6 +160,10 @@ def main() -> int:
         "nnz_per_update": n_u * n_v,
         "roofline": roofline,
     }
+    if args.calibration_copy:
+        xb.copy_(x)
+        torch.cuda.synchronize()
+        out["calibration_copy_bytes"] = int(x.numel() * 4)
     if args.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(cfg, x_np[0], args.cpu_seconds)
     print(json.dumps(out))

@@ -228,6 +228,14 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         const int groups = (d->nrows + 63) / 64;
         G->fp_rg = groups >= 8 ? 8 : (groups >= 4 ? 4 : (groups >= 2 ? 2 : 1));
         G->fp_columns = need <= 16 && G->fp_nk <= 4;
+        if (const char *env = std::getenv("LEAP_FP_VB")) {
+            const int v = std::atoi(env);
+            if (v >= 1 && v <= 1024) G->fp_vb = v;
+        }
+        if (const char *env = std::getenv("LEAP_FP_TB")) {
+            const int v = std::atoi(env);
+            if (v >= 1 && v <= 1024) G->fp_tb = v;
+        }
         if (const char *env = std::getenv("LEAP_FP_RG")) {
             const int v = std::atoi(env);
             if (v == 1 || v == 2 || v == 4 || v == 8) G->fp_rg = v;

@@ -54,9 +54,13 @@ static void launch_fp_columns(const leap_geometry *G, float *d_sino, hipStream_t
 {
     const SfGeom &g = G->g;
     const int col_tiles = (int)cdiv(g.ncols, W * CW), bands = (int)cdiv(g.nrows, RG * 64);
-    dim3 grid((unsigned)col_tiles * bands * g.nviews, 1, 1);
+    // XCD-aware block order (see the kernel): pad views to blocks of vb and each XCD's tiles to chunks of tb
+    const int vb = G->fp_vb, tb = G->fp_tb;
+    const int nviews_pad = (int)cdiv(g.nviews, vb) * vb;
+    const int tiles_per_xcd_pad = (int)cdiv(cdiv(col_tiles, 8), tb) * tb;
+    dim3 grid((unsigned)(8 * tiles_per_xcd_pad * nviews_pad * bands), 1, 1);
     hipLaunchKernelGGL((sf_project_columns<NQ, NK, RG, W, CW>), grid, dim3(W * 64, 1, 1), 0, stream, g, G->d_views, G->d_volz,
-                       d_sino, G->nzp, col_tiles, bands);
+                       d_sino, G->nzp, col_tiles, bands, vb, tb, nviews_pad, tiles_per_xcd_pad);
 }
 
 template <int NQ, int NK, int RG>

@@ -104,17 +104,31 @@ __global__ __launch_bounds__(256) void sf_volume_to_columns(const float *__restr
 template <int NQ, int NK, int RG, int FP_WAVES, int CW>
 __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, const SfView *__restrict__ views,
                                                                     const float *__restrict__ volz, float *__restrict__ sino,
-                                                                    int nzp, int col_tiles, int bands)
+                                                                    int nzp, int col_tiles, int bands, int vb, int tb,
+                                                                    int nviews_pad, int tiles_per_xcd_pad)
 {
     constexpr int SB = 64 / NQ;                       // slabs per record block
     __shared__ float out_tile[RG * 64][FP_WAVES * CW + 1];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // block -> (view, band, column tile), column tile fastest
-    const int ct = blockIdx.x % col_tiles;
-    const int band = (blockIdx.x / col_tiles) % bands;
-    const int a = blockIdx.x / (col_tiles * bands);
+    // Block -> (view, band, column tile).  Workgroups are handed to the 8 XCDs round-robin by index, and each XCD has
+    // its own L2.  Beams of the same column tile in neighbouring views overlap almost entirely, so the blocks one XCD
+    // runs at the same time are arranged as (a few column tiles) x (a run of consecutive views): index = 8 s + xcd,
+    // and within an XCD's sequence s the view runs fastest inside a block of VB views, then TB tiles, then view blocks.
+    int ct, band, a;
+    {
+        const int xcd = blockIdx.x & 7, sq = blockIdx.x >> 3;
+        const int per_chunk = tb * nviews_pad;                  // TB tiles x all (padded) views
+        const int chunk = sq / per_chunk, r = sq - chunk * per_chunk;
+        const int vblk = r / (tb * vb), r2 = r - vblk * (tb * vb);
+        const int tloc = r2 / vb, v_in = r2 - tloc * vb;
+        const int tchunks = tiles_per_xcd_pad / tb;
+        band = chunk / tchunks;
+        ct = ((chunk - band * tchunks) * tb + tloc) * 8 + xcd;
+        a = vblk * vb + v_in;
+        if (ct >= col_tiles || a >= g.nviews || band >= bands) return;   // padding blocks
+    }
     const int c0 = (ct * FP_WAVES + wave) * CW;          // first detector column of this wave
     const int band0 = band * (RG * 64);
 
