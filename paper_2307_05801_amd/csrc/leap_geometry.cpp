@@ -163,7 +163,9 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         G->bp_wh = (float)(0.5 * G->max_cols_per_voxel);
         const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T;
         const float hx = 0.5f * (float)(BP_T - 1) * g.T;
-        for (int sh = 0; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
+        int first_shape = d->nz >= 128 ? 0 : 1;       // 64-voxel chunks only pay off on tall volumes
+        if (const char *env = std::getenv("LEAP_BP_SHAPE")) first_shape = std::atoi(env) & 3;
+        for (int sh = first_shape; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
             const int zc = BP_SHAPES[sh].zc;
             const int chunks = (d->nz + zc - 1) / zc;
             int need_w = 0, need_h = 0;

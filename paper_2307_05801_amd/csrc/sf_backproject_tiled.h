@@ -25,8 +25,8 @@ constexpr int BP_T = 16;        // tile edge in voxels (x and y)
 struct SfBpShape {
     int zc, pw, ph;
 };
-constexpr SfBpShape BP_SHAPES[] = {{32, 32, 44}, {16, 32, 44}, {16, 64, 48}};
-constexpr int BP_NSHAPES = 3;
+constexpr SfBpShape BP_SHAPES[] = {{64, 32, 76}, {32, 32, 44}, {16, 32, 44}, {16, 64, 48}};
+constexpr int BP_NSHAPES = 4;
 
 // Window of the detector that one (view, tile, z-chunk) can touch.  Evaluated identically on the host
 // (limit check) and in the kernel; everything here is uniform over the workgroup.
@@ -172,26 +172,26 @@ __global__ __launch_bounds__(256, 4) void sf_backproject_tiled(SfGeom g, const S
                 for (int m = 1; m < NC; ++m) s = fmaf(fu[m], q[m], s);
                 return s;
             };
-            float lo = ax.phi0, fl = 0.0f;                       // phi0 is in [0,1)
-            float s_cur = row_sum(buf + ofs), s_next = row_sum(buf + ofs + BP_PS);
+            // f: where the voxel's lower face lies inside its first row, in [0,1); the face moves up by av per voxel.
+            float f = ax.phi0;
+            unsigned row = ofs;                                  // LDS index of the voxel's first row, at this thread's column
+            float s_cur = row_sum(buf + row), s_next = row_sum(buf + row + BP_PS);
 #pragma unroll
             for (int kk = 0; kk < BP_ZC; ++kk) {
-                const float hi = fmaf(ax.av, (float)(kk + 1), ax.phi0);
-                const float edge = fl + 1.0f;
-                const float w0 = fminf(edge, hi) - lo;
-                const float w1 = sf_clamp(hi - edge, 0.0f, 1.0f);
+                const float t = f + ax.av;                        // upper face, still measured from the first row
+                const float w1 = sf_clamp(t - 1.0f, 0.0f, 1.0f);  // part of the voxel in the next row
+                const float w0 = ax.av - w1;
                 acc[kk] = fmaf(w1, s_next, fmaf(w0, s_cur, acc[kk]));
                 if (kk + 1 < BP_ZC) {
-                    const float fl_next = floorf(hi);                 // fl or fl + 1
-                    const float *q = buf + (ofs + __umul24((unsigned)(int)fl_next, (unsigned)BP_PS) + BP_PS);
-                    const float s_new = row_sum(q);                   // row fl_next + 1 (equals s_next when no row was crossed)
-                    s_cur = fl_next > fl ? s_next : s_cur;
+                    const bool cross = t >= 1.0f;                 // the next voxel starts in the next row
+                    row += cross ? (unsigned)BP_PS : 0u;
+                    const float s_new = row_sum(buf + row + BP_PS);   // equals s_next when no row was crossed
+                    s_cur = cross ? s_next : s_cur;
                     s_next = s_new;
-                    fl = fl_next;
-                    lo = hi;
+                    f = t - (cross ? 1.0f : 0.0f);
                 }
                 if ((kk & 3) == 3)
-                    asm volatile("" : "+v"(ofs), "+v"(acc[kk - 3]), "+v"(acc[kk - 2]), "+v"(acc[kk - 1]), "+v"(acc[kk]));
+                    asm volatile("" : "+v"(row), "+v"(acc[kk - 3]), "+v"(acc[kk - 2]), "+v"(acc[kk - 1]), "+v"(acc[kk]));
             }
         } else {
         float lo = ax.phi0;
