@@ -103,8 +103,16 @@ def main() -> int:
     batch = cfg.batch
     x_np = np.stack([standard_volume(args.config, cfg, item=b) for b in range(batch)])
     geo = Geometry(cfg, device="cuda:0")
-    x = torch.from_numpy(x_np).cuda()
     y = torch.empty((batch,) + cfg.sino_shape, dtype=torch.float32, device="cuda")
+    y_meas = None
+    if args.config == 4:
+        # training step: current estimate x, photon-noise measurement of A x_true (input preparation, untimed)
+        from synthetic import measured_sinogram, perturbed_volume
+        geo.project(torch.from_numpy(x_np).cuda(), out=y)
+        ideal = y.cpu().numpy()
+        y_meas = torch.from_numpy(np.stack([measured_sinogram(ideal[b], 1004 + b) for b in range(batch)])).cuda()
+        x_np = np.stack([perturbed_volume(x_np[b], 1004 + b) for b in range(batch)])
+    x = torch.from_numpy(x_np).cuda()
     xb = torch.empty_like(x)
 
     def step(ev=None):
@@ -113,6 +121,8 @@ def main() -> int:
         geo.project(x, out=y)
         if ev:
             ev[1].record()
+        if y_meas is not None:
+            y.sub_(y_meas)                       # residual r = A x - y_meas; the gradient is A^T r
         geo.backproject(y, out=xb)
         if ev:
             ev[2].record()
@@ -148,7 +158,8 @@ def main() -> int:
         "hbm_algorithmic_frac": alg_bytes / (dom_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
     }
     out = {
-        "metric": "ray-voxel updates/s for A and A^T at 512^3 cone-beam (voxel-view pairs, both operators per step)",
+        "metric": "ray-voxel updates/s for A and A^T (voxel-view pairs, both operators per step)"
+                  + (" at 512^3 cone-beam" if args.config == 3 else f" on case {args.config}"),
         "value": value, "unit": "voxel-view updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",

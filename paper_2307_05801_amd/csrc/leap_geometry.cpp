@@ -164,7 +164,7 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T;
         const float hx = 0.5f * (float)(BP_T - 1) * g.T;
         int first_shape = d->nz >= 128 ? 0 : 1;       // 64-voxel chunks only pay off on tall volumes
-        if (const char *env = std::getenv("LEAP_BP_SHAPE")) first_shape = std::atoi(env) & 3;
+        if (const char *env = std::getenv("LEAP_BP_SHAPE")) first_shape = std::atoi(env) % BP_NSHAPES;
         for (int sh = first_shape; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
             const int zc = BP_SHAPES[sh].zc;
             const int chunks = (d->nz + zc - 1) / zc;

@@ -149,6 +149,7 @@ static bool launch_bp_shape(const leap_geometry *G, const float *d_sino, float *
     case 1: launch_bp_tiled<NC, NV, 1>(G, d_sino, d_vol, stream); return true;
     case 2: launch_bp_tiled<NC, NV, 2>(G, d_sino, d_vol, stream); return true;
     case 3: launch_bp_tiled<NC, NV, 3>(G, d_sino, d_vol, stream); return true;
+    case 4: launch_bp_tiled<NC, NV, 4>(G, d_sino, d_vol, stream); return true;
     default: return false;
     }
 }

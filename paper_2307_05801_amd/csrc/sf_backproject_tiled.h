@@ -25,8 +25,8 @@ constexpr int BP_T = 16;        // tile edge in voxels (x and y)
 struct SfBpShape {
     int zc, pw, ph;
 };
-constexpr SfBpShape BP_SHAPES[] = {{64, 32, 76}, {32, 32, 44}, {16, 32, 44}, {16, 64, 48}};
-constexpr int BP_NSHAPES = 4;
+constexpr SfBpShape BP_SHAPES[] = {{64, 32, 76}, {32, 32, 44}, {32, 32, 56}, {16, 32, 44}, {16, 64, 48}};
+constexpr int BP_NSHAPES = 5;
 
 // Window of the detector that one (view, tile, z-chunk) can touch.  Evaluated identically on the host
 // (limit check) and in the kernel; everything here is uniform over the workgroup.

@@ -15,4 +15,6 @@ from .phantoms import (  # noqa: F401
     standard_volume,
     uniform_sinogram,
     uniform_volume,
+    measured_sinogram,
+    perturbed_volume,
 )

@@ -150,3 +150,17 @@ def uniform_sinogram(cfg: CTConfig, seed: int, batch: int = 1) -> np.ndarray:
 def uniform_volume(cfg: CTConfig, seed: int, batch: int = 1) -> np.ndarray:
     rng = np.random.default_rng([seed, 3])
     return rng.random((batch,) + cfg.vol_shape, dtype=np.float32)
+
+
+def measured_sinogram(ideal: np.ndarray, seed: int, photons: float = 1e5) -> np.ndarray:
+    """Photon-counting measurement of ideal line integrals (input preparation of the training-step case):
+    counts ~ Poisson(photons * exp(-ideal)), y = -ln(max(counts, 1) / photons).  Stream [seed, 4]."""
+    rng = np.random.default_rng([seed, 4])
+    counts = rng.poisson(photons * np.exp(-np.asarray(ideal, dtype=np.float64)))
+    return (-np.log(np.maximum(counts, 1) / photons)).astype(np.float32)
+
+
+def perturbed_volume(vol: np.ndarray, seed: int, sigma: float = 1e-3) -> np.ndarray:
+    """Current estimate of the training-step case: the phantom plus N(0, sigma) per voxel.  Stream [seed, 5]."""
+    rng = np.random.default_rng([seed, 5])
+    return (vol + rng.standard_normal(vol.shape, dtype=np.float32) * np.float32(sigma)).astype(np.float32)

@@ -118,3 +118,43 @@ def test_c5_subset_of_views_large_offsets(oracle_mod):
     lhs = float((ax.astype(np.float64) * y).sum())
     rhs = float(np.dot(aty.astype(np.float64).ravel(), x.astype(np.float64).ravel()))
     assert abs(lhs - rhs) <= TOL * abs(lhs)
+
+
+def test_c5_full_size_all_views(oracle_mod):
+    """The largest case whole: 1024^3 volume, 1440 views, 1024x1024 detector shifted by 2.5 pixels (4 GiB volume,
+    5.6 GiB sinogram).  Inputs are uniform noise (rasterising 50 ellipsoids on 10^9 voxels takes minutes on the CPU);
+    outputs are sampled on the GPU and recomputed one by one by the oracle."""
+    import torch
+    from paper_2307_05801_amd import Geometry
+    cfg = config(5)
+    print("[gpu] C5 full: inputs", flush=True)
+    x = np.random.default_rng([2005, 3]).random(cfg.vol_shape, dtype=np.float32)
+    y = np.random.default_rng([2005, 2]).random(cfg.sino_shape, dtype=np.float32)
+    geo = Geometry(cfg)
+    xt, yt = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
+    print("[gpu] C5 full: project", flush=True)
+    ax = geo.project(xt)
+    torch.cuda.synchronize()
+    print("[gpu] C5 full: backproject", flush=True)
+    aty = geo.backproject(yt)
+    torch.cuda.synchronize()
+    print("[gpu] C5 full: samples", flush=True)
+    rs = np.random.default_rng(45)
+    nray, nvox = cfg.nviews * cfg.nrows * cfg.ncols, cfg.nx * cfg.ny * cfg.nz
+    rays = np.unique(np.concatenate([rs.integers(0, nray, 300), np.array([0, nray - 1, nray // 2 + 517])]))
+    vox = np.unique(np.concatenate([rs.integers(0, nvox, 6000), np.array([0, nvox - 1, nvox // 2 + 1023])]))
+    ax_s = ax.view(-1)[torch.from_numpy(rays).cuda()].cpu().numpy()
+    aty_s = aty.view(-1)[torch.from_numpy(vox).cuda()].cpu().numpy()
+
+    def dot64(p, q, chunk=1 << 26):
+        p, q, total = p.view(-1), q.view(-1), 0.0
+        for s in range(0, p.numel(), chunk):
+            total += float(torch.dot(p[s:s + chunk].double(), q[s:s + chunk].double()))
+        return total
+
+    lhs, rhs = dot64(ax, yt), dot64(aty, xt)
+    geo.close()
+    del ax, aty, xt, yt
+    assert abs(lhs - rhs) <= TOL * abs(lhs)
+    assert rel_l2(ax_s, oracle_mod.project_rays(cfg, x, rays)) <= TOL
+    assert rel_l2(aty_s, oracle_mod.backproject_voxels(cfg, y, vox)) <= TOL

@@ -237,3 +237,45 @@ def test_streams_are_honoured(torch_mod):
     s.synchronize()
     assert torch_mod.equal(ref, got)
     geo.close()
+
+
+def test_training_step_of_case_4(torch_mod, oracle_mod):
+    """Batch of volumes: y = A x, residual against a photon-noise measurement, gradient g = A^T r."""
+    from paper_2307_05801_amd import Geometry
+    from synthetic import measured_sinogram, perturbed_volume
+    cfg = reduced(config(4), 4, nviews=15, batch=3)
+    truth = [standard_volume(4, cfg, item=b) for b in range(cfg.batch)]
+    x = np.stack([perturbed_volume(t, 1004 + b) for b, t in enumerate(truth)])
+    y_meas = np.stack([measured_sinogram(oracle_mod.project(cfg, t), 1004 + b) for b, t in enumerate(truth)])
+    print(f"[gpu] training step {cfg.name} batch={cfg.batch}", flush=True)
+    geo = Geometry(cfg)
+    xt, yt = torch_mod.from_numpy(x).cuda(), torch_mod.from_numpy(y_meas).cuda()
+    r = geo.project(xt) - yt
+    g = geo.backproject(r)
+    torch_mod.cuda.synchronize()
+    r_np, g_np = r.cpu().numpy(), g.cpu().numpy()
+    geo.close()
+    for b in range(cfg.batch):
+        ax_ref = oracle_mod.project(cfg, x[b])
+        # the residual is a small difference of large numbers: judge A by the projection, A^T by the gradient
+        assert rel_l2(r_np[b] + y_meas[b], ax_ref) <= TOL
+        assert rel_l2(g_np[b], oracle_mod.backproject(cfg, r_np[b])) <= TOL
+
+
+def test_general_kernels_agree_with_fast_kernels(torch_mod, oracle_mod, monkeypatch):
+    """The fallback loop nests and the tiled kernels evaluate the same weights."""
+    from paper_2307_05801_amd import Geometry
+    cfg = reduced(config(3), 8, nviews=20)
+    x = torch_mod.from_numpy(uniform_volume(cfg, 8)[0]).cuda()
+    y = torch_mod.from_numpy(uniform_sinogram(cfg, 9)[0]).cuda()
+    fast = Geometry(cfg)
+    assert "A=columns" in fast.describe() and "AT=tiled" in fast.describe()
+    a_fast, at_fast = fast.project(x).cpu().numpy(), fast.backproject(y).cpu().numpy()
+    fast.close()
+    monkeypatch.setenv("LEAP_FORCE_GENERAL", "1")
+    slow = Geometry(cfg)
+    assert "A=general" in slow.describe() and "AT=general" in slow.describe()
+    a_slow, at_slow = slow.project(x).cpu().numpy(), slow.backproject(y).cpu().numpy()
+    slow.close()
+    assert rel_l2(a_fast, a_slow) <= 2e-6 and rel_l2(at_fast, at_slow) <= 2e-6
+    assert rel_l2(a_slow, oracle_mod.project(cfg, x.cpu().numpy())) <= TOL
