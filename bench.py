@@ -23,6 +23,14 @@ import numpy as np  # noqa: E402
 PEAK_FP32_TFLOPS = 157.3      # MI355X published vector fp32 (packed); 78.6 without packed instructions
 PEAK_HBM_GBPS = 8000.0
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this very command, scaled by a 512 MiB
+# device copy in the same run (FETCH_SIZE x 2 KiB, WRITE_SIZE x 1 KiB); summaries under profiles/.  Keyed by workload
+# and operator; None when a workload has not been profiled.
+MEASURED_TRAFFIC_BYTES = {
+    ("c3_cone_512", "A"): 1.34725e8 * 2048 + 737280 * 1024,
+    ("c3_cone_512", "AT"): 8.30858e6 * 2048 + 524288 * 1024,
+}
+
 
 def algorithmic_flops_per_update(n_u: float, n_v: float, nz: int) -> float:
     """Cheapest known evaluation of the separable weights, per voxel-view pair: 40 flops per (view, voxel
@@ -150,12 +158,15 @@ def main() -> int:
     flops_launch = fl * batch * cfg.voxel_views
     achieved = flops_launch / (dom_ms * 1e-3) / 1e12
     alg_bytes = 4.0 * batch * (cfg.nx * cfg.ny * cfg.nz + cfg.nviews * cfg.nrows * cfg.ncols)
+    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, "A" if ms_a >= ms_at else "AT"))
     roofline = {
         "bound": "alu", "kernel": dom, "achieved": achieved, "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
-        "frac": achieved / PEAK_FP32_TFLOPS, "traffic": None,
-        "flops_per_update": fl, "launch_ms": dom_ms,
+        "frac": achieved / PEAK_FP32_TFLOPS, "traffic": traffic,
+        "flops_per_update": fl, "launch_ms": dom_ms, "frac_of_unpacked_fp32_peak": achieved / (PEAK_FP32_TFLOPS / 2),
+        "hbm_algorithmic_bytes": alg_bytes,
         "hbm_algorithmic_GBps": alg_bytes / (dom_ms * 1e-3) / 1e9,
-        "hbm_algorithmic_frac": alg_bytes / (dom_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+        "hbm_measured_GBps": None if traffic is None else traffic / (dom_ms * 1e-3) / 1e9,
+        "hbm_measured_frac_of_peak": None if traffic is None else traffic / (dom_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
     }
     out = {
         "metric": "ray-voxel updates/s for A and A^T (voxel-view pairs, both operators per step)"
