@@ -201,7 +201,12 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
             const int v = std::atoi(env);
             if (v == 4 || v == 8) G->fp_waves = v;
         }
+        if (const char *env = std::getenv("LEAP_FP_WV")) {
+            const int v = std::atoi(env);
+            if (v == 1 || v == 2 || v == 4 || v == 8) G->fp_wv = v;
+        }
         if (G->fp_waves == 8 && G->fp_cw == 4) G->fp_cw = 2;
+        if (G->fp_wv > G->fp_waves) G->fp_wv = G->fp_waves;
         // candidate slots per slab: widest range of voxel columns any bundle of cw detector columns can see
         auto slots_needed = [&](int cw) {
             int need = 0;
@@ -285,9 +290,9 @@ extern "C" int leap_geometry_describe(const leap_geometry *G, char *buf, int32_t
 {
     if (!G || !buf || cap <= 0) return invalid("null handle or buffer");
     std::snprintf(buf, (size_t)cap,
-                  "type=%d A=%s(nq=%d/%d,nk=%d,rg=%d,w=%d,cw=%d) AT=%s(nc=%d,nv=%d,zc=%d,window=%dx%d) cols/voxel<=%.2f rows/voxel<=%.2f "
+                  "type=%d A=%s(nq=%d/%d,nk=%d,rg=%d,w=%d,cw=%d,wv=%d) AT=%s(nc=%d,nv=%d,zc=%d,window=%dx%d) cols/voxel<=%.2f rows/voxel<=%.2f "
                   "voxels/row<=%.2f slope<=%.2f",
-                  G->g.type, G->fp_columns ? "columns" : "general", G->fp_need_q, G->fp_nq, G->fp_nk, G->fp_rg, G->fp_waves, G->fp_cw, G->bp_tiled ? "tiled" : "general", G->bp_nc, G->bp_nv, BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h,
+                  G->g.type, G->fp_columns ? "columns" : "general", G->fp_need_q, G->fp_nq, G->fp_nk, G->fp_rg, G->fp_waves, G->fp_cw, G->fp_wv, G->bp_tiled ? "tiled" : "general", G->bp_nc, G->bp_nv, BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h,
                   G->max_cols_per_voxel, G->max_rows_per_voxel, G->max_voxels_per_row, G->max_minor_slope);
     return LEAP_OK;
 }

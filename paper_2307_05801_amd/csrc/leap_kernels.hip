@@ -49,29 +49,32 @@ __global__ __launch_bounds__(256) void sf_project_general(SfGeom g, const SfView
 
 static inline unsigned cdiv(unsigned a, unsigned b) { return (a + b - 1) / b; }
 
-template <int NQ, int NK, int RG, int W, int CW>
+template <int NQ, int NK, int RG, int W, int CW, int WV>
 static void launch_fp_columns(const leap_geometry *G, float *d_sino, hipStream_t stream)
 {
     const SfGeom &g = G->g;
-    const int col_tiles = (int)cdiv(g.ncols, W * CW), bands = (int)cdiv(g.nrows, RG * 64);
-    // XCD-aware block order (see the kernel): pad views to blocks of vb and each XCD's tiles to chunks of tb
+    const int col_tiles = (int)cdiv(g.ncols, (W / WV) * CW), bands = (int)cdiv(g.nrows, RG * 64);
+    // XCD-aware block order (see the kernel): pad view groups to blocks of vb and each XCD's tiles to chunks of tb
     const int vb = G->fp_vb, tb = G->fp_tb;
-    const int nviews_pad = (int)cdiv(g.nviews, vb) * vb;
+    const int vgroups_pad = (int)cdiv(cdiv(g.nviews, WV), vb) * vb;
     const int tiles_per_xcd_pad = (int)cdiv(cdiv(col_tiles, 8), tb) * tb;
-    dim3 grid((unsigned)(8 * tiles_per_xcd_pad * nviews_pad * bands), 1, 1);
-    hipLaunchKernelGGL((sf_project_columns<NQ, NK, RG, W, CW>), grid, dim3(W * 64, 1, 1), 0, stream, g, G->d_views, G->d_volz,
-                       d_sino, G->nzp, col_tiles, bands, vb, tb, nviews_pad, tiles_per_xcd_pad);
+    dim3 grid((unsigned)(8 * tiles_per_xcd_pad * vgroups_pad * bands), 1, 1);
+    hipLaunchKernelGGL((sf_project_columns<NQ, NK, RG, W, CW, WV>), grid, dim3(W * 64, 1, 1), 0, stream, g, G->d_views,
+                       G->d_volz, d_sino, G->nzp, col_tiles, bands, vb, tb, vgroups_pad, tiles_per_xcd_pad);
 }
 
 template <int NQ, int NK, int RG>
 static bool launch_fp_w(const leap_geometry *G, float *d_sino, hipStream_t stream)
 {
-    switch (G->fp_waves * 10 + G->fp_cw) {
-    case 41: launch_fp_columns<NQ, NK, RG, 4, 1>(G, d_sino, stream); return true;
-    case 42: launch_fp_columns<NQ, NK, RG, 4, 2>(G, d_sino, stream); return true;
-    case 44: launch_fp_columns<NQ, NK, RG, 4, 4>(G, d_sino, stream); return true;
-    case 81: launch_fp_columns<NQ, NK, RG, 8, 1>(G, d_sino, stream); return true;
-    case 82: launch_fp_columns<NQ, NK, RG, 8, 2>(G, d_sino, stream); return true;
+    switch (G->fp_waves * 100 + G->fp_cw * 10 + G->fp_wv) {
+    case 411: launch_fp_columns<NQ, NK, RG, 4, 1, 1>(G, d_sino, stream); return true;
+    case 421: launch_fp_columns<NQ, NK, RG, 4, 2, 1>(G, d_sino, stream); return true;
+    case 422: launch_fp_columns<NQ, NK, RG, 4, 2, 2>(G, d_sino, stream); return true;
+    case 424: launch_fp_columns<NQ, NK, RG, 4, 2, 4>(G, d_sino, stream); return true;
+    case 441: launch_fp_columns<NQ, NK, RG, 4, 4, 1>(G, d_sino, stream); return true;
+    case 444: launch_fp_columns<NQ, NK, RG, 4, 4, 4>(G, d_sino, stream); return true;
+    case 824: launch_fp_columns<NQ, NK, RG, 8, 2, 4>(G, d_sino, stream); return true;
+    case 828: launch_fp_columns<NQ, NK, RG, 8, 2, 8>(G, d_sino, stream); return true;
     default: return false;
     }
 }

@@ -13,8 +13,8 @@
 // the marching axis, lane (slab, slot) evaluates one candidate voxel column; a ballot picks the candidates
 // with F_u > 0 and the wave then walks them one by one, broadcasting their few parameters through
 // v_readlane, while each lane accumulates its own rows' axial overlaps from coalesced loads of volz.
-// A few waves (adjacent column groups) form a workgroup so that neighbours, which see the same voxel columns,
-// share them in L1, and so that the final stores are row segments of W * CW columns.
+// The waves of a workgroup are the same column bundle(s) in WV consecutive views: their beams overlap almost
+// entirely, they start together and do equal work, so they share the volume through the CU's L1.
 #pragma once
 
 #include "sf_footprint.h"
@@ -100,36 +100,41 @@ __global__ __launch_bounds__(256) void sf_volume_to_columns(const float *__restr
 }
 
 // NQ: candidate slots per slab (power of two <= 64); NK: voxels a detector row can overlap; RG: row groups per wave;
-// FP_WAVES: waves per workgroup; CW: adjacent detector columns per wave.
-template <int NQ, int NK, int RG, int FP_WAVES, int CW>
+// FP_WAVES: waves per workgroup; CW: adjacent detector columns per wave; WV: consecutive views per workgroup
+// (the workgroup's waves are WV views x FP_WAVES/WV column bundles).
+template <int NQ, int NK, int RG, int FP_WAVES, int CW, int WV>
 __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, const SfView *__restrict__ views,
                                                                     const float *__restrict__ volz, float *__restrict__ sino,
                                                                     int nzp, int col_tiles, int bands, int vb, int tb,
-                                                                    int nviews_pad, int tiles_per_xcd_pad)
+                                                                    int vgroups_pad, int tiles_per_xcd_pad)
 {
     constexpr int SB = 64 / NQ;                       // slabs per record block
-    __shared__ float out_tile[RG * 64][FP_WAVES * CW + 1];
+    constexpr int WC = FP_WAVES / WV;                 // column bundles per workgroup
+    static_assert(WC * WV == FP_WAVES, "waves = column bundles x views");
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // Block -> (view, band, column tile).  Workgroups are handed to the 8 XCDs round-robin by index, and each XCD has
-    // its own L2.  Beams of the same column tile in neighbouring views overlap almost entirely, so the blocks one XCD
-    // runs at the same time are arranged as (a few column tiles) x (a run of consecutive views): index = 8 s + xcd,
-    // and within an XCD's sequence s the view runs fastest inside a block of VB views, then TB tiles, then view blocks.
+    const int wv = wave % WV, wc = wave / WV;
+    // Block -> (group of WV consecutive views, band, column tile).  The WV x WC waves of a workgroup start together and
+    // do the same amount of work, so they march through the volume in step: the beams of one column tile in WV
+    // neighbouring views overlap almost entirely and are shared in the CU's L1.  Workgroups are handed to the 8 XCDs
+    // round-robin by index, and each XCD has its own L2, so the blocks one XCD runs at the same time are arranged as
+    // (a few column tiles) x (a run of consecutive view groups): index = 8 s + xcd, and within an XCD's sequence s the
+    // view group runs fastest inside a block of VB groups, then TB tiles, then blocks of view groups.
     int ct, band, a;
     {
         const int xcd = blockIdx.x & 7, sq = blockIdx.x >> 3;
-        const int per_chunk = tb * nviews_pad;                  // TB tiles x all (padded) views
+        const int per_chunk = tb * vgroups_pad;                 // TB tiles x all (padded) view groups
         const int chunk = sq / per_chunk, r = sq - chunk * per_chunk;
         const int vblk = r / (tb * vb), r2 = r - vblk * (tb * vb);
         const int tloc = r2 / vb, v_in = r2 - tloc * vb;
         const int tchunks = tiles_per_xcd_pad / tb;
         band = chunk / tchunks;
         ct = ((chunk - band * tchunks) * tb + tloc) * 8 + xcd;
-        a = vblk * vb + v_in;
-        if (ct >= col_tiles || a >= g.nviews || band >= bands) return;   // padding blocks
+        a = (vblk * vb + v_in) * WV + wv;
+        if (ct >= col_tiles || a >= g.nviews || band >= bands) return;   // padding blocks and padding views (no barrier follows)
     }
-    const int c0 = (ct * FP_WAVES + wave) * CW;          // first detector column of this wave
+    const int c0 = (ct * WC + wc) * CW;                  // first detector column of this wave
     const int band0 = band * (RG * 64);
 
     const SfView v = views[a];
@@ -224,24 +229,18 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, co
         }
     }
 
-    // ---- amplitude, then transpose through LDS so that stores are row segments of FP_WAVES * CW columns
+    // ---- amplitude and store: CW consecutive floats per lane and row
+    float *__restrict__ ya = sino + (size_t)a * g.nrows * g.ncols;
 #pragma unroll
     for (int cw = 0; cw < CW; ++cw) {
         const int c = c0 + cw;
+        if (c >= g.ncols) break;
         const SfAmpCol ac = sf_amp_col(g, v, c);
 #pragma unroll
         for (int gq = 0; gq < RG; ++gq) {
             const int r = band0 + 64 * gq + lane;
-            out_tile[64 * gq + lane][wave * CW + cw] = sf_amp(g, v, ac, r < g.nrows ? r : 0) * acc[cw][gq];
+            if (r < g.nrows) ya[(size_t)r * g.ncols + c] = sf_amp(g, v, ac, r) * acc[cw][gq];
         }
-    }
-    __syncthreads();
-    constexpr int TW = FP_WAVES * CW;
-    float *__restrict__ ya = sino + (size_t)a * g.nrows * g.ncols;
-    for (int e = threadIdx.x; e < RG * 64 * TW; e += FP_WAVES * 64) {
-        const int row = e / TW, w = e % TW;
-        const int r = band0 + row, cw = ct * TW + w;
-        if (r < g.nrows && cw < g.ncols) ya[(size_t)r * g.ncols + cw] = out_tile[row][w];
     }
 }
 
