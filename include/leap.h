@@ -18,9 +18,14 @@
  *     sinogram : float32 [batch][nviews][nrows][ncols], column fastest.
  *   - Outputs are OVERWRITTEN, never accumulated into.
  *   - Calls are asynchronous on the given HIP stream (hipStream_t passed as void*, NULL =
- *     the default stream), allocate nothing and use no scratch that grows with the volume
- *     or the sinogram ("Performance and Memory Usage": one copy of each array is all the
- *     device memory needed).  Per-view tables are uploaded once, in leap_geometry_create.
+ *     the default stream) and allocate nothing.  Per-view tables are uploaded once, in
+ *     leap_geometry_create.  Device memory beyond the caller's arrays ("Performance and
+ *     Memory Usage" asks for one copy of each array only): the handle owns ONE scratch
+ *     array of nx*ny*(nz+8) floats, a z-fastest copy of the volume that leap_project
+ *     rewrites on every call; when it cannot be allocated the handle works without it
+ *     (slower kernels).  Because of that scratch, calls that use the same handle must be
+ *     ordered (one stream at a time, or events between streams); distinct handles are
+ *     independent.
  *   - World frame: voxel centres x_i = center_x + (i-(nx-1)/2) voxel_xy (y, z alike); view
  *     angle phi counter-clockwise from +x, the source sits at sod*(cos phi, sin phi, 0);
  *     detector columns grow along (-sin phi, cos phi, 0), rows along +z; pixel centres
@@ -77,7 +82,7 @@ void leap_geometry_destroy(leap_geometry *geom);
 
 /* Forward projection y = A x ("CT Projection Models and Geometries", y = A x), ray-driven gather:
  * d_sino[b] = A d_vol[b] for b < batch.  d_vol: batch volumes, d_sino: batch sinograms (layouts above),
- * both device memory, not overlapping.  Asynchronous on hip_stream. */
+ * both device memory, not overlapping.  Asynchronous on hip_stream.  Uses the handle's scratch copy. */
 int leap_project(const leap_geometry *geom, const float *d_vol, float *d_sino, int32_t batch, void *hip_stream);
 
 /* Back projection x = A^T y, the exact transpose of leap_project ("matched projectors"), voxel-driven

@@ -213,7 +213,7 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, co
                 const double kap = fma(rd[gq], s_mu, zkp);
                 const float fr = (float)__builtin_amdgcn_fract(kap);
                 int kf = (int)kap;                                 // truncation = floor wherever the clamp leaves it alone
-                kf = max(0, min(kf, kmax));
+                asm("v_med3_i32 %0, %1, 0, %2" : "=v"(kf) : "v"(kf), "s"(kmax));   // clamp to [0, kmax] in one op
                 const float *__restrict__ x = reinterpret_cast<const float *>(col + ((unsigned)kf << 2));
                 // overlaps of [kap, kap + step) with voxels kf, kf+1, ...
                 float rem = step, s = 0.0f, w = fminf(1.0f - fr, step);
