@@ -1,0 +1,179 @@
+// Host-side harness for the HIP library's host/device code (test infrastructure; built with g++, no GPU).
+//
+// It links the library's real host geometry module against stubs of the few HIP runtime calls that module makes,
+// and supplies CPU versions of the two launchers that step the general kernel bodies thread by thread.  On top of
+// that it re-enacts, on the CPU, the index arithmetic of the tiled back projection (does every LDS access of every
+// thread of every workgroup stay inside the staged window?) and the arithmetic of the column-wise forward kernel
+// (candidate slots, padded z-columns, axial overlap cascade), so that mistakes in them show up without a GPU.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "../../paper_2307_05801_amd/csrc/leap_internal.h"
+#include "../../paper_2307_05801_amd/csrc/sf_general.h"
+#define SF_NO_KERNELS
+#include "../../paper_2307_05801_amd/csrc/sf_backproject_tiled.h"
+#include "../../paper_2307_05801_amd/csrc/sf_project_columns.h"
+
+// ---- stubs of the HIP runtime calls made by leap_geometry.cpp: "device" memory is host memory ---------------
+extern "C" {
+hipError_t hipGetDevice(int *d) { *d = 0; return hipSuccess; }
+hipError_t hipMalloc(void **p, size_t n) { *p = std::malloc(n); return *p ? hipSuccess : hipErrorOutOfMemory; }
+hipError_t hipMemcpy(void *d, const void *s, size_t n, hipMemcpyKind) { std::memcpy(d, s, n); return hipSuccess; }
+hipError_t hipMemset(void *p, int v, size_t n) { std::memset(p, v, n); return hipSuccess; }
+hipError_t hipFree(void *p) { std::free(p); return hipSuccess; }
+hipError_t hipDeviceSynchronize() { return hipSuccess; }
+hipError_t hipGetLastError() { return hipSuccess; }
+const char *hipGetErrorString(hipError_t) { return "stub"; }
+}
+
+// ---- CPU launchers: the general kernel bodies, one "thread" at a time ----------------------------------------
+int leap_launch_project(const leap_geometry *G, const float *vol, float *sino, hipStream_t)
+{
+    const SfGeom &g = G->g;
+    constexpr int RC = 8;
+#pragma omp parallel for collapse(2)
+    for (int a = 0; a < g.nviews; ++a)
+        for (int r0 = 0; r0 < g.nrows; r0 += RC)
+            for (int c = 0; c < g.ncols; ++c) {
+                float out[RC];
+                sf_project_ray_chunk<RC>(g, G->d_views[a], vol, c, r0, out);
+                for (int rr = 0; rr < RC && r0 + rr < g.nrows; ++rr) sino[((size_t)a * g.nrows + r0 + rr) * g.ncols + c] = out[rr];
+            }
+    return LEAP_OK;
+}
+
+int leap_launch_backproject(const leap_geometry *G, const float *sino, float *vol, hipStream_t)
+{
+    const SfGeom &g = G->g;
+    constexpr int ZC = 8;
+#pragma omp parallel for collapse(2)
+    for (int k0 = 0; k0 < g.nz; k0 += ZC)
+        for (int j = 0; j < g.ny; ++j)
+            for (int i = 0; i < g.nx; ++i) {
+                float acc[ZC] = {0};
+                sf_backproject_column_chunk<ZC>(g, G->d_views, sino, i, j, k0, acc);
+                for (int kk = 0; kk < ZC && k0 + kk < g.nz; ++kk) vol[((size_t)(k0 + kk) * g.ny + j) * g.nx + i] = acc[kk];
+            }
+    return LEAP_OK;
+}
+
+// ---- tiled back projection: every thread's LDS reads against the staged window --------------------------------
+// report[0..7] = {tiled?, nc, nv, zc, max column index read, max row index read, widest footprint in pixels, violations}
+extern "C" int host_check_backproject_windows(const leap_geometry *G, int64_t *report)
+{
+    const SfGeom &g = G->g;
+    std::fill(report, report + 8, 0);
+    report[0] = G->bp_tiled;
+    if (!G->bp_tiled) return 0;
+    const int NC = G->bp_nc, NV = G->bp_nv;
+    const SfBpShape S = BP_SHAPES[G->bp_shape];
+    const int tiles_x = (g.nx + BP_T - 1) / BP_T, tiles_y = (g.ny + BP_T - 1) / BP_T, chunks = (g.nz + S.zc - 1) / S.zc;
+    int maxc = -1, maxr = -1, maxspan = 0;
+    long bad = 0;
+#pragma omp parallel for collapse(2) reduction(max : maxc, maxr, maxspan) reduction(+ : bad)
+    for (int a = 0; a < g.nviews; ++a)
+        for (int ty = 0; ty < tiles_y; ++ty)
+            for (int tx = 0; tx < tiles_x; ++tx)
+                for (int ch = 0; ch < chunks; ++ch) {
+                    const int i0 = tx * BP_T, j0 = ty * BP_T, k0 = ch * S.zc;
+                    const double zlo = fma((double)k0, g.Tzd, g.zlo0d);
+                    const float z0 = (float)zlo, z1 = z0 + (float)S.zc * g.Tz;
+                    const float hx = 0.5f * (float)(BP_T - 1) * g.T;
+                    const float xc = (float)(g.x0d + ((double)i0 + 0.5 * (BP_T - 1)) * g.Td);
+                    const float yc = (float)(g.y0d + ((double)j0 + 0.5 * (BP_T - 1)) * g.Td);
+                    const SfWindow w = sf_bp_window(g, G->views[a], xc, yc, hx, z0, z1, G->bp_wh, NC, NV);
+                    for (int tj = 0; tj < BP_T; ++tj)
+                        for (int ti = 0; ti < BP_T; ++ti) {
+                            const int i = std::min(i0 + ti, g.nx - 1), j = std::min(j0 + tj, g.ny - 1);
+                            const SfColumn f = sf_column(g, G->views[a], i, j);
+                            int cf, cl;
+                            sf_col_range(f, cf, cl);
+                            const SfRowsOfVoxels ax = sf_rows_of_voxels(g, f, zlo);
+                            const int c_lo = cf - w.c0, c_hi = c_lo + NC - 1;
+                            const int r_lo = ax.rb - w.r0;
+                            // last row read: first row of the last voxel plus NV-1 (the shared-row variant reads the same set)
+                            const int r_hi = r_lo + (int)std::floor(fmaf(ax.av, (float)(S.zc - 1), ax.phi0)) + NV - 1;
+                            maxc = std::max(maxc, c_hi);
+                            maxr = std::max(maxr, r_hi);
+                            maxspan = std::max(maxspan, cl - cf + 1);
+                            if (c_lo < 0 || c_hi >= S.pw || r_lo < 0 || r_hi >= S.ph) ++bad;   // read outside the staged window
+                            if (cl - cf + 1 > NC) ++bad;                                          // footprint wider than NC columns
+                            if (ax.av > (float)(NV - 1) * 1.000001f) ++bad;                       // voxel taller than NV-1 rows
+                        }
+                }
+    report[1] = NC; report[2] = NV; report[3] = S.zc; report[4] = maxc; report[5] = maxr; report[6] = maxspan; report[7] = bad;
+    return bad != 0;
+}
+
+// ---- column-wise forward projection: its arithmetic, serially ---------------------------------------------------
+// Returns -1 when the handle does not use the column kernel, else the number of (view, bundle, slab) cases in which the
+// candidate slots do not cover the candidate range (must be 0).
+extern "C" long host_project_columns(const leap_geometry *G, const float *vol, float *sino)
+{
+    const SfGeom &g = G->g;
+    if (!G->fp_columns) return -1;
+    const int NQ = G->fp_nq, NK = G->fp_nk, CW = G->fp_cw, nzp = g.nz + 2 * FP_PAD, kmax = g.nz + FP_PAD;
+    std::vector<float> volz((size_t)g.nx * g.ny * nzp, 0.f);
+    for (int k = 0; k < g.nz; ++k)
+        for (int j = 0; j < g.ny; ++j)
+            for (int i = 0; i < g.nx; ++i) volz[((size_t)j * g.nx + i) * nzp + FP_PAD + k] = vol[((size_t)k * g.ny + j) * g.nx + i];
+    const double zkp = -g.zlo0d * g.iTzd + (double)FP_PAD, mu_scale = g.ikvd * g.iTzd;
+    long uncovered = 0;
+#pragma omp parallel for collapse(2) reduction(+ : uncovered)
+    for (int a = 0; a < g.nviews; ++a)
+        for (int c0 = 0; c0 < g.ncols; c0 += CW) {
+            const SfView v = G->views[a];
+            const SfRayLines L = sf_ray_lines(g, v, c0, CW);
+            const int n_major = L.xmajor ? g.nx : g.ny, n_minor = L.xmajor ? g.ny : g.nx;
+            std::vector<float> acc((size_t)g.nrows * CW, 0.f);
+            for (int n = 0; n < n_major; ++n) {
+                int qf, ql;
+                sf_candidates(L, n, qf, ql);
+                if (ql - qf + 1 > NQ) ++uncovered;
+                for (int s = 0; s < NQ; ++s) {
+                    const int q = qf + s;
+                    if (q < 0 || q >= n_minor || q > ql) continue;
+                    const int i = L.xmajor ? n : q, j = L.xmajor ? q : n;
+                    const SfColumn f = sf_column(g, v, i, j);
+                    const float rows_per_voxel = (float)(g.kvd * f.inv * g.Tzd);
+                    float fa[8];
+                    bool any = false;
+                    float e = sf_pixel_edge(f, c0), g0 = sf_trap_integral(f, e);
+                    for (int cw = 0; cw < CW; ++cw) {
+                        e += 1.0f;
+                        const float g1 = sf_trap_integral(f, e);
+                        const float fu = (c0 + cw < g.ncols) ? fmaxf(g1 - g0, 0.f) : 0.f;
+                        fa[cw] = fu * rows_per_voxel;
+                        any = any || fu > 0.f;
+                        g0 = g1;
+                    }
+                    if (!any) continue;
+                    const double mu = f.den * mu_scale;
+                    const float step = (float)mu;
+                    const float *col = &volz[((size_t)j * g.nx + i) * nzp];
+                    for (int r = 0; r < g.nrows; ++r) {
+                        const double kap = fma((double)r - g.row_offd, mu, zkp);
+                        const float fr = (float)(kap - std::floor(kap));
+                        const int kf = std::max(0, std::min((int)kap, kmax));
+                        float rem = step, sum = 0.f, w = fminf(1.f - fr, step);
+                        for (int t = 0; t < NK; ++t) {
+                            sum = fmaf(w, col[kf + t], sum);
+                            rem -= w;
+                            w = (t == NK - 2) ? rem : fminf(rem, 1.f);
+                        }
+                        for (int cw = 0; cw < CW; ++cw) acc[(size_t)r * CW + cw] = fmaf(fa[cw], sum, acc[(size_t)r * CW + cw]);
+                    }
+                }
+            }
+            for (int cw = 0; cw < CW && c0 + cw < g.ncols; ++cw) {
+                const SfAmpCol ac = sf_amp_col(g, v, c0 + cw);
+                for (int r = 0; r < g.nrows; ++r)
+                    sino[((size_t)a * g.nrows + r) * g.ncols + c0 + cw] = sf_amp(g, v, ac, r) * acc[(size_t)r * CW + cw];
+            }
+        }
+    return uncovered;
+}

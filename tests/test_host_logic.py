@@ -1,0 +1,132 @@
+"""Host logic of the HIP library, exercised on the CPU (no GPU): the real geometry module (validation, table
+building, kernel selection and its static limits) linked against stubs of the HIP runtime, the general kernel bodies
+stepped thread by thread, the window arithmetic of the tiled back projection, and the arithmetic of the column-wise
+forward kernel.  tests/host/host_harness.cpp holds the C++ side."""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+from paper_2307_05801_amd import binding as B
+from synthetic import CTConfig, config, reduced, standard_volume, uniform_sinogram, uniform_volume
+from synthetic.configs import CONE, FAN, PARALLEL
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+SRC = os.path.join(HERE, "host", "host_harness.cpp")
+LIB = os.path.join(HERE, "host", "libhost_harness.so")
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def host():
+    deps = [SRC, os.path.join(ROOT, "paper_2307_05801_amd", "csrc")]
+    newest = max(os.path.getmtime(os.path.join(d, f)) if os.path.isdir(d) else os.path.getmtime(d)
+                 for d in deps for f in (os.listdir(d) if os.path.isdir(d) else [""]))
+    if not os.path.exists(LIB) or os.path.getmtime(LIB) < newest:
+        cmd = ["g++", "-O2", "-fopenmp", "-std=c++17", "-fPIC", "-shared", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
+               "-o", LIB, SRC, os.path.join(ROOT, "paper_2307_05801_amd", "csrc", "leap_geometry.cpp")]
+        subprocess.run(cmd, check=True, capture_output=True)
+    lib = C.CDLL(LIB)
+    B.declare(lib)
+    lib.host_check_backproject_windows.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
+    lib.host_project_columns.restype = C.c_long
+    lib.host_project_columns.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+    return lib
+
+
+def rel_l2(got, ref):
+    return float(np.linalg.norm(np.asarray(got, np.float64) - ref) / np.linalg.norm(ref))
+
+
+def handle(lib, cfg):
+    d, keep = B.desc_from_config(cfg)
+    return B.leap_geometry_create(d, lib)
+
+
+CASES = {
+    "c1": (1, lambda: config(1)),
+    "c2_div8": (2, lambda: reduced(config(2), 8, nviews=20)),
+    "c3_div8_ragged": (3, lambda: reduced(config(3), 8, nviews=24).replace(nx=67, ny=70, nz=45, nrows=61, ncols=77)),
+    "c3_div8_offsets": (3, lambda: reduced(config(3), 8, nviews=9).replace(
+        shift_u=1.3, shift_v=-2.7, center_x=6.0, center_y=-4.5, center_z=3.25, start_deg=7.0)),
+    "c4_div4": (4, lambda: reduced(config(4), 4, nviews=10)),
+    "c5_div16": (5, lambda: reduced(config(5), 16, nviews=18)),
+    "fan": (3, lambda: CTConfig("fan", FAN, nviews=20, arc_deg=360.0, nrows=1, ncols=90, pixel_v=1.0, pixel_u=2.0,
+                                nx=70, ny=64, nz=1, voxel_xy=1.0, voxel_z=1.0, sod=300.0, sdd=500.0, shift_u=0.8)),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_general_kernel_bodies_match_oracle_on_cpu(host, oracle_mod, name):
+    number, make = CASES[name]
+    cfg = make()
+    x = standard_volume(number, cfg) if cfg.nz > 1 or number == 1 else uniform_volume(cfg, 5)[0]
+    y = uniform_sinogram(cfg, 50 + number)[0]
+    h = handle(host, cfg)
+    ax = np.zeros(cfg.sino_shape, np.float32)
+    aty = np.zeros(cfg.vol_shape, np.float32)
+    B.leap_project(h, x.ctypes.data, ax.ctypes.data, 1, 0, host)
+    B.leap_backproject(h, y.ctypes.data, aty.ctypes.data, 1, 0, host)
+    B.leap_geometry_destroy(h, host)
+    assert rel_l2(ax, oracle_mod.project(cfg, x)) <= TOL
+    assert rel_l2(aty, oracle_mod.backproject(cfg, y)) <= TOL
+    lhs, rhs = float((ax.astype(np.float64) * y).sum()), float((aty.astype(np.float64) * x).sum())
+    assert abs(lhs - rhs) <= TOL * abs(lhs)
+
+
+@pytest.mark.parametrize("name", ["c2_div8", "c3_div8_ragged", "c3_div8_offsets", "c4_div4", "c5_div16"])
+def test_column_forward_arithmetic_matches_oracle_on_cpu(host, oracle_mod, name, monkeypatch):
+    number, make = CASES[name]
+    cfg = make()
+    x = standard_volume(number, cfg)
+    ref = oracle_mod.project(cfg, x)
+    for cw in ("1", "2", "4"):
+        monkeypatch.setenv("LEAP_FP_CW", cw)
+        h = handle(host, cfg)
+        out = np.zeros(cfg.sino_shape, np.float32)
+        uncovered = host.host_project_columns(h, x.ctypes.data, out.ctypes.data)
+        desc = B.leap_geometry_describe(h, host)
+        B.leap_geometry_destroy(h, host)
+        assert uncovered == 0, desc
+        assert rel_l2(out, ref) <= TOL, desc
+
+
+def window_report(host, cfg):
+    h = handle(host, cfg)
+    rep = (C.c_int64 * 8)()
+    host.host_check_backproject_windows(h, rep)
+    desc = B.leap_geometry_describe(h, host)
+    B.leap_geometry_destroy(h, host)
+    return list(rep), desc
+
+
+@pytest.mark.parametrize("name", ["c2_div8", "c3_div8_ragged", "c3_div8_offsets", "c4_div4", "c5_div16"])
+def test_tiled_backprojection_reads_stay_inside_the_staged_window(host, name):
+    rep, desc = window_report(host, CASES[name][1]())
+    assert rep[0] == 1, desc
+    assert rep[7] == 0, (rep, desc)
+
+
+def test_window_limits_at_full_benchmark_sizes(host):
+    """Every tile and chunk of a spread of views of the 512^3 and 1024^3 cone-beam cases, and the batch case."""
+    for cfg in (config(3).with_views(list(range(0, 720, 45))), config(5).with_views([0, 181, 542, 1260]), config(4)):
+        rep, desc = window_report(host, cfg)
+        assert rep[0] == 1 and rep[7] == 0, (rep, desc)
+
+
+def test_kernel_selection(host):
+    def desc(cfg):
+        h = handle(host, cfg)
+        s = B.leap_geometry_describe(h, host)
+        B.leap_geometry_destroy(h, host)
+        return s
+    assert "A=columns" in desc(config(3)) and "AT=tiled" in desc(config(3))
+    assert "A=general" in desc(CASES["fan"][1]()) and "AT=general" in desc(CASES["fan"][1]())
+    assert "A=general" in desc(config(1))                                  # one detector row: nothing to tile
+    coarse = reduced(config(3), 8, nviews=4).replace(pixel_u=37.0, pixel_v=29.0, nrows=14, ncols=12)
+    assert "A=general" in desc(coarse)                                     # a row spans six voxels
+    fine = reduced(config(3), 8, nviews=4).replace(pixel_u=1.7, pixel_v=1.9, nrows=300, ncols=280)
+    assert "AT=general" in desc(fine)                                      # a voxel spans six pixels
