@@ -279,3 +279,16 @@ def test_general_kernels_agree_with_fast_kernels(torch_mod, oracle_mod, monkeypa
     slow.close()
     assert rel_l2(a_fast, a_slow) <= 2e-6 and rel_l2(at_fast, at_slow) <= 2e-6
     assert rel_l2(a_slow, oracle_mod.project(cfg, x.cpu().numpy())) <= TOL
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_geometries(torch_mod, oracle_mod, seed):
+    """Random scanners (cone and parallel, shifted and truncated detectors, anisotropic voxels, irregular angles)."""
+    from random_geometries import random_config
+    cfg = random_config(seed)
+    x = uniform_volume(cfg, seed)[0]
+    y = uniform_sinogram(cfg, seed)[0]
+    ax = gpu_project(torch_mod, cfg, x)
+    aty = gpu_backproject(torch_mod, cfg, y)
+    assert rel_l2(ax, oracle_mod.project(cfg, x)) <= TOL
+    assert rel_l2(aty, oracle_mod.backproject(cfg, y)) <= TOL

@@ -130,3 +130,30 @@ def test_kernel_selection(host):
     assert "A=general" in desc(coarse)                                     # a row spans six voxels
     fine = reduced(config(3), 8, nviews=4).replace(pixel_u=1.7, pixel_v=1.9, nrows=300, ncols=280)
     assert "AT=general" in desc(fine)                                      # a voxel spans six pixels
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_geometries_on_cpu(host, oracle_mod, seed):
+    """Whatever kernels a random scanner selects, their static limits hold and the arithmetic matches the oracle."""
+    from random_geometries import random_config
+    cfg = random_config(seed)
+    x = uniform_volume(cfg, seed)[0]
+    y = uniform_sinogram(cfg, seed)[0]
+    h = handle(host, cfg)
+    desc = B.leap_geometry_describe(h, host)
+    rep = (C.c_int64 * 8)()
+    host.host_check_backproject_windows(h, rep)
+    assert rep[7] == 0, (list(rep), desc)
+    ref = oracle_mod.project(cfg, x)
+    out = np.zeros(cfg.sino_shape, np.float32)
+    uncovered = host.host_project_columns(h, x.ctypes.data, out.ctypes.data)
+    if uncovered >= 0:
+        assert uncovered == 0, desc
+        assert rel_l2(out, ref) <= TOL, desc
+    ax = np.zeros(cfg.sino_shape, np.float32)
+    aty = np.zeros(cfg.vol_shape, np.float32)
+    B.leap_project(h, x.ctypes.data, ax.ctypes.data, 1, 0, host)
+    B.leap_backproject(h, y.ctypes.data, aty.ctypes.data, 1, 0, host)
+    B.leap_geometry_destroy(h, host)
+    assert rel_l2(ax, ref) <= TOL, desc
+    assert rel_l2(aty, oracle_mod.backproject(cfg, y)) <= TOL, desc
