@@ -1,10 +1,12 @@
-"""CPU oracle of the separable-footprint projector pair.  Test infrastructure only.
+"""CPU oracles of the projector pairs: separable footprint (the functions of this package) and Siddon
+(`oracle.siddon`).  Test infrastructure only.
 
 Only tests, the smoke check and the benchmark's cpu_baseline leg may import this
 package; the product (paper_2307_05801_amd) never does.
 """
+from . import siddon_oracle as siddon  # noqa: F401
+from .sf_oracle import build as _build_sf
 from .sf_oracle import (  # noqa: F401
-    build,
     project,
     backproject,
     backproject_voxels,
@@ -17,3 +19,8 @@ from .sf_oracle import (  # noqa: F401
     num_threads,
     set_num_threads,
 )
+
+
+def build(force: bool = False):
+    """Compile both C oracles (gcc); returns the paths of the two libraries."""
+    return _build_sf(force), siddon.build(force)

@@ -1,0 +1,263 @@
+/*
+ * CPU oracle for the Siddon projector pair.  TEST INFRASTRUCTURE ONLY.  See siddon_oracle.h for the definition
+ * (weight = length of the pixel-centre ray inside the half-open voxel box) and for the statement of the paper it
+ * serves.  Every weight that enters a sum comes from ONE routine, chord(), which clips the ray's parameter range
+ * against the box one axis at a time (the textbook slab test).  The loops around it only enumerate a superset of the
+ * voxels (A) or pixels (A^T) that can have a non-zero weight; tests compare them with the dense matrix, which calls
+ * the same routine for every (ray, voxel) pair.  Double precision throughout; OpenMP splits the outermost loop only.
+ */
+#include "siddon_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---- coordinates -------------------------------------------------------------------------------------------- */
+
+static double grid_lo(double centre, int n, double pitch) { return centre - 0.5 * n * pitch; }   /* lower face of voxel 0 */
+static double pix_u(const sdo_scan *s, int c) { return (c - 0.5 * (s->ncols - 1) + s->shift_u) * s->pu; }
+static double pix_v(const sdo_scan *s, int r) { return (r - 0.5 * (s->nrows - 1) + s->shift_v) * s->pv; }
+
+/* the line o + t d (t real) of ray (view, r, c); len = |d| converts parameter length to mm */
+typedef struct { double o[3], d[3], len; int ndim; } ray_t;
+
+static void ray_of(const sdo_scan *s, int view, int r, int c, ray_t *ray)
+{
+    double cphi = cos(s->phi[view]), sphi = sin(s->phi[view]);
+    double es[3] = { cphi, sphi, 0.0 }, eu[3] = { -sphi, cphi, 0.0 }, ez[3] = { 0.0, 0.0, 1.0 };
+    double u = pix_u(s, c), v = (s->geom == SDO_FAN) ? 0.0 : pix_v(s, r);
+    ray->ndim = (s->geom == SDO_FAN) ? 2 : 3;
+    for (int a = 0; a < 3; ++a) {
+        if (s->geom == SDO_PARALLEL) {
+            ray->o[a] = u * eu[a] + v * ez[a];
+            ray->d[a] = es[a];
+        } else {
+            ray->o[a] = s->sod * es[a];                                   /* source */
+            ray->d[a] = -s->sdd * es[a] + u * eu[a] + v * ez[a];          /* pixel centre minus source */
+        }
+    }
+    double q = 0.0;
+    for (int a = 0; a < ray->ndim; ++a) q += ray->d[a] * ray->d[a];
+    ray->len = sqrt(q);
+}
+
+/* length of the line inside the half-open box [lo, hi) */
+static double chord(const ray_t *ray, const double lo[3], const double hi[3])
+{
+    double t0 = -INFINITY, t1 = INFINITY;
+    for (int a = 0; a < ray->ndim; ++a) {
+        if (ray->d[a] == 0.0) {
+            if (!(lo[a] <= ray->o[a] && ray->o[a] < hi[a])) return 0.0;
+        } else {
+            double ta = (lo[a] - ray->o[a]) / ray->d[a], tb = (hi[a] - ray->o[a]) / ray->d[a];
+            if (ta > tb) { double w = ta; ta = tb; tb = w; }
+            if (ta > t0) t0 = ta;
+            if (tb < t1) t1 = tb;
+        }
+    }
+    return t1 > t0 ? (t1 - t0) * ray->len : 0.0;
+}
+
+static void voxel_box(const sdo_scan *s, int i, int j, int k, double lo[3], double hi[3])
+{
+    lo[0] = grid_lo(s->cx, s->nx, s->T) + i * s->T;   hi[0] = lo[0] + s->T;
+    lo[1] = grid_lo(s->cy, s->ny, s->T) + j * s->T;   hi[1] = lo[1] + s->T;
+    lo[2] = grid_lo(s->cz, s->nz, s->Tz) + k * s->Tz; hi[2] = lo[2] + s->Tz;
+}
+
+double sdo_weight(const sdo_scan *s, int view, int r, int c, int i, int j, int k)
+{
+    ray_t ray;
+    double lo[3], hi[3];
+    ray_of(s, view, r, c, &ray);
+    voxel_box(s, i, j, k, lo, hi);
+    return chord(&ray, lo, hi);
+}
+
+/* ---- A: one ray ----------------------------------------------------------------------------------------------- */
+
+/* Index range [*a, *b] of the cells (pitch p, first lower face g0, n cells) that the closed interval between x0 and
+ * x1 can touch, widened by a hair so that rounding never loses a cell; clipped to the grid. */
+static void cell_range(double x0, double x1, double g0, double p, int n, int *a, int *b)
+{
+    double lo = fmin(x0, x1), hi = fmax(x0, x1);
+    double fa = floor((lo - g0) / p - 1e-9), fb = floor((hi - g0) / p + 1e-9);
+    *a = fa < 0.0 ? 0 : (fa > n ? n : (int)fa);
+    *b = fb > n - 1 ? n - 1 : (fb < -1.0 ? -1 : (int)fb);
+}
+
+/* Visits every voxel the ray can cross: walks the slabs of the in-plane axis along which the ray advances fastest,
+ * and inside each slab tries every voxel of the bounding box of the ray's piece in that slab.  `vol` may be NULL
+ * (then only non-zero weights are counted into *count). */
+static double ray_sum(const sdo_scan *s, const ray_t *ray, const float *vol, int64_t *count)
+{
+    int major = fabs(ray->d[0]) >= fabs(ray->d[1]) ? 0 : 1, minor = 1 - major;
+    int nmaj = major == 0 ? s->nx : s->ny, nmin = major == 0 ? s->ny : s->nx;
+    double gmaj = grid_lo(major == 0 ? s->cx : s->cy, nmaj, s->T);
+    double gmin = grid_lo(major == 0 ? s->cy : s->cx, nmin, s->T);
+    double gz = grid_lo(s->cz, s->nz, s->Tz);
+    double sum = 0.0;
+    for (int n = 0; n < nmaj; ++n) {
+        double ta = (gmaj + n * s->T - ray->o[major]) / ray->d[major];
+        double tb = (gmaj + (n + 1) * s->T - ray->o[major]) / ray->d[major];
+        int q0, q1, k0 = 0, k1 = 0;
+        cell_range(ray->o[minor] + ta * ray->d[minor], ray->o[minor] + tb * ray->d[minor], gmin, s->T, nmin, &q0, &q1);
+        if (ray->ndim == 3)
+            cell_range(ray->o[2] + ta * ray->d[2], ray->o[2] + tb * ray->d[2], gz, s->Tz, s->nz, &k0, &k1);
+        for (int k = k0; k <= k1; ++k)
+            for (int q = q0; q <= q1; ++q) {
+                int i = major == 0 ? n : q, j = major == 0 ? q : n;
+                double lo[3], hi[3];
+                voxel_box(s, i, j, k, lo, hi);
+                double w = chord(ray, lo, hi);
+                if (w > 0.0) {
+                    if (vol) sum += w * (double)vol[((int64_t)k * s->ny + j) * s->nx + i];
+                    if (count) ++*count;
+                }
+            }
+    }
+    return sum;
+}
+
+int sdo_project(const sdo_scan *s, const float *vol, double *sino)
+{
+    int64_t lines = (int64_t)s->nviews * s->nrows;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t l = 0; l < lines; ++l) {
+        int view = (int)(l / s->nrows), r = (int)(l % s->nrows);
+        for (int c = 0; c < s->ncols; ++c) {
+            ray_t ray;
+            ray_of(s, view, r, c, &ray);
+            sino[l * s->ncols + c] = ray_sum(s, &ray, vol, NULL);
+        }
+    }
+    return 0;
+}
+
+int sdo_project_rays(const sdo_scan *s, const float *vol, int64_t n, const int64_t *rayidx, double *out)
+{
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t m = 0; m < n; ++m) {
+        int c = (int)(rayidx[m] % s->ncols);
+        int r = (int)((rayidx[m] / s->ncols) % s->nrows);
+        int view = (int)(rayidx[m] / ((int64_t)s->ncols * s->nrows));
+        ray_t ray;
+        ray_of(s, view, r, c, &ray);
+        out[m] = ray_sum(s, &ray, vol, NULL);
+    }
+    return 0;
+}
+
+int64_t sdo_nnz(const sdo_scan *s, int view_begin, int view_end)
+{
+    int64_t total = 0;
+    int64_t lines = (int64_t)(view_end - view_begin) * s->nrows;
+#pragma omp parallel for schedule(dynamic, 4) reduction(+ : total)
+    for (int64_t l = 0; l < lines; ++l) {
+        int view = view_begin + (int)(l / s->nrows), r = (int)(l % s->nrows);
+        for (int c = 0; c < s->ncols; ++c) {
+            ray_t ray;
+            int64_t cnt = 0;
+            ray_of(s, view, r, c, &ray);
+            ray_sum(s, &ray, NULL, &cnt);
+            total += cnt;
+        }
+    }
+    return total;
+}
+
+/* ---- A^T: one voxel ------------------------------------------------------------------------------------------- */
+
+/* Pixel-index range whose centres can lie between detector coordinates a and b (pitch p, `off` = index of coordinate
+ * 0), widened by a hair; clipped to [0, n-1]. */
+static void pixel_range(double a, double b, double p, double off, int n, int *i0, int *i1)
+{
+    double lo = fmin(a, b) / p + off, hi = fmax(a, b) / p + off;
+    double fa = ceil(lo - 1e-9), fb = floor(hi + 1e-9);
+    *i0 = fa < 0.0 ? 0 : (fa > n ? n : (int)fa);
+    *i1 = fb > n - 1 ? n - 1 : (fb < -1.0 ? -1 : (int)fb);
+}
+
+/* Only rays whose pixel centre lies inside the bounding rectangle of the voxel's eight projected corners can meet
+ * the voxel (a perspective or parallel image of a box is the hull of its projected corners). */
+static double voxel_sum(const sdo_scan *s, int i, int j, int k, const float *sino)
+{
+    double lo[3], hi[3], sum = 0.0;
+    voxel_box(s, i, j, k, lo, hi);
+    for (int view = 0; view < s->nviews; ++view) {
+        double cphi = cos(s->phi[view]), sphi = sin(s->phi[view]);
+        double umin = INFINITY, umax = -INFINITY, vmin = INFINITY, vmax = -INFINITY;
+        for (int corner = 0; corner < 8; ++corner) {
+            double x = (corner & 1) ? hi[0] : lo[0], y = (corner & 2) ? hi[1] : lo[1], z = (corner & 4) ? hi[2] : lo[2];
+            double t = -x * sphi + y * cphi, l = x * cphi + y * sphi;
+            double mag = (s->geom == SDO_PARALLEL) ? 1.0 : s->sdd / (s->sod - l);
+            double u = mag * t, v = mag * z;
+            umin = fmin(umin, u); umax = fmax(umax, u);
+            vmin = fmin(vmin, v); vmax = fmax(vmax, v);
+        }
+        int c0, c1, r0 = 0, r1 = 0;
+        pixel_range(umin, umax, s->pu, 0.5 * (s->ncols - 1) - s->shift_u, s->ncols, &c0, &c1);
+        if (s->geom != SDO_FAN)
+            pixel_range(vmin, vmax, s->pv, 0.5 * (s->nrows - 1) - s->shift_v, s->nrows, &r0, &r1);
+        for (int r = r0; r <= r1; ++r)
+            for (int c = c0; c <= c1; ++c) {
+                ray_t ray;
+                ray_of(s, view, r, c, &ray);
+                double w = chord(&ray, lo, hi);
+                if (w > 0.0) sum += w * (double)sino[((int64_t)view * s->nrows + r) * s->ncols + c];
+            }
+    }
+    return sum;
+}
+
+int sdo_backproject(const sdo_scan *s, const float *sino, double *vol)
+{
+    int64_t lines = (int64_t)s->nz * s->ny;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t l = 0; l < lines; ++l) {
+        int k = (int)(l / s->ny), j = (int)(l % s->ny);
+        for (int i = 0; i < s->nx; ++i) vol[l * s->nx + i] = voxel_sum(s, i, j, k, sino);
+    }
+    return 0;
+}
+
+int sdo_backproject_voxels(const sdo_scan *s, const float *sino, int64_t n, const int64_t *voxel, double *out)
+{
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t m = 0; m < n; ++m) {
+        int i = (int)(voxel[m] % s->nx);
+        int j = (int)((voxel[m] / s->nx) % s->ny);
+        int k = (int)(voxel[m] / ((int64_t)s->nx * s->ny));
+        out[m] = voxel_sum(s, i, j, k, sino);
+    }
+    return 0;
+}
+
+/* ---- dense matrix: every pair from the single-weight routine --------------------------------------------------- */
+
+int sdo_dense_matrix(const sdo_scan *s, double *A)
+{
+    int64_t nvox = (int64_t)s->nx * s->ny * s->nz;
+    int64_t nray = (int64_t)s->nviews * s->nrows * s->ncols;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < nray; ++m) {
+        int c = (int)(m % s->ncols), r = (int)((m / s->ncols) % s->nrows);
+        int view = (int)(m / ((int64_t)s->ncols * s->nrows));
+        for (int k = 0; k < s->nz; ++k)
+            for (int j = 0; j < s->ny; ++j)
+                for (int i = 0; i < s->nx; ++i)
+                    A[m * nvox + ((int64_t)k * s->ny + j) * s->nx + i] = sdo_weight(s, view, r, c, i, j, k);
+    }
+    return 0;
+}
+
+int sdo_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,6 +1,6 @@
 """The pins must be able to fail: plant one plausible mistake at a time into a COPY of the oracle's C source
-(dropped term, wrong sign, transposed index, wrong magnification, ...) and check that tests/test_oracle_pins.py
-rejects every one of them.  Everything happens on the CPU in a temporary directory; the real oracle is untouched."""
+(dropped term, wrong sign, transposed index, wrong magnification, ...) and check that the pin tests of that oracle
+(tests/test_oracle_pins.py, tests/test_siddon_pins.py) reject every one of them.  Everything happens on the CPU in a temporary directory; the real oracle is untouched."""
 import os
 import shutil
 import subprocess
@@ -47,11 +47,47 @@ MUTATIONS = [
 ]
 
 
-@pytest.mark.parametrize("what,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
-def test_pins_reject_a_planted_mistake(tmp_path, what, old, new):
+SIDDON_MUTATIONS = [
+    ("face plane given to the lower voxel",
+     "if (!(lo[a] <= ray->o[a] && ray->o[a] < hi[a])) return 0.0;",
+     "if (!(lo[a] < ray->o[a] && ray->o[a] <= hi[a])) return 0.0;"),
+    ("ray length measured in the plane only",
+     "for (int a = 0; a < ray->ndim; ++a) q += ray->d[a] * ray->d[a];",
+     "for (int a = 0; a < 2; ++a) q += ray->d[a] * ray->d[a];"),
+    ("parameter length not converted to mm",
+     "return t1 > t0 ? (t1 - t0) * ray->len : 0.0;", "return t1 > t0 ? (t1 - t0) : 0.0;"),
+    ("parallel rays ignore the detector row",
+     "ray->o[a] = u * eu[a] + v * ez[a];", "ray->o[a] = u * eu[a];"),
+    ("sign of the detector axis",
+     "eu[3] = { -sphi, cphi, 0.0 }", "eu[3] = { sphi, cphi, 0.0 }"),
+    ("detector placed at the source-to-detector distance behind the axis",
+     "ray->d[a] = -s->sdd * es[a] + u * eu[a] + v * ez[a];",
+     "ray->d[a] = -(s->sdd + s->sod) * es[a] + u * eu[a] + v * ez[a];"),
+    ("grid shifted by half a voxel",
+     "return centre - 0.5 * n * pitch;", "return centre - 0.5 * (n - 1) * pitch;"),
+    ("ray walk keeps only the first cell of a slab",
+     "fb = floor((hi - g0) / p + 1e-9);", "fb = floor((lo - g0) / p + 1e-9);"),
+    ("sign of the horizontal shift in the voxel's pixel search",
+     "0.5 * (s->ncols - 1) - s->shift_u, s->ncols", "0.5 * (s->ncols - 1) + s->shift_u, s->ncols"),
+    ("pixel search forgets the axial magnification",
+     "double u = mag * t, v = mag * z;", "double u = mag * t, v = z;"),
+    ("volume indexed transposed in A",
+     "sum += w * (double)vol[((int64_t)k * s->ny + j) * s->nx + i];",
+     "sum += w * (double)vol[((int64_t)k * s->nx + i) * s->ny + j];"),
+    ("sinogram indexed transposed in A^T",
+     "sum += w * (double)sino[((int64_t)view * s->nrows + r) * s->ncols + c];",
+     "sum += w * (double)sino[((int64_t)view * s->ncols + c) * s->nrows + r];"),
+]
+
+CASES = ([("sf_oracle.c", "test_oracle_pins.py") + m for m in MUTATIONS]
+         + [("siddon_oracle.c", "test_siddon_pins.py") + m for m in SIDDON_MUTATIONS])
+
+
+@pytest.mark.parametrize("source,pins,what,old,new", CASES, ids=[c[0][:-9] + ": " + c[2] for c in CASES])
+def test_pins_reject_a_planted_mistake(tmp_path, source, pins, what, old, new):
     shutil.copytree(os.path.join(ROOT, "oracle"), tmp_path / "oracle",
                     ignore=shutil.ignore_patterns("*.so", "__pycache__"))
-    src = tmp_path / "oracle" / "sf_oracle.c"
+    src = tmp_path / "oracle" / source
     text = src.read_text()
     assert text.count(old) >= 1, "mutation site not found: the oracle changed, update this list"
     src.write_text(text.replace(old, new, 1))
@@ -59,7 +95,7 @@ def test_pins_reject_a_planted_mistake(tmp_path, what, old, new):
     check = subprocess.run([sys.executable, "-c", "import oracle, os; print(os.path.dirname(oracle.__file__))"],
                            env=env, cwd=str(tmp_path), capture_output=True, text=True)
     assert check.stdout.strip() == str(tmp_path / "oracle"), check.stdout + check.stderr
-    run = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
+    run = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", pins), "-x", "-q",
                           "-p", "no:cacheprovider", "--rootdir", str(tmp_path), "-c", os.devnull],
                          env=env, cwd=str(tmp_path), capture_output=True, text=True)
     assert run.returncode != 0, f"the pins accepted: {what}"
