@@ -1,12 +1,14 @@
 /*
- * leap.h - C ABI of the MI355X separable-footprint CT projector pair.
+ * leap.h - C ABI of the MI355X CT projector pairs (separable footprint and Siddon).
  *
  * The library computes, on one GPU, the forward projector A (line integrals of a voxel
  * volume along every source-detector ray) and its exact transpose A^T for parallel-,
  * fan- and flat-panel cone-beam scanners.  The operator and its transpose are the ones
  * the paper states in its Method section ("CT Projection Models and Geometries":
- * y = A x, back projection as the exact transpose, separable-footprint weights that
- * model finite voxel and detector-pixel width, quantities in mm and 1/mm).  The calling
+ * y = A x, back projection as the exact transpose, quantities in mm and 1/mm), for the two
+ * projector models named there: separable-footprint weights, which model finite voxel and
+ * detector-pixel width, and Siddon weights, the exact length of the thin ray through each
+ * pixel centre inside each voxel.  The calling
  * convention follows "Core CUDA Implementation" (the user hands over pointers to
  * contiguous 32-bit float arrays) and "PyTorch Interfaces and CT Parameters" (the list
  * of scanner parameters).
@@ -23,7 +25,8 @@
  *     Memory Usage" asks for one copy of each array only): the handle owns ONE scratch
  *     array of nx*ny*(nz+8) floats, a z-fastest copy of the volume that leap_project
  *     rewrites on every call; when it cannot be allocated the handle works without it
- *     (slower kernels).  Because of that scratch, calls that use the same handle must be
+ *     (slower kernels).  A LEAP_MODEL_SIDDON handle also keeps a table of 48 bytes per
+ *     (view, detector column): the constants of each ray's line.  Because of the scratch copy, calls that use the same handle must be
  *     ordered (one stream at a time, or events between streams); distinct handles are
  *     independent.
  *   - World frame: voxel centres x_i = center_x + (i-(nx-1)/2) voxel_xy (y, z alike); view
@@ -45,9 +48,14 @@ extern "C" {
  * one-slice case of the flat-panel cone-beam scanner). */
 enum { LEAP_PARALLEL = 0, LEAP_FAN = 1, LEAP_CONE = 2 };
 
+/* Projector models ("CT Projection Models and Geometries").  LEAP_MODEL_SF: separable footprints.
+ * LEAP_MODEL_SIDDON: weight = length (mm) of the ray through the pixel centre inside the voxel; a voxel is
+ * the half-open box [lo, hi) on every axis, so a ray running inside a face plane belongs to the voxel above. */
+enum { LEAP_MODEL_SF = 0, LEAP_MODEL_SIDDON = 1 };
+
 enum {
     LEAP_OK = 0,
-    LEAP_INVALID_ARG = -1,   /* null pointer, non-positive size or count, FAN with nrows != 1 or nz != 1 */
+    LEAP_INVALID_ARG = -1,   /* null pointer, non-positive size or count, unknown type or model, FAN with nrows != 1 or nz != 1 */
     LEAP_BAD_GEOMETRY = -2,  /* cone/fan: source not strictly outside the volume's bounding circle, or sdd <= 0 */
     LEAP_HIP_ERROR = -3,     /* a HIP runtime call failed (the message is kept, see leap_last_error) */
     LEAP_UNSUPPORTED = -4    /* sizes beyond what the index arithmetic of the kernels covers */
@@ -67,6 +75,7 @@ typedef struct {
     double  voxel_xy, voxel_z;    /* mm: in-plane voxels are square */
     double  center_x, center_y, center_z; /* mm: volume centre */
     const double *angles_rad;     /* nviews view angles, any spacing */
+    int32_t model;                /* LEAP_MODEL_SF (0, so a zero-filled struct keeps the footprint model) / LEAP_MODEL_SIDDON */
 } leap_geometry_desc;
 
 typedef struct leap_geometry leap_geometry;   /* opaque; owned by the library */

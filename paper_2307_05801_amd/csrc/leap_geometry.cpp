@@ -44,11 +44,59 @@ static int invalid(const char *why)
 
 static bool finite_pos(double v) { return std::isfinite(v) && v > 0.0; }
 
+// Siddon model: constants of the line of every (view, detector column), in double ("sd_ray.h" states the formulation).
+static void build_ray_table(leap_geometry *G)
+{
+    const leap_geometry_desc &d = G->desc;
+    const SfGeom &g = G->g;
+    const double T = d.voxel_xy, Tz = d.voxel_z;
+    const double xlo = g.x0d - 0.5 * T, ylo = g.y0d - 0.5 * T;      // lower faces of voxel (0, 0)
+    G->raycols.resize((size_t)d.nviews * d.ncols);
+    double max_dh = 0.0;
+    for (int a = 0; a < d.nviews; ++a) {
+        const double c = G->views[a].cd, s = G->views[a].sd;
+        for (int col = 0; col < d.ncols; ++col) {
+            const double u = ((double)col - g.col_offd) * d.pixel_u;
+            double ox, oy, dx, dy;
+            if (d.type == LEAP_PARALLEL) {
+                ox = -u * s; oy = u * c; dx = c; dy = s;
+            } else {
+                ox = d.sod * c; oy = d.sod * s;
+                dx = -d.sdd * c - u * s; dy = -d.sdd * s + u * c;
+            }
+            SdRayCol R;
+            R.xmajor = std::fabs(dx) >= std::fabs(dy) ? 1 : 0;
+            const double dmaj = R.xmajor ? dx : dy, dmin = R.xmajor ? dy : dx;
+            const double omaj = R.xmajor ? ox : oy, omin = R.xmajor ? oy : ox;
+            const double lomaj = R.xmajor ? xlo : ylo, lomin = R.xmajor ? ylo : xlo;
+            R.m = dmin / dmaj;
+            R.b = (omin - lomin) / T - R.m * (omaj - lomaj) / T;
+            const double inv_m = R.m != 0.0 ? 1.0 / R.m : 1e30;
+            R.inv_m = (float)std::fmin(std::fmax(inv_m, -1e30), 1e30);
+            R.lxy = (float)(T * std::sqrt(dx * dx + dy * dy) / std::fabs(dmaj));
+            if (d.type == LEAP_CONE) {
+                R.h0 = (lomaj - omaj) / (dmaj * Tz);
+                R.dh = T / (dmaj * Tz);
+                R.vscale = (float)(T / std::fabs(dmaj));
+            } else if (d.type == LEAP_PARALLEL) {
+                R.h0 = 1.0 / Tz; R.dh = 0.0; R.vscale = 0.0f;
+            } else {
+                R.h0 = 0.0; R.dh = 0.0; R.vscale = 0.0f;
+            }
+            max_dh = std::fmax(max_dh, std::fabs(R.dh));
+            G->raycols[(size_t)a * d.ncols + col] = R;
+        }
+    }
+    const double vmax = std::fmax(std::fabs(g.v0d), std::fabs(g.v0d + (d.nrows - 1) * g.pvd));
+    G->sd_max_axial_slope = max_dh * vmax;
+}
+
 extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry **out)
 {
     if (out) *out = nullptr;
     if (!d || !out) return invalid("null descriptor or output pointer");
     if (d->type != LEAP_PARALLEL && d->type != LEAP_FAN && d->type != LEAP_CONE) return invalid("unknown geometry type");
+    if (d->model != LEAP_MODEL_SF && d->model != LEAP_MODEL_SIDDON) return invalid("unknown projector model");
     if (d->nviews <= 0 || d->nrows <= 0 || d->ncols <= 0) return invalid("nviews, nrows and ncols must be positive");
     if (d->nx <= 0 || d->ny <= 0 || d->nz <= 0) return invalid("nx, ny and nz must be positive");
     if (!finite_pos(d->pixel_u) || !finite_pos(d->pixel_v)) return invalid("pixel sizes must be positive");
@@ -118,6 +166,10 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
     g.ku = (float)g.kud;
     g.col_off = (float)g.col_offd;
     g.v0 = (float)((-0.5 * (d->nrows - 1) + d->shift_v) * d->pixel_v);
+    g.model = d->model;
+    g.v0d = (-0.5 * (d->nrows - 1) + d->shift_v) * d->pixel_v;
+    g.pvd = d->pixel_v;
+    g.zk0d = d->type == LEAP_FAN ? 0.5 : -g.zlo0d / d->voxel_z;
 
     G->views.resize(d->nviews);
     for (int a = 0; a < d->nviews; ++a) {
@@ -131,6 +183,8 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         v.par_amp = (float)(T / std::fmax(std::fabs(c), std::fabs(s)));
         v.xmajor = std::fabs(c) >= std::fabs(s) ? 1 : 0;
     }
+
+    if (d->model == LEAP_MODEL_SIDDON) build_ray_table(G);
 
     // Footprint bounds over the whole volume (double).  Magnification is extreme at the corner of the volume's
     // bounding circle; a flat detector stretches a footprint seen at fan angle gamma by 1/cos(gamma).
@@ -154,7 +208,7 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
 
     // Tiled back projection: pick the template instance and verify its staged window against every
     // (view, tile, z-chunk) with the very function the kernel evaluates.
-    if (d->type != LEAP_FAN && d->nz >= 8 && std::isfinite(G->max_cols_per_voxel) && G->max_cols_per_voxel <= 4.0 &&
+    if (d->model == LEAP_MODEL_SF && d->type != LEAP_FAN && d->nz >= 8 && std::isfinite(G->max_cols_per_voxel) && G->max_cols_per_voxel <= 4.0 &&
         G->max_rows_per_voxel <= 3.0) {
         G->bp_nc = (int)std::ceil(G->max_cols_per_voxel) + 1;
         if (G->bp_nc < 2) G->bp_nc = 2;
@@ -190,7 +244,7 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
     }
 
     // Column-wise forward projection: static limits, then its scratch copy of the volume.
-    if (d->type != LEAP_FAN && d->nrows >= 32 && std::isfinite(G->max_voxels_per_row) && G->max_voxels_per_row <= 3.0 &&
+    if (d->model == LEAP_MODEL_SF && d->type != LEAP_FAN && d->nrows >= 32 && std::isfinite(G->max_voxels_per_row) && G->max_voxels_per_row <= 3.0 &&
         (double)d->nx * d->ny * (d->nz + 2.0 * FP_PAD) < 4294967296.0 && d->ny <= 65535) {
         // tuning aids (read once per handle)
         if (const char *env = std::getenv("LEAP_FP_CW")) {
@@ -269,8 +323,15 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
             (void)hipGetLastError();
         }
     }
+    if (e == hipSuccess && !G->raycols.empty()) {
+        const size_t bytes = sizeof(SdRayCol) * G->raycols.size();
+        e = hipMalloc((void **)&G->d_raycols, bytes);
+        if (e == hipSuccess) e = hipMemcpy(G->d_raycols, G->raycols.data(), bytes, hipMemcpyHostToDevice);
+    }
     if (e != hipSuccess) {
         if (G->d_views) (void)hipFree(G->d_views);
+        if (G->d_volz) (void)hipFree(G->d_volz);
+        if (G->d_raycols) (void)hipFree(G->d_raycols);
         delete G;
         return leap_hip_fail(e, "uploading the view table");
     }
@@ -283,12 +344,18 @@ extern "C" void leap_geometry_destroy(leap_geometry *G)
     if (!G) return;
     if (G->d_views) (void)hipFree(G->d_views);
     if (G->d_volz) (void)hipFree(G->d_volz);
+    if (G->d_raycols) (void)hipFree(G->d_raycols);
     delete G;
 }
 
 extern "C" int leap_geometry_describe(const leap_geometry *G, char *buf, int32_t cap)
 {
     if (!G || !buf || cap <= 0) return invalid("null handle or buffer");
+    if (G->g.model == SF_MODEL_SIDDON) {
+        std::snprintf(buf, (size_t)cap, "type=%d model=siddon A=general AT=general axial-slope<=%.3f", G->g.type,
+                      G->sd_max_axial_slope);
+        return LEAP_OK;
+    }
     std::snprintf(buf, (size_t)cap,
                   "type=%d A=%s(nq=%d/%d,nk=%d,rg=%d,w=%d,cw=%d,wv=%d) AT=%s(nc=%d,nv=%d,zc=%d,window=%dx%d) cols/voxel<=%.2f rows/voxel<=%.2f "
                   "voxels/row<=%.2f slope<=%.2f",

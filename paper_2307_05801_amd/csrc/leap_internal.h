@@ -8,6 +8,7 @@
 
 #include "../../include/leap.h"
 #include "sf_types.h"
+#include "sd_ray.h"
 
 struct leap_geometry {
     leap_geometry_desc desc;            // caller's parameters (angles_rad re-pointed at `angles`)
@@ -31,6 +32,10 @@ struct leap_geometry {
     bool fp_columns = false;
     float *d_volz = nullptr;            // z-fastest padded copy of one volume (scratch)
     int nzp = 0;
+    // Siddon model: per-(view, detector column) ray constants, host copy and device copy
+    std::vector<SdRayCol> raycols;
+    SdRayCol *d_raycols = nullptr;
+    double sd_max_axial_slope = 0;      // largest |dZ/dX| of any ray: voxels of z crossed per slab
 };
 
 void leap_set_error(const std::string &msg);

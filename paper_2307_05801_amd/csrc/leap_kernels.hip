@@ -1,4 +1,4 @@
-// HIP kernels (gfx950) and launchers of the separable-footprint projector pair.
+// HIP kernels (gfx950) and launchers of the projector pairs (separable footprint and Siddon).
 #include <hip/hip_runtime.h>
 
 #include "leap_internal.h"
@@ -47,7 +47,58 @@ __global__ __launch_bounds__(256) void sf_project_general(SfGeom g, const SfView
         if (r0 + rr < g.nrows) y[(size_t)(r0 + rr) * g.ncols] = out[rr];
 }
 
+// Siddon model, general kernels: one thread per ray / per voxel.
+// grid: x = ceil(ncols/64), y = ceil(nrows/4), z = nviews; block 64x4.
+__global__ __launch_bounds__(256) void sd_project_general(SfGeom g, const SdRayCol *__restrict__ rays,
+                                                          const float *__restrict__ vol, float *__restrict__ sino)
+{
+    const int c = blockIdx.x * 64 + threadIdx.x;
+    const int r = blockIdx.y * 4 + threadIdx.y;
+    const int a = blockIdx.z;
+    if (c >= g.ncols || r >= g.nrows) return;
+    const SdRayCol R = rays[(size_t)a * g.ncols + c];
+    sino[((size_t)a * g.nrows + r) * g.ncols + c] = sd_project_ray(g, R, vol, r);
+}
+
+// grid: x = ceil(nx/64), y = ceil(ny/4), z = nz; block 64x4.
+__global__ __launch_bounds__(256) void sd_backproject_general(SfGeom g, const SfView *__restrict__ views,
+                                                              const SdRayCol *__restrict__ rays,
+                                                              const float *__restrict__ sino, float *__restrict__ vol)
+{
+    const int i = blockIdx.x * 64 + threadIdx.x;
+    const int j = blockIdx.y * 4 + threadIdx.y;
+    const int k = blockIdx.z;
+    if (i >= g.nx || j >= g.ny) return;
+    vol[((size_t)k * g.ny + j) * g.nx + i] = sd_backproject_voxel(g, views, rays, sino, i, j, k);
+}
+
 static inline unsigned cdiv(unsigned a, unsigned b) { return (a + b - 1) / b; }
+
+static int launch_sd_project(const leap_geometry *G, const float *d_vol, float *d_sino, hipStream_t stream)
+{
+    const SfGeom &g = G->g;
+    dim3 grid(cdiv(g.ncols, 64), cdiv(g.nrows, 4), g.nviews);
+    if (grid.y > 65535u) {
+        leap_set_error("detector has too many rows for one launch");
+        return LEAP_UNSUPPORTED;
+    }
+    hipLaunchKernelGGL(sd_project_general, grid, dim3(64, 4, 1), 0, stream, g, G->d_raycols, d_vol, d_sino);
+    LEAP_HIP_CHECK(hipGetLastError());
+    return LEAP_OK;
+}
+
+static int launch_sd_backproject(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
+{
+    const SfGeom &g = G->g;
+    dim3 grid(cdiv(g.nx, 64), cdiv(g.ny, 4), g.nz);
+    if (grid.y > 65535u || grid.z > 65535u) {
+        leap_set_error("volume has too many voxels along y or z for one launch");
+        return LEAP_UNSUPPORTED;
+    }
+    hipLaunchKernelGGL(sd_backproject_general, grid, dim3(64, 4, 1), 0, stream, g, G->d_views, G->d_raycols, d_sino, d_vol);
+    LEAP_HIP_CHECK(hipGetLastError());
+    return LEAP_OK;
+}
 
 template <int NQ, int NK, int RG, int W, int CW, int WV>
 static void launch_fp_columns(const leap_geometry *G, float *d_sino, hipStream_t stream)
@@ -105,6 +156,7 @@ static bool launch_fp_nk(const leap_geometry *G, float *d_sino, hipStream_t stre
 int leap_launch_project(const leap_geometry *G, const float *d_vol, float *d_sino, hipStream_t stream)
 {
     const SfGeom &g = G->g;
+    if (g.model == SF_MODEL_SIDDON) return launch_sd_project(G, d_vol, d_sino, stream);
     if (G->fp_columns) {
         dim3 tgrid(cdiv(g.nx, 32), cdiv(g.nz, 32), g.ny);
         hipLaunchKernelGGL(sf_volume_to_columns, tgrid, dim3(32, 8, 1), 0, stream, d_vol, G->d_volz, g.nx, g.ny, g.nz, G->nzp);
@@ -160,6 +212,7 @@ static bool launch_bp_shape(const leap_geometry *G, const float *d_sino, float *
 int leap_launch_backproject(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
 {
     const SfGeom &g = G->g;
+    if (g.model == SF_MODEL_SIDDON) return launch_sd_backproject(G, d_sino, d_vol, stream);
     if (G->bp_tiled) {
         bool ok = false;
         switch (G->bp_nc * 10 + G->bp_nv) {

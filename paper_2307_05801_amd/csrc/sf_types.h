@@ -15,12 +15,13 @@
 #include <stdint.h>
 
 enum { SF_PARALLEL = 0, SF_FAN = 1, SF_CONE = 2 };
+enum { SF_MODEL_FOOTPRINT = 0, SF_MODEL_SIDDON = 1 };
 
 struct SfGeom {
     int32_t type;
     int32_t nviews, nrows, ncols;
     int32_t nx, ny, nz;
-    int32_t pad_;
+    int32_t model;        // SF_MODEL_FOOTPRINT / SF_MODEL_SIDDON
     // double: bases
     double Td, Tzd;       // voxel sizes, mm
     double x0d, y0d;      // centre of voxel (i,j) = (0,0), mm
@@ -32,6 +33,8 @@ struct SfGeom {
     double iTzd;          // 1 / Tz
     double col_offd;      // (ncols-1)/2 - shift_u
     double row_offd;      // (nrows-1)/2 - shift_v + 1/2
+    double v0d, pvd;      // v (mm) of row 0's centre and the row pitch: v_r = v0d + r pvd
+    double zk0d;          // kappa of the plane z = 0: -zlo0 / Tz  (fan-beam: 1/2, the middle of the only slice)
     // float: relative quantities
     float T, Tz;
     float sod, sdd;

@@ -14,13 +14,19 @@ from . import binding as B
 class Geometry:
     """Owns one leap_geometry handle on one GPU."""
 
-    def __init__(self, cfg=None, device="cuda:0", **desc_kwargs):
+    def __init__(self, cfg=None, device="cuda:0", model="sf", **desc_kwargs):
         self.device = torch.device(device)
         if self.device.type != "cuda":
             raise RuntimeError("the projector runs on a GPU only (device must be cuda:N); there is no CPU path")
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible to PyTorch; the projector has no CPU path")
-        desc, keep = B.desc_from_config(cfg) if cfg is not None else B.make_desc(**desc_kwargs)
+        if model not in B.MODELS:
+            raise ValueError(f"model must be one of {sorted(B.MODELS)}")
+        self.model = model
+        if cfg is not None:
+            desc, keep = B.desc_from_config(cfg, B.MODELS[model])
+        else:
+            desc, keep = B.make_desc(model=B.MODELS[model], **desc_kwargs)
         self.nviews, self.nrows, self.ncols = desc.nviews, desc.nrows, desc.ncols
         self.nx, self.ny, self.nz = desc.nx, desc.ny, desc.nz
         with torch.cuda.device(self.device):
@@ -113,9 +119,9 @@ class _BackprojectFn(torch.autograd.Function):
 class Projector(torch.nn.Module):
     """y = A x as a differentiable module; `backproject` gives A^T (also differentiable)."""
 
-    def __init__(self, cfg=None, device="cuda:0", **desc_kwargs):
+    def __init__(self, cfg=None, device="cuda:0", model="sf", **desc_kwargs):
         super().__init__()
-        self.geometry = Geometry(cfg, device=device, **desc_kwargs)
+        self.geometry = Geometry(cfg, device=device, model=model, **desc_kwargs)
 
     def forward(self, vol: torch.Tensor) -> torch.Tensor:
         return _ProjectFn.apply(vol, self.geometry)
