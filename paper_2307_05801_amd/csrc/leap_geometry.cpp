@@ -303,23 +303,44 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         }
     }
 
+    // Siddon model, wave-per-column forward projection: no ray may cross more than one z-face per slab.
+    if (d->model == LEAP_MODEL_SIDDON && d->type != LEAP_FAN && d->nrows >= 32 && G->sd_max_axial_slope <= 0.999 &&
+        ((double)d->nx * d->ny + 1.0) * (d->nz + 2.0 * FP_PAD) < 4294967296.0 && d->ny <= 65535) {
+        G->sd_columns = true;
+        const int groups = (d->nrows + 63) / 64;
+        G->fp_rg = groups >= 8 ? 8 : (groups >= 4 ? 4 : (groups >= 2 ? 2 : 1));
+        if (const char *env = std::getenv("LEAP_FP_VB")) {
+            const int v = std::atoi(env);
+            if (v >= 1 && v <= 1024) G->fp_vb = v;
+        }
+        if (const char *env = std::getenv("LEAP_FP_TB")) {
+            const int v = std::atoi(env);
+            if (v >= 1 && v <= 1024) G->fp_tb = v;
+        }
+        if (const char *env = std::getenv("LEAP_FP_RG")) {
+            const int v = std::atoi(env);
+            if (v == 1 || v == 2 || v == 4 || v == 8) G->fp_rg = v;
+        }
+    }
+
     // Testing aid: LEAP_FORCE_GENERAL=1 keeps every call on the general kernels.
     if (const char *env = std::getenv("LEAP_FORCE_GENERAL"))
-        if (env[0] == '1') G->bp_tiled = G->fp_columns = false;
+        if (env[0] == '1') G->bp_tiled = G->fp_columns = G->sd_columns = false;
 
     hipError_t e = hipGetDevice(&G->device);
     if (e == hipSuccess) e = hipMalloc((void **)&G->d_views, sizeof(SfView) * (size_t)d->nviews);
     if (e == hipSuccess) e = hipMemcpy(G->d_views, G->views.data(), sizeof(SfView) * (size_t)d->nviews, hipMemcpyHostToDevice);
-    if (e == hipSuccess && G->fp_columns) {
+    if (e == hipSuccess && (G->fp_columns || G->sd_columns)) {
         G->nzp = d->nz + 2 * FP_PAD;
-        const size_t bytes = sizeof(float) * (size_t)d->nx * d->ny * G->nzp;
+        // one more column than the volume has: it stays zero and stands for cells outside the volume (Siddon kernel)
+        const size_t bytes = sizeof(float) * ((size_t)d->nx * d->ny + 1) * G->nzp;
         hipError_t es = hipMalloc((void **)&G->d_volz, bytes);
         if (es == hipSuccess) es = hipMemset(G->d_volz, 0, bytes);       // the pads stay zero for the handle's life
         if (es == hipSuccess) es = hipDeviceSynchronize();
         if (es != hipSuccess) {                                           // no room for the copy: use the general kernel
             if (G->d_volz) (void)hipFree(G->d_volz);
             G->d_volz = nullptr;
-            G->fp_columns = false;
+            G->fp_columns = G->sd_columns = false;
             (void)hipGetLastError();
         }
     }
@@ -352,8 +373,8 @@ extern "C" int leap_geometry_describe(const leap_geometry *G, char *buf, int32_t
 {
     if (!G || !buf || cap <= 0) return invalid("null handle or buffer");
     if (G->g.model == SF_MODEL_SIDDON) {
-        std::snprintf(buf, (size_t)cap, "type=%d model=siddon A=general AT=general axial-slope<=%.3f", G->g.type,
-                      G->sd_max_axial_slope);
+        std::snprintf(buf, (size_t)cap, "type=%d model=siddon A=%s(rg=%d) AT=general axial-slope<=%.3f", G->g.type,
+                      G->sd_columns ? "columns" : "general", G->fp_rg, G->sd_max_axial_slope);
         return LEAP_OK;
     }
     std::snprintf(buf, (size_t)cap,

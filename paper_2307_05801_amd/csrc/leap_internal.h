@@ -36,6 +36,7 @@ struct leap_geometry {
     std::vector<SdRayCol> raycols;
     SdRayCol *d_raycols = nullptr;
     double sd_max_axial_slope = 0;      // largest |dZ/dX| of any ray: voxels of z crossed per slab
+    bool sd_columns = false;            // wave-per-column forward kernel (needs the scratch copy and slope <= 1)
 };
 
 void leap_set_error(const std::string &msg);

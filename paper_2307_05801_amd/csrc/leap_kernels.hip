@@ -5,6 +5,7 @@
 #include "sf_general.h"
 #include "sf_backproject_tiled.h"
 #include "sf_project_columns.h"
+#include "sd_project_columns.h"
 
 // ------------------------------------------------------------------------------------------------
 // General kernels: plain loop nests over global memory, valid for every validated geometry.
@@ -74,9 +75,37 @@ __global__ __launch_bounds__(256) void sd_backproject_general(SfGeom g, const Sf
 
 static inline unsigned cdiv(unsigned a, unsigned b) { return (a + b - 1) / b; }
 
+constexpr int SD_WAVES = 4;   // adjacent detector columns per workgroup of the Siddon forward kernel
+
+template <int RG>
+static void launch_sd_columns(const leap_geometry *G, float *d_sino, hipStream_t stream)
+{
+    const SfGeom &g = G->g;
+    const int col_tiles = (int)cdiv(g.ncols, SD_WAVES), bands = (int)cdiv(g.nrows, RG * 64);
+    const int vb = G->fp_vb, tb = G->fp_tb;
+    const int views_pad = (int)cdiv(g.nviews, vb) * vb;
+    const int tiles_per_xcd_pad = (int)cdiv(cdiv(col_tiles, 8), tb) * tb;
+    const unsigned zero_col = (unsigned)g.nx * (unsigned)g.ny * (unsigned)G->nzp;
+    dim3 grid((unsigned)(8 * tiles_per_xcd_pad * views_pad * bands), 1, 1);
+    hipLaunchKernelGGL((sd_project_columns<RG, SD_WAVES>), grid, dim3(SD_WAVES * 64, 1, 1), 0, stream, g, G->d_raycols,
+                       G->d_volz, d_sino, G->nzp, zero_col, col_tiles, bands, vb, tb, views_pad, tiles_per_xcd_pad);
+}
+
 static int launch_sd_project(const leap_geometry *G, const float *d_vol, float *d_sino, hipStream_t stream)
 {
     const SfGeom &g = G->g;
+    if (G->sd_columns) {
+        dim3 tgrid(cdiv(g.nx, 32), cdiv(g.nz, 32), g.ny);
+        hipLaunchKernelGGL(sf_volume_to_columns, tgrid, dim3(32, 8, 1), 0, stream, d_vol, G->d_volz, g.nx, g.ny, g.nz, G->nzp);
+        switch (G->fp_rg) {
+        case 1: launch_sd_columns<1>(G, d_sino, stream); break;
+        case 2: launch_sd_columns<2>(G, d_sino, stream); break;
+        case 4: launch_sd_columns<4>(G, d_sino, stream); break;
+        default: launch_sd_columns<8>(G, d_sino, stream); break;
+        }
+        LEAP_HIP_CHECK(hipGetLastError());
+        return LEAP_OK;
+    }
     dim3 grid(cdiv(g.ncols, 64), cdiv(g.nrows, 4), g.nviews);
     if (grid.y > 65535u) {
         leap_set_error("detector has too many rows for one launch");

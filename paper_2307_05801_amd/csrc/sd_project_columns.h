@@ -1,0 +1,133 @@
+// Forward projection (A) of the Siddon model: ray-driven gather, one wavefront per detector column.
+//
+// Uses the z-fastest padded copy of the volume that the footprint kernel uses (sf_project_columns.h), plus one
+// all-zero column at its end that stands in for every in-plane cell outside the volume.
+//
+// Work split.  One 64-lane wavefront owns one detector column of one view and a band of RG * 64 detector rows: lane l
+// owns rows band0 + 64 g + l, g < RG.  All those rays share their in-plane line, so which voxel columns they cross in
+// a slab, and where inside the slab they change from one to the next, is wave-uniform: 64 slabs at a time, lane n
+// works that out for slab n, and the wave then walks the slabs, broadcasting the few numbers through v_readlane.
+// What differs between the lanes is the axial position: each lane follows its own Z through the slab and splits the
+// slab's piece(s) between the two axial cells it can touch (the kernel is only chosen when no ray crosses more than
+// one z-face per slab).  A workgroup is SD_WAVES adjacent columns of one view, which share voxel columns in L1.
+#pragma once
+
+#include "sd_ray.h"
+#include "sf_project_columns.h"
+
+#if defined(__HIPCC__) && !defined(SF_NO_KERNELS)
+
+template <int RG, int SD_WAVES>
+__global__ __launch_bounds__(SD_WAVES * 64) void sd_project_columns(SfGeom g, const SdRayCol *__restrict__ rays,
+                                                                    const float *__restrict__ volz, float *__restrict__ sino,
+                                                                    int nzp, unsigned zero_col, int col_tiles, int bands,
+                                                                    int vb, int tb, int views_pad, int tiles_per_xcd_pad)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // Block -> (view, band, column tile), in the XCD-aware order of the footprint kernel: index = 8 s + xcd, and
+    // within an XCD's sequence s the view runs fastest inside a block of VB views, then TB tiles, then blocks of views.
+    int ct, band, a;
+    {
+        const int xcd = blockIdx.x & 7, sq = blockIdx.x >> 3;
+        const int per_chunk = tb * views_pad;
+        const int chunk = sq / per_chunk, r = sq - chunk * per_chunk;
+        const int vblk = r / (tb * vb), r2 = r - vblk * (tb * vb);
+        const int tloc = r2 / vb, v_in = r2 - tloc * vb;
+        const int tchunks = tiles_per_xcd_pad / tb;
+        band = chunk / tchunks;
+        ct = ((chunk - band * tchunks) * tb + tloc) * 8 + xcd;
+        a = vblk * vb + v_in;
+        if (ct >= col_tiles || a >= g.nviews || band >= bands) return;   // padding blocks (no barrier follows)
+    }
+    const int c = ct * SD_WAVES + wave;
+    if (c >= g.ncols) return;
+    const int band0 = band * (RG * 64);
+
+    const SdRayCol R = rays[(size_t)a * g.ncols + c];
+    const int n_major = R.xmajor ? g.nx : g.ny;
+    const int n_minor = R.xmajor ? g.ny : g.nx;
+    const int kmax = nzp - 2;
+
+    // per lane and row group: the row's v, the constant of its lower-Z map, 1/|dZ per slab|, and the sign of dZ
+    double vr[RG], zadj[RG];
+    float inv_amz[RG], acc[RG];
+    bool inc[RG];
+#pragma unroll
+    for (int gq = 0; gq < RG; ++gq) {
+        vr[gq] = sd_row_v(g, band0 + 64 * gq + lane);
+        const double mz = vr[gq] * R.dh;
+        zadj[gq] = g.zk0d + (double)FP_PAD + fmin(mz, 0.0);     // Z of the lower end of the slab's piece, plus the pad
+        const float amz = fabsf((float)mz);
+        inv_amz[gq] = amz > 1e-30f ? 1.0f / amz : 1e30f;
+        inc[gq] = mz >= 0.0;
+        acc[gq] = 0.0f;
+    }
+
+    for (int nb = 0; nb < n_major; nb += 64) {
+        // ---- lane-parallel: the in-plane part of slab nb + lane
+        const int n = nb + lane;
+        const SdSplit s = sd_slab_split(R, n);
+        const bool in_n = n < n_major;
+        const bool a_ok = in_n && s.qa >= 0 && s.qa < n_minor;
+        const bool b_ok = in_n && s.qa != s.qb && s.qb >= 0 && s.qb < n_minor;
+        const unsigned base_a = a_ok ? (unsigned)(R.xmajor ? s.qa * g.nx + n : n * g.nx + s.qa) * (unsigned)nzp : zero_col;
+        const unsigned base_b = b_ok ? (unsigned)(R.xmajor ? s.qb * g.nx + n : n * g.nx + s.qb) * (unsigned)nzp : zero_col;
+        const double h = fma((double)n, R.dh, R.h0);
+        const int h_lo = __double2loint(h), h_hi = __double2hiint(h);
+        const float f = s.f, omf = 1.0f - s.f;
+        const unsigned long long cross = __ballot(in_n && s.qa != s.qb);
+        const int count = n_major - nb < 64 ? n_major - nb : 64;
+
+        // ---- wave-uniform walk over the slabs
+        for (int e = 0; e < count; ++e) {
+            const double s_h = __hiloint2double(__builtin_amdgcn_readlane(h_hi, e), __builtin_amdgcn_readlane(h_lo, e));
+            const float s_f = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, f), e));
+            const char *__restrict__ col_a =
+                reinterpret_cast<const char *>(volz + (unsigned)__builtin_amdgcn_readlane((int)base_a, e));
+            if ((cross >> e) & 1ull) {
+                const float s_omf = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, omf), e));
+                const char *__restrict__ col_b =
+                    reinterpret_cast<const char *>(volz + (unsigned)__builtin_amdgcn_readlane((int)base_b, e));
+#pragma unroll
+                for (int gq = 0; gq < RG; ++gq) {
+                    const double zlo = fma(vr[gq], s_h, zadj[gq]);
+                    const float fr = (float)__builtin_amdgcn_fract(zlo);
+                    int kf = (int)zlo;
+                    asm("v_med3_i32 %0, %1, 0, %2" : "=v"(kf) : "v"(kf), "s"(kmax));
+                    const float *__restrict__ xa = reinterpret_cast<const float *>(col_a + ((unsigned)kf << 2));
+                    const float *__restrict__ xb = reinterpret_cast<const float *>(col_b + ((unsigned)kf << 2));
+                    const float tlow = fminf((1.0f - fr) * inv_amz[gq], 1.0f);   // share of the slab spent in the lower cell
+                    // rising rays are in the lower cell first (while still in in-plane cell a), falling rays last
+                    const float p = fminf(inc[gq] ? s_f : s_omf, tlow), q = tlow - p;
+                    const float a_low = inc[gq] ? p : q, b_low = inc[gq] ? q : p;
+                    float t = acc[gq];
+                    t = fmaf(a_low, xa[0], t);
+                    t = fmaf(s_f - a_low, xa[1], t);
+                    t = fmaf(b_low, xb[0], t);
+                    acc[gq] = fmaf(s_omf - b_low, xb[1], t);
+                }
+            } else {
+#pragma unroll
+                for (int gq = 0; gq < RG; ++gq) {
+                    const double zlo = fma(vr[gq], s_h, zadj[gq]);
+                    const float fr = (float)__builtin_amdgcn_fract(zlo);
+                    int kf = (int)zlo;
+                    asm("v_med3_i32 %0, %1, 0, %2" : "=v"(kf) : "v"(kf), "s"(kmax));
+                    const float *__restrict__ xa = reinterpret_cast<const float *>(col_a + ((unsigned)kf << 2));
+                    const float tlow = fminf((1.0f - fr) * inv_amz[gq], 1.0f);
+                    acc[gq] = fmaf(tlow, xa[0], fmaf(1.0f - tlow, xa[1], acc[gq]));
+                }
+            }
+        }
+    }
+
+    float *__restrict__ ya = sino + (size_t)a * g.nrows * g.ncols + c;
+#pragma unroll
+    for (int gq = 0; gq < RG; ++gq) {
+        const int r = band0 + 64 * gq + lane;
+        if (r < g.nrows) ya[(size_t)r * g.ncols] = sd_ray_length(R, vr[gq]) * acc[gq];
+    }
+}
+
+#endif

@@ -34,6 +34,8 @@ def host():
     lib.host_check_backproject_windows.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
     lib.host_project_columns.restype = C.c_long
     lib.host_project_columns.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.host_sd_project_columns.restype = C.c_long
+    lib.host_sd_project_columns.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     return lib
 
 
@@ -83,7 +85,7 @@ SIDDON_CASES["steep_thin_slices"] = (3, lambda: CTConfig(
     voxel_xy=1.0, voxel_z=0.21, sod=40.0, sdd=62.0, shift_u=0.3, shift_v=-0.4, center_x=0.7, center_z=-0.3,
     start_deg=3.0))
 SIDDON_CASES["parallel_3d"] = (3, lambda: CTConfig(
-    "par3", PARALLEL, nviews=13, arc_deg=180.0, nrows=26, ncols=50, pixel_v=0.9, pixel_u=0.8, nx=40, ny=36, nz=21,
+    "par3", PARALLEL, nviews=13, arc_deg=180.0, nrows=40, ncols=50, pixel_v=0.9, pixel_u=0.8, nx=40, ny=36, nz=21,
     voxel_xy=1.0, voxel_z=1.1, sod=0.0, sdd=0.0, shift_u=0.3, shift_v=-0.4, center_y=0.7, center_z=-0.3,
     start_deg=1.0))
 
@@ -102,8 +104,16 @@ def test_siddon_kernel_bodies_match_oracle_on_cpu(host, oracle_mod, name):
     aty = np.zeros(cfg.vol_shape, np.float32)
     B.leap_project(h, x.ctypes.data, ax.ctypes.data, 1, 0, host)
     B.leap_backproject(h, y.ctypes.data, aty.ctypes.data, 1, 0, host)
+    fast = np.zeros(cfg.sino_shape, np.float32)
+    bad = host.host_sd_project_columns(h, x.ctypes.data, fast.ctypes.data)
+    desc = B.leap_geometry_describe(h, host)
     B.leap_geometry_destroy(h, host)
     sd = oracle_mod.siddon
+    assert ("A=columns" in desc) == (bad >= 0)
+    assert ("A=columns" in desc) == (name not in ("c1", "fan", "steep_thin_slices")), desc
+    if bad >= 0:
+        assert bad == 0, desc
+        assert rel_l2(fast, sd.project(cfg, x)) <= TOL, desc
     assert rel_l2(ax, sd.project(cfg, x)) <= TOL
     assert rel_l2(aty, sd.backproject(cfg, y)) <= TOL
     lhs, rhs = float((ax.astype(np.float64) * y).sum()), float((aty.astype(np.float64) * x).sum())
