@@ -11,6 +11,7 @@
 #define SF_NO_KERNELS   // this file needs the kernels' host-side limit functions only
 #include "sf_backproject_tiled.h"
 #include "sf_project_columns.h"
+#include "sd_backproject_tiled.h"
 
 static thread_local std::string g_last_error;
 
@@ -323,6 +324,42 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         }
     }
 
+    // Siddon model, tiled back projection: same slope limit, at most 4 pixel centres inside a voxel's footprint, and
+    // the staged window of every (view, tile, z-chunk) must fit the instance (checked with the kernel's own function).
+    if (d->model == LEAP_MODEL_SIDDON && d->type != LEAP_FAN && d->nz >= 8 && G->sd_max_axial_slope <= 0.999 &&
+        std::isfinite(G->max_cols_per_voxel) && G->max_cols_per_voxel < 3.9) {
+        G->bp_nc = (int)std::floor(G->max_cols_per_voxel + 0.01) + 1;
+        if (G->bp_nc < 2) G->bp_nc = 2;
+        const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T;
+        const float hx = 0.5f * (float)BP_T * g.T;
+        int first_shape = 1;                          // the 64-voxel shape does not fit: the sums live in LDS
+        if (const char *env = std::getenv("LEAP_BP_SHAPE")) {
+            first_shape = std::atoi(env) % BP_NSHAPES;
+            if (first_shape < 1) first_shape = 1;
+        }
+        for (int sh = first_shape; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
+            const int zc = BP_SHAPES[sh].zc;
+            const int chunks = (d->nz + zc - 1) / zc;
+            int need_w = 0, need_h = 0;
+            for (int a = 0; a < d->nviews; ++a)
+                for (int ty = 0; ty < tiles_y; ++ty)
+                    for (int tx = 0; tx < tiles_x; ++tx) {
+                        const float xc = (float)(g.x0d + ((double)(tx * BP_T) + 0.5 * (BP_T - 1)) * g.Td);
+                        const float yc = (float)(g.y0d + ((double)(ty * BP_T) + 0.5 * (BP_T - 1)) * g.Td);
+                        for (int ch = 0; ch < chunks; ch += (chunks > 1 ? chunks - 1 : 1)) {
+                            const float z0 = (float)(g.zlo0d + (double)(ch * zc) * g.Tzd), z1 = z0 + (float)zc * g.Tz;
+                            const SfWindow w = sd_bp_window(g, G->views[a], xc, yc, hx, z0, z1);
+                            need_w = w.need_w > need_w ? w.need_w : need_w;
+                            need_h = w.need_h > need_h ? w.need_h : need_h;
+                        }
+                    }
+            G->bp_need_w = need_w;
+            G->bp_need_h = need_h;
+            G->bp_shape = sh;
+            G->bp_tiled = need_w <= BP_SHAPES[sh].pw - 1 && need_h <= BP_SHAPES[sh].ph - 1;
+        }
+    }
+
     // Testing aid: LEAP_FORCE_GENERAL=1 keeps every call on the general kernels.
     if (const char *env = std::getenv("LEAP_FORCE_GENERAL"))
         if (env[0] == '1') G->bp_tiled = G->fp_columns = G->sd_columns = false;
@@ -373,8 +410,10 @@ extern "C" int leap_geometry_describe(const leap_geometry *G, char *buf, int32_t
 {
     if (!G || !buf || cap <= 0) return invalid("null handle or buffer");
     if (G->g.model == SF_MODEL_SIDDON) {
-        std::snprintf(buf, (size_t)cap, "type=%d model=siddon A=%s(rg=%d) AT=general axial-slope<=%.3f", G->g.type,
-                      G->sd_columns ? "columns" : "general", G->fp_rg, G->sd_max_axial_slope);
+        std::snprintf(buf, (size_t)cap, "type=%d model=siddon A=%s(rg=%d) AT=%s(nc=%d,zc=%d,window=%dx%d) axial-slope<=%.3f "
+                      "cols/voxel<=%.2f", G->g.type, G->sd_columns ? "columns" : "general", G->fp_rg,
+                      G->bp_tiled ? "tiled" : "general", G->bp_nc, BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h,
+                      G->sd_max_axial_slope, G->max_cols_per_voxel);
         return LEAP_OK;
     }
     std::snprintf(buf, (size_t)cap,

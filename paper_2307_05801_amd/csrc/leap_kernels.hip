@@ -6,6 +6,7 @@
 #include "sf_backproject_tiled.h"
 #include "sf_project_columns.h"
 #include "sd_project_columns.h"
+#include "sd_backproject_tiled.h"
 
 // ------------------------------------------------------------------------------------------------
 // General kernels: plain loop nests over global memory, valid for every validated geometry.
@@ -116,9 +117,47 @@ static int launch_sd_project(const leap_geometry *G, const float *d_vol, float *
     return LEAP_OK;
 }
 
+template <int NCS, int SH>
+static void launch_sd_tiled(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
+{
+    constexpr SfBpShape S = BP_SHAPES[SH];
+    const SfGeom &g = G->g;
+    const unsigned tiles_x = cdiv(g.nx, BP_T), tiles_y = cdiv(g.ny, BP_T);
+    dim3 grid(tiles_x * tiles_y, cdiv(g.nz, S.zc), 1);
+    hipLaunchKernelGGL((sd_backproject_tiled<NCS, S.zc, S.pw, S.ph>), grid, dim3(256, 1, 1), 0, stream, g, G->d_views,
+                       G->d_raycols, d_sino, d_vol, (int)tiles_x);
+}
+
+template <int NCS>
+static bool launch_sd_shape(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
+{
+    switch (G->bp_shape) {
+    case 1: launch_sd_tiled<NCS, 1>(G, d_sino, d_vol, stream); return true;
+    case 2: launch_sd_tiled<NCS, 2>(G, d_sino, d_vol, stream); return true;
+    case 3: launch_sd_tiled<NCS, 3>(G, d_sino, d_vol, stream); return true;
+    case 4: launch_sd_tiled<NCS, 4>(G, d_sino, d_vol, stream); return true;
+    default: return false;
+    }
+}
+
 static int launch_sd_backproject(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
 {
     const SfGeom &g = G->g;
+    if (G->bp_tiled) {
+        bool ok = false;
+        switch (G->bp_nc) {
+        case 2: ok = launch_sd_shape<2>(G, d_sino, d_vol, stream); break;
+        case 3: ok = launch_sd_shape<3>(G, d_sino, d_vol, stream); break;
+        case 4: ok = launch_sd_shape<4>(G, d_sino, d_vol, stream); break;
+        default: break;
+        }
+        if (!ok) {
+            leap_set_error("internal: no tiled Siddon back-projection instance for this geometry");
+            return LEAP_UNSUPPORTED;
+        }
+        LEAP_HIP_CHECK(hipGetLastError());
+        return LEAP_OK;
+    }
     dim3 grid(cdiv(g.nx, 64), cdiv(g.ny, 4), g.nz);
     if (grid.y > 65535u || grid.z > 65535u) {
         leap_set_error("volume has too many voxels along y or z for one launch");

@@ -155,3 +155,84 @@ def test_batch_autograd_and_overwrite(torch_mod, oracle_mod):
     torch.cuda.synchronize()
     assert torch.equal(out, ax.detach())
     P.geometry.close()
+
+
+def test_general_kernels_agree_with_fast_kernels(torch_mod, oracle_mod, monkeypatch):
+    """The same geometry through the column-wise / tiled kernels and through the general kernels."""
+    from paper_2307_05801_amd import Geometry
+    torch = torch_mod
+    cfg = off_face(reduced(config(3), 4, nviews=10)).replace(center_x=2.5, shift_v=0.4)
+    x = torch.from_numpy(standard_volume(3, cfg)).cuda()
+    y = torch.from_numpy(uniform_sinogram(cfg, 8)[0]).cuda()
+    print("[gpu] siddon fast vs general", flush=True)
+    fast = Geometry(cfg, model="siddon")
+    assert "A=columns" in fast.describe() and "AT=tiled" in fast.describe(), fast.describe()
+    ax_f, aty_f = fast.project(x), fast.backproject(y)
+    fast.close()
+    monkeypatch.setenv("LEAP_FORCE_GENERAL", "1")
+    gen = Geometry(cfg, model="siddon")
+    assert "A=general" in gen.describe() and "AT=general" in gen.describe(), gen.describe()
+    ax_g, aty_g = gen.project(x), gen.backproject(y)
+    torch.cuda.synchronize()
+    gen.close()
+    assert rel_l2(ax_f.cpu().numpy(), ax_g.cpu().numpy()) <= 2e-6
+    assert rel_l2(aty_f.cpu().numpy(), aty_g.cpu().numpy()) <= 2e-6
+    assert rel_l2(ax_f.cpu().numpy(), oracle_mod.siddon.project(cfg, x.cpu().numpy())) <= TOL
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_geometries(torch_mod, oracle_mod, seed):
+    from random_geometries import random_config
+    cfg = random_config(seed)
+    cfg = cfg.replace(shift_u=cfg.shift_u + 0.0617)
+    sd = oracle_mod.siddon
+    x = uniform_volume(cfg, 100 + seed)[0]
+    y = uniform_sinogram(cfg, 200 + seed)[0]
+    ax, aty = run_pair(torch_mod, cfg, x, y)
+    e_a, e_t = rel_l2(ax, sd.project(cfg, x)), rel_l2(aty, sd.backproject(cfg, y))
+    print(f"seed {seed}: A {e_a:.2e}  A^T {e_t:.2e}")
+    assert e_a <= TOL and e_t <= TOL
+
+
+@pytest.fixture(scope="module")
+def c3_siddon(oracle_mod):
+    import torch
+    from paper_2307_05801_amd import Geometry
+    cfg = config(3)
+    print("[gpu] siddon full-size C3: inputs", flush=True)
+    x = standard_volume(3, cfg)
+    noise = np.random.default_rng([1003, 2]).random(cfg.sino_shape, dtype=np.float32)
+    geo = Geometry(cfg, model="siddon")
+    desc = geo.describe()
+    print("[gpu] siddon full-size C3: " + desc, flush=True)
+    ax = geo.project(torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    print("[gpu] siddon full-size C3: backproject", flush=True)
+    atn = geo.backproject(torch.from_numpy(noise).cuda())
+    torch.cuda.synchronize()
+    out = dict(cfg=cfg, x=x, noise=noise, ax=ax.cpu().numpy(), atn=atn.cpu().numpy(), describe=desc)
+    geo.close()
+    return out
+
+
+def test_c3_full_size_samples_match_oracle(c3_siddon, oracle_mod):
+    """512^3 cone-beam, 720 views, in the launch configuration the benchmark times: two whole views, random rays and
+    random voxels recomputed one by one by the oracle; adjoint identity over the full arrays."""
+    run, sd = c3_siddon, oracle_mod.siddon
+    cfg = run["cfg"]
+    assert "A=columns" in run["describe"] and "AT=tiled" in run["describe"], run["describe"]
+    views = [89, 404]
+    ref = sd.project(cfg.with_views(views), run["x"])
+    for n, a in enumerate(views):
+        assert rel_l2(run["ax"][a], ref[n]) <= TOL
+    rng = np.random.default_rng(46)
+    rays = rng.integers(0, cfg.nviews * cfg.nrows * cfg.ncols, 600)
+    assert rel_l2(run["ax"].ravel()[rays], sd.project_rays(cfg, run["x"], rays)) <= TOL
+    n = cfg.nx * cfg.ny * cfg.nz
+    vox = np.unique(np.concatenate([rng.integers(0, n, 8000), np.array([0, cfg.nx - 1, n - 1, n - cfg.nx, n // 2 + 255])]))
+    got, want = run["atn"].ravel()[vox], sd.backproject_voxels(cfg, run["noise"], vox)
+    assert rel_l2(got, want) <= TOL
+    assert np.abs(got - want).max() <= 5e-5 * np.abs(want).max()
+    lhs = float((run["ax"].astype(np.float64) * run["noise"]).sum())
+    rhs = float((run["atn"].astype(np.float64) * run["x"]).sum())
+    assert abs(lhs - rhs) <= TOL * abs(lhs)
