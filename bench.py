@@ -29,6 +29,8 @@ PEAK_HBM_GBPS = 8000.0
 MEASURED_TRAFFIC_BYTES = {
     ("c3_cone_512", "A"): 1.34725e8 * 2048 + 737280 * 1024,
     ("c3_cone_512", "AT"): 8.30858e6 * 2048 + 524288 * 1024,
+    ("c3_cone_512:siddon", "A"): 1.06982e8 * 2048 + 2.88743e6 * 1024,
+    ("c3_cone_512:siddon", "AT"): 3.59896e7 * 2048 + 524288 * 1024,
 }
 
 
@@ -37,6 +39,18 @@ def algorithmic_flops_per_update(n_u: float, n_v: float, nz: int) -> float:
     column) for knots and magnification, 15 per transaxial weight, 5 per axial weight, 3 per nonzero
     (ray, voxel) pair (two multiplies to combine, one add to accumulate)."""
     return 40.0 / nz + 15.0 * n_u / nz + 5.0 * n_v + 3.0 * n_u * n_v
+
+
+def siddon_flops_per_update(cfg) -> tuple:
+    """Cheapest known evaluation of the Siddon weights, per voxel-view pair.  Per (ray, slab): 10 flops for the two
+    positions at the slab's exit face, the in-plane and the axial crossing parameter; per nonzero (ray, voxel) pair 3
+    (difference of two parameters, multiply, accumulate).  A ray meets 1 + |m| + |m_z| voxels per slab (|m| averages
+    2 ln(2)/pi... taken as 0.44 over a full turn, |m_z| as a quarter of the cone's half angle slope), and there are
+    nrows*ncols rays per view against ny*nz voxel columns per slab.  Returns (flops per update, nonzeros per update)."""
+    rays_per_column = (cfg.nrows * cfg.ncols) / float(cfg.ny * cfg.nz)
+    mz = 0.0 if cfg.geom != 2 else 0.25 * (0.5 * cfg.nrows * cfg.pixel_v / cfg.sdd) * cfg.voxel_xy / cfg.voxel_z
+    per_slab = 1.0 + 0.44 + mz
+    return rays_per_column * (10.0 + 3.0 * per_slab), rays_per_column * per_slab
 
 
 def footprint_counts(cfg) -> tuple:
@@ -51,9 +65,12 @@ def footprint_counts(cfg) -> tuple:
     return n_u, n_v
 
 
-def cpu_baseline(cfg, x, seconds_target: float):
+def cpu_baseline(cfg, x, seconds_target: float, model: str = "sf"):
     """Times the CPU oracle, as it stands, on a bounded sample of the same workload."""
     import oracle
+    if model == "siddon":
+        oracle = oracle.siddon
+        oracle.build()
     threads = oracle.num_threads()
     nview_sample = max(threads, 8)
     views = [int(v) for v in np.linspace(0, cfg.nviews, nview_sample, endpoint=False)]
@@ -91,6 +108,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=3, help="benchmark case number (3 = the headline 512^3 cone-beam)")
+    ap.add_argument("--model", choices=["sf", "siddon"], default="sf",
+                    help="projector model: sf = separable footprint (the headline), siddon = thin rays")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="CPU time budget of the oracle baseline; 0 skips it")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed region, run one device-to-device copy of the volume (a plain copy kernel of "
@@ -110,7 +129,7 @@ def main() -> int:
     cfg = config(args.config)
     batch = cfg.batch
     x_np = np.stack([standard_volume(args.config, cfg, item=b) for b in range(batch)])
-    geo = Geometry(cfg, device="cuda:0")
+    geo = Geometry(cfg, device="cuda:0", model=args.model)
     y = torch.empty((batch,) + cfg.sino_shape, dtype=torch.float32, device="cuda")
     y_meas = None
     if args.config == 4:
@@ -152,13 +171,18 @@ def main() -> int:
     updates = 2.0 * batch * cfg.voxel_views
     value = updates / (ms_step * 1e-3)
 
-    n_u, n_v = footprint_counts(cfg)
-    fl = algorithmic_flops_per_update(n_u, n_v, cfg.nz)
+    if args.model == "siddon":
+        fl, nnz_per_update = siddon_flops_per_update(cfg)
+    else:
+        n_u, n_v = footprint_counts(cfg)
+        fl = algorithmic_flops_per_update(n_u, n_v, cfg.nz)
+        nnz_per_update = n_u * n_v
     dom, dom_ms = ("leap_project (A)", ms_a) if ms_a >= ms_at else ("leap_backproject (A^T)", ms_at)
     flops_launch = fl * batch * cfg.voxel_views
     achieved = flops_launch / (dom_ms * 1e-3) / 1e12
     alg_bytes = 4.0 * batch * (cfg.nx * cfg.ny * cfg.nz + cfg.nviews * cfg.nrows * cfg.ncols)
-    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, "A" if ms_a >= ms_at else "AT"))
+    workload = cfg.name if args.model == "sf" else cfg.name + ":" + args.model
+    traffic = MEASURED_TRAFFIC_BYTES.get((workload, "A" if ms_a >= ms_at else "AT"))
     roofline = {
         "bound": "alu", "kernel": dom, "achieved": achieved, "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
         "frac": achieved / PEAK_FP32_TFLOPS, "traffic": traffic,
@@ -170,16 +194,17 @@ def main() -> int:
     }
     out = {
         "metric": "ray-voxel updates/s for A and A^T (voxel-view pairs, both operators per step)"
-                  + (" at 512^3 cone-beam" if args.config == 3 else f" on case {args.config}"),
+                  + (" at 512^3 cone-beam" if args.config == 3 else f" on case {args.config}")
+                  + ("" if args.model == "sf" else ", Siddon model"),
         "value": value, "unit": "voxel-view updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": cfg.name, "nviews": cfg.nviews, "volume": list(cfg.vol_shape),
+        "config": {"workload": workload, "model": args.model, "nviews": cfg.nviews, "volume": list(cfg.vol_shape),
                    "detector": [cfg.nrows, cfg.ncols], "batch": batch, "kernels": geo.describe()},
         "A_ms": ms_a, "AT_ms": ms_at,
         "A_updates_per_s": batch * cfg.voxel_views / (ms_a * 1e-3),
         "AT_updates_per_s": batch * cfg.voxel_views / (ms_at * 1e-3),
-        "nnz_per_update": n_u * n_v,
+        "nnz_per_update": nnz_per_update,
         "roofline": roofline,
     }
     if args.calibration_copy:
@@ -187,7 +212,7 @@ def main() -> int:
         torch.cuda.synchronize()
         out["calibration_copy_bytes"] = int(x.numel() * 4)
     if args.cpu_seconds > 0:
-        out["cpu_baseline"] = cpu_baseline(cfg, x_np[0], args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(cfg, x_np[0], args.cpu_seconds, args.model)
     print(json.dumps(out))
     geo.close()
     return 0
