@@ -28,6 +28,7 @@ static double project_u(const sfo_scan *s, double cphi, double sphi, double x, d
     double t = -x * sphi + y * cphi;
     if (s->geom == SFO_PARALLEL) return t;
     double l = x * cphi + y * sphi;
+    if (s->geom == SFO_CONE_CURVED) return s->sdd * atan2(t, s->sod - l);     /* arc length on the cylinder */
     return s->sdd * t / (s->sod - l);
 }
 
@@ -53,6 +54,7 @@ static void knots_xy(const sfo_scan *s, double phi, double x, double y, double t
     sort4(tau);
     if (mag) {
         if (s->geom == SFO_PARALLEL) *mag = 1.0;
+        else if (s->geom == SFO_CONE_CURVED) *mag = s->sdd / hypot(s->sod - (x * cphi + y * sphi), -x * sphi + y * cphi);
         else *mag = s->sdd / (s->sod - (x * cphi + y * sphi));
     }
 }
@@ -102,6 +104,11 @@ static double amplitude(const sfo_scan *s, double phi, int r, int c)
     double v = (s->geom == SFO_FAN) ? 0.0 : pix_v(s, r);
     double dx = -s->sdd * cphi - u * sphi;
     double dy = -s->sdd * sphi + u * cphi;
+    if (s->geom == SFO_CONE_CURVED) {            /* pixel at fan angle gamma = u / SDD on the cylinder */
+        double gam = u / s->sdd;
+        dx = s->sdd * (-cos(gam) * cphi - sin(gam) * sphi);
+        dy = s->sdd * (-cos(gam) * sphi + sin(gam) * cphi);
+    }
     double len = sqrt(dx * dx + dy * dy + v * v);
     return s->T * len / fmax(fabs(dx), fabs(dy));
 }

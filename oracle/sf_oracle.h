@@ -28,6 +28,13 @@
  *   weight  w(view,r,c; i,j,k) = amp * F_u * F_v      (mm)
  *   A       y[view][r][c] = sum_voxels w x[k][j][i];     A^T  x[k][j][i] = sum_rays w y[view][r][c]
  *
+ * Curved detector (SFO_CONE_CURVED; the paper's "axial cone-beam (planar or curved)"): the detector is the cylinder
+ * of radius SDD around the vertical line through the source; its columns are equally spaced in arc length, so pixel
+ * (r,c) sits at the fan angle gamma_c = u_c / SDD:  P = S + SDD (-cos gamma e_s + sin gamma e_u) + v_r e_v.  The same
+ * four steps apply with the detector coordinate of a point taken on the cylinder: u = SDD atan2(t, SOD-l) (arc
+ * length) in step 1, and the magnification in step 3 is SDD over the in-plane distance of the voxel centre from the
+ * source, SDD / hypot(SOD-l, t).  Step 4 uses D = P - S as before.
+ *
  * Footprints partly off the detector are truncated; rays that miss the volume give 0.
  * For parallel-beam w * pu * pv equals the volume of (pixel beam  intersect  voxel) exactly.
  *
@@ -44,7 +51,7 @@
 extern "C" {
 #endif
 
-enum { SFO_PARALLEL = 0, SFO_FAN = 1, SFO_CONE = 2 };
+enum { SFO_PARALLEL = 0, SFO_FAN = 1, SFO_CONE = 2, SFO_CONE_CURVED = 3 };
 
 typedef struct {
     int32_t geom;

@@ -33,6 +33,10 @@ static void ray_of(const sdo_scan *s, int view, int r, int c, ray_t *ray)
         if (s->geom == SDO_PARALLEL) {
             ray->o[a] = u * eu[a] + v * ez[a];
             ray->d[a] = es[a];
+        } else if (s->geom == SDO_CONE_CURVED) {
+            double gam = u / s->sdd;
+            ray->o[a] = s->sod * es[a];
+            ray->d[a] = s->sdd * (-cos(gam) * es[a] + sin(gam) * eu[a]) + v * ez[a];
         } else {
             ray->o[a] = s->sod * es[a];                                   /* source */
             ray->d[a] = -s->sdd * es[a] + u * eu[a] + v * ez[a];          /* pixel centre minus source */
@@ -181,7 +185,8 @@ static void pixel_range(double a, double b, double p, double off, int n, int *i0
 }
 
 /* Only rays whose pixel centre lies inside the bounding rectangle of the voxel's eight projected corners can meet
- * the voxel (a perspective or parallel image of a box is the hull of its projected corners). */
+ * the voxel (a perspective or parallel image of a box is the hull of its projected corners; on a cylindrical
+ * detector the rectangle is bounded separately, see below). */
 static double voxel_sum(const sdo_scan *s, int i, int j, int k, const float *sino)
 {
     double lo[3], hi[3], sum = 0.0;
@@ -194,6 +199,15 @@ static double voxel_sum(const sdo_scan *s, int i, int j, int k, const float *sin
             double t = -x * sphi + y * cphi, l = x * cphi + y * sphi;
             double mag = (s->geom == SDO_PARALLEL) ? 1.0 : s->sdd / (s->sod - l);
             double u = mag * t, v = mag * z;
+            if (s->geom == SDO_CONE_CURVED) {
+                /* on the cylinder: the fan angle is extreme at a corner; the height z SDD / (in-plane distance from
+                 * the source) is bounded with the distance of the voxel centre -+ half a diagonal */
+                double xc = 0.5 * (lo[0] + hi[0]), yc = 0.5 * (lo[1] + hi[1]);
+                double rc = hypot(s->sod - (xc * cphi + yc * sphi), -xc * sphi + yc * cphi), hd = s->T * 0.70710678118654757;
+                u = s->sdd * atan2(t, s->sod - l);
+                v = z * s->sdd / (z >= 0.0 ? rc - hd : rc + hd);
+                vmin = fmin(vmin, z * s->sdd / (z >= 0.0 ? rc + hd : rc - hd));
+            }
             umin = fmin(umin, u); umax = fmax(umax, u);
             vmin = fmin(vmin, v); vmax = fmax(vmax, v);
         }

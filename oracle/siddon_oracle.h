@@ -12,6 +12,8 @@
  *     parallel : { u_c e_u + v_r e_v + s e_s , s real }
  *     cone     : the line through the source S = SOD e_s and the pixel centre P = (SOD-SDD) e_s + u_c e_u + v_r e_v
  *     fan      : the cone formula with v = 0 in the plane z = center_z; the voxel is its in-plane square
+ *     curved   : cone-beam with a cylindrical detector of radius SDD around the source's vertical axis, columns equally
+ *                spaced in arc length: P = S + SDD (-cos g e_s + sin g e_u) + v_r e_v with g = u_c / SDD
  * (same world frame, voxel and pixel centres as the separable-footprint oracle, see sf_oracle.h).  A voxel is the
  * half-open box [lo, hi) on every axis, which only matters for a ray that runs exactly inside a face plane: it then
  * belongs to the voxel on the upper side.  A = sum over voxels, A^T = exact transpose.
@@ -28,7 +30,7 @@
 extern "C" {
 #endif
 
-enum { SDO_PARALLEL = 0, SDO_FAN = 1, SDO_CONE = 2 };
+enum { SDO_PARALLEL = 0, SDO_FAN = 1, SDO_CONE = 2, SDO_CONE_CURVED = 3 };
 
 typedef struct {
     int32_t geom;

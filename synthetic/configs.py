@@ -12,14 +12,14 @@ from typing import Optional
 
 import numpy as np
 
-PARALLEL, FAN, CONE = 0, 1, 2
-GEOM_NAMES = {PARALLEL: "parallel", FAN: "fan", CONE: "cone"}
+PARALLEL, FAN, CONE, CONE_CURVED = 0, 1, 2, 3
+GEOM_NAMES = {PARALLEL: "parallel", FAN: "fan", CONE: "cone", CONE_CURVED: "cone_curved"}
 
 
 @dataclasses.dataclass(frozen=True)
 class CTConfig:
     name: str
-    geom: int                 # PARALLEL / FAN / CONE (flat detector)
+    geom: int                 # PARALLEL / FAN / CONE (flat detector) / CONE_CURVED (cylindrical detector)
     nviews: int
     arc_deg: float            # views are a*arc/nviews, end point excluded
     nrows: int

@@ -26,7 +26,11 @@ def ray_endpoints(cfg, view, u, v):
     src = cfg.sod * es
     if cfg.geom == 1:
         v = 0.0 * v
-    pix = (cfg.sod - cfg.sdd) * es + u * eu + v * ev
+    if cfg.geom == 3:       # cylindrical detector of radius sdd around the source axis, u is arc length
+        gam = u / cfg.sdd
+        pix = src + cfg.sdd * (-np.cos(gam) * es + np.sin(gam) * eu) + v * ev
+    else:
+        pix = (cfg.sod - cfg.sdd) * es + u * eu + v * ev
     d = pix - src
     d = d / np.linalg.norm(d, axis=-1, keepdims=True)
     return np.broadcast_to(src, d.shape), d

@@ -79,8 +79,31 @@ SIDDON_MUTATIONS = [
      "sum += w * (double)sino[((int64_t)view * s->ncols + c) * s->nrows + r];"),
 ]
 
+CURVED_SF_MUTATIONS = [
+    ("curved detector: arc length replaced by the tangent",
+     "return s->sdd * atan2(t, s->sod - l);", "return s->sdd * t / (s->sod - l);"),
+    ("curved detector: axial magnification taken along the central ray",
+     "*mag = s->sdd / hypot(s->sod - (x * cphi + y * sphi), -x * sphi + y * cphi);",
+     "*mag = s->sdd / (s->sod - (x * cphi + y * sphi));"),
+    ("curved detector: amplitude of the flat detector's ray",
+     "double gam = u / s->sdd;", "double gam = atan(u / s->sdd);"),
+    ("curved detector: fan angle counted the other way in the amplitude",
+     "dy = s->sdd * (-cos(gam) * sphi + sin(gam) * cphi);", "dy = s->sdd * (-cos(gam) * sphi - sin(gam) * cphi);"),
+]
+CURVED_SIDDON_MUTATIONS = [
+    ("curved detector: pixels placed at flat-detector angles",
+     "double gam = u / s->sdd;", "double gam = atan(u / s->sdd);"),
+    ("curved detector: fan angle counted the other way",
+     "ray->d[a] = s->sdd * (-cos(gam) * es[a] + sin(gam) * eu[a]) + v * ez[a];",
+     "ray->d[a] = s->sdd * (-cos(gam) * es[a] - sin(gam) * eu[a]) + v * ez[a];"),
+    ("curved detector: voxel's pixel search uses flat-detector columns",
+     "u = s->sdd * atan2(t, s->sod - l);", "u = s->sdd * t / (s->sod - l);"),
+]
+
 CASES = ([("sf_oracle.c", "test_oracle_pins.py") + m for m in MUTATIONS]
-         + [("siddon_oracle.c", "test_siddon_pins.py") + m for m in SIDDON_MUTATIONS])
+         + [("siddon_oracle.c", "test_siddon_pins.py") + m for m in SIDDON_MUTATIONS]
+         + [("sf_oracle.c", "test_curved_pins.py") + m for m in CURVED_SF_MUTATIONS]
+         + [("siddon_oracle.c", "test_curved_pins.py") + m for m in CURVED_SIDDON_MUTATIONS])
 
 
 @pytest.mark.parametrize("source,pins,what,old,new", CASES, ids=[c[0][:-9] + ": " + c[2] for c in CASES])
