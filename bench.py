@@ -110,6 +110,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3, help="benchmark case number (3 = the headline 512^3 cone-beam)")
     ap.add_argument("--model", choices=["sf", "siddon"], default="sf",
                     help="projector model: sf = separable footprint (the headline), siddon = thin rays")
+    ap.add_argument("--detector", choices=["flat", "curved"], default="flat",
+                    help="cone-beam cases only: flat panel (the headline) or cylindrical detector of the same pixel pitch")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="CPU time budget of the oracle baseline; 0 skips it")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed region, run one device-to-device copy of the volume (a plain copy kernel of "
@@ -127,6 +129,11 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     cfg = config(args.config)
+    if args.detector == "curved":
+        if cfg.geom != 2:
+            print("bench.py: --detector curved needs a cone-beam case", file=sys.stderr)
+            return 2
+        cfg = cfg.replace(geom=3, name=cfg.name + "_curved")
     batch = cfg.batch
     x_np = np.stack([standard_volume(args.config, cfg, item=b) for b in range(batch)])
     geo = Geometry(cfg, device="cuda:0", model=args.model)

@@ -44,9 +44,11 @@
 extern "C" {
 #endif
 
-/* Scanner families ("CT Projection Models and Geometries"; fan-beam is the one-row,
- * one-slice case of the flat-panel cone-beam scanner). */
-enum { LEAP_PARALLEL = 0, LEAP_FAN = 1, LEAP_CONE = 2 };
+/* Scanner families ("CT Projection Models and Geometries": parallel-beam, axial cone-beam with a planar or a curved
+ * detector; fan-beam is the one-row, one-slice case of the flat-panel cone-beam scanner).  LEAP_CONE_CURVED: the
+ * detector is the cylinder of radius sdd around the vertical line through the source; columns are equally spaced in
+ * arc length (pixel_u mm), so pixel (r, c) sits at fan angle u_c / sdd and height v_r on the cylinder. */
+enum { LEAP_PARALLEL = 0, LEAP_FAN = 1, LEAP_CONE = 2, LEAP_CONE_CURVED = 3 };
 
 /* Projector models ("CT Projection Models and Geometries").  LEAP_MODEL_SF: separable footprints.
  * LEAP_MODEL_SIDDON: weight = length (mm) of the ray through the pixel centre inside the voxel; a voxel is
@@ -56,7 +58,7 @@ enum { LEAP_MODEL_SF = 0, LEAP_MODEL_SIDDON = 1 };
 enum {
     LEAP_OK = 0,
     LEAP_INVALID_ARG = -1,   /* null pointer, non-positive size or count, unknown type or model, FAN with nrows != 1 or nz != 1 */
-    LEAP_BAD_GEOMETRY = -2,  /* cone/fan: source not strictly outside the volume's bounding circle, or sdd <= 0 */
+    LEAP_BAD_GEOMETRY = -2,  /* cone/fan: source not strictly outside the volume's bounding circle, sdd <= 0, curved fan wider than +-1.5 rad */
     LEAP_HIP_ERROR = -3,     /* a HIP runtime call failed (the message is kept, see leap_last_error) */
     LEAP_UNSUPPORTED = -4    /* sizes beyond what the index arithmetic of the kernels covers */
 };
@@ -66,7 +68,7 @@ enum {
  * and source-to-object distance, horizontal/vertical detector shift, voxel counts, voxel sizes,
  * volume centre.  Host memory; copied by leap_geometry_create. */
 typedef struct {
-    int32_t type;                 /* LEAP_PARALLEL / LEAP_FAN / LEAP_CONE */
+    int32_t type;                 /* LEAP_PARALLEL / LEAP_FAN / LEAP_CONE / LEAP_CONE_CURVED */
     int32_t nviews, nrows, ncols; /* projections, detector rows (v), detector columns (u) */
     int32_t nx, ny, nz;           /* voxels */
     double  pixel_v, pixel_u;     /* mm: pixel height, pixel width */

@@ -12,7 +12,7 @@ from typing import Optional, Sequence
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("LEAP_LIB_PATH") or os.path.join(HERE, "libleap_hip.so")   # override: testing a variant build
 
-LEAP_PARALLEL, LEAP_FAN, LEAP_CONE = 0, 1, 2
+LEAP_PARALLEL, LEAP_FAN, LEAP_CONE, LEAP_CONE_CURVED = 0, 1, 2, 3
 LEAP_MODEL_SF, LEAP_MODEL_SIDDON = 0, 1
 MODELS = {"sf": LEAP_MODEL_SF, "siddon": LEAP_MODEL_SIDDON}
 LEAP_OK, LEAP_INVALID_ARG, LEAP_BAD_GEOMETRY, LEAP_HIP_ERROR, LEAP_UNSUPPORTED = 0, -1, -2, -3, -4

@@ -61,6 +61,10 @@ static void build_ray_table(leap_geometry *G)
             double ox, oy, dx, dy;
             if (d.type == LEAP_PARALLEL) {
                 ox = -u * s; oy = u * c; dx = c; dy = s;
+            } else if (d.type == LEAP_CONE_CURVED) {    // pixel at fan angle u / sdd on the cylinder
+                const double cg = std::cos(u / d.sdd), sg = std::sin(u / d.sdd);
+                ox = d.sod * c; oy = d.sod * s;
+                dx = -d.sdd * (cg * c + sg * s); dy = d.sdd * (sg * c - cg * s);
             } else {
                 ox = d.sod * c; oy = d.sod * s;
                 dx = -d.sdd * c - u * s; dy = -d.sdd * s + u * c;
@@ -75,7 +79,7 @@ static void build_ray_table(leap_geometry *G)
             const double inv_m = R.m != 0.0 ? 1.0 / R.m : 1e30;
             R.inv_m = (float)std::fmin(std::fmax(inv_m, -1e30), 1e30);
             R.lxy = (float)(T * std::sqrt(dx * dx + dy * dy) / std::fabs(dmaj));
-            if (d.type == LEAP_CONE) {
+            if (d.type == LEAP_CONE || d.type == LEAP_CONE_CURVED) {
                 R.h0 = (lomaj - omaj) / (dmaj * Tz);
                 R.dh = T / (dmaj * Tz);
                 R.vscale = (float)(T / std::fabs(dmaj));
@@ -96,7 +100,8 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
 {
     if (out) *out = nullptr;
     if (!d || !out) return invalid("null descriptor or output pointer");
-    if (d->type != LEAP_PARALLEL && d->type != LEAP_FAN && d->type != LEAP_CONE) return invalid("unknown geometry type");
+    if (d->type != LEAP_PARALLEL && d->type != LEAP_FAN && d->type != LEAP_CONE && d->type != LEAP_CONE_CURVED)
+        return invalid("unknown geometry type");
     if (d->model != LEAP_MODEL_SF && d->model != LEAP_MODEL_SIDDON) return invalid("unknown projector model");
     if (d->nviews <= 0 || d->nrows <= 0 || d->ncols <= 0) return invalid("nviews, nrows and ncols must be positive");
     if (d->nx <= 0 || d->ny <= 0 || d->nz <= 0) return invalid("nx, ny and nz must be positive");
@@ -134,6 +139,10 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         }
         if (!(d->pixel_u < 0.25 * d->sdd)) {
             leap_set_error("detector pixel wider than a quarter of sdd");
+            return LEAP_BAD_GEOMETRY;
+        }
+        if (d->type == LEAP_CONE_CURVED && !((0.5 * d->ncols + std::fabs(d->shift_u) + 1.0) * d->pixel_u < 1.5 * d->sdd)) {
+            leap_set_error("curved detector spans a fan of more than +-1.5 rad");
             return LEAP_BAD_GEOMETRY;
         }
     }
@@ -197,8 +206,8 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
             mag_max = d->sdd / std::fmax(d->sod - reach, 1e-9 * d->sod);
             mag_min = d->sdd / (d->sod + reach);
             const double umax = (0.5 * d->ncols + std::fabs(d->shift_u) + 2.0) * d->pixel_u;
-            const double gam = std::atan(umax / d->sdd);
-            stretch = 1.02 / std::cos(gam);
+            const double gam = d->type == LEAP_CONE_CURVED ? std::fmin(umax / d->sdd, 1.57) : std::atan(umax / d->sdd);
+            stretch = d->type == LEAP_CONE_CURVED ? 1.02 : 1.02 / std::cos(gam);     // no stretch on the cylinder
             slope = (gam < 0.78) ? std::tan(0.7853981633974483 + gam) : 1e30;
         }
         G->max_cols_per_voxel = mag_max * T * std::sqrt(2.0) / d->pixel_u * stretch;
@@ -252,16 +261,7 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
             const int v = std::atoi(env);
             if (v == 1 || v == 2 || v == 4) G->fp_cw = v;
         }
-        if (const char *env = std::getenv("LEAP_FP_WAVES")) {
-            const int v = std::atoi(env);
-            if (v == 4 || v == 8) G->fp_waves = v;
-        }
-        if (const char *env = std::getenv("LEAP_FP_WV")) {
-            const int v = std::atoi(env);
-            if (v == 1 || v == 2 || v == 4 || v == 8) G->fp_wv = v;
-        }
-        if (G->fp_waves == 8 && G->fp_cw == 4) G->fp_cw = 2;
-        if (G->fp_wv > G->fp_waves) G->fp_wv = G->fp_waves;
+        if (d->type == LEAP_CONE_CURVED) G->fp_cw = 2;      // the cylinder has one instance per shape
         // candidate slots per slab: widest range of voxel columns any bundle of cw detector columns can see
         auto slots_needed = [&](int cw) {
             int need = 0;
@@ -289,7 +289,7 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         if (G->fp_nk < 2) G->fp_nk = 2;
         const int groups = (d->nrows + 63) / 64;
         G->fp_rg = groups >= 8 ? 8 : (groups >= 4 ? 4 : (groups >= 2 ? 2 : 1));
-        G->fp_columns = need <= 16 && G->fp_nk <= 4;
+        G->fp_columns = need <= 16 && G->fp_nk <= 4 && (d->type != LEAP_CONE_CURVED || G->fp_cw == 2);
         if (const char *env = std::getenv("LEAP_FP_VB")) {
             const int v = std::atoi(env);
             if (v >= 1 && v <= 1024) G->fp_vb = v;

@@ -168,32 +168,33 @@ static int launch_sd_backproject(const leap_geometry *G, const float *d_sino, fl
     return LEAP_OK;
 }
 
-template <int NQ, int NK, int RG, int W, int CW, int WV>
+template <int NQ, int NK, int RG, int CW, int GT>
 static void launch_fp_columns(const leap_geometry *G, float *d_sino, hipStream_t stream)
 {
+    constexpr int W = 4;          // waves per workgroup (8 and 16 measured slower)
     const SfGeom &g = G->g;
-    const int col_tiles = (int)cdiv(g.ncols, (W / WV) * CW), bands = (int)cdiv(g.nrows, RG * 64);
-    // XCD-aware block order (see the kernel): pad view groups to blocks of vb and each XCD's tiles to chunks of tb
+    const int col_tiles = (int)cdiv(g.ncols, W * CW), bands = (int)cdiv(g.nrows, RG * 64);
+    // XCD-aware block order (see the kernel): pad views to blocks of vb and each XCD's tiles to chunks of tb
     const int vb = G->fp_vb, tb = G->fp_tb;
-    const int vgroups_pad = (int)cdiv(cdiv(g.nviews, WV), vb) * vb;
+    const int vgroups_pad = (int)cdiv(g.nviews, vb) * vb;
     const int tiles_per_xcd_pad = (int)cdiv(cdiv(col_tiles, 8), tb) * tb;
     dim3 grid((unsigned)(8 * tiles_per_xcd_pad * vgroups_pad * bands), 1, 1);
-    hipLaunchKernelGGL((sf_project_columns<NQ, NK, RG, W, CW, WV>), grid, dim3(W * 64, 1, 1), 0, stream, g, G->d_views,
+    hipLaunchKernelGGL((sf_project_columns<NQ, NK, RG, W, CW, 1, GT>), grid, dim3(W * 64, 1, 1), 0, stream, g, G->d_views,
                        G->d_volz, d_sino, G->nzp, col_tiles, bands, vb, tb, vgroups_pad, tiles_per_xcd_pad);
 }
 
 template <int NQ, int NK, int RG>
 static bool launch_fp_w(const leap_geometry *G, float *d_sino, hipStream_t stream)
 {
-    switch (G->fp_waves * 100 + G->fp_cw * 10 + G->fp_wv) {
-    case 411: launch_fp_columns<NQ, NK, RG, 4, 1, 1>(G, d_sino, stream); return true;
-    case 421: launch_fp_columns<NQ, NK, RG, 4, 2, 1>(G, d_sino, stream); return true;
-    case 422: launch_fp_columns<NQ, NK, RG, 4, 2, 2>(G, d_sino, stream); return true;
-    case 424: launch_fp_columns<NQ, NK, RG, 4, 2, 4>(G, d_sino, stream); return true;
-    case 441: launch_fp_columns<NQ, NK, RG, 4, 4, 1>(G, d_sino, stream); return true;
-    case 444: launch_fp_columns<NQ, NK, RG, 4, 4, 4>(G, d_sino, stream); return true;
-    case 824: launch_fp_columns<NQ, NK, RG, 8, 2, 4>(G, d_sino, stream); return true;
-    case 828: launch_fp_columns<NQ, NK, RG, 8, 2, 8>(G, d_sino, stream); return true;
+    if (G->g.type == SF_CONE_CURVED) {          // cylinder: the default bundle width only
+        if (G->fp_cw != 2) return false;
+        launch_fp_columns<NQ, NK, RG, 2, 1>(G, d_sino, stream);
+        return true;
+    }
+    switch (G->fp_cw) {
+    case 1: launch_fp_columns<NQ, NK, RG, 1, 0>(G, d_sino, stream); return true;
+    case 2: launch_fp_columns<NQ, NK, RG, 2, 0>(G, d_sino, stream); return true;
+    case 4: launch_fp_columns<NQ, NK, RG, 4, 0>(G, d_sino, stream); return true;
     default: return false;
     }
 }
@@ -253,15 +254,22 @@ int leap_launch_project(const leap_geometry *G, const float *d_vol, float *d_sin
     return LEAP_OK;
 }
 
-template <int NC, int NV, int SH>
-static void launch_bp_tiled(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
+template <int NC, int NV, int SH, int GT>
+static void launch_bp_tiled_gt(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
 {
     constexpr SfBpShape S = BP_SHAPES[SH];
     const SfGeom &g = G->g;
     const unsigned tiles_x = cdiv(g.nx, BP_T), tiles_y = cdiv(g.ny, BP_T);
     dim3 grid(tiles_x * tiles_y, cdiv(g.nz, S.zc), 1);
-    hipLaunchKernelGGL((sf_backproject_tiled<NC, NV, S.zc, S.pw, S.ph>), grid, dim3(256, 1, 1), 0, stream, g, G->d_views,
+    hipLaunchKernelGGL((sf_backproject_tiled<NC, NV, S.zc, S.pw, S.ph, GT>), grid, dim3(256, 1, 1), 0, stream, g, G->d_views,
                        d_sino, d_vol, (int)tiles_x, G->bp_wh);
+}
+
+template <int NC, int NV, int SH>
+static void launch_bp_tiled(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
+{
+    if (G->g.type == SF_CONE_CURVED) launch_bp_tiled_gt<NC, NV, SH, 1>(G, d_sino, d_vol, stream);
+    else launch_bp_tiled_gt<NC, NV, SH, 0>(G, d_sino, d_vol, stream);
 }
 
 template <int NC, int NV>

@@ -27,14 +27,19 @@ SF_HD SfWindow sd_bp_window(const SfGeom &g, const SfView &v, float xc, float yc
     const float rho = hx * (fabsf(v.c) + fabsf(v.s));
     const float tlo = tc - rho, thi = tc + rho;
     float ilo = 1.0f, ihi = 1.0f;       // smallest / largest 1/den over the tile
-    if (g.type != SF_PARALLEL) {
-        const float lc = fmaf(xc, v.c, yc * v.s);
-        ilo = sf_rcp(g.sod - lc + rho);
-        ihi = sf_rcp(g.sod - lc - rho);
+    float xi_lo, xi_hi;
+    if (g.type == SF_CONE_CURVED) {
+        sf_curved_tile_bounds(g, v, xc, yc, hx, xi_lo, xi_hi, ilo, ihi);
+    } else {
+        if (g.type != SF_PARALLEL) {
+            const float lc = fmaf(xc, v.c, yc * v.s);
+            ilo = sf_rcp(g.sod - lc + rho);
+            ihi = sf_rcp(g.sod - lc - rho);
+        }
+        xi_lo = fmaf(g.ku * tlo, tlo >= 0.0f ? ilo : ihi, g.col_off);
+        xi_hi = fmaf(g.ku * thi, thi >= 0.0f ? ihi : ilo, g.col_off);
     }
     const float kv = (float)g.kvd, row_off = (float)g.row_offd;
-    const float xi_lo = fmaf(g.ku * tlo, tlo >= 0.0f ? ilo : ihi, g.col_off);
-    const float xi_hi = fmaf(g.ku * thi, thi >= 0.0f ? ihi : ilo, g.col_off);
     const float eta_lo = fmaf(kv * z0, z0 >= 0.0f ? ilo : ihi, row_off);
     const float eta_hi = fmaf(kv * z1, z1 >= 0.0f ? ihi : ilo, row_off);
     // pixel c has its centre at xi = c; row r at eta = r + 1/2.  A margin of 0.02 pixels for float rounding.

@@ -35,9 +35,27 @@ struct SfWindow {
     int need_w, need_h;
 };
 
+// Cylindrical detector: column-coordinate range [xi_lo, xi_hi] and the range [ilo, ihi] of 1 / (in-plane distance from
+// the source) over the square of half extent hx around (xc, yc).  The fan angle of a convex set is extreme at a
+// corner; the distance is bounded by the centre's distance -+ the half diagonal.
+SF_HD void sf_curved_tile_bounds(const SfGeom &g, const SfView &v, float xc, float yc, float hx, float &xi_lo, float &xi_hi,
+                                 float &ilo, float &ihi)
+{
+    const float tc = fmaf(yc, v.c, -xc * v.s), dc = g.sod - fmaf(xc, v.c, yc * v.s);
+    const float a = hx * (v.c - v.s), b = hx * (v.c + v.s);      // corner (+hx, +hx): (dt, dl) = (a, b); (+hx, -hx): (-b, a)
+    const float g0 = atan2f(tc + a, dc - b), g1 = atan2f(tc - a, dc + b);
+    const float g2 = atan2f(tc - b, dc - a), g3 = atan2f(tc + b, dc + a);
+    xi_lo = fmaf(g.ku, fminf(fminf(g0, g1), fminf(g2, g3)), g.col_off);
+    xi_hi = fmaf(g.ku, fmaxf(fmaxf(g0, g1), fmaxf(g2, g3)), g.col_off);
+    const float dist = sf_sqrt(fmaf(tc, tc, dc * dc)), rad = 1.4143f * hx;
+    ilo = sf_rcp(dist + rad);
+    ihi = sf_rcp(fmaxf(dist - rad, 1e-3f * dist));
+}
+
 // xc, yc: tile centre (mm); hx: half extent of the voxel centres in x and y (mm); z0, z1: lower / upper face
 // of the chunk (mm); wh: half of the widest transaxial footprint (pixels); nc, nv: columns / rows a thread reads
 // per voxel (starting at the first one its footprint touches).
+template <int GT = -1>
 SF_HD SfWindow sf_bp_window(const SfGeom &g, const SfView &v, float xc, float yc, float hx, float z0, float z1, float wh,
                             int nc, int nv)
 {
@@ -46,14 +64,19 @@ SF_HD SfWindow sf_bp_window(const SfGeom &g, const SfView &v, float xc, float yc
     const float rho = hx * (fabsf(v.c) + fabsf(v.s));
     const float tlo = tc - rho, thi = tc + rho;
     float ilo = 1.0f, ihi = 1.0f;       // smallest / largest 1/den over the tile
-    if (g.type != SF_PARALLEL) {
-        const float lc = fmaf(xc, v.c, yc * v.s);
-        ilo = sf_rcp(g.sod - lc + rho);
-        ihi = sf_rcp(g.sod - lc - rho);
+    float xi_lo, xi_hi;
+    if (sf_is_curved<GT>(g)) {
+        sf_curved_tile_bounds(g, v, xc, yc, hx, xi_lo, xi_hi, ilo, ihi);
+    } else {
+        if (g.type != SF_PARALLEL) {
+            const float lc = fmaf(xc, v.c, yc * v.s);
+            ilo = sf_rcp(g.sod - lc + rho);
+            ihi = sf_rcp(g.sod - lc - rho);
+        }
+        xi_lo = fmaf(g.ku * tlo, tlo >= 0.0f ? ilo : ihi, g.col_off);
+        xi_hi = fmaf(g.ku * thi, thi >= 0.0f ? ihi : ilo, g.col_off);
     }
     const float kv = (float)g.kvd, row_off = (float)g.row_offd;
-    const float xi_lo = fmaf(g.ku * tlo, tlo >= 0.0f ? ilo : ihi, g.col_off);
-    const float xi_hi = fmaf(g.ku * thi, thi >= 0.0f ? ihi : ilo, g.col_off);
     const float eta_lo = fmaf(kv * z0, z0 >= 0.0f ? ilo : ihi, row_off);
     const float eta_hi = fmaf(kv * z1, z1 >= 0.0f ? ihi : ilo, row_off);
     w.c0 = (int)floorf(xi_lo - wh + 0.48f);
@@ -66,13 +89,13 @@ SF_HD SfWindow sf_bp_window(const SfGeom &g, const SfView &v, float xc, float yc
 #if defined(__HIPCC__) && !defined(SF_NO_KERNELS)
 
 // Staging, first half: fetch this thread's share of the window of one view into registers.  ya points at the view.
-template <int NC, int NV, int PW, int PH, int NSTAGE>
+template <int NC, int NV, int PW, int PH, int NSTAGE, int GT>
 __device__ __forceinline__ void bp_load_view(const SfGeom &g, const SfView v, const float *__restrict__ ya, float xc, float yc,
                                              float hx, float z0, float z1, float wh, int sc, int sr, SfWindow &w,
                                              float (&stage)[NSTAGE])
 {
     constexpr int RSTEP = 256 / PW;
-    w = sf_bp_window(g, v, xc, yc, hx, z0, z1, wh, NC, NV);
+    w = sf_bp_window<GT>(g, v, xc, yc, hx, z0, z1, wh, NC, NV);
     const int c = w.c0 + sc;
     const bool cin = c >= 0 && c < g.ncols;
     ya += cin ? c : 0;
@@ -85,12 +108,12 @@ __device__ __forceinline__ void bp_load_view(const SfGeom &g, const SfView v, co
 }
 
 // Staging, second half: scale by the ray amplitude and write to LDS.
-template <int PW, int PH, int NSTAGE>
+template <int PW, int PH, int NSTAGE, int GT>
 __device__ __forceinline__ void bp_store_view(const SfGeom &g, const SfView v, int sc, int sr, const SfWindow &w,
                                               const float (&stage)[NSTAGE], float *__restrict__ buf)
 {
     constexpr int RSTEP = 256 / PW, PS = PW + BP_ROW_PAD;
-    const SfAmpCol ac = sf_amp_col(g, v, w.c0 + sc);
+    const SfAmpCol ac = sf_amp_col<GT>(g, v, w.c0 + sc);
 #pragma unroll
     for (int s = 0; s < NSTAGE; ++s) {
         const int row = sr + RSTEP * s;
@@ -98,7 +121,7 @@ __device__ __forceinline__ void bp_store_view(const SfGeom &g, const SfView v, i
     }
 }
 
-template <int NC, int NV, int BP_ZC, int BP_PW, int BP_PH>
+template <int NC, int NV, int BP_ZC, int BP_PW, int BP_PH, int GT>
 __global__ __launch_bounds__(256, 4) void sf_backproject_tiled(SfGeom g, const SfView *__restrict__ views,
                                                             const float *__restrict__ sino, float *__restrict__ vol,
                                                             int tiles_x, float wh)
@@ -133,19 +156,19 @@ __global__ __launch_bounds__(256, 4) void sf_backproject_tiled(SfGeom g, const S
     SfWindow win_next;
 
     SfWindow win;
-    bp_load_view<NC, NV, BP_PW, BP_PH, NSTAGE>(g, views[0], sino, xc, yc, hx, z0, z1, wh, sc, sr, win, stage);
+    bp_load_view<NC, NV, BP_PW, BP_PH, NSTAGE, GT>(g, views[0], sino, xc, yc, hx, z0, z1, wh, sc, sr, win, stage);
     win_next = win;
-    bp_store_view<BP_PW, BP_PH, NSTAGE>(g, views[0], sc, sr, win, stage, patch[0]);
+    bp_store_view<BP_PW, BP_PH, NSTAGE, GT>(g, views[0], sc, sr, win, stage, patch[0]);
     __syncthreads();
 
     for (int a = 0; a < g.nviews; ++a) {
         const float *buf = patch[a & 1];
         if (a + 1 < g.nviews)      // global loads in flight during the gather
-            bp_load_view<NC, NV, BP_PW, BP_PH, NSTAGE>(g, views[a + 1], sino + (size_t)(a + 1) * view_stride, xc, yc, hx, z0, z1, wh, sc,
+            bp_load_view<NC, NV, BP_PW, BP_PH, NSTAGE, GT>(g, views[a + 1], sino + (size_t)(a + 1) * view_stride, xc, yc, hx, z0, z1, wh, sc,
                                                        sr, win_next, stage);
 
         const SfView v = views[a];
-        const SfColumn f = sf_column(g, v, ic, jc);
+        const SfColumn f = sf_column<GT>(g, v, ic, jc);
         int cf, cl;
         sf_col_range(f, cf, cl);
         float fu[NC];
@@ -223,7 +246,7 @@ __global__ __launch_bounds__(256, 4) void sf_backproject_tiled(SfGeom g, const S
 
         }
 
-        if (a + 1 < g.nviews) bp_store_view<BP_PW, BP_PH, NSTAGE>(g, views[a + 1], sc, sr, win_next, stage, patch[(a + 1) & 1]);
+        if (a + 1 < g.nviews) bp_store_view<BP_PW, BP_PH, NSTAGE, GT>(g, views[a + 1], sc, sr, win_next, stage, patch[(a + 1) & 1]);
         win = win_next;
         __syncthreads();
     }

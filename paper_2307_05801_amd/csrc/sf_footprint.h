@@ -82,6 +82,15 @@ SF_HD void sf_sort4(float a, float b, float c, float d, float &o0, float &o1, fl
     o2 = fmaxf(m1, m2);
 }
 
+// GT: what the caller knows about the detector at compile time (-1: nothing, look at g.type; 0: not curved; 1: curved).
+// The fast kernels pass it so that the flat-detector instances carry no code for the cylinder.
+template <int GT>
+SF_HD bool sf_is_curved(const SfGeom &g)
+{
+    return GT < 0 ? g.type == SF_CONE_CURVED : GT == 1;
+}
+
+template <int GT = -1>
 SF_HD SfColumn sf_column(const SfGeom &g, const SfView &v, int i, int j)
 {
     SfColumn f;
@@ -93,6 +102,23 @@ SF_HD SfColumn sf_column(const SfGeom &g, const SfView &v, int i, int j)
         f.den = 1.0;
         f.inv = 1.0;
         f.o0 = -v.par_out; f.o1 = -v.par_in; f.o2 = v.par_in; f.o3 = v.par_out;
+    } else if (sf_is_curved<GT>(g)) {
+        // Cylindrical detector: the column coordinate is the fan angle (arc length over the pixel width), and the axial
+        // magnification goes with the in-plane distance from the source.
+        const double dn = g.sodd - fma(x, v.cd, y * v.sd);
+        const double r2 = fma(dn, dn, t * t);
+        f.den = sqrt(r2);
+        f.inv = sf_rcp_d(f.den);
+        f.xi = fma(g.kud, atan2(t, dn), g.col_offd);
+        // Knot offsets in float: the angle between the centre and a corner displaced by (dt, dl) is
+        //   atan2(dt dn + t dl, r2 - dn dl + t dt).
+        const float tf = (float)t, dnf = (float)dn, r2f = (float)r2;
+        const float dtA = v.p - v.q, dlA = v.p + v.q;
+        const float dtB = -dlA, dlB = dtA;
+        const float nA = fmaf(dtA, dnf, tf * dlA), nB = fmaf(dtB, dnf, tf * dlB);
+        const float eA = fmaf(tf, dtA, -dnf * dlA), eB = fmaf(tf, dtB, -dnf * dlB);
+        sf_sort4(g.ku * atanf(nA * sf_rcp(r2f + eA)), -g.ku * atanf(nA * sf_rcp(r2f - eA)),
+                 g.ku * atanf(nB * sf_rcp(r2f + eB)), -g.ku * atanf(nB * sf_rcp(r2f - eB)), f.o0, f.o1, f.o2, f.o3);
     } else {
         const double l = fma(x, v.cd, y * v.sd);
         f.den = g.sodd - l;
@@ -207,10 +233,20 @@ struct SfAmpCol {
     float gcol, wcol;
 };
 
+template <int GT = -1>
 SF_HD SfAmpCol sf_amp_col(const SfGeom &g, const SfView &v, int c)
 {
     SfAmpCol a;
     const float u = ((float)c - g.col_off) * g.pu;
+    if (sf_is_curved<GT>(g)) {       // pixel at fan angle u / sdd on the cylinder: |D_xy| = sdd
+        float sg, cg;
+        sincosf(u / g.sdd, &sg, &cg);
+        const float dx = -g.sdd * fmaf(cg, v.c, sg * v.s);
+        const float dy = g.sdd * fmaf(sg, v.c, -cg * v.s);
+        a.gcol = g.T * sf_rcp(fmaxf(fabsf(dx), fabsf(dy)));
+        a.wcol = g.sdd * g.sdd;
+        return a;
+    }
     const float dx = fmaf(-g.sdd, v.c, -u * v.s);
     const float dy = fmaf(-g.sdd, v.s, u * v.c);
     a.gcol = g.T * sf_rcp(fmaxf(fabsf(dx), fabsf(dy)));

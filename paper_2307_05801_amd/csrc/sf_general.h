@@ -83,10 +83,20 @@ SF_HD void sf_project_ray_chunk(const SfGeom &g, const SfView &v, const float *_
         }
     } else {
         const float sx = g.sod * v.c, sy = g.sod * v.s;
-        const float dxc = fmaf(-g.sdd, v.c, -uc * v.s), dyc = fmaf(-g.sdd, v.s, uc * v.c);
+        float dxc = fmaf(-g.sdd, v.c, -uc * v.s), dyc = fmaf(-g.sdd, v.s, uc * v.c);
+        if (g.type == SF_CONE_CURVED) {      // u is arc length on the cylinder: direction at the fan angle u / sdd
+            float sg, cg;
+            sincosf(uc / g.sdd, &sg, &cg);
+            dxc = -fmaf(cg, v.c, sg * v.s); dyc = fmaf(sg, v.c, -cg * v.s);
+        }
         xmajor = fabsf(dxc) >= fabsf(dyc);
         for (int e = 0; e < 2; ++e) {
-            const float dx = fmaf(-g.sdd, v.c, -ue[e] * v.s), dy = fmaf(-g.sdd, v.s, ue[e] * v.c);
+            float dx = fmaf(-g.sdd, v.c, -ue[e] * v.s), dy = fmaf(-g.sdd, v.s, ue[e] * v.c);
+            if (g.type == SF_CONE_CURVED) {
+                float sg, cg;
+                sincosf(ue[e] / g.sdd, &sg, &cg);
+                dx = -fmaf(cg, v.c, sg * v.s); dy = fmaf(sg, v.c, -cg * v.s);
+            }
             if (xmajor) {
                 m[e] = dy / dx;
                 b[e] = (sy - y0 + (x0 - sx) * m[e]) / g.T;

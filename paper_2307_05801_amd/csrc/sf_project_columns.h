@@ -28,6 +28,7 @@ struct SfRayLines {
     int xmajor;
 };
 
+template <int GT = -1>
 SF_HD SfRayLines sf_ray_lines(const SfGeom &g, const SfView &v, int c, int cw)
 {
     SfRayLines L;
@@ -48,10 +49,21 @@ SF_HD SfRayLines sf_ray_lines(const SfGeom &g, const SfView &v, int c, int cw)
     } else {
         const float uc = 0.5f * (ue0 + ue1);
         const float sx = g.sod * v.c, sy = g.sod * v.s;
-        const float dxc = fmaf(-g.sdd, v.c, -uc * v.s), dyc = fmaf(-g.sdd, v.s, uc * v.c);
+        float dxc, dyc, dx0, dy0, dx1, dy1;
+        if (sf_is_curved<GT>(g)) {      // u is arc length: directions at the fan angles u / sdd
+            float sg, cg;
+            sincosf(uc / g.sdd, &sg, &cg);
+            dxc = -fmaf(cg, v.c, sg * v.s); dyc = fmaf(sg, v.c, -cg * v.s);
+            sincosf(ue0 / g.sdd, &sg, &cg);
+            dx0 = -fmaf(cg, v.c, sg * v.s); dy0 = fmaf(sg, v.c, -cg * v.s);
+            sincosf(ue1 / g.sdd, &sg, &cg);
+            dx1 = -fmaf(cg, v.c, sg * v.s); dy1 = fmaf(sg, v.c, -cg * v.s);
+        } else {
+            dxc = fmaf(-g.sdd, v.c, -uc * v.s); dyc = fmaf(-g.sdd, v.s, uc * v.c);
+            dx0 = fmaf(-g.sdd, v.c, -ue0 * v.s); dy0 = fmaf(-g.sdd, v.s, ue0 * v.c);
+            dx1 = fmaf(-g.sdd, v.c, -ue1 * v.s); dy1 = fmaf(-g.sdd, v.s, ue1 * v.c);
+        }
         L.xmajor = fabsf(dxc) >= fabsf(dyc);
-        const float dx0 = fmaf(-g.sdd, v.c, -ue0 * v.s), dy0 = fmaf(-g.sdd, v.s, ue0 * v.c);
-        const float dx1 = fmaf(-g.sdd, v.c, -ue1 * v.s), dy1 = fmaf(-g.sdd, v.s, ue1 * v.c);
         if (L.xmajor) {
             L.m0 = dy0 / dx0;
             L.m1 = dy1 / dx1;
@@ -101,8 +113,8 @@ __global__ __launch_bounds__(256) void sf_volume_to_columns(const float *__restr
 
 // NQ: candidate slots per slab (power of two <= 64); NK: voxels a detector row can overlap; RG: row groups per wave;
 // FP_WAVES: waves per workgroup; CW: adjacent detector columns per wave; WV: consecutive views per workgroup
-// (the workgroup's waves are WV views x FP_WAVES/WV column bundles).
-template <int NQ, int NK, int RG, int FP_WAVES, int CW, int WV>
+// (the workgroup's waves are WV views x FP_WAVES/WV column bundles); GT: 0 flat or parallel, 1 cylindrical detector.
+template <int NQ, int NK, int RG, int FP_WAVES, int CW, int WV, int GT>
 __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, const SfView *__restrict__ views,
                                                                     const float *__restrict__ volz, float *__restrict__ sino,
                                                                     int nzp, int col_tiles, int bands, int vb, int tb,
@@ -138,7 +150,7 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, co
     const int band0 = band * (RG * 64);
 
     const SfView v = views[a];
-    const SfRayLines L = sf_ray_lines(g, v, c0, CW);
+    const SfRayLines L = sf_ray_lines<GT>(g, v, c0, CW);
     const int n_major = L.xmajor ? g.nx : g.ny;
     const int n_minor = L.xmajor ? g.ny : g.nx;
 
@@ -168,7 +180,7 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, co
         const bool valid = n < n_major && q >= 0 && q < n_minor && q <= ql;
         const int i = L.xmajor ? n : q, j = L.xmajor ? q : n;
         const int ic = valid ? i : 0, jc = valid ? j : 0;
-        const SfColumn f = sf_column(g, v, ic, jc);
+        const SfColumn f = sf_column<GT>(g, v, ic, jc);
         const double mu = f.den * mu_scale;                       // voxels per detector row at this column
         const float rows_per_voxel = fan ? 1.0f : (float)(g.kvd * f.inv * g.Tzd);
         float fa[CW];                                              // F_u times rows per voxel, per detector column
@@ -235,7 +247,7 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, co
     for (int cw = 0; cw < CW; ++cw) {
         const int c = c0 + cw;
         if (c >= g.ncols) break;
-        const SfAmpCol ac = sf_amp_col(g, v, c);
+        const SfAmpCol ac = sf_amp_col<GT>(g, v, c);
 #pragma unroll
         for (int gq = 0; gq < RG; ++gq) {
             const int r = band0 + 64 * gq + lane;

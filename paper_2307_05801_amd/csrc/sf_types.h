@@ -14,7 +14,7 @@
 
 #include <stdint.h>
 
-enum { SF_PARALLEL = 0, SF_FAN = 1, SF_CONE = 2 };
+enum { SF_PARALLEL = 0, SF_FAN = 1, SF_CONE = 2, SF_CONE_CURVED = 3 };   // CURVED: cylindrical detector, columns equally spaced in arc length
 enum { SF_MODEL_FOOTPRINT = 0, SF_MODEL_SIDDON = 1 };
 
 struct SfGeom {
@@ -27,8 +27,8 @@ struct SfGeom {
     double x0d, y0d;      // centre of voxel (i,j) = (0,0), mm
     double zlo0d;         // lower face of voxel k = 0, mm
     double sodd;          // source to rotation axis, mm
-    double kud;           // parallel: 1/pu ; cone/fan: sdd/pu   (xi  = kud * t / den + col_offd)
-    double kvd;           // parallel: 1/pv ; cone    : sdd/pv   (eta = kvd * z / den + row_offd)
+    double kud;           // parallel: 1/pu ; cone/fan: sdd/pu   (xi  = kud * t / den + col_offd; curved: kud * fan angle + col_offd)
+    double kvd;           // parallel: 1/pv ; cone    : sdd/pv   (eta = kvd * z / den + row_offd; curved: den = in-plane distance from the source)
     double ikvd;          // 1 / kvd
     double iTzd;          // 1 / Tz
     double col_offd;      // (ncols-1)/2 - shift_u

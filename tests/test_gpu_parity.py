@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 from synthetic import CTConfig, config, reduced, standard_volume, uniform_sinogram, uniform_volume
-from synthetic.configs import CONE, FAN, PARALLEL
+from synthetic.configs import CONE, CONE_CURVED, FAN, PARALLEL
 
 pytestmark = pytest.mark.gpu
 
@@ -70,6 +70,15 @@ SMALL_CASES = [
                                 sdd=900.0, shift_u=0.8, center_x=2.0)),
     ("fine_detector", 3, lambda: reduced(config(3), 8, nviews=9).replace(pixel_u=1.7, pixel_v=1.9, nrows=300, ncols=280)),
     ("coarse_detector", 3, lambda: reduced(config(3), 8, nviews=9).replace(pixel_u=37.0, pixel_v=29.0, nrows=14, ncols=12)),
+    ("curved_c3_div8_ragged", 3, lambda: ragged(reduced(config(3), 8, nviews=40), geom=CONE_CURVED, nx=67, ny=70, nz=45,
+                                                nrows=61, ncols=77, shift_u=0.6, shift_v=-1.2, center_x=3.0)),
+    ("curved_c3_div4", 3, lambda: reduced(config(3), 4, nviews=12).replace(geom=CONE_CURVED, start_deg=7.0)),
+    ("curved_wide_fan", 3, lambda: CTConfig("curved_wide", CONE_CURVED, nviews=16, arc_deg=360.0, nrows=48, ncols=120,
+                                            pixel_v=2.0, pixel_u=1.6, nx=64, ny=60, nz=40, voxel_xy=1.0, voxel_z=1.2,
+                                            sod=110.0, sdd=170.0, shift_u=-0.8, shift_v=0.3, center_y=1.5, start_deg=4.0)),
+    ("curved_close_source", 3, lambda: CTConfig("curved_close", CONE_CURVED, nviews=9, arc_deg=360.0, nrows=40, ncols=200,
+                                                pixel_v=2.0, pixel_u=1.0, nx=48, ny=48, nz=24, voxel_xy=1.0, voxel_z=1.5,
+                                                sod=45.0, sdd=90.0, shift_u=0.4, shift_v=0.0, start_deg=2.0)),
 ]
 
 
@@ -283,9 +292,22 @@ def test_general_kernels_agree_with_fast_kernels(torch_mod, oracle_mod, monkeypa
 
 @pytest.mark.parametrize("seed", range(16))
 def test_random_geometries(torch_mod, oracle_mod, seed):
+    _random_case(torch_mod, oracle_mod, seed, curved=False)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 5, 7, 8, 10, 11, 13])
+def test_random_geometries_curved_detector(torch_mod, oracle_mod, seed):
+    _random_case(torch_mod, oracle_mod, seed, curved=True)
+
+
+def _random_case(torch_mod, oracle_mod, seed, curved):
     """Random scanners (cone and parallel, shifted and truncated detectors, anisotropic voxels, irregular angles)."""
     from random_geometries import random_config
     cfg = random_config(seed)
+    if curved:
+        if cfg.geom != CONE:
+            pytest.skip("parallel-beam draw")
+        cfg = cfg.replace(geom=CONE_CURVED)
     x = uniform_volume(cfg, seed)[0]
     y = uniform_sinogram(cfg, seed)[0]
     ax = gpu_project(torch_mod, cfg, x)

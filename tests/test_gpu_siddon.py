@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 
 from synthetic import CTConfig, config, reduced, standard_volume, uniform_sinogram, uniform_volume
-from synthetic.configs import CONE, FAN, PARALLEL
+from synthetic.configs import CONE, CONE_CURVED, FAN, PARALLEL
 
 pytestmark = pytest.mark.gpu
 
@@ -69,6 +69,11 @@ SMALL_CASES = [
         "steep", CONE, nviews=11, arc_deg=360.0, nrows=40, ncols=36, pixel_v=2.9, pixel_u=1.4, nx=30, ny=28, nz=60,
         voxel_xy=1.0, voxel_z=0.21, sod=40.0, sdd=62.0, shift_u=0.3, shift_v=-0.4, center_x=0.7, center_z=-0.3,
         start_deg=3.0)),
+    ("curved_c3_div8_ragged", 3, lambda: reduced(config(3), 8, nviews=40).replace(
+        geom=CONE_CURVED, nx=67, ny=70, nz=45, nrows=61, ncols=77, shift_u=0.6, shift_v=-1.2, center_x=3.0)),
+    ("curved_wide_fan", 3, lambda: CTConfig("curved_wide", CONE_CURVED, nviews=16, arc_deg=360.0, nrows=48, ncols=120,
+                                            pixel_v=2.0, pixel_u=1.6, nx=64, ny=60, nz=40, voxel_xy=1.0, voxel_z=1.2,
+                                            sod=110.0, sdd=170.0, shift_u=-0.8, shift_v=0.3, center_y=1.5, start_deg=4.0)),
     ("parallel_3d", 3, lambda: CTConfig(
         "par3", PARALLEL, nviews=13, arc_deg=180.0, nrows=66, ncols=90, pixel_v=0.9, pixel_u=0.8, nx=70, ny=66, nz=51,
         voxel_xy=1.0, voxel_z=1.1, sod=0.0, sdd=0.0, shift_u=0.3, shift_v=-0.4, center_y=0.7, center_z=-0.3,
@@ -180,11 +185,15 @@ def test_general_kernels_agree_with_fast_kernels(torch_mod, oracle_mod, monkeypa
     assert rel_l2(ax_f.cpu().numpy(), oracle_mod.siddon.project(cfg, x.cpu().numpy())) <= TOL
 
 
-@pytest.mark.parametrize("seed", range(12))
-def test_random_geometries(torch_mod, oracle_mod, seed):
+@pytest.mark.parametrize("seed,curved", [(s, False) for s in range(12)] + [(s, True) for s in (1, 2, 5, 7, 8, 10)])
+def test_random_geometries(torch_mod, oracle_mod, seed, curved):
     from random_geometries import random_config
     cfg = random_config(seed)
     cfg = cfg.replace(shift_u=cfg.shift_u + 0.0617)
+    if curved:
+        if cfg.geom != CONE:
+            pytest.skip("parallel-beam draw")
+        cfg = cfg.replace(geom=CONE_CURVED)
     sd = oracle_mod.siddon
     x = uniform_volume(cfg, 100 + seed)[0]
     y = uniform_sinogram(cfg, 200 + seed)[0]

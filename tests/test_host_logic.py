@@ -11,7 +11,7 @@ import pytest
 
 from paper_2307_05801_amd import binding as B
 from synthetic import CTConfig, config, reduced, standard_volume, uniform_sinogram, uniform_volume
-from synthetic.configs import CONE, FAN, PARALLEL
+from synthetic.configs import CONE, CONE_CURVED, FAN, PARALLEL
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -25,10 +25,16 @@ def host():
     deps = [SRC, os.path.join(ROOT, "paper_2307_05801_amd", "csrc")]
     newest = max(os.path.getmtime(os.path.join(d, f)) if os.path.isdir(d) else os.path.getmtime(d)
                  for d in deps for f in (os.listdir(d) if os.path.isdir(d) else [""]))
-    if not os.path.exists(LIB) or os.path.getmtime(LIB) < newest:
-        cmd = ["g++", "-O2", "-fopenmp", "-std=c++17", "-fPIC", "-shared", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
-               "-o", LIB, SRC, os.path.join(ROOT, "paper_2307_05801_amd", "csrc", "leap_geometry.cpp")]
-        subprocess.run(cmd, check=True, capture_output=True)
+    import fcntl
+    with open(LIB + ".lock", "w") as lock:          # several pytest-xdist workers may arrive here together
+        fcntl.flock(lock, fcntl.LOCK_EX)
+        if not os.path.exists(LIB) or os.path.getmtime(LIB) < newest:
+            tmp = f"{LIB}.{os.getpid()}.tmp"
+            cmd = ["g++", "-O2", "-fopenmp", "-std=c++17", "-fPIC", "-shared", "-D__HIP_PLATFORM_AMD__",
+                   "-I/opt/rocm/include", "-o", tmp, SRC,
+                   os.path.join(ROOT, "paper_2307_05801_amd", "csrc", "leap_geometry.cpp")]
+            subprocess.run(cmd, check=True, capture_output=True)
+            os.replace(tmp, LIB)
     lib = C.CDLL(LIB)
     B.declare(lib)
     lib.host_check_backproject_windows.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
@@ -56,6 +62,11 @@ CASES = {
         shift_u=1.3, shift_v=-2.7, center_x=6.0, center_y=-4.5, center_z=3.25, start_deg=7.0)),
     "c4_div4": (4, lambda: reduced(config(4), 4, nviews=10)),
     "c5_div16": (5, lambda: reduced(config(5), 16, nviews=18)),
+    "curved_c3_div8": (3, lambda: reduced(config(3), 8, nviews=24).replace(
+        geom=CONE_CURVED, nx=67, ny=70, nz=45, nrows=61, ncols=77, shift_u=0.6, shift_v=-1.2, center_x=3.0)),
+    "curved_wide_fan": (3, lambda: CTConfig("curved_wide", CONE_CURVED, nviews=16, arc_deg=360.0, nrows=48, ncols=120,
+                                            pixel_v=2.0, pixel_u=1.6, nx=64, ny=60, nz=40, voxel_xy=1.0, voxel_z=1.2,
+                                            sod=110.0, sdd=170.0, shift_u=-0.8, shift_v=0.3, center_y=1.5, start_deg=4.0)),
     "fan": (3, lambda: CTConfig("fan", FAN, nviews=20, arc_deg=360.0, nrows=1, ncols=90, pixel_v=1.0, pixel_u=2.0,
                                 nx=70, ny=64, nz=1, voxel_xy=1.0, voxel_z=1.0, sod=300.0, sdd=500.0, shift_u=0.8)),
 }
@@ -120,7 +131,8 @@ def test_siddon_kernel_bodies_match_oracle_on_cpu(host, oracle_mod, name):
     assert abs(lhs - rhs) <= TOL * abs(lhs)
 
 
-@pytest.mark.parametrize("name", ["c2_div8", "c3_div8_ragged", "c3_div8_offsets", "c4_div4", "c5_div16"])
+@pytest.mark.parametrize("name", ["c2_div8", "c3_div8_ragged", "c3_div8_offsets", "c4_div4", "c5_div16", "curved_c3_div8",
+                                  "curved_wide_fan"])
 def test_column_forward_arithmetic_matches_oracle_on_cpu(host, oracle_mod, name, monkeypatch):
     number, make = CASES[name]
     cfg = make()
@@ -146,7 +158,8 @@ def window_report(host, cfg):
     return list(rep), desc
 
 
-@pytest.mark.parametrize("name", ["c2_div8", "c3_div8_ragged", "c3_div8_offsets", "c4_div4", "c5_div16"])
+@pytest.mark.parametrize("name", ["c2_div8", "c3_div8_ragged", "c3_div8_offsets", "c4_div4", "c5_div16", "curved_c3_div8",
+                                  "curved_wide_fan"])
 def test_tiled_backprojection_reads_stay_inside_the_staged_window(host, name):
     rep, desc = window_report(host, CASES[name][1]())
     assert rep[0] == 1, desc
