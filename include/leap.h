@@ -100,6 +100,28 @@ int leap_project(const leap_geometry *geom, const float *d_vol, float *d_sino, i
  * gather without atomics (bitwise reproducible): d_vol[b] = A^T d_sino[b].  Asynchronous on hip_stream. */
 int leap_backproject(const leap_geometry *geom, const float *d_sino, float *d_vol, int32_t batch, void *hip_stream);
 
+/* ---- iterative reconstruction on top of the pair ------------------------------------------------------------
+ * "CT Projection Models and Geometries" motivates the matched transpose with the least-squares cost
+ * 1/2 ||A x - y||^2, whose gradient is A^T (A x - y), and with iterations that stay stable over a thousand or
+ * more steps.  Both solvers below run entirely on the caller's stream (projector calls, streaming elementwise
+ * kernels, reductions whose results stay on the device), allocate nothing and never synchronise with the host.
+ * One volume and one sinogram (batch 1).  d_work: device memory of leap_recon_workspace_floats() floats, contents
+ * undefined before and after. */
+
+/* Number of floats the solvers need in d_work: 2 sinograms + 2 volumes + a small reduction scratch. */
+int leap_recon_workspace_floats(const leap_geometry *geom, int64_t *n_floats);
+
+/* SIRT: x <- x + relaxation * C .* A^T ( R .* (y - A x) ), `iterations` times, with R = 1 / (A 1) per ray and
+ * C = 1 / (A^T 1) per voxel (0 where the sum is 0).  d_vol holds the start value on entry and the result on return;
+ * nonneg != 0 clips every update at zero from below. */
+int leap_sirt(const leap_geometry *geom, const float *d_sino, float *d_vol, float *d_work, int32_t iterations,
+              float relaxation, int32_t nonneg, void *hip_stream);
+
+/* Steepest descent on 1/2 ||A x - y||^2 with the exact line search: g = A^T (A x - y), x <- x - (|g|^2 / |A g|^2) g,
+ * `iterations` times (the step length is formed on the device, in double). */
+int leap_least_squares_descent(const leap_geometry *geom, const float *d_sino, float *d_vol, float *d_work,
+                               int32_t iterations, void *hip_stream);
+
 /* Static description of a status code. */
 const char *leap_status_string(int status);
 

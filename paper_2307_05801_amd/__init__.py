@@ -1,11 +1,12 @@
-"""MI355X-native separable-footprint CT projector pair (forward A, matched transpose A^T).
+"""MI355X-native CT projector pairs (forward A, matched transpose A^T; separable-footprint and Siddon models).
 
 The compute path is the HIP library libleap_hip.so (C ABI in include/leap.h); this package only
 marshals arguments.  There is no CPU or PyTorch fallback: a missing library raises.
 """
 from .binding import (  # noqa: F401
-    LEAP_PARALLEL, LEAP_FAN, LEAP_CONE, LeapError, leap_geometry_desc, make_desc, desc_from_config, load_library,
+    LEAP_PARALLEL, LEAP_FAN, LEAP_CONE, LEAP_CONE_CURVED, LEAP_MODEL_SF, LEAP_MODEL_SIDDON, LeapError, leap_geometry_desc, make_desc, desc_from_config, load_library,
     leap_geometry_create, leap_geometry_destroy, leap_geometry_describe, leap_project, leap_backproject,
+    leap_recon_workspace_floats, leap_sirt, leap_least_squares_descent,
 )
 
 
@@ -14,4 +15,7 @@ def __getattr__(name):
     if name in ("Geometry", "Projector"):
         from . import projector
         return getattr(projector, name)
+    if name == "recon":
+        import importlib
+        return importlib.import_module(".recon", __name__)
     raise AttributeError(name)

@@ -18,7 +18,8 @@ MODELS = {"sf": LEAP_MODEL_SF, "siddon": LEAP_MODEL_SIDDON}
 LEAP_OK, LEAP_INVALID_ARG, LEAP_BAD_GEOMETRY, LEAP_HIP_ERROR, LEAP_UNSUPPORTED = 0, -1, -2, -3, -4
 
 EXPORTS = ("leap_geometry_create", "leap_geometry_destroy", "leap_project", "leap_backproject",
-           "leap_status_string", "leap_last_error", "leap_geometry_describe")
+           "leap_status_string", "leap_last_error", "leap_geometry_describe",
+           "leap_recon_workspace_floats", "leap_sirt", "leap_least_squares_descent")
 
 
 class leap_geometry_desc(C.Structure):
@@ -54,6 +55,12 @@ def declare(lib) -> None:
     for fn in (lib.leap_project, lib.leap_backproject):
         fn.restype = C.c_int
         fn.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+    lib.leap_recon_workspace_floats.restype = C.c_int
+    lib.leap_recon_workspace_floats.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
+    lib.leap_sirt.restype = C.c_int
+    lib.leap_sirt.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_int32, C.c_void_p]
+    lib.leap_least_squares_descent.restype = C.c_int
+    lib.leap_least_squares_descent.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
     lib.leap_status_string.restype = C.c_char_p
     lib.leap_status_string.argtypes = [C.c_int]
     lib.leap_last_error.restype = C.c_char_p
@@ -137,3 +144,24 @@ def leap_project(handle: int, d_vol: int, d_sino: int, batch: int, stream: int =
 def leap_backproject(handle: int, d_sino: int, d_vol: int, batch: int, stream: int = 0, lib=None) -> None:
     lib = lib or load_library()
     _check(lib, lib.leap_backproject(C.c_void_p(handle), C.c_void_p(d_sino), C.c_void_p(d_vol), batch, C.c_void_p(stream)))
+
+
+def leap_recon_workspace_floats(handle: int, lib=None) -> int:
+    lib = lib or load_library()
+    n = C.c_int64()
+    _check(lib, lib.leap_recon_workspace_floats(C.c_void_p(handle), C.byref(n)))
+    return n.value
+
+
+def leap_sirt(handle: int, d_sino: int, d_vol: int, d_work: int, iterations: int, relaxation: float = 1.0,
+              nonneg: bool = False, stream: int = 0, lib=None) -> None:
+    lib = lib or load_library()
+    _check(lib, lib.leap_sirt(C.c_void_p(handle), C.c_void_p(d_sino), C.c_void_p(d_vol), C.c_void_p(d_work), iterations,
+                              relaxation, int(bool(nonneg)), C.c_void_p(stream)))
+
+
+def leap_least_squares_descent(handle: int, d_sino: int, d_vol: int, d_work: int, iterations: int, stream: int = 0,
+                               lib=None) -> None:
+    lib = lib or load_library()
+    _check(lib, lib.leap_least_squares_descent(C.c_void_p(handle), C.c_void_p(d_sino), C.c_void_p(d_vol),
+                                               C.c_void_p(d_work), iterations, C.c_void_p(stream)))

@@ -169,7 +169,6 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, co
         for (int gq = 0; gq < RG; ++gq) acc[cw][gq] = 0.0f;
 
     const int slot = lane & (NQ - 1), nrel = lane / NQ;
-    const bool fan = g.type == SF_FAN;
 
     for (int nb = 0; nb < n_major; nb += SB) {
         // ---- lane-parallel: one candidate voxel column per lane
@@ -182,7 +181,7 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, co
         const int ic = valid ? i : 0, jc = valid ? j : 0;
         const SfColumn f = sf_column<GT>(g, v, ic, jc);
         const double mu = f.den * mu_scale;                       // voxels per detector row at this column
-        const float rows_per_voxel = fan ? 1.0f : (float)(g.kvd * f.inv * g.Tzd);
+        const float rows_per_voxel = (float)(g.kvd * f.inv * g.Tzd);
         float fa[CW];                                              // F_u times rows per voxel, per detector column
         bool any = false;
         {
@@ -214,11 +213,6 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, co
             const double s_mu = __hiloint2double(__builtin_amdgcn_readlane(mu_hi, e), __builtin_amdgcn_readlane(mu_lo, e));
             const float step = (float)s_mu;
             const char *__restrict__ col = reinterpret_cast<const char *>(volz + s_base);   // wave-uniform base address
-            if (fan) {
-#pragma unroll
-                for (int cw = 0; cw < CW; ++cw) acc[cw][0] = fmaf(s_fa[cw], volz[s_base + FP_PAD], acc[cw][0]);
-                continue;
-            }
 #pragma unroll
             for (int gq = 0; gq < RG; ++gq) {
                 // kappa measured from the start of the padded column; negative values only occur inside the pad
