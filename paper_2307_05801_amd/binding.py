@@ -46,8 +46,9 @@ class LeapError(RuntimeError):
 _lib = None
 
 
-def declare(lib) -> None:
-    """Attach the prototypes of include/leap.h to a loaded library."""
+def declare(lib, solvers: bool = True) -> None:
+    """Attach the prototypes of include/leap.h to a loaded library (solvers=False: the projector entry points only,
+    for test builds that link the geometry module alone)."""
     lib.leap_geometry_create.restype = C.c_int
     lib.leap_geometry_create.argtypes = [C.POINTER(leap_geometry_desc), C.POINTER(C.c_void_p)]
     lib.leap_geometry_destroy.restype = None
@@ -55,12 +56,14 @@ def declare(lib) -> None:
     for fn in (lib.leap_project, lib.leap_backproject):
         fn.restype = C.c_int
         fn.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
-    lib.leap_recon_workspace_floats.restype = C.c_int
-    lib.leap_recon_workspace_floats.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
-    lib.leap_sirt.restype = C.c_int
-    lib.leap_sirt.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_int32, C.c_void_p]
-    lib.leap_least_squares_descent.restype = C.c_int
-    lib.leap_least_squares_descent.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+    if solvers:
+        lib.leap_recon_workspace_floats.restype = C.c_int
+        lib.leap_recon_workspace_floats.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
+        lib.leap_sirt.restype = C.c_int
+        lib.leap_sirt.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_int32,
+                                  C.c_void_p]
+        lib.leap_least_squares_descent.restype = C.c_int
+        lib.leap_least_squares_descent.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
     lib.leap_status_string.restype = C.c_char_p
     lib.leap_status_string.argtypes = [C.c_int]
     lib.leap_last_error.restype = C.c_char_p

@@ -36,7 +36,7 @@ def host():
             subprocess.run(cmd, check=True, capture_output=True)
             os.replace(tmp, LIB)
     lib = C.CDLL(LIB)
-    B.declare(lib)
+    B.declare(lib, solvers=False)
     lib.host_check_backproject_windows.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
     lib.host_project_columns.restype = C.c_long
     lib.host_project_columns.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
