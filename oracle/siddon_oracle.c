@@ -25,6 +25,18 @@ typedef struct { double o[3], d[3], len; int ndim; } ray_t;
 
 static void ray_of(const sdo_scan *s, int view, int r, int c, ray_t *ray)
 {
+    if (s->geom == SDO_MODULAR) {
+        const double *S = s->poses + 12 * (int64_t)view, *C = S + 3, *uc = S + 6, *vr = S + 9;
+        double pu_ = pix_u(s, c), pv_ = pix_v(s, r), q = 0.0;
+        ray->ndim = 3;
+        for (int a = 0; a < 3; ++a) {
+            ray->o[a] = S[a];
+            ray->d[a] = C[a] + pu_ * uc[a] + pv_ * vr[a] - S[a];
+            q += ray->d[a] * ray->d[a];
+        }
+        ray->len = sqrt(q);
+        return;
+    }
     double cphi = cos(s->phi[view]), sphi = sin(s->phi[view]);
     double es[3] = { cphi, sphi, 0.0 }, eu[3] = { -sphi, cphi, 0.0 }, ez[3] = { 0.0, 0.0, 1.0 };
     double u = pix_u(s, c), v = (s->geom == SDO_FAN) ? 0.0 : pix_v(s, r);
@@ -92,35 +104,38 @@ static void cell_range(double x0, double x1, double g0, double p, int n, int *a,
     *b = fb > n - 1 ? n - 1 : (fb < -1.0 ? -1 : (int)fb);
 }
 
-/* Visits every voxel the ray can cross: walks the slabs of the in-plane axis along which the ray advances fastest,
- * and inside each slab tries every voxel of the bounding box of the ray's piece in that slab.  `vol` may be NULL
+/* Visits every voxel the ray can cross: walks the slabs of the axis along which the ray advances fastest, and
+ * inside each slab tries every voxel of the bounding box of the ray's piece in that slab.  `vol` may be NULL
  * (then only non-zero weights are counted into *count). */
 static double ray_sum(const sdo_scan *s, const ray_t *ray, const float *vol, int64_t *count)
 {
-    int major = fabs(ray->d[0]) >= fabs(ray->d[1]) ? 0 : 1, minor = 1 - major;
-    int nmaj = major == 0 ? s->nx : s->ny, nmin = major == 0 ? s->ny : s->nx;
-    double gmaj = grid_lo(major == 0 ? s->cx : s->cy, nmaj, s->T);
-    double gmin = grid_lo(major == 0 ? s->cy : s->cx, nmin, s->T);
-    double gz = grid_lo(s->cz, s->nz, s->Tz);
+    /* the axis the ray advances fastest on (any of the three for a modular scan; fan-beam rays live in the plane) */
+    int major = fabs(ray->d[0]) >= fabs(ray->d[1]) ? 0 : 1;
+    if (ray->ndim == 3 && fabs(ray->d[2]) > fabs(ray->d[major])) major = 2;
+    int n[3] = { s->nx, s->ny, s->nz };
+    double pitch[3] = { s->T, s->T, s->Tz };
+    double g0[3] = { grid_lo(s->cx, s->nx, s->T), grid_lo(s->cy, s->ny, s->T), grid_lo(s->cz, s->nz, s->Tz) };
     double sum = 0.0;
-    for (int n = 0; n < nmaj; ++n) {
-        double ta = (gmaj + n * s->T - ray->o[major]) / ray->d[major];
-        double tb = (gmaj + (n + 1) * s->T - ray->o[major]) / ray->d[major];
-        int q0, q1, k0 = 0, k1 = 0;
-        cell_range(ray->o[minor] + ta * ray->d[minor], ray->o[minor] + tb * ray->d[minor], gmin, s->T, nmin, &q0, &q1);
-        if (ray->ndim == 3)
-            cell_range(ray->o[2] + ta * ray->d[2], ray->o[2] + tb * ray->d[2], gz, s->Tz, s->nz, &k0, &k1);
-        for (int k = k0; k <= k1; ++k)
-            for (int q = q0; q <= q1; ++q) {
-                int i = major == 0 ? n : q, j = major == 0 ? q : n;
-                double lo[3], hi[3];
-                voxel_box(s, i, j, k, lo, hi);
-                double w = chord(ray, lo, hi);
-                if (w > 0.0) {
-                    if (vol) sum += w * (double)vol[((int64_t)k * s->ny + j) * s->nx + i];
-                    if (count) ++*count;
+    for (int m = 0; m < n[major]; ++m) {
+        double ta = (g0[major] + m * pitch[major] - ray->o[major]) / ray->d[major];
+        double tb = (g0[major] + (m + 1) * pitch[major] - ray->o[major]) / ray->d[major];
+        int lo_[3], hi_[3];
+        for (int a = 0; a < 3; ++a) {
+            if (a == major) { lo_[a] = hi_[a] = m; }
+            else if (a == 2 && ray->ndim == 2) { lo_[a] = hi_[a] = 0; }
+            else cell_range(ray->o[a] + ta * ray->d[a], ray->o[a] + tb * ray->d[a], g0[a], pitch[a], n[a], &lo_[a], &hi_[a]);
+        }
+        for (int k = lo_[2]; k <= hi_[2]; ++k)
+            for (int j = lo_[1]; j <= hi_[1]; ++j)
+                for (int i = lo_[0]; i <= hi_[0]; ++i) {
+                    double lo[3], hi[3];
+                    voxel_box(s, i, j, k, lo, hi);
+                    double w = chord(ray, lo, hi);
+                    if (w > 0.0) {
+                        if (vol) sum += w * (double)vol[((int64_t)k * s->ny + j) * s->nx + i];
+                        if (count) ++*count;
+                    }
                 }
-            }
     }
     return sum;
 }
@@ -192,9 +207,27 @@ static double voxel_sum(const sdo_scan *s, int i, int j, int k, const float *sin
     double lo[3], hi[3], sum = 0.0;
     voxel_box(s, i, j, k, lo, hi);
     for (int view = 0; view < s->nviews; ++view) {
-        double cphi = cos(s->phi[view]), sphi = sin(s->phi[view]);
+        double cphi = 1.0, sphi = 0.0;
+        if (s->geom != SDO_MODULAR) { cphi = cos(s->phi[view]); sphi = sin(s->phi[view]); }
         double umin = INFINITY, umax = -INFINITY, vmin = INFINITY, vmax = -INFINITY;
-        for (int corner = 0; corner < 8; ++corner) {
+        for (int corner = 0; corner < 8 && s->geom == SDO_MODULAR; ++corner) {
+            /* central projection of the corner onto the detector plane; a corner that is not in front of the source
+             * (seen from the detector) makes the search cover the whole detector */
+            const double *S = s->poses + 12 * (int64_t)view, *C = S + 3, *uc = S + 6, *vr = S + 9;
+            double X[3] = { (corner & 1) ? hi[0] : lo[0], (corner & 2) ? hi[1] : lo[1], (corner & 4) ? hi[2] : lo[2] };
+            double nrm[3] = { uc[1] * vr[2] - uc[2] * vr[1], uc[2] * vr[0] - uc[0] * vr[2], uc[0] * vr[1] - uc[1] * vr[0] };
+            double num = 0.0, den = 0.0;
+            for (int a = 0; a < 3; ++a) { num += (C[a] - S[a]) * nrm[a]; den += (X[a] - S[a]) * nrm[a]; }
+            if (!(num * den > 0.0)) { umin = vmin = -INFINITY; umax = vmax = INFINITY; break; }
+            double u = 0.0, v = 0.0;
+            for (int a = 0; a < 3; ++a) {
+                double H = S[a] + (num / den) * (X[a] - S[a]) - C[a];
+                u += H * uc[a]; v += H * vr[a];
+            }
+            umin = fmin(umin, u); umax = fmax(umax, u);
+            vmin = fmin(vmin, v); vmax = fmax(vmax, v);
+        }
+        for (int corner = 0; corner < 8 && s->geom != SDO_MODULAR; ++corner) {
             double x = (corner & 1) ? hi[0] : lo[0], y = (corner & 2) ? hi[1] : lo[1], z = (corner & 4) ? hi[2] : lo[2];
             double t = -x * sphi + y * cphi, l = x * cphi + y * sphi;
             double mag = (s->geom == SDO_PARALLEL) ? 1.0 : s->sdd / (s->sod - l);

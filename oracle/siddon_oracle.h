@@ -14,6 +14,10 @@
  *     fan      : the cone formula with v = 0 in the plane z = center_z; the voxel is its in-plane square
  *     curved   : cone-beam with a cylindrical detector of radius SDD around the source's vertical axis, columns equally
  *                spaced in arc length: P = S + SDD (-cos g e_s + sin g e_u) + v_r e_v with g = u_c / SDD
+ *     modular  : the paper's flexible geometry ("the 3D location of every source-detector pair, as well as an arbitrary
+ *                orientation of the detector"): view a has its own source position S_a, detector centre C_a and
+ *                orthonormal detector axes ucol_a (along columns' index) and vrow_a (along rows' index), 12 doubles per
+ *                view in `poses`; the ray of pixel (r, c) runs from S_a to C_a + u_c ucol_a + v_r vrow_a
  * (same world frame, voxel and pixel centres as the separable-footprint oracle, see sf_oracle.h).  A voxel is the
  * half-open box [lo, hi) on every axis, which only matters for a ray that runs exactly inside a face plane: it then
  * belongs to the voxel on the upper side.  A = sum over voxels, A^T = exact transpose.
@@ -30,7 +34,7 @@
 extern "C" {
 #endif
 
-enum { SDO_PARALLEL = 0, SDO_FAN = 1, SDO_CONE = 2, SDO_CONE_CURVED = 3 };
+enum { SDO_PARALLEL = 0, SDO_FAN = 1, SDO_CONE = 2, SDO_CONE_CURVED = 3, SDO_MODULAR = 4 };
 
 typedef struct {
     int32_t geom;
@@ -42,6 +46,7 @@ typedef struct {
     double  T, Tz;
     double  cx, cy, cz;
     const double *phi;
+    const double *poses;   /* SDO_MODULAR only: nviews x {S[3], C[3], ucol[3], vrow[3]}; phi is not read then */
 } sdo_scan;
 
 /* chord length (mm) of ray (view, r, c) in voxel (i, j, k) */

@@ -5,7 +5,7 @@ phantoms only.  Nothing here evaluates a projector weight, a footprint or a
 line integral: the method's arithmetic lives in the oracle and in the HIP
 library, separately.
 """
-from .configs import CTConfig, CONFIGS, config, reduced  # noqa: F401
+from .configs import CTConfig, CONFIGS, config, reduced, modular_from, perturbed_poses  # noqa: F401
 from .phantoms import (  # noqa: F401
     Ellipsoid,
     draw_ellipses_2d,

@@ -12,8 +12,8 @@ from typing import Optional
 
 import numpy as np
 
-PARALLEL, FAN, CONE, CONE_CURVED = 0, 1, 2, 3
-GEOM_NAMES = {PARALLEL: "parallel", FAN: "fan", CONE: "cone", CONE_CURVED: "cone_curved"}
+PARALLEL, FAN, CONE, CONE_CURVED, MODULAR = 0, 1, 2, 3, 4
+GEOM_NAMES = {PARALLEL: "parallel", FAN: "fan", CONE: "cone", CONE_CURVED: "cone_curved", MODULAR: "modular"}
 
 
 @dataclasses.dataclass(frozen=True)
@@ -41,6 +41,7 @@ class CTConfig:
     batch: int = 1
     start_deg: float = 0.0
     angles_override: Optional[tuple] = None   # explicit radian list (non-equispaced views)
+    poses: Optional[tuple] = None             # MODULAR only: per view (S[3], C[3], ucol[3], vrow[3]) as 12 floats
 
     def angles(self) -> np.ndarray:
         if self.angles_override is not None:
@@ -64,7 +65,8 @@ class CTConfig:
     def with_views(self, view_indices) -> "CTConfig":
         """Same scanner, only the listed views (a subset is just another angle list)."""
         ang = self.angles()[np.asarray(view_indices, dtype=np.int64)]
-        return dataclasses.replace(self, nviews=len(ang), angles_override=tuple(float(v) for v in ang))
+        poses = None if self.poses is None else tuple(self.poses[int(v)] for v in view_indices)
+        return dataclasses.replace(self, nviews=len(ang), angles_override=tuple(float(v) for v in ang), poses=poses)
 
     def replace(self, **kw) -> "CTConfig":
         return dataclasses.replace(self, **kw)
@@ -111,3 +113,41 @@ def reduced(cfg: CTConfig, factor: int, nviews: Optional[int] = None, batch: Opt
         shift_u=cfg.shift_u / factor, shift_v=cfg.shift_v / factor,
         batch=cfg.batch if batch is None else batch,
     )
+
+
+def modular_from(cfg: CTConfig) -> CTConfig:
+    """The flat-panel cone-beam scan `cfg` written as a modular one: the same sources, detector centres and axes, view
+    by view (a description of the scanner, no projector arithmetic)."""
+    assert cfg.geom == CONE
+    poses = []
+    for phi in cfg.angles():
+        es = np.array([np.cos(phi), np.sin(phi), 0.0])
+        eu = np.array([-np.sin(phi), np.cos(phi), 0.0])
+        ev = np.array([0.0, 0.0, 1.0])
+        poses.append(tuple(float(v) for v in np.concatenate([cfg.sod * es, (cfg.sod - cfg.sdd) * es, eu, ev])))
+    return cfg.replace(geom=MODULAR, name=cfg.name + "_modular", poses=tuple(poses))
+
+
+def perturbed_poses(cfg: CTConfig, seed: int, shift_mm: float = 3.0, tilt_rad: float = 0.08, upright: bool = False) -> CTConfig:
+    """A modular scan near `cfg` (cone-beam or modular): every view's source and detector centre moved by up to
+    shift_mm per axis and the detector rotated by up to tilt_rad about each of its own axes and its normal
+    (upright=True: about the vertical only, and no vertical component in the column axis)."""
+    base = cfg if cfg.geom == MODULAR else modular_from(cfg)
+    rng = np.random.default_rng([seed, 6])
+    out = []
+    for p in base.poses:
+        p = np.asarray(p, dtype=np.float64)
+        S, C, eu, ev = p[0:3].copy(), p[3:6].copy(), p[6:9].copy(), p[9:12].copy()
+        S += rng.uniform(-shift_mm, shift_mm, 3)
+        C += rng.uniform(-shift_mm, shift_mm, 3)
+        n = np.cross(eu, ev)
+        angles = rng.uniform(-tilt_rad, tilt_rad, 3)
+        axes = [ev] if upright else [ev, eu, n]
+        for axis, ang in zip(axes, angles):
+            k = axis / np.linalg.norm(axis)
+            rot = lambda w: w * np.cos(ang) + np.cross(k, w) * np.sin(ang) + k * np.dot(k, w) * (1 - np.cos(ang))
+            eu, ev = rot(eu), rot(ev)
+        ev = ev - np.dot(ev, eu) * eu
+        eu, ev = eu / np.linalg.norm(eu), ev / np.linalg.norm(ev)
+        out.append(tuple(float(v) for v in np.concatenate([S, C, eu, ev])))
+    return base.replace(name=base.name + f"_perturbed{seed}", poses=tuple(out))

@@ -13,6 +13,14 @@ import numpy as np
 
 def ray_endpoints(cfg, view, u, v):
     """(point p, unit direction d) of the ray that hits detector coordinates (u, v) mm in `view`."""
+    if cfg.geom == 4:       # modular: source S, detector centre C, column axis, row axis of this view
+        pose = np.asarray(cfg.poses[view], dtype=np.float64)
+        S, C_, eu, ev = pose[0:3], pose[3:6], pose[6:9], pose[9:12]
+        uu = np.asarray(u, dtype=np.float64)[..., None]
+        vv = np.asarray(v, dtype=np.float64)[..., None]
+        d = C_ + uu * eu + vv * ev - S
+        d = d / np.linalg.norm(d, axis=-1, keepdims=True)
+        return np.broadcast_to(S, d.shape), d
     phi = cfg.angles()[view]
     es = np.array([np.cos(phi), np.sin(phi), 0.0])
     eu = np.array([-np.sin(phi), np.cos(phi), 0.0])

@@ -100,10 +100,22 @@ CURVED_SIDDON_MUTATIONS = [
      "u = s->sdd * atan2(t, s->sod - l);", "u = s->sdd * t / (s->sod - l);"),
 ]
 
+MODULAR_SIDDON_MUTATIONS = [
+    ("modular: detector axes swapped",
+     "ray->d[a] = C[a] + pu_ * uc[a] + pv_ * vr[a] - S[a];", "ray->d[a] = C[a] + pu_ * vr[a] + pv_ * uc[a] - S[a];"),
+    ("modular: rays leave from the detector centre",
+     "ray->o[a] = S[a];\n            ray->d[a] = C[a]", "ray->o[a] = C[a];\n            ray->d[a] = C[a]"),
+    ("modular: voxel's pixel search swaps the detector axes",
+     "u += H * uc[a]; v += H * vr[a];", "u += H * vr[a]; v += H * uc[a];"),
+    ("ray walk never takes z as its marching axis",
+     "if (ray->ndim == 3 && fabs(ray->d[2]) > fabs(ray->d[major])) major = 2;", ";"),
+]
+
 CASES = ([("sf_oracle.c", "test_oracle_pins.py") + m for m in MUTATIONS]
          + [("siddon_oracle.c", "test_siddon_pins.py") + m for m in SIDDON_MUTATIONS]
          + [("sf_oracle.c", "test_curved_pins.py") + m for m in CURVED_SF_MUTATIONS]
-         + [("siddon_oracle.c", "test_curved_pins.py") + m for m in CURVED_SIDDON_MUTATIONS])
+         + [("siddon_oracle.c", "test_curved_pins.py") + m for m in CURVED_SIDDON_MUTATIONS]
+         + [("siddon_oracle.c", "test_modular_pins.py") + m for m in MODULAR_SIDDON_MUTATIONS])
 
 
 @pytest.mark.parametrize("source,pins,what,old,new", CASES, ids=[c[0][:-9] + ": " + c[2] for c in CASES])
