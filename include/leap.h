@@ -47,8 +47,13 @@ extern "C" {
 /* Scanner families ("CT Projection Models and Geometries": parallel-beam, axial cone-beam with a planar or a curved
  * detector; fan-beam is the one-row, one-slice case of the flat-panel cone-beam scanner).  LEAP_CONE_CURVED: the
  * detector is the cylinder of radius sdd around the vertical line through the source; columns are equally spaced in
- * arc length (pixel_u mm), so pixel (r, c) sits at fan angle u_c / sdd and height v_r on the cylinder. */
-enum { LEAP_PARALLEL = 0, LEAP_FAN = 1, LEAP_CONE = 2, LEAP_CONE_CURVED = 3 };
+ * arc length (pixel_u mm), so pixel (r, c) sits at fan angle u_c / sdd and height v_r on the cylinder.
+ * LEAP_MODULAR: the flexible geometry of the same section (sources and detectors at any position and orientation):
+ * every view has its own pose, 12 doubles in `poses`: source position S, detector centre C, unit vector along the
+ * column index, unit vector along the row index (orthogonal to each other); pixel (r, c) sits at
+ * C + u_c ucol + v_r vrow.  sod, sdd and angles_rad are not read.  Built for LEAP_MODEL_SIDDON; with
+ * LEAP_MODEL_SF leap_geometry_create returns LEAP_UNSUPPORTED. */
+enum { LEAP_PARALLEL = 0, LEAP_FAN = 1, LEAP_CONE = 2, LEAP_CONE_CURVED = 3, LEAP_MODULAR = 4 };
 
 /* Projector models ("CT Projection Models and Geometries").  LEAP_MODEL_SF: separable footprints.
  * LEAP_MODEL_SIDDON: weight = length (mm) of the ray through the pixel centre inside the voxel; a voxel is
@@ -68,7 +73,7 @@ enum {
  * and source-to-object distance, horizontal/vertical detector shift, voxel counts, voxel sizes,
  * volume centre.  Host memory; copied by leap_geometry_create. */
 typedef struct {
-    int32_t type;                 /* LEAP_PARALLEL / LEAP_FAN / LEAP_CONE / LEAP_CONE_CURVED */
+    int32_t type;                 /* LEAP_PARALLEL / LEAP_FAN / LEAP_CONE / LEAP_CONE_CURVED / LEAP_MODULAR */
     int32_t nviews, nrows, ncols; /* projections, detector rows (v), detector columns (u) */
     int32_t nx, ny, nz;           /* voxels */
     double  pixel_v, pixel_u;     /* mm: pixel height, pixel width */
@@ -76,8 +81,9 @@ typedef struct {
     double  sod, sdd;             /* mm: source to rotation axis, source to detector; ignored for PARALLEL */
     double  voxel_xy, voxel_z;    /* mm: in-plane voxels are square */
     double  center_x, center_y, center_z; /* mm: volume centre */
-    const double *angles_rad;     /* nviews view angles, any spacing */
+    const double *angles_rad;     /* nviews view angles, any spacing (not read for LEAP_MODULAR) */
     int32_t model;                /* LEAP_MODEL_SF (0, so a zero-filled struct keeps the footprint model) / LEAP_MODEL_SIDDON */
+    const double *poses;          /* LEAP_MODULAR only: nviews x 12 doubles {S[3], C[3], ucol[3], vrow[3]}, mm; else ignored */
 } leap_geometry_desc;
 
 typedef struct leap_geometry leap_geometry;   /* opaque; owned by the library */

@@ -12,7 +12,7 @@ from typing import Optional, Sequence
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("LEAP_LIB_PATH") or os.path.join(HERE, "libleap_hip.so")   # override: testing a variant build
 
-LEAP_PARALLEL, LEAP_FAN, LEAP_CONE, LEAP_CONE_CURVED = 0, 1, 2, 3
+LEAP_PARALLEL, LEAP_FAN, LEAP_CONE, LEAP_CONE_CURVED, LEAP_MODULAR = 0, 1, 2, 3, 4
 LEAP_MODEL_SF, LEAP_MODEL_SIDDON = 0, 1
 MODELS = {"sf": LEAP_MODEL_SF, "siddon": LEAP_MODEL_SIDDON}
 LEAP_OK, LEAP_INVALID_ARG, LEAP_BAD_GEOMETRY, LEAP_HIP_ERROR, LEAP_UNSUPPORTED = 0, -1, -2, -3, -4
@@ -34,6 +34,7 @@ class leap_geometry_desc(C.Structure):
         ("center_x", C.c_double), ("center_y", C.c_double), ("center_z", C.c_double),
         ("angles_rad", C.POINTER(C.c_double)),
         ("model", C.c_int32),
+        ("poses", C.POINTER(C.c_double)),
     ]
 
 
@@ -98,15 +99,23 @@ def _check(lib, status: int) -> None:
 def make_desc(*, type: int, nviews: int, nrows: int, ncols: int, nx: int, ny: int, nz: int,
               pixel_v: float, pixel_u: float, voxel_xy: float, voxel_z: float, angles_rad: Sequence[float],
               shift_v: float = 0.0, shift_u: float = 0.0, sod: float = 0.0, sdd: float = 0.0,
-              center_x: float = 0.0, center_y: float = 0.0, center_z: float = 0.0, model: int = LEAP_MODEL_SF):
-    """(desc, keep-alive) from keyword arguments named like the C struct's fields."""
+              center_x: float = 0.0, center_y: float = 0.0, center_z: float = 0.0, model: int = LEAP_MODEL_SF,
+              poses=None):
+    """(desc, keep-alive) from keyword arguments named like the C struct's fields; poses: nviews rows of 12 numbers."""
     ang = (C.c_double * len(angles_rad))(*[float(a) for a in angles_rad])
     if len(angles_rad) != nviews:
         raise ValueError("angles_rad must hold nviews entries")
+    pp, flat = C.POINTER(C.c_double)(), None
+    if poses is not None:
+        vals = [float(v) for row in poses for v in row]
+        if len(vals) != 12 * nviews:
+            raise ValueError("poses must hold nviews rows of 12 numbers")
+        flat = (C.c_double * len(vals))(*vals)
+        pp = C.cast(flat, C.POINTER(C.c_double))
     d = leap_geometry_desc(type, nviews, nrows, ncols, nx, ny, nz, pixel_v, pixel_u, shift_v, shift_u,
                            sod, sdd, voxel_xy, voxel_z, center_x, center_y, center_z,
-                           C.cast(ang, C.POINTER(C.c_double)), model)
-    return d, ang
+                           C.cast(ang, C.POINTER(C.c_double)), model, pp)
+    return d, (ang, flat)
 
 
 def desc_from_config(cfg, model: int = LEAP_MODEL_SF):
@@ -115,7 +124,7 @@ def desc_from_config(cfg, model: int = LEAP_MODEL_SF):
                      nz=cfg.nz, pixel_v=cfg.pixel_v, pixel_u=cfg.pixel_u, voxel_xy=cfg.voxel_xy,
                      voxel_z=cfg.voxel_z, angles_rad=list(cfg.angles()), shift_v=cfg.shift_v, shift_u=cfg.shift_u,
                      sod=cfg.sod, sdd=cfg.sdd, center_x=cfg.center_x, center_y=cfg.center_y, center_z=cfg.center_z,
-                     model=model)
+                     model=model, poses=getattr(cfg, "poses", None) if cfg.geom == LEAP_MODULAR else None)
 
 
 def leap_geometry_create(desc: leap_geometry_desc, lib=None) -> int:

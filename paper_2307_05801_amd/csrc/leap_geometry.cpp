@@ -96,11 +96,76 @@ static void build_ray_table(leap_geometry *G)
     G->sd_max_axial_slope = max_dh * vmax;
 }
 
+// Modular geometry: per-view poses instead of the angle list; only the fields the modular kernels read are filled.
+static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
+{
+    if (!d->poses) return invalid("poses is null");
+    if (d->model != LEAP_MODEL_SIDDON) {
+        leap_set_error("the footprint model is not built for the modular geometry; use LEAP_MODEL_SIDDON");
+        return LEAP_UNSUPPORTED;
+    }
+    if (d->nviews > 65535 || (double)d->nx * d->ny * d->nz >= 4294967296.0 ||
+        (double)d->nviews * d->nrows * d->ncols >= 4294967296.0 || d->ny > 262140 || d->nz > 65535 || d->nrows > 262140) {
+        leap_set_error("sizes beyond what one launch covers");
+        return LEAP_UNSUPPORTED;
+    }
+    const double half[3] = {0.5 * d->nx * d->voxel_xy, 0.5 * d->ny * d->voxel_xy, 0.5 * d->nz * d->voxel_z};
+    const double ctr[3] = {d->center_x, d->center_y, d->center_z};
+    for (int a = 0; a < d->nviews; ++a) {
+        const double *p = d->poses + 12 * (size_t)a;
+        for (int q = 0; q < 12; ++q)
+            if (!std::isfinite(p[q])) return invalid("poses must be finite");
+        const double uu = p[6] * p[6] + p[7] * p[7] + p[8] * p[8], vv = p[9] * p[9] + p[10] * p[10] + p[11] * p[11];
+        const double uv = p[6] * p[9] + p[7] * p[10] + p[8] * p[11];
+        if (std::fabs(uu - 1.0) > 1e-9 || std::fabs(vv - 1.0) > 1e-9 || std::fabs(uv) > 1e-9)
+            return invalid("detector axes must be orthonormal");
+        bool inside = true;
+        for (int q = 0; q < 3; ++q) inside = inside && std::fabs(p[q] - ctr[q]) <= half[q];
+        if (inside) {
+            leap_set_error("a source lies inside the volume");
+            return LEAP_BAD_GEOMETRY;
+        }
+    }
+    leap_geometry *G = new (std::nothrow) leap_geometry;
+    if (!G) return invalid("out of host memory");
+    G->desc = *d;
+    G->desc.angles_rad = nullptr;
+    SfGeom &g = G->g;
+    std::memset(&g, 0, sizeof(g));
+    g.type = d->type; g.model = d->model;
+    g.nviews = d->nviews; g.nrows = d->nrows; g.ncols = d->ncols;
+    g.nx = d->nx; g.ny = d->ny; g.nz = d->nz;
+    g.Td = d->voxel_xy; g.Tzd = d->voxel_z;
+    g.x0d = d->center_x - 0.5 * (d->nx - 1) * d->voxel_xy;
+    g.y0d = d->center_y - 0.5 * (d->ny - 1) * d->voxel_xy;
+    g.zlo0d = d->center_z - 0.5 * d->nz * d->voxel_z;
+    g.col_offd = 0.5 * (d->ncols - 1) - d->shift_u;
+    g.row_offd = 0.5 * (d->nrows - 1) - d->shift_v + 0.5;
+    g.v0d = (-0.5 * (d->nrows - 1) + d->shift_v) * d->pixel_v;
+    g.pvd = d->pixel_v;
+    g.pu_d = d->pixel_u;
+    g.T = (float)d->voxel_xy; g.Tz = (float)d->voxel_z; g.pu = (float)d->pixel_u; g.pv = (float)d->pixel_v;
+    G->poses.resize(d->nviews);
+    std::memcpy(G->poses.data(), d->poses, sizeof(MdPose) * (size_t)d->nviews);
+    G->desc.poses = reinterpret_cast<const double *>(G->poses.data());
+    hipError_t e = hipGetDevice(&G->device);
+    if (e == hipSuccess) e = hipMalloc((void **)&G->d_poses, sizeof(MdPose) * (size_t)d->nviews);
+    if (e == hipSuccess) e = hipMemcpy(G->d_poses, G->poses.data(), sizeof(MdPose) * (size_t)d->nviews, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        if (G->d_poses) (void)hipFree(G->d_poses);
+        delete G;
+        return leap_hip_fail(e, "uploading the pose table");
+    }
+    *out = G;
+    return LEAP_OK;
+}
+
 extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry **out)
 {
     if (out) *out = nullptr;
     if (!d || !out) return invalid("null descriptor or output pointer");
-    if (d->type != LEAP_PARALLEL && d->type != LEAP_FAN && d->type != LEAP_CONE && d->type != LEAP_CONE_CURVED)
+    if (d->type != LEAP_PARALLEL && d->type != LEAP_FAN && d->type != LEAP_CONE && d->type != LEAP_CONE_CURVED &&
+        d->type != LEAP_MODULAR)
         return invalid("unknown geometry type");
     if (d->model != LEAP_MODEL_SF && d->model != LEAP_MODEL_SIDDON) return invalid("unknown projector model");
     if (d->nviews <= 0 || d->nrows <= 0 || d->ncols <= 0) return invalid("nviews, nrows and ncols must be positive");
@@ -110,6 +175,7 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
     if (!std::isfinite(d->shift_u) || !std::isfinite(d->shift_v)) return invalid("detector shifts must be finite");
     if (!std::isfinite(d->center_x) || !std::isfinite(d->center_y) || !std::isfinite(d->center_z))
         return invalid("volume centre must be finite");
+    if (d->type == LEAP_MODULAR) return create_modular(d, out);
     if (!d->angles_rad) return invalid("angles_rad is null");
     for (int a = 0; a < d->nviews; ++a)
         if (!std::isfinite(d->angles_rad[a])) return invalid("view angles must be finite");
@@ -179,6 +245,7 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
     g.model = d->model;
     g.v0d = (-0.5 * (d->nrows - 1) + d->shift_v) * d->pixel_v;
     g.pvd = d->pixel_v;
+    g.pu_d = d->pixel_u;
     g.zk0d = d->type == LEAP_FAN ? 0.5 : -g.zlo0d / d->voxel_z;
 
     G->views.resize(d->nviews);
@@ -403,12 +470,17 @@ extern "C" void leap_geometry_destroy(leap_geometry *G)
     if (G->d_views) (void)hipFree(G->d_views);
     if (G->d_volz) (void)hipFree(G->d_volz);
     if (G->d_raycols) (void)hipFree(G->d_raycols);
+    if (G->d_poses) (void)hipFree(G->d_poses);
     delete G;
 }
 
 extern "C" int leap_geometry_describe(const leap_geometry *G, char *buf, int32_t cap)
 {
     if (!G || !buf || cap <= 0) return invalid("null handle or buffer");
+    if (G->g.type == SF_MODULAR) {
+        std::snprintf(buf, (size_t)cap, "type=4 model=siddon A=general AT=general (modular: one thread per ray / per voxel)");
+        return LEAP_OK;
+    }
     if (G->g.model == SF_MODEL_SIDDON) {
         std::snprintf(buf, (size_t)cap, "type=%d model=siddon A=%s(rg=%d) AT=%s(nc=%d,zc=%d,window=%dx%d) axial-slope<=%.3f "
                       "cols/voxel<=%.2f", G->g.type, G->sd_columns ? "columns" : "general", G->fp_rg,

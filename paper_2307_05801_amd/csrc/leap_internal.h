@@ -9,6 +9,7 @@
 #include "../../include/leap.h"
 #include "sf_types.h"
 #include "sd_ray.h"
+#include "md_siddon.h"
 
 struct leap_geometry {
     leap_geometry_desc desc;            // caller's parameters (angles_rad re-pointed at `angles`)
@@ -36,6 +37,9 @@ struct leap_geometry {
     std::vector<SdRayCol> raycols;
     SdRayCol *d_raycols = nullptr;
     double sd_max_axial_slope = 0;      // largest |dZ/dX| of any ray: voxels of z crossed per slab
+    // modular geometry: per-view poses, host copy and device copy
+    std::vector<MdPose> poses;
+    MdPose *d_poses = nullptr;
     bool sd_columns = false;            // wave-per-column forward kernel (needs the scratch copy and slope <= 1)
 };
 

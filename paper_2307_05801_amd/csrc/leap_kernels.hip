@@ -74,6 +74,28 @@ __global__ __launch_bounds__(256) void sd_backproject_general(SfGeom g, const Sf
     vol[((size_t)k * g.ny + j) * g.nx + i] = sd_backproject_voxel(g, views, rays, sino, i, j, k);
 }
 
+// Modular geometry, Siddon model: one thread per ray / per voxel.  Same grids as the general Siddon kernels.
+__global__ __launch_bounds__(256) void md_project_general(SfGeom g, const MdPose *__restrict__ poses,
+                                                          const float *__restrict__ vol, float *__restrict__ sino)
+{
+    const int c = blockIdx.x * 64 + threadIdx.x;
+    const int r = blockIdx.y * 4 + threadIdx.y;
+    const int a = blockIdx.z;
+    if (c >= g.ncols || r >= g.nrows) return;
+    const MdPose P = poses[a];
+    sino[((size_t)a * g.nrows + r) * g.ncols + c] = md_project_ray(g, P, vol, r, c);
+}
+
+__global__ __launch_bounds__(256) void md_backproject_general(SfGeom g, const MdPose *__restrict__ poses,
+                                                              const float *__restrict__ sino, float *__restrict__ vol)
+{
+    const int i = blockIdx.x * 64 + threadIdx.x;
+    const int j = blockIdx.y * 4 + threadIdx.y;
+    const int k = blockIdx.z;
+    if (i >= g.nx || j >= g.ny) return;
+    vol[((size_t)k * g.ny + j) * g.nx + i] = md_backproject_voxel(g, poses, sino, i, j, k);
+}
+
 static inline unsigned cdiv(unsigned a, unsigned b) { return (a + b - 1) / b; }
 
 constexpr int SD_WAVES = 4;   // adjacent detector columns per workgroup of the Siddon forward kernel
@@ -95,6 +117,12 @@ static void launch_sd_columns(const leap_geometry *G, float *d_sino, hipStream_t
 static int launch_sd_project(const leap_geometry *G, const float *d_vol, float *d_sino, hipStream_t stream)
 {
     const SfGeom &g = G->g;
+    if (g.type == SF_MODULAR) {        // sizes were checked against the grid limits at creation
+        dim3 grid(cdiv(g.ncols, 64), cdiv(g.nrows, 4), g.nviews);
+        hipLaunchKernelGGL(md_project_general, grid, dim3(64, 4, 1), 0, stream, g, G->d_poses, d_vol, d_sino);
+        LEAP_HIP_CHECK(hipGetLastError());
+        return LEAP_OK;
+    }
     if (G->sd_columns) {
         dim3 tgrid(cdiv(g.nx, 32), cdiv(g.nz, 32), g.ny);
         hipLaunchKernelGGL(sf_volume_to_columns, tgrid, dim3(32, 8, 1), 0, stream, d_vol, G->d_volz, g.nx, g.ny, g.nz, G->nzp);
@@ -143,6 +171,12 @@ static bool launch_sd_shape(const leap_geometry *G, const float *d_sino, float *
 static int launch_sd_backproject(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
 {
     const SfGeom &g = G->g;
+    if (g.type == SF_MODULAR) {
+        dim3 grid(cdiv(g.nx, 64), cdiv(g.ny, 4), g.nz);
+        hipLaunchKernelGGL(md_backproject_general, grid, dim3(64, 4, 1), 0, stream, g, G->d_poses, d_sino, d_vol);
+        LEAP_HIP_CHECK(hipGetLastError());
+        return LEAP_OK;
+    }
     if (G->bp_tiled) {
         bool ok = false;
         switch (G->bp_nc) {

@@ -14,7 +14,7 @@
 
 #include <stdint.h>
 
-enum { SF_PARALLEL = 0, SF_FAN = 1, SF_CONE = 2, SF_CONE_CURVED = 3 };   // CURVED: cylindrical detector, columns equally spaced in arc length
+enum { SF_PARALLEL = 0, SF_FAN = 1, SF_CONE = 2, SF_CONE_CURVED = 3, SF_MODULAR = 4 };   // CURVED: cylindrical detector, columns equally spaced in arc length; MODULAR: per-view poses
 enum { SF_MODEL_FOOTPRINT = 0, SF_MODEL_SIDDON = 1 };
 
 struct SfGeom {
@@ -34,6 +34,7 @@ struct SfGeom {
     double col_offd;      // (ncols-1)/2 - shift_u
     double row_offd;      // (nrows-1)/2 - shift_v + 1/2
     double v0d, pvd;      // v (mm) of row 0's centre and the row pitch: v_r = v0d + r pvd
+    double pu_d;          // column pitch, mm
     double zk0d;          // kappa of the plane z = 0: -zlo0 / Tz  (fan-beam: 1/2, the middle of the only slice)
     // float: relative quantities
     float T, Tz;

@@ -10,7 +10,8 @@ import numpy as np
 import pytest
 
 from paper_2307_05801_amd import binding as B
-from synthetic import CTConfig, config, reduced, standard_volume, uniform_sinogram, uniform_volume
+from synthetic import (CTConfig, config, modular_from, perturbed_poses, reduced, standard_volume, uniform_sinogram,
+                       uniform_volume)
 from synthetic.configs import CONE, CONE_CURVED, FAN, PARALLEL
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -213,3 +214,49 @@ def test_random_geometries_on_cpu(host, oracle_mod, seed):
     B.leap_geometry_destroy(h, host)
     assert rel_l2(ax, ref) <= TOL, desc
     assert rel_l2(aty, oracle_mod.backproject(cfg, y)) <= TOL, desc
+
+
+MODULAR_CASES = {
+    "cone_as_modular": lambda: modular_from(reduced(config(3), 16, nviews=10).replace(shift_u=0.123)),
+    "tilted_modules": lambda: perturbed_poses(reduced(config(3), 16, nviews=9).replace(nx=29, ny=35, nz=22, nrows=27, ncols=31),
+                                              3, shift_mm=20.0, tilt_rad=0.25),
+    "looking_down": lambda: CTConfig("down", 4, nviews=2, arc_deg=360.0, nrows=20, ncols=24, pixel_v=1.5, pixel_u=1.4,
+                                     nx=18, ny=16, nz=12, voxel_xy=1.0, voxel_z=1.3, shift_u=0.2, shift_v=-0.3,
+                                     poses=((0.3, -0.2, 40.0, 0.0, 0.0, -30.0, 1.0, 0.0, 0.0, 0.0, 1.0, 0.0),
+                                            (6.0, 2.0, 38.0, -2.0, 1.0, -28.0, 0.8, 0.6, 0.0, -0.6, 0.8, 0.0))),
+}
+
+
+@pytest.mark.parametrize("name", list(MODULAR_CASES))
+def test_modular_siddon_bodies_match_oracle_on_cpu(host, oracle_mod, name):
+    cfg = MODULAR_CASES[name]()
+    x = uniform_volume(cfg, 5)[0]
+    y = uniform_sinogram(cfg, 6)[0]
+    h = handle(host, cfg, B.LEAP_MODEL_SIDDON)
+    ax = np.zeros(cfg.sino_shape, np.float32)
+    aty = np.zeros(cfg.vol_shape, np.float32)
+    B.leap_project(h, x.ctypes.data, ax.ctypes.data, 1, 0, host)
+    B.leap_backproject(h, y.ctypes.data, aty.ctypes.data, 1, 0, host)
+    B.leap_geometry_destroy(h, host)
+    sd = oracle_mod.siddon
+    assert rel_l2(ax, sd.project(cfg, x)) <= TOL
+    assert rel_l2(aty, sd.backproject(cfg, y)) <= TOL
+    if name == "cone_as_modular":
+        cone = reduced(config(3), 16, nviews=10).replace(shift_u=0.123)
+        assert rel_l2(ax, sd.project(cone, x)) <= TOL
+
+
+def test_modular_argument_checks(host):
+    cfg = MODULAR_CASES["looking_down"]()
+    d, keep = B.desc_from_config(cfg, B.LEAP_MODEL_SF)
+    hnd = C.c_void_p()
+    assert host.leap_geometry_create(C.byref(d), C.byref(hnd)) == B.LEAP_UNSUPPORTED      # footprints: not built
+    d, keep = B.desc_from_config(cfg, B.LEAP_MODEL_SIDDON)
+    d.poses = C.POINTER(C.c_double)()
+    assert host.leap_geometry_create(C.byref(d), C.byref(hnd)) == B.LEAP_INVALID_ARG
+    skew = cfg.replace(poses=((0.3, -0.2, 40.0, 0.0, 0.0, -30.0, 1.0, 0.0, 0.0, 0.1, 1.0, 0.0),) * 2)
+    d, keep = B.desc_from_config(skew, B.LEAP_MODEL_SIDDON)
+    assert host.leap_geometry_create(C.byref(d), C.byref(hnd)) == B.LEAP_INVALID_ARG
+    inside = cfg.replace(poses=((0.3, -0.2, 1.0, 0.0, 0.0, -30.0, 1.0, 0.0, 0.0, 0.0, 1.0, 0.0),) * 2)
+    d, keep = B.desc_from_config(inside, B.LEAP_MODEL_SIDDON)
+    assert host.leap_geometry_create(C.byref(d), C.byref(hnd)) == B.LEAP_BAD_GEOMETRY
