@@ -22,14 +22,39 @@ static double vox_z(const sfo_scan *s, int k) { return s->cz + (k - 0.5 * (s->nz
 static double pix_u(const sfo_scan *s, int c) { return (c - 0.5 * (s->ncols - 1) + s->shift_u) * s->pu; }
 static double pix_v(const sfo_scan *s, int r) { return (r - 0.5 * (s->nrows - 1) + s->shift_v) * s->pv; }
 
-/* detector-u coordinate of the in-plane point (x,y) seen from view angle phi */
-static double project_u(const sfo_scan *s, double cphi, double sphi, double x, double y)
+/* The frame of one view: unit vectors e_s = (cphi, sphi, 0) (towards the source side) and e_u = (-sphi, cphi, 0), the
+ * source at l = lS along e_s, t = tS along e_u, height zS; the detector plane at l = lS - sdd with its centre at
+ * t = tC, height zC.  The circular scanners have tS = zS = tC = zC = 0, lS = SOD.  Modular scans (upright modules
+ * only: column axis horizontal, row axis +z) read these from the view's pose. */
+typedef struct { double cphi, sphi, lS, tS, zS, sdd, tC, zC; } view_frame;
+
+static int frame_of(const sfo_scan *s, int view, view_frame *f)
 {
-    double t = -x * sphi + y * cphi;
+    if (s->geom == SFO_MODULAR) {
+        const double *S = s->poses + 12 * (int64_t)view, *C = S + 3, *uc = S + 6, *vr = S + 9;
+        if (fabs(uc[2]) > 1e-12 || fabs(vr[0]) > 1e-12 || fabs(vr[1]) > 1e-12 || fabs(vr[2] - 1.0) > 1e-12) return -1;
+        f->cphi = uc[1]; f->sphi = -uc[0];
+        f->lS = S[0] * f->cphi + S[1] * f->sphi;
+        f->tS = -S[0] * f->sphi + S[1] * f->cphi;
+        f->zS = S[2];
+        f->sdd = f->lS - (C[0] * f->cphi + C[1] * f->sphi);
+        f->tC = -C[0] * f->sphi + C[1] * f->cphi;
+        f->zC = C[2];
+        return f->sdd > 0.0 ? 0 : -1;
+    }
+    f->cphi = cos(s->phi[view]); f->sphi = sin(s->phi[view]);
+    f->lS = s->sod; f->tS = 0.0; f->zS = 0.0; f->sdd = s->sdd; f->tC = 0.0; f->zC = 0.0;
+    return 0;
+}
+
+/* detector-u coordinate (measured from the detector centre) of the in-plane point (x,y) in a view */
+static double project_u(const sfo_scan *s, const view_frame *f, double x, double y)
+{
+    double t = -x * f->sphi + y * f->cphi;
     if (s->geom == SFO_PARALLEL) return t;
-    double l = x * cphi + y * sphi;
+    double l = x * f->cphi + y * f->sphi;
     if (s->geom == SFO_CONE_CURVED) return s->sdd * atan2(t, s->sod - l);     /* arc length on the cylinder */
-    return s->sdd * t / (s->sod - l);
+    return f->tS + f->sdd * (t - f->tS) / (f->lS - l) - f->tC;
 }
 
 static void sort4(double a[4])
@@ -44,24 +69,27 @@ static void sort4(double a[4])
 
 /* ---- step 1: knots ---------------------------------------------------------------- */
 
-static void knots_xy(const sfo_scan *s, double phi, double x, double y, double tau[4], double *mag)
+static void knots_xy(const sfo_scan *s, int view, double x, double y, double tau[4], double *mag)
 {
-    double cphi = cos(phi), sphi = sin(phi), h = 0.5 * s->T;
-    tau[0] = project_u(s, cphi, sphi, x - h, y - h);
-    tau[1] = project_u(s, cphi, sphi, x + h, y - h);
-    tau[2] = project_u(s, cphi, sphi, x - h, y + h);
-    tau[3] = project_u(s, cphi, sphi, x + h, y + h);
+    view_frame f;
+    frame_of(s, view, &f);
+    double h = 0.5 * s->T;
+    tau[0] = project_u(s, &f, x - h, y - h);
+    tau[1] = project_u(s, &f, x + h, y - h);
+    tau[2] = project_u(s, &f, x - h, y + h);
+    tau[3] = project_u(s, &f, x + h, y + h);
     sort4(tau);
     if (mag) {
+        double l = x * f.cphi + y * f.sphi, t = -x * f.sphi + y * f.cphi;
         if (s->geom == SFO_PARALLEL) *mag = 1.0;
-        else if (s->geom == SFO_CONE_CURVED) *mag = s->sdd / hypot(s->sod - (x * cphi + y * sphi), -x * sphi + y * cphi);
-        else *mag = s->sdd / (s->sod - (x * cphi + y * sphi));
+        else if (s->geom == SFO_CONE_CURVED) *mag = s->sdd / hypot(s->sod - l, t);
+        else *mag = f.sdd / (f.lS - l);
     }
 }
 
 void sfo_knots(const sfo_scan *s, int view, int i, int j, double tau[4], double *mag)
 {
-    knots_xy(s, s->phi[view], vox_x(s, i), vox_y(s, j), tau, mag);
+    knots_xy(s, view, vox_x(s, i), vox_y(s, j), tau, mag);
 }
 
 /* ---- step 2: trapezoid and F_u ---------------------------------------------------- */
@@ -84,11 +112,22 @@ static double footprint_u(const sfo_scan *s, const double tau[4], int c)
 
 /* ---- step 3: F_v ------------------------------------------------------------------ */
 
-static double footprint_v(const sfo_scan *s, double mag, int k, int r)
+/* axial interval of voxel k on the detector (v measured from the detector centre): the voxel's faces magnified about
+ * the source height */
+static void axial_interval(const sfo_scan *s, int view, double mag, int k, double *vlo, double *vhi)
+{
+    view_frame f;
+    frame_of(s, view, &f);
+    double z = vox_z(s, k);
+    *vlo = f.zS + mag * (z - 0.5 * s->Tz - f.zS) - f.zC;
+    *vhi = f.zS + mag * (z + 0.5 * s->Tz - f.zS) - f.zC;
+}
+
+static double footprint_v(const sfo_scan *s, int view, double mag, int k, int r)
 {
     if (s->geom == SFO_FAN) return 1.0;
-    double z = vox_z(s, k);
-    double vlo = mag * (z - 0.5 * s->Tz), vhi = mag * (z + 0.5 * s->Tz);
+    double vlo, vhi;
+    axial_interval(s, view, mag, k, &vlo, &vhi);
     double vr = pix_v(s, r);
     double lo = fmax(vr - 0.5 * s->pv, vlo), hi = fmin(vr + 0.5 * s->pv, vhi);
     return fmax(0.0, hi - lo) / s->pv;
@@ -96,20 +135,24 @@ static double footprint_v(const sfo_scan *s, double mag, int k, int r)
 
 /* ---- step 4: amplitude ------------------------------------------------------------ */
 
-static double amplitude(const sfo_scan *s, double phi, int r, int c)
+static double amplitude(const sfo_scan *s, int view, int r, int c)
 {
-    double cphi = cos(phi), sphi = sin(phi);
+    view_frame f;
+    frame_of(s, view, &f);
+    double cphi = f.cphi, sphi = f.sphi;
     if (s->geom == SFO_PARALLEL) return s->T / fmax(fabs(cphi), fabs(sphi));
     double u = pix_u(s, c);
     double v = (s->geom == SFO_FAN) ? 0.0 : pix_v(s, r);
-    double dx = -s->sdd * cphi - u * sphi;
-    double dy = -s->sdd * sphi + u * cphi;
+    /* pixel minus source in the view's frame: -sdd along e_s, (u + tC - tS) along e_u, (v + zC - zS) along z */
+    double du = u + f.tC - f.tS, dz = v + f.zC - f.zS;
+    double dx = -f.sdd * cphi - du * sphi;
+    double dy = -f.sdd * sphi + du * cphi;
     if (s->geom == SFO_CONE_CURVED) {            /* pixel at fan angle gamma = u / SDD on the cylinder */
         double gam = u / s->sdd;
         dx = s->sdd * (-cos(gam) * cphi - sin(gam) * sphi);
         dy = s->sdd * (-cos(gam) * sphi + sin(gam) * cphi);
     }
-    double len = sqrt(dx * dx + dy * dy + v * v);
+    double len = sqrt(dx * dx + dy * dy + dz * dz);
     return s->T * len / fmax(fabs(dx), fabs(dy));
 }
 
@@ -121,8 +164,8 @@ double sfo_weight(const sfo_scan *s, int view, int r, int c, int i, int j, int k
     double tau[4], mag;
     sfo_knots(s, view, i, j, tau, &mag);
     double fu = footprint_u(s, tau, c);
-    double fv = footprint_v(s, mag, k, r);
-    double am = amplitude(s, s->phi[view], r, c);
+    double fv = footprint_v(s, view, mag, k, r);
+    double am = amplitude(s, view, r, c);
     if (Fu) *Fu = fu;
     if (Fv) *Fv = fv;
     if (amp) *amp = am;
@@ -169,7 +212,7 @@ int sfo_project(const sfo_scan *s, const float *vol, double *sino)
         double *y = sino + a * per_view;
         double *amp = (double *)malloc(sizeof(double) * per_view);   /* amp depends on the ray only */
         for (int r = 0; r < s->nrows; ++r)
-            for (int c = 0; c < s->ncols; ++c) amp[(int64_t)r * s->ncols + c] = amplitude(s, s->phi[a], r, c);
+            for (int c = 0; c < s->ncols; ++c) amp[(int64_t)r * s->ncols + c] = amplitude(s, a, r, c);
         for (int j = 0; j < s->ny; ++j)
             for (int i = 0; i < s->nx; ++i) {
                 double tau[4], mag;
@@ -183,11 +226,12 @@ int sfo_project(const sfo_scan *s, const float *vol, double *sino)
                         double x = vol[((int64_t)k * s->ny + j) * s->nx + i];
                         int r0 = 0, r1 = 0;
                         if (s->geom != SFO_FAN) {
-                            double z = vox_z(s, k);
-                            candidates(mag * (z - 0.5 * s->Tz), mag * (z + 0.5 * s->Tz), s->pv, s->shift_v, s->nrows, &r0, &r1);
+                            double vlo, vhi;
+                            axial_interval(s, a, mag, k, &vlo, &vhi);
+                            candidates(vlo, vhi, s->pv, s->shift_v, s->nrows, &r0, &r1);
                         }
                         for (int r = r0; r <= r1; ++r) {
-                            double fv = footprint_v(s, mag, k, r);
+                            double fv = footprint_v(s, a, mag, k, r);
                             if (fv <= 0.0) continue;
                             y[(int64_t)r * s->ncols + c] += amp[(int64_t)r * s->ncols + c] * fu * fv * x;
                         }
@@ -207,7 +251,7 @@ int sfo_project_rays(const sfo_scan *s, const float *vol, int64_t n, const int64
         int c = (int)(id % s->ncols);
         int r = (int)((id / s->ncols) % s->nrows);
         int a = (int)(id / ((int64_t)s->ncols * s->nrows));
-        double am = amplitude(s, s->phi[a], r, c), acc = 0.0;
+        double am = amplitude(s, a, r, c), acc = 0.0;
         for (int j = 0; j < s->ny; ++j)
             for (int i = 0; i < s->nx; ++i) {
                 double tau[4], mag;
@@ -215,7 +259,7 @@ int sfo_project_rays(const sfo_scan *s, const float *vol, int64_t n, const int64
                 double fu = footprint_u(s, tau, c);
                 if (fu <= 0.0) continue;
                 for (int k = 0; k < s->nz; ++k) {
-                    double fv = footprint_v(s, mag, k, r);
+                    double fv = footprint_v(s, a, mag, k, r);
                     if (fv > 0.0) acc += am * fu * fv * vol[((int64_t)k * s->ny + j) * s->nx + i];
                 }
             }
@@ -236,16 +280,17 @@ static double backproject_one(const sfo_scan *s, const float *sino, int i, int j
         int c0, c1, r0 = 0, r1 = 0;
         candidates(tau[0], tau[3], s->pu, s->shift_u, s->ncols, &c0, &c1);
         if (s->geom != SFO_FAN) {
-            double z = vox_z(s, k);
-            candidates(mag * (z - 0.5 * s->Tz), mag * (z + 0.5 * s->Tz), s->pv, s->shift_v, s->nrows, &r0, &r1);
+            double vlo, vhi;
+            axial_interval(s, a, mag, k, &vlo, &vhi);
+            candidates(vlo, vhi, s->pv, s->shift_v, s->nrows, &r0, &r1);
         }
         for (int c = c0; c <= c1; ++c) {
             double fu = footprint_u(s, tau, c);
             if (fu <= 0.0) continue;
             for (int r = r0; r <= r1; ++r) {
-                double fv = footprint_v(s, mag, k, r);
+                double fv = footprint_v(s, a, mag, k, r);
                 if (fv <= 0.0) continue;
-                acc += amplitude(s, s->phi[a], r, c) * fu * fv * y[(int64_t)r * s->ncols + c];
+                acc += amplitude(s, a, r, c) * fu * fv * y[(int64_t)r * s->ncols + c];
             }
         }
     }
@@ -294,11 +339,12 @@ int64_t sfo_nnz(const sfo_scan *s, int view_begin, int view_end)
                 for (int k = 0; k < s->nz; ++k) {
                     int r0 = 0, r1 = 0;
                     if (s->geom != SFO_FAN) {
-                        double z = vox_z(s, k);
-                        candidates(mag * (z - 0.5 * s->Tz), mag * (z + 0.5 * s->Tz), s->pv, s->shift_v, s->nrows, &r0, &r1);
+                        double vlo, vhi;
+                        axial_interval(s, a, mag, k, &vlo, &vhi);
+                        candidates(vlo, vhi, s->pv, s->shift_v, s->nrows, &r0, &r1);
                     }
                     int64_t nv = 0;
-                    for (int r = r0; r <= r1; ++r) nv += footprint_v(s, mag, k, r) > 0.0;
+                    for (int r = r0; r <= r1; ++r) nv += footprint_v(s, a, mag, k, r) > 0.0;
                     total += nu * nv;
                 }
             }

@@ -35,6 +35,14 @@
  * length) in step 1, and the magnification in step 3 is SDD over the in-plane distance of the voxel centre from the
  * source, SDD / hypot(SOD-l, t).  Step 4 uses D = P - S as before.
  *
+ * Modular geometry (SFO_MODULAR; the paper's flexible geometry with a pose per view), UPRIGHT modules only: the column
+ * axis is horizontal, the row axis is +z.  The paper gives no footprint construction for it; the reading here is the
+ * cone-beam construction carried out in each view's own frame: e_u = the module's column axis, e_s = the horizontal
+ * unit vector orthogonal to it on the source's side, source at (l, t, z) = (lS, tS, zS), detector plane at
+ * l = lS - sdd_a with its centre at (tC, zC).  Step 1: u = tS + sdd_a (t - tS)/(lS - l) - tC; step 3: magnification
+ * sdd_a/(lS - l) about the source height, [v-,v+] = zS + m (z_k -+ Tz/2 - zS) - zC; step 4: D = pixel - source.
+ * A tilted module has no such reading (its oracle calls return an error); the Siddon oracle covers those.
+ *
  * Footprints partly off the detector are truncated; rays that miss the volume give 0.
  * For parallel-beam w * pu * pv equals the volume of (pixel beam  intersect  voxel) exactly.
  *
@@ -51,7 +59,7 @@
 extern "C" {
 #endif
 
-enum { SFO_PARALLEL = 0, SFO_FAN = 1, SFO_CONE = 2, SFO_CONE_CURVED = 3 };
+enum { SFO_PARALLEL = 0, SFO_FAN = 1, SFO_CONE = 2, SFO_CONE_CURVED = 3, SFO_MODULAR = 4 };
 
 typedef struct {
     int32_t geom;
@@ -63,6 +71,7 @@ typedef struct {
     double  T, Tz;               /* voxel size in-plane and axial, mm */
     double  cx, cy, cz;          /* volume centre, mm */
     const double *phi;           /* nviews angles, radians */
+    const double *poses;         /* SFO_MODULAR only: nviews x {S[3], C[3], ucol[3], vrow[3]}; phi is not read then */
 } sfo_scan;
 
 /* One weight and its factors, straight from the definition (any of the out pointers may be NULL). */

@@ -31,6 +31,7 @@ class _Scan(C.Structure):
         ("T", C.c_double), ("Tz", C.c_double),
         ("cx", C.c_double), ("cy", C.c_double), ("cz", C.c_double),
         ("phi", C.POINTER(C.c_double)),
+        ("poses", C.POINTER(C.c_double)),
     ]
 
 
@@ -75,11 +76,19 @@ def _scan(cfg):
     """(struct, keep-alive) for a synthetic.CTConfig-like object."""
     phi = np.ascontiguousarray(cfg.angles(), dtype=np.float64)
     assert phi.shape == (cfg.nviews,)
+    poses = None
+    if cfg.geom == 4:
+        poses = np.ascontiguousarray(cfg.poses, dtype=np.float64).reshape(cfg.nviews, 12)
+        assert np.abs(poses[:, 8]).max() < 1e-12 and np.abs(poses[:, 9:12] - [0.0, 0.0, 1.0]).max() < 1e-12, \
+            "footprint oracle: upright modules only (column axis horizontal, row axis +z)"
+        pp = poses.ctypes.data_as(C.POINTER(C.c_double))
+    else:
+        pp = C.POINTER(C.c_double)()
     s = _Scan(cfg.geom, cfg.nviews, cfg.nrows, cfg.ncols, cfg.nx, cfg.ny, cfg.nz,
               cfg.pixel_u, cfg.pixel_v, cfg.shift_u, cfg.shift_v, cfg.sod, cfg.sdd,
               cfg.voxel_xy, cfg.voxel_z, cfg.center_x, cfg.center_y, cfg.center_z,
-              phi.ctypes.data_as(C.POINTER(C.c_double)))
-    return s, phi
+              phi.ctypes.data_as(C.POINTER(C.c_double)), pp)
+    return s, (phi, poses)
 
 
 def _f32(a, shape):

@@ -12,35 +12,34 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 MUTATIONS = [
     ("magnification taken at the axis instead of the voxel centre",
-     "*mag = s->sdd / (s->sod - (x * cphi + y * sphi));", "*mag = s->sdd / s->sod;"),
+     "else *mag = f.sdd / (f.lS - l);", "else *mag = f.sdd / f.lS;"),
     ("amplitude divides by the smaller direction component",
      "fmax(fabs(dx), fabs(dy))", "fmin(fabs(dx), fabs(dy))"),
     ("parallel amplitude ignores the view angle",
      "return s->T / fmax(fabs(cphi), fabs(sphi));", "return s->T;"),
     ("sign of the detector axis",
-     "double t = -x * sphi + y * cphi;", "double t = x * sphi + y * cphi;"),
+     "double t = -x * f->sphi + y * f->cphi;", "double t = x * f->sphi + y * f->cphi;"),
     ("source on the wrong side",
-     "return s->sdd * t / (s->sod - l);", "return s->sdd * t / (s->sod + l);"),
+     "return f->tS + f->sdd * (t - f->tS) / (f->lS - l) - f->tC;", "return f->tS + f->sdd * (t - f->tS) / (f->lS + l) - f->tC;"),
     ("sign of the horizontal detector shift",
      "(c - 0.5 * (s->ncols - 1) + s->shift_u) * s->pu", "(c - 0.5 * (s->ncols - 1) - s->shift_u) * s->pu"),
     ("row centres off by half a pixel",
      "(r - 0.5 * (s->nrows - 1) + s->shift_v) * s->pv", "(r - 0.5 * (s->nrows) + s->shift_v) * s->pv"),
     ("axial extent uses the in-plane voxel size",
-     "double vlo = mag * (z - 0.5 * s->Tz), vhi = mag * (z + 0.5 * s->Tz);",
-     "double vlo = mag * (z - 0.5 * s->T), vhi = mag * (z + 0.5 * s->T);"),
+     "*vhi = f.zS + mag * (z + 0.5 * s->Tz - f.zS) - f.zC;", "*vhi = f.zS + mag * (z + 0.5 * s->T - f.zS) - f.zC;"),
     ("ramp area counted twice",
      "if (u <= tau[2]) return 0.5 * (tau[1] - tau[0]) + (u - tau[1]);",
      "if (u <= tau[2]) return (tau[1] - tau[0]) + (u - tau[1]);"),
     ("ray length ignores the cone angle",
-     "double len = sqrt(dx * dx + dy * dy + v * v);", "double len = sqrt(dx * dx + dy * dy);"),
+     "double len = sqrt(dx * dx + dy * dy + dz * dz);", "double len = sqrt(dx * dx + dy * dy);"),
     ("candidate range drops the last pixel",
      "double f = floor(ilo - 0.5), l = ceil(ihi + 0.5);", "double f = floor(ilo - 0.5), l = floor(ihi - 0.5);"),
     ("amplitude table indexed transposed in A",
      "y[(int64_t)r * s->ncols + c] += amp[(int64_t)r * s->ncols + c] * fu * fv * x;",
      "y[(int64_t)r * s->ncols + c] += amp[(int64_t)c * s->ncols + r] * fu * fv * x;"),
     ("amplitude arguments swapped in A^T",
-     "acc += amplitude(s, s->phi[a], r, c) * fu * fv * y[(int64_t)r * s->ncols + c];",
-     "acc += amplitude(s, s->phi[a], c, r) * fu * fv * y[(int64_t)r * s->ncols + c];"),
+     "acc += amplitude(s, a, r, c) * fu * fv * y[(int64_t)r * s->ncols + c];",
+     "acc += amplitude(s, a, c, r) * fu * fv * y[(int64_t)r * s->ncols + c];"),
     ("sign of the axial volume offset",
      "static double vox_z(const sfo_scan *s, int k) { return s->cz + (k - 0.5 * (s->nz - 1)) * s->Tz; }",
      "static double vox_z(const sfo_scan *s, int k) { return -s->cz + (k - 0.5 * (s->nz - 1)) * s->Tz; }"),
@@ -83,8 +82,8 @@ CURVED_SF_MUTATIONS = [
     ("curved detector: arc length replaced by the tangent",
      "return s->sdd * atan2(t, s->sod - l);", "return s->sdd * t / (s->sod - l);"),
     ("curved detector: axial magnification taken along the central ray",
-     "*mag = s->sdd / hypot(s->sod - (x * cphi + y * sphi), -x * sphi + y * cphi);",
-     "*mag = s->sdd / (s->sod - (x * cphi + y * sphi));"),
+     "else if (s->geom == SFO_CONE_CURVED) *mag = s->sdd / hypot(s->sod - l, t);",
+     "else if (s->geom == SFO_CONE_CURVED) *mag = s->sdd / (s->sod - l);"),
     ("curved detector: amplitude of the flat detector's ray",
      "double gam = u / s->sdd;", "double gam = atan(u / s->sdd);"),
     ("curved detector: fan angle counted the other way in the amplitude",
@@ -111,11 +110,23 @@ MODULAR_SIDDON_MUTATIONS = [
      "if (ray->ndim == 3 && fabs(ray->d[2]) > fabs(ray->d[major])) major = 2;", ";"),
 ]
 
+MODULAR_SF_MUTATIONS = [
+    ("modular: axial interval magnified about z = 0 instead of the source height",
+     "*vlo = f.zS + mag * (z - 0.5 * s->Tz - f.zS) - f.zC;", "*vlo = mag * (z - 0.5 * s->Tz) - f.zC;"),
+    ("modular: detector centre offset added instead of subtracted",
+     "return f->tS + f->sdd * (t - f->tS) / (f->lS - l) - f->tC;", "return f->tS + f->sdd * (t - f->tS) / (f->lS - l) + f->tC;"),
+    ("modular: amplitude of the ray of a centred module",
+     "double du = u + f.tC - f.tS, dz = v + f.zC - f.zS;", "double du = u, dz = v;"),
+    ("modular: source distance taken from the world origin",
+     "f->lS = S[0] * f->cphi + S[1] * f->sphi;", "f->lS = sqrt(S[0] * S[0] + S[1] * S[1]);"),
+]
+
 CASES = ([("sf_oracle.c", "test_oracle_pins.py") + m for m in MUTATIONS]
          + [("siddon_oracle.c", "test_siddon_pins.py") + m for m in SIDDON_MUTATIONS]
          + [("sf_oracle.c", "test_curved_pins.py") + m for m in CURVED_SF_MUTATIONS]
          + [("siddon_oracle.c", "test_curved_pins.py") + m for m in CURVED_SIDDON_MUTATIONS]
-         + [("siddon_oracle.c", "test_modular_pins.py") + m for m in MODULAR_SIDDON_MUTATIONS])
+         + [("siddon_oracle.c", "test_modular_pins.py") + m for m in MODULAR_SIDDON_MUTATIONS]
+         + [("sf_oracle.c", "test_modular_pins.py") + m for m in MODULAR_SF_MUTATIONS])
 
 
 @pytest.mark.parametrize("source,pins,what,old,new", CASES, ids=[c[0][:-9] + ": " + c[2] for c in CASES])
