@@ -51,8 +51,9 @@ extern "C" {
  * LEAP_MODULAR: the flexible geometry of the same section (sources and detectors at any position and orientation):
  * every view has its own pose, 12 doubles in `poses`: source position S, detector centre C, unit vector along the
  * column index, unit vector along the row index (orthogonal to each other); pixel (r, c) sits at
- * C + u_c ucol + v_r vrow.  sod, sdd and angles_rad are not read.  Built for LEAP_MODEL_SIDDON; with
- * LEAP_MODEL_SF leap_geometry_create returns LEAP_UNSUPPORTED. */
+ * C + u_c ucol + v_r vrow.  sod, sdd and angles_rad are not read.  LEAP_MODEL_SIDDON takes any pose.
+ * LEAP_MODEL_SF needs upright modules (ucol horizontal, vrow = +z): the cone-beam footprint construction is carried
+ * out in each view's own frame; for a tilted module leap_geometry_create returns LEAP_UNSUPPORTED. */
 enum { LEAP_PARALLEL = 0, LEAP_FAN = 1, LEAP_CONE = 2, LEAP_CONE_CURVED = 3, LEAP_MODULAR = 4 };
 
 /* Projector models ("CT Projection Models and Geometries").  LEAP_MODEL_SF: separable footprints.

@@ -100,10 +100,6 @@ static void build_ray_table(leap_geometry *G)
 static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
 {
     if (!d->poses) return invalid("poses is null");
-    if (d->model != LEAP_MODEL_SIDDON) {
-        leap_set_error("the footprint model is not built for the modular geometry; use LEAP_MODEL_SIDDON");
-        return LEAP_UNSUPPORTED;
-    }
     if (d->nviews > 65535 || (double)d->nx * d->ny * d->nz >= 4294967296.0 ||
         (double)d->nviews * d->nrows * d->ncols >= 4294967296.0 || d->ny > 262140 || d->nz > 65535 || d->nrows > 262140) {
         leap_set_error("sizes beyond what one launch covers");
@@ -124,6 +120,26 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
         if (inside) {
             leap_set_error("a source lies inside the volume");
             return LEAP_BAD_GEOMETRY;
+        }
+    }
+    if (d->model == LEAP_MODEL_SF) {
+        // The footprint construction needs the module upright: column axis horizontal, row axis +z, detector behind
+        // the volume as seen from the source, source clear of the volume's bounding circle in the module's frame.
+        const double rx = std::fabs(d->center_x) + half[0], ry = std::fabs(d->center_y) + half[1];
+        const double reach = std::sqrt(rx * rx + ry * ry);
+        for (int a = 0; a < d->nviews; ++a) {
+            const double *p = d->poses + 12 * (size_t)a;
+            if (std::fabs(p[8]) > 1e-9 || std::fabs(p[9]) > 1e-9 || std::fabs(p[10]) > 1e-9 || std::fabs(p[11] - 1.0) > 1e-9) {
+                leap_set_error("the footprint model needs upright modules (column axis horizontal, row axis +z); "
+                               "use LEAP_MODEL_SIDDON for tilted ones");
+                return LEAP_UNSUPPORTED;
+            }
+            const double c = p[7], s = -p[6];
+            const double lS = p[0] * c + p[1] * s, lD = p[3] * c + p[4] * s;
+            if (!(lS - lD > 0.0) || !(lS > reach) || !(d->pixel_u < 0.25 * (lS - lD))) {
+                leap_set_error("module does not face its source across the volume");
+                return LEAP_BAD_GEOMETRY;
+            }
         }
     }
     leap_geometry *G = new (std::nothrow) leap_geometry;
@@ -148,11 +164,51 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
     G->poses.resize(d->nviews);
     std::memcpy(G->poses.data(), d->poses, sizeof(MdPose) * (size_t)d->nviews);
     G->desc.poses = reinterpret_cast<const double *>(G->poses.data());
+    if (d->model == LEAP_MODEL_SF) {
+        // per view: the same scene translated so that the source sits on the frame's axis at height 0
+        g.iTzd = 1.0 / d->voxel_z;
+        G->views.resize(d->nviews);
+        G->geoms.resize(d->nviews);
+        const double h = 0.5 * d->voxel_xy;
+        for (int a = 0; a < d->nviews; ++a) {
+            const MdPose &P = G->poses[a];
+            const double c = P.ucol[1], s = -P.ucol[0];
+            const double lS = P.S[0] * c + P.S[1] * s, tS = -P.S[0] * s + P.S[1] * c, zS = P.S[2];
+            const double sdd = lS - (P.C[0] * c + P.C[1] * s), tC = -P.C[0] * s + P.C[1] * c, zC = P.C[2];
+            SfView &v = G->views[a];
+            std::memset(&v, 0, sizeof(v));
+            v.cd = c; v.sd = s; v.c = (float)c; v.s = (float)s;
+            v.p = (float)(h * c); v.q = (float)(h * s);
+            v.xmajor = std::fabs(c) >= std::fabs(s) ? 1 : 0;
+            SfGeom &ga = G->geoms[a];
+            ga = g;
+            ga.type = SF_CONE;
+            ga.x0d = g.x0d - tS * P.ucol[0];
+            ga.y0d = g.y0d - tS * P.ucol[1];
+            ga.zlo0d = g.zlo0d - zS;
+            ga.sodd = lS;
+            ga.kud = sdd / d->pixel_u; ga.kvd = sdd / d->pixel_v; ga.ikvd = 1.0 / ga.kvd;
+            ga.col_offd = g.col_offd - (tC - tS) / d->pixel_u;
+            ga.row_offd = g.row_offd - (zC - zS) / d->pixel_v;
+            ga.v0d = g.v0d + (zC - zS);
+            ga.zk0d = -ga.zlo0d / d->voxel_z;
+            ga.sod = (float)lS; ga.sdd = (float)sdd; ga.ku = (float)ga.kud;
+            ga.col_off = (float)ga.col_offd; ga.v0 = (float)ga.v0d;
+        }
+    }
     hipError_t e = hipGetDevice(&G->device);
+    if (e == hipSuccess && !G->geoms.empty()) {
+        e = hipMalloc((void **)&G->d_geoms, sizeof(SfGeom) * G->geoms.size());
+        if (e == hipSuccess) e = hipMemcpy(G->d_geoms, G->geoms.data(), sizeof(SfGeom) * G->geoms.size(), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMalloc((void **)&G->d_views, sizeof(SfView) * G->views.size());
+        if (e == hipSuccess) e = hipMemcpy(G->d_views, G->views.data(), sizeof(SfView) * G->views.size(), hipMemcpyHostToDevice);
+    }
     if (e == hipSuccess) e = hipMalloc((void **)&G->d_poses, sizeof(MdPose) * (size_t)d->nviews);
     if (e == hipSuccess) e = hipMemcpy(G->d_poses, G->poses.data(), sizeof(MdPose) * (size_t)d->nviews, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
         if (G->d_poses) (void)hipFree(G->d_poses);
+        if (G->d_geoms) (void)hipFree(G->d_geoms);
+        if (G->d_views) (void)hipFree(G->d_views);
         delete G;
         return leap_hip_fail(e, "uploading the pose table");
     }
@@ -471,6 +527,7 @@ extern "C" void leap_geometry_destroy(leap_geometry *G)
     if (G->d_volz) (void)hipFree(G->d_volz);
     if (G->d_raycols) (void)hipFree(G->d_raycols);
     if (G->d_poses) (void)hipFree(G->d_poses);
+    if (G->d_geoms) (void)hipFree(G->d_geoms);
     delete G;
 }
 
@@ -478,7 +535,8 @@ extern "C" int leap_geometry_describe(const leap_geometry *G, char *buf, int32_t
 {
     if (!G || !buf || cap <= 0) return invalid("null handle or buffer");
     if (G->g.type == SF_MODULAR) {
-        std::snprintf(buf, (size_t)cap, "type=4 model=siddon A=general AT=general (modular: one thread per ray / per voxel)");
+        std::snprintf(buf, (size_t)cap, "type=4 model=%s A=general AT=general (modular: one thread per ray / per voxel chunk)",
+                      G->g.model == SF_MODEL_SIDDON ? "siddon" : "sf");
         return LEAP_OK;
     }
     if (G->g.model == SF_MODEL_SIDDON) {

@@ -40,6 +40,9 @@ struct leap_geometry {
     // modular geometry: per-view poses, host copy and device copy
     std::vector<MdPose> poses;
     MdPose *d_poses = nullptr;
+    // footprint model on upright modules: every view is a cone-beam view with its own parameter block
+    std::vector<SfGeom> geoms;
+    SfGeom *d_geoms = nullptr;
     bool sd_columns = false;            // wave-per-column forward kernel (needs the scratch copy and slope <= 1)
 };
 

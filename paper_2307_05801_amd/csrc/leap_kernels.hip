@@ -49,6 +49,42 @@ __global__ __launch_bounds__(256) void sf_project_general(SfGeom g, const SfView
         if (r0 + rr < g.nrows) y[(size_t)(r0 + rr) * g.ncols] = out[rr];
 }
 
+// Modular geometry, footprint model on upright modules: the general bodies with one parameter block per view.
+__global__ __launch_bounds__(256) void sf_backproject_general_modular(SfGeom g, const SfGeom *__restrict__ geoms,
+                                                                      const SfView *__restrict__ views,
+                                                                      const float *__restrict__ sino, float *__restrict__ vol)
+{
+    const int i = blockIdx.x * 64 + threadIdx.x;
+    const int j = blockIdx.y * 4 + threadIdx.y;
+    const int k0 = blockIdx.z * GEN_ZC;
+    if (i >= g.nx || j >= g.ny) return;
+    float acc[GEN_ZC];
+#pragma unroll
+    for (int kk = 0; kk < GEN_ZC; ++kk) acc[kk] = 0.0f;
+    sf_backproject_column_chunk<GEN_ZC>(g, views, sino, i, j, k0, acc, geoms);
+#pragma unroll
+    for (int kk = 0; kk < GEN_ZC; ++kk)
+        if (k0 + kk < g.nz) vol[((size_t)(k0 + kk) * g.ny + j) * g.nx + i] = acc[kk];
+}
+
+__global__ __launch_bounds__(256) void sf_project_general_modular(const SfGeom *__restrict__ geoms,
+                                                                  const SfView *__restrict__ views,
+                                                                  const float *__restrict__ vol, float *__restrict__ sino)
+{
+    const int a = blockIdx.z;
+    const SfGeom g = geoms[a];
+    const int c = blockIdx.x * 64 + threadIdx.x;
+    const int r0 = (blockIdx.y * 4 + threadIdx.y) * GEN_RC;
+    if (c >= g.ncols || r0 >= g.nrows) return;
+    const SfView v = views[a];
+    float out[GEN_RC];
+    sf_project_ray_chunk<GEN_RC>(g, v, vol, c, r0, out);
+    float *__restrict__ y = sino + ((size_t)a * g.nrows) * g.ncols + c;
+#pragma unroll
+    for (int rr = 0; rr < GEN_RC; ++rr)
+        if (r0 + rr < g.nrows) y[(size_t)(r0 + rr) * g.ncols] = out[rr];
+}
+
 // Siddon model, general kernels: one thread per ray / per voxel.
 // grid: x = ceil(ncols/64), y = ceil(nrows/4), z = nviews; block 64x4.
 __global__ __launch_bounds__(256) void sd_project_general(SfGeom g, const SdRayCol *__restrict__ rays,
@@ -283,7 +319,10 @@ int leap_launch_project(const leap_geometry *G, const float *d_vol, float *d_sin
         leap_set_error("detector has too many rows for one launch");
         return LEAP_UNSUPPORTED;
     }
-    hipLaunchKernelGGL(sf_project_general, grid, block, 0, stream, g, G->d_views, d_vol, d_sino);
+    if (g.type == SF_MODULAR)
+        hipLaunchKernelGGL(sf_project_general_modular, grid, block, 0, stream, G->d_geoms, G->d_views, d_vol, d_sino);
+    else
+        hipLaunchKernelGGL(sf_project_general, grid, block, 0, stream, g, G->d_views, d_vol, d_sino);
     LEAP_HIP_CHECK(hipGetLastError());
     return LEAP_OK;
 }
@@ -353,7 +392,10 @@ int leap_launch_backproject(const leap_geometry *G, const float *d_sino, float *
         leap_set_error("volume has too many voxels along y or z for one launch");
         return LEAP_UNSUPPORTED;
     }
-    hipLaunchKernelGGL(sf_backproject_general, grid, block, 0, stream, g, G->d_views, d_sino, d_vol);
+    if (g.type == SF_MODULAR)
+        hipLaunchKernelGGL(sf_backproject_general_modular, grid, block, 0, stream, g, G->d_geoms, G->d_views, d_sino, d_vol);
+    else
+        hipLaunchKernelGGL(sf_backproject_general, grid, block, 0, stream, g, G->d_views, d_sino, d_vol);
     LEAP_HIP_CHECK(hipGetLastError());
     return LEAP_OK;
 }

@@ -10,13 +10,17 @@
 #include "sf_footprint.h"
 
 // Back projection: voxels (i, j, k0 .. k0+ZC-1) of one batch item; acc must be zero-initialised.
+// geoms: null, or one parameter block per view (modular geometry: every view is a cone-beam view of its own); the
+// sizes in `g0` hold for all views.
 template <int ZC>
-SF_HD void sf_backproject_column_chunk(const SfGeom &g, const SfView *__restrict__ views,
-                                       const float *__restrict__ sino, int i, int j, int k0, float acc[ZC])
+SF_HD void sf_backproject_column_chunk(const SfGeom &g0, const SfView *__restrict__ views,
+                                       const float *__restrict__ sino, int i, int j, int k0, float acc[ZC],
+                                       const SfGeom *__restrict__ geoms = nullptr)
 {
-    const size_t view_stride = (size_t)g.nrows * g.ncols;
-    const double zlo_k0 = fma((double)k0, g.Tzd, g.zlo0d);
-    for (int a = 0; a < g.nviews; ++a) {
+    const size_t view_stride = (size_t)g0.nrows * g0.ncols;
+    for (int a = 0; a < g0.nviews; ++a) {
+        const SfGeom &g = geoms ? geoms[a] : g0;
+        const double zlo_k0 = fma((double)k0, g.Tzd, g.zlo0d);
         const SfView v = views[a];
         const SfColumn f = sf_column(g, v, i, j);
         int c0, c1;

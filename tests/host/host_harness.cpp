@@ -35,7 +35,7 @@ int leap_launch_project(const leap_geometry *G, const float *vol, float *sino, h
 {
     const SfGeom &g = G->g;
     constexpr int RC = 8;
-    if (g.type == SF_MODULAR) {
+    if (g.type == SF_MODULAR && g.model == SF_MODEL_SIDDON) {
 #pragma omp parallel for collapse(2)
         for (int a = 0; a < g.nviews; ++a)
             for (int r = 0; r < g.nrows; ++r)
@@ -56,7 +56,7 @@ int leap_launch_project(const leap_geometry *G, const float *vol, float *sino, h
         for (int r0 = 0; r0 < g.nrows; r0 += RC)
             for (int c = 0; c < g.ncols; ++c) {
                 float out[RC];
-                sf_project_ray_chunk<RC>(g, G->d_views[a], vol, c, r0, out);
+                sf_project_ray_chunk<RC>(G->d_geoms ? G->d_geoms[a] : g, G->d_views[a], vol, c, r0, out);
                 for (int rr = 0; rr < RC && r0 + rr < g.nrows; ++rr) sino[((size_t)a * g.nrows + r0 + rr) * g.ncols + c] = out[rr];
             }
     return LEAP_OK;
@@ -66,7 +66,7 @@ int leap_launch_backproject(const leap_geometry *G, const float *sino, float *vo
 {
     const SfGeom &g = G->g;
     constexpr int ZC = 8;
-    if (g.type == SF_MODULAR) {
+    if (g.type == SF_MODULAR && g.model == SF_MODEL_SIDDON) {
 #pragma omp parallel for collapse(2)
         for (int k = 0; k < g.nz; ++k)
             for (int j = 0; j < g.ny; ++j)
@@ -86,7 +86,7 @@ int leap_launch_backproject(const leap_geometry *G, const float *sino, float *vo
         for (int j = 0; j < g.ny; ++j)
             for (int i = 0; i < g.nx; ++i) {
                 float acc[ZC] = {0};
-                sf_backproject_column_chunk<ZC>(g, G->d_views, sino, i, j, k0, acc);
+                sf_backproject_column_chunk<ZC>(g, G->d_views, sino, i, j, k0, acc, G->d_geoms);
                 for (int kk = 0; kk < ZC && k0 + kk < g.nz; ++kk) vol[((size_t)(k0 + kk) * g.ny + j) * g.nx + i] = acc[kk];
             }
     return LEAP_OK;

@@ -276,8 +276,3 @@ def test_modular_geometry_matches_oracle(torch_mod, oracle_mod, name, make):
     assert abs(lhs - rhs) <= TOL * abs(lhs)
 
 
-def test_modular_footprints_are_refused(torch_mod):
-    from paper_2307_05801_amd import Geometry, binding as B
-    with pytest.raises(B.LeapError) as err:
-        Geometry(MODULAR_CASES[3][1](), model="sf")
-    assert err.value.status == B.LEAP_UNSUPPORTED

@@ -246,11 +246,35 @@ def test_modular_siddon_bodies_match_oracle_on_cpu(host, oracle_mod, name):
         assert rel_l2(ax, sd.project(cone, x)) <= TOL
 
 
+UPRIGHT_CASES = {
+    "cone_as_modular": lambda: modular_from(reduced(config(3), 16, nviews=10).replace(shift_u=0.3, shift_v=-0.4)),
+    "shifted_upright_modules": lambda: perturbed_poses(
+        reduced(config(3), 16, nviews=9).replace(nx=29, ny=35, nz=22, nrows=27, ncols=31), 3, shift_mm=25.0, tilt_rad=0.3,
+        upright=True),
+    "wobbly_orbit": lambda: perturbed_poses(reduced(config(5), 32, nviews=12), 11, shift_mm=10.0, tilt_rad=0.1, upright=True),
+}
+
+
+@pytest.mark.parametrize("name", list(UPRIGHT_CASES))
+def test_modular_footprint_bodies_match_oracle_on_cpu(host, oracle_mod, name):
+    cfg = UPRIGHT_CASES[name]()
+    x = uniform_volume(cfg, 5)[0]
+    y = uniform_sinogram(cfg, 6)[0]
+    h = handle(host, cfg, B.LEAP_MODEL_SF)
+    ax = np.zeros(cfg.sino_shape, np.float32)
+    aty = np.zeros(cfg.vol_shape, np.float32)
+    B.leap_project(h, x.ctypes.data, ax.ctypes.data, 1, 0, host)
+    B.leap_backproject(h, y.ctypes.data, aty.ctypes.data, 1, 0, host)
+    B.leap_geometry_destroy(h, host)
+    assert rel_l2(ax, oracle_mod.project(cfg, x)) <= TOL
+    assert rel_l2(aty, oracle_mod.backproject(cfg, y)) <= TOL
+
+
 def test_modular_argument_checks(host):
     cfg = MODULAR_CASES["looking_down"]()
     d, keep = B.desc_from_config(cfg, B.LEAP_MODEL_SF)
     hnd = C.c_void_p()
-    assert host.leap_geometry_create(C.byref(d), C.byref(hnd)) == B.LEAP_UNSUPPORTED      # footprints: not built
+    assert host.leap_geometry_create(C.byref(d), C.byref(hnd)) == B.LEAP_UNSUPPORTED      # footprints need upright modules
     d, keep = B.desc_from_config(cfg, B.LEAP_MODEL_SIDDON)
     d.poses = C.POINTER(C.c_double)()
     assert host.leap_geometry_create(C.byref(d), C.byref(hnd)) == B.LEAP_INVALID_ARG
