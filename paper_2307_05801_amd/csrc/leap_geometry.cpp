@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
+#include <algorithm>
 #include <cstring>
 #include <new>
 
@@ -96,6 +97,79 @@ static void build_ray_table(leap_geometry *G)
     G->sd_max_axial_slope = max_dh * vmax;
 }
 
+// Modular geometry, footprint model: static limits of the two fast kernels, checked view by view on each view's own
+// parameter block (the same checks the circular scanners get in leap_geometry_create).
+static void select_modular_fast_kernels(leap_geometry *G)
+{
+    const leap_geometry_desc *d = &G->desc;
+    const double T = d->voxel_xy, half_x = 0.5 * d->nx * T, half_y = 0.5 * d->ny * T;
+    double cols = 0.0, rows = 0.0, vpr = 0.0;
+    for (int a = 0; a < d->nviews; ++a) {
+        const SfGeom &ga = G->geoms[a];
+        const double cx = ga.x0d + 0.5 * (d->nx - 1) * T, cy = ga.y0d + 0.5 * (d->ny - 1) * T;
+        const double rx = std::fabs(cx) + half_x, ry = std::fabs(cy) + half_y;
+        const double reach = std::sqrt(rx * rx + ry * ry) + T;
+        const double sdd = ga.kud * d->pixel_u, lS = ga.sodd;
+        if (!(lS > reach)) return;
+        const double mag_max = sdd / (lS - reach), mag_min = sdd / (lS + reach);
+        const double umax = std::fmax(std::fabs(-2.0 - ga.col_offd), std::fabs(d->ncols + 1.0 - ga.col_offd)) * d->pixel_u;
+        const double stretch = 1.02 / std::cos(std::atan(umax / sdd));
+        cols = std::fmax(cols, mag_max * T * std::sqrt(2.0) / d->pixel_u * stretch);
+        rows = std::fmax(rows, mag_max * d->voxel_z / d->pixel_v);
+        vpr = std::fmax(vpr, d->pixel_v / (mag_min * d->voxel_z));
+    }
+    G->max_cols_per_voxel = cols; G->max_rows_per_voxel = rows; G->max_voxels_per_row = vpr;
+    if (const char *env = std::getenv("LEAP_FORCE_GENERAL"))
+        if (env[0] == '1') return;
+
+    if (d->nz >= 8 && std::isfinite(cols) && cols <= 4.0 && rows <= 3.0) {
+        G->bp_nc = std::max(2, (int)std::ceil(cols) + 1);
+        G->bp_nv = std::max(2, (int)std::ceil(rows - 1e-6) + 1);
+        G->bp_wh = (float)(0.5 * cols);
+        const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T;
+        const float hx = 0.5f * (float)(BP_T - 1) * G->g.T;
+        for (int sh = d->nz >= 128 ? 0 : 1; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
+            const int zc = BP_SHAPES[sh].zc, chunks = (d->nz + zc - 1) / zc;
+            int need_w = 0, need_h = 0;
+            for (int a = 0; a < d->nviews; ++a)
+                for (int ty = 0; ty < tiles_y; ++ty)
+                    for (int tx = 0; tx < tiles_x; ++tx)
+                        for (int ch = 0; ch < chunks; ch += (chunks > 1 ? chunks - 1 : 1)) {
+                            const SfGeom &ga = G->geoms[a];
+                            const float xc = (float)(ga.x0d + ((double)(tx * BP_T) + 0.5 * (BP_T - 1)) * ga.Td);
+                            const float yc = (float)(ga.y0d + ((double)(ty * BP_T) + 0.5 * (BP_T - 1)) * ga.Td);
+                            const float z0 = (float)(ga.zlo0d + (double)(ch * zc) * ga.Tzd), z1 = z0 + (float)zc * ga.Tz;
+                            const SfWindow w = sf_bp_window(ga, G->views[a], xc, yc, hx, z0, z1, G->bp_wh, G->bp_nc, G->bp_nv);
+                            need_w = std::max(need_w, w.need_w);
+                            need_h = std::max(need_h, w.need_h);
+                        }
+            G->bp_need_w = need_w; G->bp_need_h = need_h; G->bp_shape = sh;
+            G->bp_tiled = need_w <= BP_SHAPES[sh].pw - 1 && need_h <= BP_SHAPES[sh].ph - 1;
+        }
+    }
+    if (d->nrows >= 32 && std::isfinite(vpr) && vpr <= 3.0 && (double)d->nx * d->ny * (d->nz + 2.0 * FP_PAD) < 4294967296.0 &&
+        d->ny <= 65535) {
+        G->fp_cw = 2;
+        int need = 0;
+        for (int a = 0; a < d->nviews && need <= 16; ++a)
+            for (int c = 0; c < d->ncols; c += 2) {
+                const SfRayLines L = sf_ray_lines(G->geoms[a], G->views[a], c, 2);
+                const int n_major = L.xmajor ? d->nx : d->ny;
+                const float d0 = std::fabs(L.b0 - L.b1);
+                const float d1 = std::fabs(fmaf(L.m0 - L.m1, (float)(n_major - 1), L.b0 - L.b1));
+                const float dm = d0 > d1 ? d0 : d1;
+                if (!(dm < 1e6f)) { need = 1 << 20; break; }
+                need = std::max(need, (int)std::floor(dm + 2.0f * L.spread + 1e-3f) + 2);
+            }
+        G->fp_need_q = need;
+        G->fp_nq = need <= 4 ? 4 : (need <= 8 ? 8 : 16);
+        G->fp_nk = std::max(2, (int)std::ceil(vpr - 1e-6) + 1);
+        const int groups = (d->nrows + 63) / 64;
+        G->fp_rg = groups >= 8 ? 8 : (groups >= 4 ? 4 : (groups >= 2 ? 2 : 1));
+        G->fp_columns = need <= 16 && G->fp_nk <= 4;
+    }
+}
+
 // Modular geometry: per-view poses instead of the angle list; only the fields the modular kernels read are filled.
 static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
 {
@@ -125,8 +199,6 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
     if (d->model == LEAP_MODEL_SF) {
         // The footprint construction needs the module upright: column axis horizontal, row axis +z, detector behind
         // the volume as seen from the source, source clear of the volume's bounding circle in the module's frame.
-        const double rx = std::fabs(d->center_x) + half[0], ry = std::fabs(d->center_y) + half[1];
-        const double reach = std::sqrt(rx * rx + ry * ry);
         for (int a = 0; a < d->nviews; ++a) {
             const double *p = d->poses + 12 * (size_t)a;
             if (std::fabs(p[8]) > 1e-9 || std::fabs(p[9]) > 1e-9 || std::fabs(p[10]) > 1e-9 || std::fabs(p[11] - 1.0) > 1e-9) {
@@ -135,8 +207,11 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
                 return LEAP_UNSUPPORTED;
             }
             const double c = p[7], s = -p[6];
-            const double lS = p[0] * c + p[1] * s, lD = p[3] * c + p[4] * s;
-            if (!(lS - lD > 0.0) || !(lS > reach) || !(d->pixel_u < 0.25 * (lS - lD))) {
+            const double lS = p[0] * c + p[1] * s, lD = p[3] * c + p[4] * s, tS = -p[0] * s + p[1] * c;
+            // the volume as this view sees it: moved by -tS along the column axis
+            const double mx = std::fabs(d->center_x - tS * p[6]) + half[0], my = std::fabs(d->center_y - tS * p[7]) + half[1];
+            const double reach_a = std::sqrt(mx * mx + my * my);
+            if (!(lS - lD > 0.0) || !(lS > reach_a) || !(d->pixel_u < 0.25 * (lS - lD))) {
                 leap_set_error("module does not face its source across the volume");
                 return LEAP_BAD_GEOMETRY;
             }
@@ -196,7 +271,21 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
             ga.col_off = (float)ga.col_offd; ga.v0 = (float)ga.v0d;
         }
     }
+    if (d->model == LEAP_MODEL_SF) select_modular_fast_kernels(G);
     hipError_t e = hipGetDevice(&G->device);
+    if (e == hipSuccess && G->fp_columns) {
+        G->nzp = d->nz + 2 * FP_PAD;
+        const size_t bytes = sizeof(float) * ((size_t)d->nx * d->ny + 1) * G->nzp;
+        hipError_t es = hipMalloc((void **)&G->d_volz, bytes);
+        if (es == hipSuccess) es = hipMemset(G->d_volz, 0, bytes);
+        if (es == hipSuccess) es = hipDeviceSynchronize();
+        if (es != hipSuccess) {
+            if (G->d_volz) (void)hipFree(G->d_volz);
+            G->d_volz = nullptr;
+            G->fp_columns = false;
+            (void)hipGetLastError();
+        }
+    }
     if (e == hipSuccess && !G->geoms.empty()) {
         e = hipMalloc((void **)&G->d_geoms, sizeof(SfGeom) * G->geoms.size());
         if (e == hipSuccess) e = hipMemcpy(G->d_geoms, G->geoms.data(), sizeof(SfGeom) * G->geoms.size(), hipMemcpyHostToDevice);
@@ -209,6 +298,7 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
         if (G->d_poses) (void)hipFree(G->d_poses);
         if (G->d_geoms) (void)hipFree(G->d_geoms);
         if (G->d_views) (void)hipFree(G->d_views);
+        if (G->d_volz) (void)hipFree(G->d_volz);
         delete G;
         return leap_hip_fail(e, "uploading the pose table");
     }
@@ -535,8 +625,14 @@ extern "C" int leap_geometry_describe(const leap_geometry *G, char *buf, int32_t
 {
     if (!G || !buf || cap <= 0) return invalid("null handle or buffer");
     if (G->g.type == SF_MODULAR) {
-        std::snprintf(buf, (size_t)cap, "type=4 model=%s A=general AT=general (modular: one thread per ray / per voxel chunk)",
-                      G->g.model == SF_MODEL_SIDDON ? "siddon" : "sf");
+        if (G->g.model == SF_MODEL_SIDDON)
+            std::snprintf(buf, (size_t)cap, "type=4 model=siddon A=general AT=general (modular: one thread per ray / per voxel)");
+        else
+            std::snprintf(buf, (size_t)cap, "type=4 model=sf A=%s(nq=%d/%d,nk=%d,rg=%d) AT=%s(nc=%d,nv=%d,zc=%d,window=%dx%d) "
+                          "cols/voxel<=%.2f rows/voxel<=%.2f voxels/row<=%.2f", G->fp_columns ? "columns" : "general", G->fp_need_q,
+                          G->fp_nq, G->fp_nk, G->fp_rg, G->bp_tiled ? "tiled" : "general", G->bp_nc, G->bp_nv,
+                          BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h, G->max_cols_per_voxel, G->max_rows_per_voxel,
+                          G->max_voxels_per_row);
         return LEAP_OK;
     }
     if (G->g.model == SF_MODEL_SIDDON) {

@@ -250,15 +250,17 @@ static void launch_fp_columns(const leap_geometry *G, float *d_sino, hipStream_t
     const int tiles_per_xcd_pad = (int)cdiv(cdiv(col_tiles, 8), tb) * tb;
     dim3 grid((unsigned)(8 * tiles_per_xcd_pad * vgroups_pad * bands), 1, 1);
     hipLaunchKernelGGL((sf_project_columns<NQ, NK, RG, W, CW, 1, GT>), grid, dim3(W * 64, 1, 1), 0, stream, g, G->d_views,
-                       G->d_volz, d_sino, G->nzp, col_tiles, bands, vb, tb, vgroups_pad, tiles_per_xcd_pad);
+                       G->d_volz, d_sino, G->nzp, col_tiles, bands, vb, tb, vgroups_pad, tiles_per_xcd_pad,
+                       (const SfGeom *)G->d_geoms);
 }
 
 template <int NQ, int NK, int RG>
 static bool launch_fp_w(const leap_geometry *G, float *d_sino, hipStream_t stream)
 {
-    if (G->g.type == SF_CONE_CURVED) {          // cylinder: the default bundle width only
+    if (G->g.type == SF_CONE_CURVED || G->g.type == SF_MODULAR) {     // the default bundle width only
         if (G->fp_cw != 2) return false;
-        launch_fp_columns<NQ, NK, RG, 2, 1>(G, d_sino, stream);
+        if (G->g.type == SF_MODULAR) launch_fp_columns<NQ, NK, RG, 2, 2>(G, d_sino, stream);
+        else launch_fp_columns<NQ, NK, RG, 2, 1>(G, d_sino, stream);
         return true;
     }
     switch (G->fp_cw) {
@@ -335,13 +337,14 @@ static void launch_bp_tiled_gt(const leap_geometry *G, const float *d_sino, floa
     const unsigned tiles_x = cdiv(g.nx, BP_T), tiles_y = cdiv(g.ny, BP_T);
     dim3 grid(tiles_x * tiles_y, cdiv(g.nz, S.zc), 1);
     hipLaunchKernelGGL((sf_backproject_tiled<NC, NV, S.zc, S.pw, S.ph, GT>), grid, dim3(256, 1, 1), 0, stream, g, G->d_views,
-                       d_sino, d_vol, (int)tiles_x, G->bp_wh);
+                       d_sino, d_vol, (int)tiles_x, G->bp_wh, (const SfGeom *)G->d_geoms);
 }
 
 template <int NC, int NV, int SH>
 static void launch_bp_tiled(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
 {
     if (G->g.type == SF_CONE_CURVED) launch_bp_tiled_gt<NC, NV, SH, 1>(G, d_sino, d_vol, stream);
+    else if (G->g.type == SF_MODULAR) launch_bp_tiled_gt<NC, NV, SH, 2>(G, d_sino, d_vol, stream);
     else launch_bp_tiled_gt<NC, NV, SH, 0>(G, d_sino, d_vol, stream);
 }
 

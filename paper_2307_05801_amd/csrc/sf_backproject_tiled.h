@@ -121,10 +121,30 @@ __device__ __forceinline__ void bp_store_view(const SfGeom &g, const SfView v, i
     }
 }
 
+// Where a workgroup's tile and z-chunk lie in the scene a view sees (mm): tile centre, chunk faces.
+struct SfBpScene {
+    float xc, yc, z0, z1;
+    double zlo_k0;
+};
+
+template <int BP_ZC>
+SF_HD SfBpScene sf_bp_scene(const SfGeom &g, int i0, int j0, int k0)
+{
+    SfBpScene s;
+    s.zlo_k0 = fma((double)k0, g.Tzd, g.zlo0d);
+    s.z0 = (float)s.zlo_k0;
+    s.z1 = s.z0 + (float)BP_ZC * g.Tz;
+    s.xc = (float)(g.x0d + ((double)i0 + 0.5 * (BP_T - 1)) * g.Td);
+    s.yc = (float)(g.y0d + ((double)j0 + 0.5 * (BP_T - 1)) * g.Td);
+    return s;
+}
+
+// GT: 0 flat or parallel, 1 cylindrical detector, 2 modular geometry with upright modules (every view brings its own
+// parameter block geoms[a]: the scene translated so that the view is a circular cone-beam view; g holds the sizes).
 template <int NC, int NV, int BP_ZC, int BP_PW, int BP_PH, int GT>
 __global__ __launch_bounds__(256, 4) void sf_backproject_tiled(SfGeom g, const SfView *__restrict__ views,
                                                             const float *__restrict__ sino, float *__restrict__ vol,
-                                                            int tiles_x, float wh)
+                                                            int tiles_x, float wh, const SfGeom *__restrict__ geoms)
 {
     constexpr int BP_PS = BP_PW + BP_ROW_PAD;      // LDS row stride (floats)
     __shared__ float patch[2][BP_PH * BP_PS];
@@ -137,11 +157,12 @@ __global__ __launch_bounds__(256, 4) void sf_backproject_tiled(SfGeom g, const S
     const int i = i0 + ti, j = j0 + tj;
     const int ic = i < g.nx ? i : g.nx - 1, jc = j < g.ny ? j : g.ny - 1;   // out-of-volume threads shadow the edge
 
-    const double zlo_k0 = fma((double)k0, g.Tzd, g.zlo0d);
-    const float z0 = (float)zlo_k0, z1 = z0 + (float)BP_ZC * g.Tz;
     const float hx = 0.5f * (float)(BP_T - 1) * g.T;
-    const float xc = (float)(g.x0d + ((double)i0 + 0.5 * (BP_T - 1)) * g.Td);
-    const float yc = (float)(g.y0d + ((double)j0 + 0.5 * (BP_T - 1)) * g.Td);
+    auto geom_of = [&](int a) -> const SfGeom & {
+        if constexpr (GT == 2) return geoms[a];
+        else return g;
+    };
+    const SfBpScene scene0 = sf_bp_scene<BP_ZC>(geom_of(0), i0, j0, k0);
 
     // staging role: element e = tid + 256 s  ->  window column tid % PW, window row tid / PW + RSTEP s
     const int sc = tid & (BP_PW - 1), sr = tid / BP_PW;
@@ -156,19 +177,24 @@ __global__ __launch_bounds__(256, 4) void sf_backproject_tiled(SfGeom g, const S
     SfWindow win_next;
 
     SfWindow win;
-    bp_load_view<NC, NV, BP_PW, BP_PH, NSTAGE, GT>(g, views[0], sino, xc, yc, hx, z0, z1, wh, sc, sr, win, stage);
+    bp_load_view<NC, NV, BP_PW, BP_PH, NSTAGE, GT>(geom_of(0), views[0], sino, scene0.xc, scene0.yc, hx, scene0.z0, scene0.z1, wh,
+                                                   sc, sr, win, stage);
     win_next = win;
-    bp_store_view<BP_PW, BP_PH, NSTAGE, GT>(g, views[0], sc, sr, win, stage, patch[0]);
+    bp_store_view<BP_PW, BP_PH, NSTAGE, GT>(geom_of(0), views[0], sc, sr, win, stage, patch[0]);
     __syncthreads();
 
     for (int a = 0; a < g.nviews; ++a) {
         const float *buf = patch[a & 1];
-        if (a + 1 < g.nviews)      // global loads in flight during the gather
-            bp_load_view<NC, NV, BP_PW, BP_PH, NSTAGE, GT>(g, views[a + 1], sino + (size_t)(a + 1) * view_stride, xc, yc, hx, z0, z1, wh, sc,
-                                                       sr, win_next, stage);
+        if (a + 1 < g.nviews) {    // global loads in flight during the gather
+            const SfBpScene sn = GT == 2 ? sf_bp_scene<BP_ZC>(geom_of(a + 1), i0, j0, k0) : scene0;
+            bp_load_view<NC, NV, BP_PW, BP_PH, NSTAGE, GT>(geom_of(a + 1), views[a + 1], sino + (size_t)(a + 1) * view_stride, sn.xc,
+                                                           sn.yc, hx, sn.z0, sn.z1, wh, sc, sr, win_next, stage);
+        }
+        const SfGeom &gv = geom_of(a);
+        const double zlo_k0 = GT == 2 ? fma((double)k0, gv.Tzd, gv.zlo0d) : scene0.zlo_k0;
 
         const SfView v = views[a];
-        const SfColumn f = sf_column<GT>(g, v, ic, jc);
+        const SfColumn f = sf_column<GT>(gv, v, ic, jc);
         int cf, cl;
         sf_col_range(f, cf, cl);
         float fu[NC];
@@ -183,7 +209,7 @@ __global__ __launch_bounds__(256, 4) void sf_backproject_tiled(SfGeom g, const S
                 g0 = g1;
             }
         }
-        const SfRowsOfVoxels ax = sf_rows_of_voxels(g, f, zlo_k0);
+        const SfRowsOfVoxels ax = sf_rows_of_voxels(gv, f, zlo_k0);
         unsigned ofs = (unsigned)((ax.rb - win.r0) * BP_PS + (cf - win.c0));
 
         if constexpr (NV == 2) {
@@ -246,7 +272,8 @@ __global__ __launch_bounds__(256, 4) void sf_backproject_tiled(SfGeom g, const S
 
         }
 
-        if (a + 1 < g.nviews) bp_store_view<BP_PW, BP_PH, NSTAGE, GT>(g, views[a + 1], sc, sr, win_next, stage, patch[(a + 1) & 1]);
+        if (a + 1 < g.nviews)
+            bp_store_view<BP_PW, BP_PH, NSTAGE, GT>(geom_of(a + 1), views[a + 1], sc, sr, win_next, stage, patch[(a + 1) & 1]);
         win = win_next;
         __syncthreads();
     }

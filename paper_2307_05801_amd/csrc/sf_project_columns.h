@@ -115,11 +115,15 @@ __global__ __launch_bounds__(256) void sf_volume_to_columns(const float *__restr
 // FP_WAVES: waves per workgroup; CW: adjacent detector columns per wave; WV: consecutive views per workgroup
 // (the workgroup's waves are WV views x FP_WAVES/WV column bundles); GT: 0 flat or parallel, 1 cylindrical detector.
 template <int NQ, int NK, int RG, int FP_WAVES, int CW, int WV, int GT>
-__global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, const SfView *__restrict__ views,
+__global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom gk, const SfView *__restrict__ views,
                                                                     const float *__restrict__ volz, float *__restrict__ sino,
                                                                     int nzp, int col_tiles, int bands, int vb, int tb,
-                                                                    int vgroups_pad, int tiles_per_xcd_pad)
+                                                                    int vgroups_pad, int tiles_per_xcd_pad,
+                                                                    const SfGeom *__restrict__ geoms)
 {
+    // GT == 2 (modular geometry, upright modules): the wave's view brings its own parameter block, the scene
+    // translated so that the view is a circular cone-beam view; gk holds the sizes, which all views share.
+    const SfGeom &gsz = gk;
     constexpr int SB = 64 / NQ;                       // slabs per record block
     constexpr int WC = FP_WAVES / WV;                 // column bundles per workgroup
     static_assert(WC * WV == FP_WAVES, "waves = column bundles x views");
@@ -144,11 +148,12 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom g, co
         band = chunk / tchunks;
         ct = ((chunk - band * tchunks) * tb + tloc) * 8 + xcd;
         a = (vblk * vb + v_in) * WV + wv;
-        if (ct >= col_tiles || a >= g.nviews || band >= bands) return;   // padding blocks and padding views (no barrier follows)
+        if (ct >= col_tiles || a >= gsz.nviews || band >= bands) return;   // padding blocks and padding views (no barrier follows)
     }
     const int c0 = (ct * WC + wc) * CW;                  // first detector column of this wave
     const int band0 = band * (RG * 64);
 
+    const SfGeom &g = GT == 2 ? geoms[a] : gk;
     const SfView v = views[a];
     const SfRayLines L = sf_ray_lines<GT>(g, v, c0, CW);
     const int n_major = L.xmajor ? g.nx : g.ny;

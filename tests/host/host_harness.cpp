@@ -110,6 +110,7 @@ extern "C" int host_check_backproject_windows(const leap_geometry *G, int64_t *r
         for (int ty = 0; ty < tiles_y; ++ty)
             for (int tx = 0; tx < tiles_x; ++tx)
                 for (int ch = 0; ch < chunks; ++ch) {
+                    const SfGeom &g = G->geoms.empty() ? G->g : G->geoms[a];      // modular: the view's own parameter block
                     const int i0 = tx * BP_T, j0 = ty * BP_T, k0 = ch * S.zc;
                     const double zlo = fma((double)k0, g.Tzd, g.zlo0d);
                     const float z0 = (float)zlo, z1 = z0 + (float)S.zc * g.Tz;
@@ -152,11 +153,12 @@ extern "C" long host_project_columns(const leap_geometry *G, const float *vol, f
     for (int k = 0; k < g.nz; ++k)
         for (int j = 0; j < g.ny; ++j)
             for (int i = 0; i < g.nx; ++i) volz[((size_t)j * g.nx + i) * nzp + FP_PAD + k] = vol[((size_t)k * g.ny + j) * g.nx + i];
-    const double zkp = -g.zlo0d * g.iTzd + (double)FP_PAD, mu_scale = g.ikvd * g.iTzd;
     long uncovered = 0;
 #pragma omp parallel for collapse(2) reduction(+ : uncovered)
-    for (int a = 0; a < g.nviews; ++a)
-        for (int c0 = 0; c0 < g.ncols; c0 += CW) {
+    for (int a = 0; a < G->g.nviews; ++a)
+        for (int c0 = 0; c0 < G->g.ncols; c0 += CW) {
+            const SfGeom &g = G->geoms.empty() ? G->g : G->geoms[a];      // modular: the view's own parameter block
+            const double zkp = -g.zlo0d * g.iTzd + (double)FP_PAD, mu_scale = g.ikvd * g.iTzd;
             const SfView v = G->views[a];
             const SfRayLines L = sf_ray_lines(g, v, c0, CW);
             const int n_major = L.xmajor ? g.nx : g.ny, n_minor = L.xmajor ? g.ny : g.nx;

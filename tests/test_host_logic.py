@@ -249,7 +249,7 @@ def test_modular_siddon_bodies_match_oracle_on_cpu(host, oracle_mod, name):
 UPRIGHT_CASES = {
     "cone_as_modular": lambda: modular_from(reduced(config(3), 16, nviews=10).replace(shift_u=0.3, shift_v=-0.4)),
     "shifted_upright_modules": lambda: perturbed_poses(
-        reduced(config(3), 16, nviews=9).replace(nx=29, ny=35, nz=22, nrows=27, ncols=31), 3, shift_mm=25.0, tilt_rad=0.3,
+        reduced(config(3), 16, nviews=9).replace(nx=29, ny=35, nz=22, nrows=41, ncols=31), 3, shift_mm=25.0, tilt_rad=0.3,
         upright=True),
     "wobbly_orbit": lambda: perturbed_poses(reduced(config(5), 32, nviews=12), 11, shift_mm=10.0, tilt_rad=0.1, upright=True),
 }
@@ -265,9 +265,22 @@ def test_modular_footprint_bodies_match_oracle_on_cpu(host, oracle_mod, name):
     aty = np.zeros(cfg.vol_shape, np.float32)
     B.leap_project(h, x.ctypes.data, ax.ctypes.data, 1, 0, host)
     B.leap_backproject(h, y.ctypes.data, aty.ctypes.data, 1, 0, host)
+    # the fast kernels' host-side re-enactments on the per-view parameter blocks
+    rep = (C.c_int64 * 8)()
+    host.host_check_backproject_windows(h, rep)
+    fast = np.zeros(cfg.sino_shape, np.float32)
+    uncovered = host.host_project_columns(h, x.ctypes.data, fast.ctypes.data)
+    desc = B.leap_geometry_describe(h, host)
     B.leap_geometry_destroy(h, host)
-    assert rel_l2(ax, oracle_mod.project(cfg, x)) <= TOL
+    ref = oracle_mod.project(cfg, x)
+    assert rel_l2(ax, ref) <= TOL
     assert rel_l2(aty, oracle_mod.backproject(cfg, y)) <= TOL
+    assert "AT=tiled" in desc and rep[0] == 1 and rep[7] == 0, (list(rep), desc)
+    if name != "wobbly_orbit":          # that one has 32 detector rows at most: below the column kernel's minimum
+        assert "A=columns" in desc, desc
+    if uncovered >= 0:
+        assert uncovered == 0, desc
+        assert rel_l2(fast, ref) <= TOL, desc
 
 
 def test_modular_argument_checks(host):
