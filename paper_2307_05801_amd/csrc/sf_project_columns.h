@@ -240,18 +240,32 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom gk, c
         }
     }
 
-    // ---- amplitude and store: CW consecutive floats per lane and row
+    // ---- amplitude and store: CW consecutive floats per lane and row, written together (storing the columns of a
+    // bundle one after the other, hundreds of instructions apart, cost 3.7 times the sinogram in partial-line writes)
     float *__restrict__ ya = sino + (size_t)a * g.nrows * g.ncols;
+    SfAmpCol ac[CW];
 #pragma unroll
-    for (int cw = 0; cw < CW; ++cw) {
-        const int c = c0 + cw;
-        if (c >= g.ncols) break;
-        const SfAmpCol ac = sf_amp_col<GT>(g, v, c);
+    for (int cw = 0; cw < CW; ++cw) ac[cw] = sf_amp_col<GT>(g, v, c0 + cw < g.ncols ? c0 + cw : g.ncols - 1);
+    struct __attribute__((packed, aligned(4))) Pair { float lo, hi; };
 #pragma unroll
-        for (int gq = 0; gq < RG; ++gq) {
-            const int r = band0 + 64 * gq + lane;
-            if (r < g.nrows) ya[(size_t)r * g.ncols + c] = sf_amp(g, v, ac, r) * acc[cw][gq];
+    for (int gq = 0; gq < RG; ++gq) {
+        const int r = band0 + 64 * gq + lane;
+        if (r >= g.nrows) continue;
+        float out[CW];
+#pragma unroll
+        for (int cw = 0; cw < CW; ++cw) out[cw] = sf_amp(g, v, ac[cw], r) * acc[cw][gq];
+        float *__restrict__ dst = ya + (size_t)r * g.ncols + c0;
+        if constexpr (CW == 2) {
+            if (c0 + 1 < g.ncols) {
+                Pair pr;
+                pr.lo = out[0]; pr.hi = out[1];
+                *reinterpret_cast<Pair *>(dst) = pr;
+                continue;
+            }
         }
+#pragma unroll
+        for (int cw = 0; cw < CW; ++cw)
+            if (c0 + cw < g.ncols) dst[cw] = out[cw];
     }
 }
 
