@@ -7,7 +7,7 @@
 // the (few) detector columns whose centre ray crosses its in-plane square, and for each the piece [t0, t1] of the
 // ray's slab parameter that lies inside the square (the same split function the forward kernel uses).  Along z the
 // roles are turned round: instead of asking, for each voxel, which rows hit it, the thread walks the rows of the
-// window that can hit its ZC voxels; each row's piece lies in at most two axial cells (the kernel is only chosen when
+// window; each row's piece lies in at most two axial cells (the kernel is only chosen when
 // no ray crosses more than one z-face per slab) and adds its two shares to those cells.  The ZC sums of a thread live
 // in LDS (slot-major, so the 64 lanes of a wave never collide on a bank whatever cells they address), which makes the
 // data-dependent cell index cheap; each slot has exactly one writer and is updated by a plain read-add-write, so the
@@ -161,40 +161,39 @@ __global__ __launch_bounds__(256) void sd_backproject_tiled(SfGeom g, const SfVi
             const float dt = t1 - t0;
             if (!(dt > 0.0f)) continue;
             const double ha = fma((double)n + (double)t0, R.dh, R.h0), hb = fma((double)n + (double)t1, R.dh, R.h0);
-            // rows that can reach the chunk: v between (k0 - zk0)/h and (k0 + ZC - zk0)/h at either end of the piece
-            int ra, rb;
-            if (g.type == SF_PARALLEL) {
-                const double e0 = ((double)k0 - g.zk0d) * g.Tzd, e1 = e0 + (double)ZC * g.Tzd;
-                ra = (int)ceil((e0 - g.v0d) / g.pvd) - 1;
-                rb = (int)floor((e1 - g.v0d) / g.pvd) + 1;
-            } else {
-                const double e0 = (double)k0 - g.zk0d, e1 = e0 + (double)ZC;
-                const double ia = sf_rcp_d(ha), ib = sf_rcp_d(hb), ipv = sf_rcp_d(g.pvd);
-                const double vlo = fmin(e0 * ia, e0 * ib), vhi = fmax(e1 * ia, e1 * ib);
-                ra = (int)ceil((vlo - g.v0d) * ipv) - 1;
-                rb = (int)floor((vhi - g.v0d) * ipv) + 1;
-            }
-            ra = ra < win.r0 ? win.r0 : ra;                       // the window holds zeros outside the detector
-            rb = rb > win.r0 + PH - 1 ? win.r0 + PH - 1 : rb;
-            const float dh = fabsf((float)(hb - ha));
-            const float scale = dt * (dh > 1e-30f ? 1.0f / dh : 1e30f);   // times 1/|v_r|: dt over the piece's rise in Z
-            double vr = sd_row_v(g, ra);
-            unsigned ofs = (unsigned)((ra - win.r0) * PS + wc);
-            for (int r = ra; r <= rb; ++r) {
-                const double za = fma(vr, ha, zrel0), zb = fma(vr, hb, zrel0);
-                const double lo = fmin(za, zb), fl = floor(lo);
-                int slot = (int)fl;
-                slot = slot < 0 ? 0 : (slot > ZC + 2 ? ZC + 2 : slot);
-                const float up = (float)(fl + 1.0 - lo);          // distance from the lower end to the next z-face
-                const float wl = fminf(up * scale * ri[r - win.r0], dt);
-                const float y = buf[ofs];
-                float *__restrict__ cell = sums + (slot * 256 + tid);
-                // plain read-add-write: the slot has no other writer, and a wave's LDS accesses retire in order
-                // (the LDS float atomic measured 7x slower than this on the 512^3 case)
-                cell[0] += wl * y;
-                cell[256] += (dt - wl) * y;
-                vr += g.pvd;
-                ofs += PS;
+            // Every row of the window is walked (rows that cannot reach the chunk fall into the dump slots), in two
+            // wave-uniform runs: rows below the source plane (v < 0), whose lower end in Z is where h is larger, and
+            // rows at or above it.  Within a run the lower end advances by pv * h per row; it is carried as a 32.32
+            // fixed-point number whose upper word is the slot and whose lower word the fraction.
+            const double hmin = fmin(ha, hb), hmax = fmax(ha, hb);
+            const float dh = (float)(hmax - hmin);
+            // dt over the piece's rise in Z is scale / |v_r| / 2^32 times the fixed-point distance to the next z-face
+            const float scale = dt * (dh > 1e-30f ? 1.0f / dh : 1e30f) * 2.3283064365386963e-10f;
+            const int H = win.need_h < PH ? win.need_h : PH;
+            int rz = (int)ceil(-g.v0d / g.pvd) - win.r0;         // first window row with v >= 0
+            rz = rz < 0 ? 0 : (rz > H ? H : rz);
+#pragma unroll
+            for (int run = 0; run < 2; ++run) {
+                const int rs = run ? rz : 0, re = run ? H : rz;
+                if (rs >= re) continue;
+                const double h = run ? hmin : hmax;
+                long long q = (long long)floor(fma(sd_row_v(g, win.r0 + rs), h, zrel0) * 4294967296.0);
+                const long long dq = (long long)rint(g.pvd * h * 4294967296.0);
+                unsigned ofs = (unsigned)(rs * PS + wc);
+                for (int row = rs; row < re; ++row) {
+                    int slot = (int)(q >> 32);
+                    slot = slot < 0 ? 0 : (slot > ZC + 2 ? ZC + 2 : slot);
+                    const float up = (float)(~(unsigned)q) + 1.0f;     // (1 - fraction) * 2^32, at least 1
+                    const float wl = fminf(up * (scale * ri[row]), dt);
+                    const float y = buf[ofs];
+                    float *__restrict__ cell = sums + (slot * 256 + tid);
+                    // plain read-add-write: the slot has no other writer, and a wave's LDS accesses retire in order
+                    // (the LDS float atomic measured 7x slower than this on the 512^3 case)
+                    cell[0] += wl * y;
+                    cell[256] += (dt - wl) * y;
+                    q += dq;
+                    ofs += PS;
+                }
             }
         }
 
