@@ -30,7 +30,7 @@ MEASURED_TRAFFIC_BYTES = {
     ("c3_cone_512", "A"): 1.42119e8 * 2048 + 2.54274e6 * 1024,
     ("c3_cone_512", "AT"): 8.45518e6 * 2048 + 524288 * 1024,
     ("c3_cone_512:siddon", "A"): 1.06982e8 * 2048 + 2.88743e6 * 1024,
-    ("c3_cone_512:siddon", "AT"): 3.59896e7 * 2048 + 524288 * 1024,
+    ("c3_cone_512:siddon", "AT"): 3.54689e7 * 2048 + 524288 * 1024,
 }
 
 
