@@ -50,25 +50,31 @@ static bool finite_pos(double v) { return std::isfinite(v) && v > 0.0; }
 static void build_ray_table(leap_geometry *G)
 {
     const leap_geometry_desc &d = G->desc;
-    const SfGeom &g = G->g;
     const double T = d.voxel_xy, Tz = d.voxel_z;
-    const double xlo = g.x0d - 0.5 * T, ylo = g.y0d - 0.5 * T;      // lower faces of voxel (0, 0)
     G->raycols.resize((size_t)d.nviews * d.ncols);
-    double max_dh = 0.0;
+    double max_slope = 0.0;
     for (int a = 0; a < d.nviews; ++a) {
+        // modular scans with upright modules bring one parameter block per view: a circular cone-beam view of the
+        // translated scene, with its own source distance, detector distance and column offset
+        const bool per_view = !G->geoms.empty();
+        const SfGeom &g = per_view ? G->geoms[a] : G->g;
+        const int type = per_view ? (int)LEAP_CONE : d.type;
+        const double sod = per_view ? g.sodd : d.sod, sdd = per_view ? g.kud * d.pixel_u : d.sdd;
+        const double xlo = g.x0d - 0.5 * T, ylo = g.y0d - 0.5 * T;      // lower faces of voxel (0, 0)
         const double c = G->views[a].cd, s = G->views[a].sd;
+        double max_dh = 0.0;
         for (int col = 0; col < d.ncols; ++col) {
             const double u = ((double)col - g.col_offd) * d.pixel_u;
             double ox, oy, dx, dy;
-            if (d.type == LEAP_PARALLEL) {
+            if (type == LEAP_PARALLEL) {
                 ox = -u * s; oy = u * c; dx = c; dy = s;
-            } else if (d.type == LEAP_CONE_CURVED) {    // pixel at fan angle u / sdd on the cylinder
-                const double cg = std::cos(u / d.sdd), sg = std::sin(u / d.sdd);
-                ox = d.sod * c; oy = d.sod * s;
-                dx = -d.sdd * (cg * c + sg * s); dy = d.sdd * (sg * c - cg * s);
+            } else if (type == LEAP_CONE_CURVED) {    // pixel at fan angle u / sdd on the cylinder
+                const double cg = std::cos(u / sdd), sg = std::sin(u / sdd);
+                ox = sod * c; oy = sod * s;
+                dx = -sdd * (cg * c + sg * s); dy = sdd * (sg * c - cg * s);
             } else {
-                ox = d.sod * c; oy = d.sod * s;
-                dx = -d.sdd * c - u * s; dy = -d.sdd * s + u * c;
+                ox = sod * c; oy = sod * s;
+                dx = -sdd * c - u * s; dy = -sdd * s + u * c;
             }
             SdRayCol R;
             R.xmajor = std::fabs(dx) >= std::fabs(dy) ? 1 : 0;
@@ -80,11 +86,11 @@ static void build_ray_table(leap_geometry *G)
             const double inv_m = R.m != 0.0 ? 1.0 / R.m : 1e30;
             R.inv_m = (float)std::fmin(std::fmax(inv_m, -1e30), 1e30);
             R.lxy = (float)(T * std::sqrt(dx * dx + dy * dy) / std::fabs(dmaj));
-            if (d.type == LEAP_CONE || d.type == LEAP_CONE_CURVED) {
+            if (type == LEAP_CONE || type == LEAP_CONE_CURVED) {
                 R.h0 = (lomaj - omaj) / (dmaj * Tz);
                 R.dh = T / (dmaj * Tz);
                 R.vscale = (float)(T / std::fabs(dmaj));
-            } else if (d.type == LEAP_PARALLEL) {
+            } else if (type == LEAP_PARALLEL) {
                 R.h0 = 1.0 / Tz; R.dh = 0.0; R.vscale = 0.0f;
             } else {
                 R.h0 = 0.0; R.dh = 0.0; R.vscale = 0.0f;
@@ -92,9 +98,10 @@ static void build_ray_table(leap_geometry *G)
             max_dh = std::fmax(max_dh, std::fabs(R.dh));
             G->raycols[(size_t)a * d.ncols + col] = R;
         }
+        const double vmax = std::fmax(std::fabs(g.v0d), std::fabs(g.v0d + (d.nrows - 1) * g.pvd));
+        max_slope = std::fmax(max_slope, max_dh * vmax);
     }
-    const double vmax = std::fmax(std::fabs(g.v0d), std::fabs(g.v0d + (d.nrows - 1) * g.pvd));
-    G->sd_max_axial_slope = max_dh * vmax;
+    G->sd_max_axial_slope = max_slope;
 }
 
 // Modular geometry, footprint model: static limits of the two fast kernels, checked view by view on each view's own
@@ -170,6 +177,73 @@ static void select_modular_fast_kernels(leap_geometry *G)
     }
 }
 
+// Siddon model: static limits of the two fast kernels.  With per-view parameter blocks (upright modular scans) every
+// view is checked on its own block.
+static void select_siddon_fast_kernels(leap_geometry *G)
+{
+    const leap_geometry_desc *d = &G->desc;
+    const bool per_view = !G->geoms.empty();
+    if (d->type == LEAP_FAN || !(G->sd_max_axial_slope <= 0.999)) return;
+    if (const char *env = std::getenv("LEAP_FORCE_GENERAL"))
+        if (env[0] == '1') return;
+
+    // wave-per-column forward projection: no ray may cross more than one z-face per slab
+    if (d->nrows >= 32 && ((double)d->nx * d->ny + 1.0) * (d->nz + 2.0 * FP_PAD) < 4294967296.0 && d->ny <= 65535) {
+        G->sd_columns = true;
+        const int groups = (d->nrows + 63) / 64;
+        G->fp_rg = groups >= 8 ? 8 : (groups >= 4 ? 4 : (groups >= 2 ? 2 : 1));
+        if (const char *env = std::getenv("LEAP_FP_VB")) {
+            const int v = std::atoi(env);
+            if (v >= 1 && v <= 1024) G->fp_vb = v;
+        }
+        if (const char *env = std::getenv("LEAP_FP_TB")) {
+            const int v = std::atoi(env);
+            if (v >= 1 && v <= 1024) G->fp_tb = v;
+        }
+        if (const char *env = std::getenv("LEAP_FP_RG")) {
+            const int v = std::atoi(env);
+            if (v == 1 || v == 2 || v == 4 || v == 8) G->fp_rg = v;
+        }
+    }
+
+    // tiled back projection: at most 4 pixel centres inside a voxel's footprint, and the staged window of every
+    // (view, tile, z-chunk) must fit the instance (checked with the kernel's own function)
+    if (d->nz >= 8 && std::isfinite(G->max_cols_per_voxel) && G->max_cols_per_voxel > 0.0 && G->max_cols_per_voxel < 3.9) {
+        G->bp_nc = (int)std::floor(G->max_cols_per_voxel + 0.01) + 1;
+        if (G->bp_nc < 2) G->bp_nc = 2;
+        const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T;
+        const float hx = 0.5f * (float)BP_T * G->g.T;
+        int first_shape = 1;                          // the 64-voxel shape does not fit: the sums live in LDS
+        if (const char *env = std::getenv("LEAP_BP_SHAPE")) {
+            first_shape = std::atoi(env) % BP_NSHAPES;
+            if (first_shape < 1) first_shape = 1;
+        }
+        for (int sh = first_shape; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
+            const int zc = BP_SHAPES[sh].zc;
+            const int chunks = (d->nz + zc - 1) / zc;
+            int need_w = 0, need_h = 0;
+            for (int a = 0; a < d->nviews; ++a) {
+                const SfGeom &g = per_view ? G->geoms[a] : G->g;
+                for (int ty = 0; ty < tiles_y; ++ty)
+                    for (int tx = 0; tx < tiles_x; ++tx) {
+                        const float xc = (float)(g.x0d + ((double)(tx * BP_T) + 0.5 * (BP_T - 1)) * g.Td);
+                        const float yc = (float)(g.y0d + ((double)(ty * BP_T) + 0.5 * (BP_T - 1)) * g.Td);
+                        for (int ch = 0; ch < chunks; ch += (chunks > 1 ? chunks - 1 : 1)) {
+                            const float z0 = (float)(g.zlo0d + (double)(ch * zc) * g.Tzd), z1 = z0 + (float)zc * g.Tz;
+                            const SfWindow w = sd_bp_window(g, G->views[a], xc, yc, hx, z0, z1);
+                            need_w = w.need_w > need_w ? w.need_w : need_w;
+                            need_h = w.need_h > need_h ? w.need_h : need_h;
+                        }
+                    }
+            }
+            G->bp_need_w = need_w;
+            G->bp_need_h = need_h;
+            G->bp_shape = sh;
+            G->bp_tiled = need_w <= BP_SHAPES[sh].pw - 1 && need_h <= BP_SHAPES[sh].ph - 1;
+        }
+    }
+}
+
 // Modular geometry: per-view poses instead of the angle list; only the fields the modular kernels read are filled.
 static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
 {
@@ -196,26 +270,35 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
             return LEAP_BAD_GEOMETRY;
         }
     }
-    if (d->model == LEAP_MODEL_SF) {
-        // The footprint construction needs the module upright: column axis horizontal, row axis +z, detector behind
-        // the volume as seen from the source, source clear of the volume's bounding circle in the module's frame.
-        for (int a = 0; a < d->nviews; ++a) {
-            const double *p = d->poses + 12 * (size_t)a;
-            if (std::fabs(p[8]) > 1e-9 || std::fabs(p[9]) > 1e-9 || std::fabs(p[10]) > 1e-9 || std::fabs(p[11] - 1.0) > 1e-9) {
-                leap_set_error("the footprint model needs upright modules (column axis horizontal, row axis +z); "
-                               "use LEAP_MODEL_SIDDON for tilted ones");
-                return LEAP_UNSUPPORTED;
-            }
-            const double c = p[7], s = -p[6];
-            const double lS = p[0] * c + p[1] * s, lD = p[3] * c + p[4] * s, tS = -p[0] * s + p[1] * c;
-            // the volume as this view sees it: moved by -tS along the column axis
-            const double mx = std::fabs(d->center_x - tS * p[6]) + half[0], my = std::fabs(d->center_y - tS * p[7]) + half[1];
-            const double reach_a = std::sqrt(mx * mx + my * my);
-            if (!(lS - lD > 0.0) || !(lS > reach_a) || !(d->pixel_u < 0.25 * (lS - lD))) {
-                leap_set_error("module does not face its source across the volume");
-                return LEAP_BAD_GEOMETRY;
-            }
+    // Upright modules (column axis horizontal, row axis +z, detector behind the volume as seen from the source, source
+    // clear of the volume's bounding circle in the module's frame) are circular cone-beam views of a translated scene:
+    // the footprint construction needs them, the Siddon model uses them for its fast kernels.
+    bool upright = true;
+    const char *why_not = "";
+    int why_status = LEAP_OK;
+    for (int a = 0; a < d->nviews && upright; ++a) {
+        const double *p = d->poses + 12 * (size_t)a;
+        if (std::fabs(p[8]) > 1e-9 || std::fabs(p[9]) > 1e-9 || std::fabs(p[10]) > 1e-9 || std::fabs(p[11] - 1.0) > 1e-9) {
+            upright = false;
+            why_not = "the footprint model needs upright modules (column axis horizontal, row axis +z); "
+                      "use LEAP_MODEL_SIDDON for tilted ones";
+            why_status = LEAP_UNSUPPORTED;
+            break;
         }
+        const double c = p[7], s = -p[6];
+        const double lS = p[0] * c + p[1] * s, lD = p[3] * c + p[4] * s, tS = -p[0] * s + p[1] * c;
+        // the volume as this view sees it: moved by -tS along the column axis
+        const double mx = std::fabs(d->center_x - tS * p[6]) + half[0], my = std::fabs(d->center_y - tS * p[7]) + half[1];
+        const double reach_a = std::sqrt(mx * mx + my * my);
+        if (!(lS - lD > 0.0) || !(lS > reach_a) || !(d->pixel_u < 0.25 * (lS - lD))) {
+            upright = false;
+            why_not = "module does not face its source across the volume";
+            why_status = LEAP_BAD_GEOMETRY;
+        }
+    }
+    if (d->model == LEAP_MODEL_SF && !upright) {
+        leap_set_error(why_not);
+        return why_status;
     }
     leap_geometry *G = new (std::nothrow) leap_geometry;
     if (!G) return invalid("out of host memory");
@@ -239,7 +322,7 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
     G->poses.resize(d->nviews);
     std::memcpy(G->poses.data(), d->poses, sizeof(MdPose) * (size_t)d->nviews);
     G->desc.poses = reinterpret_cast<const double *>(G->poses.data());
-    if (d->model == LEAP_MODEL_SF) {
+    if (upright) {
         // per view: the same scene translated so that the source sits on the frame's axis at height 0
         g.iTzd = 1.0 / d->voxel_z;
         G->views.resize(d->nviews);
@@ -272,8 +355,15 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
         }
     }
     if (d->model == LEAP_MODEL_SF) select_modular_fast_kernels(G);
+    if (d->model == LEAP_MODEL_SIDDON && upright) {
+        build_ray_table(G);
+        select_modular_fast_kernels(G);      // footprint bounds (columns per voxel) are what the Siddon limits need too
+        G->bp_tiled = G->fp_columns = false;
+        G->bp_shape = 0;
+        select_siddon_fast_kernels(G);
+    }
     hipError_t e = hipGetDevice(&G->device);
-    if (e == hipSuccess && G->fp_columns) {
+    if (e == hipSuccess && (G->fp_columns || G->sd_columns)) {
         G->nzp = d->nz + 2 * FP_PAD;
         const size_t bytes = sizeof(float) * ((size_t)d->nx * d->ny + 1) * G->nzp;
         hipError_t es = hipMalloc((void **)&G->d_volz, bytes);
@@ -282,9 +372,14 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
         if (es != hipSuccess) {
             if (G->d_volz) (void)hipFree(G->d_volz);
             G->d_volz = nullptr;
-            G->fp_columns = false;
+            G->fp_columns = G->sd_columns = false;
             (void)hipGetLastError();
         }
+    }
+    if (e == hipSuccess && (G->sd_columns || (G->bp_tiled && d->model == LEAP_MODEL_SIDDON))) {
+        const size_t bytes = sizeof(SdRayCol) * G->raycols.size();
+        e = hipMalloc((void **)&G->d_raycols, bytes);
+        if (e == hipSuccess) e = hipMemcpy(G->d_raycols, G->raycols.data(), bytes, hipMemcpyHostToDevice);
     }
     if (e == hipSuccess && !G->geoms.empty()) {
         e = hipMalloc((void **)&G->d_geoms, sizeof(SfGeom) * G->geoms.size());
@@ -299,6 +394,7 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
         if (G->d_geoms) (void)hipFree(G->d_geoms);
         if (G->d_views) (void)hipFree(G->d_views);
         if (G->d_volz) (void)hipFree(G->d_volz);
+        if (G->d_raycols) (void)hipFree(G->d_raycols);
         delete G;
         return leap_hip_fail(e, "uploading the pose table");
     }
@@ -517,61 +613,7 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         }
     }
 
-    // Siddon model, wave-per-column forward projection: no ray may cross more than one z-face per slab.
-    if (d->model == LEAP_MODEL_SIDDON && d->type != LEAP_FAN && d->nrows >= 32 && G->sd_max_axial_slope <= 0.999 &&
-        ((double)d->nx * d->ny + 1.0) * (d->nz + 2.0 * FP_PAD) < 4294967296.0 && d->ny <= 65535) {
-        G->sd_columns = true;
-        const int groups = (d->nrows + 63) / 64;
-        G->fp_rg = groups >= 8 ? 8 : (groups >= 4 ? 4 : (groups >= 2 ? 2 : 1));
-        if (const char *env = std::getenv("LEAP_FP_VB")) {
-            const int v = std::atoi(env);
-            if (v >= 1 && v <= 1024) G->fp_vb = v;
-        }
-        if (const char *env = std::getenv("LEAP_FP_TB")) {
-            const int v = std::atoi(env);
-            if (v >= 1 && v <= 1024) G->fp_tb = v;
-        }
-        if (const char *env = std::getenv("LEAP_FP_RG")) {
-            const int v = std::atoi(env);
-            if (v == 1 || v == 2 || v == 4 || v == 8) G->fp_rg = v;
-        }
-    }
-
-    // Siddon model, tiled back projection: same slope limit, at most 4 pixel centres inside a voxel's footprint, and
-    // the staged window of every (view, tile, z-chunk) must fit the instance (checked with the kernel's own function).
-    if (d->model == LEAP_MODEL_SIDDON && d->type != LEAP_FAN && d->nz >= 8 && G->sd_max_axial_slope <= 0.999 &&
-        std::isfinite(G->max_cols_per_voxel) && G->max_cols_per_voxel < 3.9) {
-        G->bp_nc = (int)std::floor(G->max_cols_per_voxel + 0.01) + 1;
-        if (G->bp_nc < 2) G->bp_nc = 2;
-        const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T;
-        const float hx = 0.5f * (float)BP_T * g.T;
-        int first_shape = 1;                          // the 64-voxel shape does not fit: the sums live in LDS
-        if (const char *env = std::getenv("LEAP_BP_SHAPE")) {
-            first_shape = std::atoi(env) % BP_NSHAPES;
-            if (first_shape < 1) first_shape = 1;
-        }
-        for (int sh = first_shape; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
-            const int zc = BP_SHAPES[sh].zc;
-            const int chunks = (d->nz + zc - 1) / zc;
-            int need_w = 0, need_h = 0;
-            for (int a = 0; a < d->nviews; ++a)
-                for (int ty = 0; ty < tiles_y; ++ty)
-                    for (int tx = 0; tx < tiles_x; ++tx) {
-                        const float xc = (float)(g.x0d + ((double)(tx * BP_T) + 0.5 * (BP_T - 1)) * g.Td);
-                        const float yc = (float)(g.y0d + ((double)(ty * BP_T) + 0.5 * (BP_T - 1)) * g.Td);
-                        for (int ch = 0; ch < chunks; ch += (chunks > 1 ? chunks - 1 : 1)) {
-                            const float z0 = (float)(g.zlo0d + (double)(ch * zc) * g.Tzd), z1 = z0 + (float)zc * g.Tz;
-                            const SfWindow w = sd_bp_window(g, G->views[a], xc, yc, hx, z0, z1);
-                            need_w = w.need_w > need_w ? w.need_w : need_w;
-                            need_h = w.need_h > need_h ? w.need_h : need_h;
-                        }
-                    }
-            G->bp_need_w = need_w;
-            G->bp_need_h = need_h;
-            G->bp_shape = sh;
-            G->bp_tiled = need_w <= BP_SHAPES[sh].pw - 1 && need_h <= BP_SHAPES[sh].ph - 1;
-        }
-    }
+    if (d->model == LEAP_MODEL_SIDDON) select_siddon_fast_kernels(G);
 
     // Testing aid: LEAP_FORCE_GENERAL=1 keeps every call on the general kernels.
     if (const char *env = std::getenv("LEAP_FORCE_GENERAL"))
@@ -626,7 +668,10 @@ extern "C" int leap_geometry_describe(const leap_geometry *G, char *buf, int32_t
     if (!G || !buf || cap <= 0) return invalid("null handle or buffer");
     if (G->g.type == SF_MODULAR) {
         if (G->g.model == SF_MODEL_SIDDON)
-            std::snprintf(buf, (size_t)cap, "type=4 model=siddon A=general AT=general (modular: one thread per ray / per voxel)");
+            std::snprintf(buf, (size_t)cap, "type=4 model=siddon A=%s(rg=%d) AT=%s(nc=%d,zc=%d,window=%dx%d) %s",
+                          G->sd_columns ? "columns" : "general", G->fp_rg, G->bp_tiled ? "tiled" : "general", G->bp_nc,
+                          BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h,
+                          G->geoms.empty() ? "(tilted modules: one thread per ray / per voxel)" : "(upright modules)");
         else
             std::snprintf(buf, (size_t)cap, "type=4 model=sf A=%s(nq=%d/%d,nk=%d,rg=%d) AT=%s(nc=%d,nv=%d,zc=%d,window=%dx%d) "
                           "cols/voxel<=%.2f rows/voxel<=%.2f voxels/row<=%.2f", G->fp_columns ? "columns" : "general", G->fp_need_q,

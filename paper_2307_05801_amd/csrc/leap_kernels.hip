@@ -146,14 +146,20 @@ static void launch_sd_columns(const leap_geometry *G, float *d_sino, hipStream_t
     const int tiles_per_xcd_pad = (int)cdiv(cdiv(col_tiles, 8), tb) * tb;
     const unsigned zero_col = (unsigned)g.nx * (unsigned)g.ny * (unsigned)G->nzp;
     dim3 grid((unsigned)(8 * tiles_per_xcd_pad * views_pad * bands), 1, 1);
-    hipLaunchKernelGGL((sd_project_columns<RG, SD_WAVES>), grid, dim3(SD_WAVES * 64, 1, 1), 0, stream, g, G->d_raycols,
-                       G->d_volz, d_sino, G->nzp, zero_col, col_tiles, bands, vb, tb, views_pad, tiles_per_xcd_pad);
+    if (g.type == SF_MODULAR)
+        hipLaunchKernelGGL((sd_project_columns<RG, SD_WAVES, true>), grid, dim3(SD_WAVES * 64, 1, 1), 0, stream, g, G->d_raycols,
+                           G->d_volz, d_sino, G->nzp, zero_col, col_tiles, bands, vb, tb, views_pad, tiles_per_xcd_pad,
+                           (const SfGeom *)G->d_geoms);
+    else
+        hipLaunchKernelGGL((sd_project_columns<RG, SD_WAVES, false>), grid, dim3(SD_WAVES * 64, 1, 1), 0, stream, g, G->d_raycols,
+                           G->d_volz, d_sino, G->nzp, zero_col, col_tiles, bands, vb, tb, views_pad, tiles_per_xcd_pad,
+                           (const SfGeom *)nullptr);
 }
 
 static int launch_sd_project(const leap_geometry *G, const float *d_vol, float *d_sino, hipStream_t stream)
 {
     const SfGeom &g = G->g;
-    if (g.type == SF_MODULAR) {        // sizes were checked against the grid limits at creation
+    if (g.type == SF_MODULAR && !G->sd_columns) {     // sizes were checked against the grid limits at creation
         dim3 grid(cdiv(g.ncols, 64), cdiv(g.nrows, 4), g.nviews);
         hipLaunchKernelGGL(md_project_general, grid, dim3(64, 4, 1), 0, stream, g, G->d_poses, d_vol, d_sino);
         LEAP_HIP_CHECK(hipGetLastError());
@@ -188,8 +194,12 @@ static void launch_sd_tiled(const leap_geometry *G, const float *d_sino, float *
     const SfGeom &g = G->g;
     const unsigned tiles_x = cdiv(g.nx, BP_T), tiles_y = cdiv(g.ny, BP_T);
     dim3 grid(tiles_x * tiles_y, cdiv(g.nz, S.zc), 1);
-    hipLaunchKernelGGL((sd_backproject_tiled<NCS, S.zc, S.pw, S.ph>), grid, dim3(256, 1, 1), 0, stream, g, G->d_views,
-                       G->d_raycols, d_sino, d_vol, (int)tiles_x);
+    if (g.type == SF_MODULAR)
+        hipLaunchKernelGGL((sd_backproject_tiled<NCS, S.zc, S.pw, S.ph, true>), grid, dim3(256, 1, 1), 0, stream, g, G->d_views,
+                           G->d_raycols, d_sino, d_vol, (int)tiles_x, (const SfGeom *)G->d_geoms);
+    else
+        hipLaunchKernelGGL((sd_backproject_tiled<NCS, S.zc, S.pw, S.ph, false>), grid, dim3(256, 1, 1), 0, stream, g, G->d_views,
+                           G->d_raycols, d_sino, d_vol, (int)tiles_x, (const SfGeom *)nullptr);
 }
 
 template <int NCS>
@@ -207,7 +217,7 @@ static bool launch_sd_shape(const leap_geometry *G, const float *d_sino, float *
 static int launch_sd_backproject(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
 {
     const SfGeom &g = G->g;
-    if (g.type == SF_MODULAR) {
+    if (g.type == SF_MODULAR && !G->bp_tiled) {
         dim3 grid(cdiv(g.nx, 64), cdiv(g.ny, 4), g.nz);
         hipLaunchKernelGGL(md_backproject_general, grid, dim3(64, 4, 1), 0, stream, g, G->d_poses, d_sino, d_vol);
         LEAP_HIP_CHECK(hipGetLastError());

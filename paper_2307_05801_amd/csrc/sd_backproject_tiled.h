@@ -96,11 +96,31 @@ __device__ __forceinline__ void sd_store_view(const SfGeom &g, const SdRayCol *_
     }
 }
 
-// NCS: detector columns whose centre can fall inside one voxel's in-plane footprint.
-template <int NCS, int ZC, int PW, int PH>
+// Where a workgroup's tile and z-chunk lie in the scene a view sees.
+struct SdBpScene {
+    float xc, yc, z0, z1;
+    double zrel0;          // Z of the plane z = 0 measured in slots of this chunk
+};
+
+template <int ZC>
+SF_HD SdBpScene sd_bp_scene(const SfGeom &g, int i0, int j0, int k0)
+{
+    SdBpScene s;
+    s.z0 = (float)fma((double)k0, g.Tzd, g.zlo0d);
+    s.z1 = s.z0 + (float)ZC * g.Tz;
+    s.xc = (float)(g.x0d + ((double)i0 + 0.5 * (BP_T - 1)) * g.Td);
+    s.yc = (float)(g.y0d + ((double)j0 + 0.5 * (BP_T - 1)) * g.Td);
+    s.zrel0 = g.zk0d - (double)k0 + 2.0;
+    return s;
+}
+
+// NCS: detector columns whose centre can fall inside one voxel's in-plane footprint.  MOD: modular geometry with
+// upright modules, one parameter block geoms[a] per view (g holds the sizes).
+template <int NCS, int ZC, int PW, int PH, bool MOD>
 __global__ __launch_bounds__(256) void sd_backproject_tiled(SfGeom g, const SfView *__restrict__ views,
                                                             const SdRayCol *__restrict__ rays, const float *__restrict__ sino,
-                                                            float *__restrict__ vol, int tiles_x)
+                                                            float *__restrict__ vol, int tiles_x,
+                                                            const SfGeom *__restrict__ geoms)
 {
     constexpr int PS = PW + BP_ROW_PAD;
     constexpr int NSLOT = ZC + 4;                  // slot s holds voxel k0 + s - 2; slots 0, 1, ZC+2, ZC+3 are dumps
@@ -116,11 +136,12 @@ __global__ __launch_bounds__(256) void sd_backproject_tiled(SfGeom g, const SfVi
     const int i = i0 + ti, j = j0 + tj;
     const int ic = i < g.nx ? i : g.nx - 1, jc = j < g.ny ? j : g.ny - 1;   // out-of-volume threads shadow the edge
 
-    const float z0 = (float)fma((double)k0, g.Tzd, g.zlo0d), z1 = z0 + (float)ZC * g.Tz;
     const float hx = 0.5f * (float)BP_T * g.T;
-    const float xc = (float)(g.x0d + ((double)i0 + 0.5 * (BP_T - 1)) * g.Td);
-    const float yc = (float)(g.y0d + ((double)j0 + 0.5 * (BP_T - 1)) * g.Td);
-    const double zrel0 = g.zk0d - (double)k0 + 2.0;       // Z measured in slots
+    auto geom_of = [&](int a) -> const SfGeom & {
+        if constexpr (MOD) return geoms[a];
+        else return g;
+    };
+    const SdBpScene scene0 = sd_bp_scene<ZC>(geom_of(0), i0, j0, k0);
 
     const int sc = tid & (PW - 1), sr = tid / PW;
     constexpr int NSTAGE = (PH * PW + 255) / 256;
@@ -131,19 +152,23 @@ __global__ __launch_bounds__(256) void sd_backproject_tiled(SfGeom g, const SfVi
 
     float stage[NSTAGE];
     SfWindow win, win_next;
-    sd_load_view<PW, PH, NSTAGE>(g, views[0], sino, xc, yc, hx, z0, z1, sc, sr, win, stage);
+    sd_load_view<PW, PH, NSTAGE>(geom_of(0), views[0], sino, scene0.xc, scene0.yc, hx, scene0.z0, scene0.z1, sc, sr, win, stage);
     win_next = win;
-    sd_store_view<PW, PH, NSTAGE>(g, rays, sc, sr, win, stage, patch[0], rinv[0]);
+    sd_store_view<PW, PH, NSTAGE>(geom_of(0), rays, sc, sr, win, stage, patch[0], rinv[0]);
     __syncthreads();
 
     for (int a = 0; a < g.nviews; ++a) {
         const float *__restrict__ buf = patch[a & 1];
         const float *__restrict__ ri = rinv[a & 1];
-        if (a + 1 < g.nviews)      // global loads in flight during the gather
-            sd_load_view<PW, PH, NSTAGE>(g, views[a + 1], sino + (size_t)(a + 1) * view_stride, xc, yc, hx, z0, z1, sc, sr,
-                                         win_next, stage);
+        if (a + 1 < g.nviews) {    // global loads in flight during the gather
+            const SdBpScene sn = MOD ? sd_bp_scene<ZC>(geom_of(a + 1), i0, j0, k0) : scene0;
+            sd_load_view<PW, PH, NSTAGE>(geom_of(a + 1), views[a + 1], sino + (size_t)(a + 1) * view_stride, sn.xc, sn.yc, hx, sn.z0,
+                                         sn.z1, sc, sr, win_next, stage);
+        }
+        const SfGeom &gv = geom_of(a);
+        const double zrel0 = MOD ? gv.zk0d - (double)k0 + 2.0 : scene0.zrel0;
 
-        const SfColumn f = sf_column(g, views[a], ic, jc);
+        const SfColumn f = sf_column(gv, views[a], ic, jc);
         const int cfirst = (int)ceil(f.xi + (double)f.o0 - 1e-3), clast = (int)floor(f.xi + (double)f.o3 + 1e-3);
         const SdRayCol *__restrict__ rays_a = rays + (size_t)a * g.ncols;
 #pragma unroll
@@ -170,15 +195,15 @@ __global__ __launch_bounds__(256) void sd_backproject_tiled(SfGeom g, const SfVi
             // dt over the piece's rise in Z is scale / |v_r| / 2^32 times the fixed-point distance to the next z-face
             const float scale = dt * (dh > 1e-30f ? 1.0f / dh : 1e30f) * 2.3283064365386963e-10f;
             const int H = win.need_h < PH ? win.need_h : PH;
-            int rz = (int)ceil(-g.v0d / g.pvd) - win.r0;         // first window row with v >= 0
+            int rz = (int)ceil(-gv.v0d / gv.pvd) - win.r0;       // first window row with v >= 0
             rz = rz < 0 ? 0 : (rz > H ? H : rz);
 #pragma unroll
             for (int run = 0; run < 2; ++run) {
                 const int rs = run ? rz : 0, re = run ? H : rz;
                 if (rs >= re) continue;
                 const double h = run ? hmin : hmax;
-                long long q = (long long)floor(fma(sd_row_v(g, win.r0 + rs), h, zrel0) * 4294967296.0);
-                const long long dq = (long long)rint(g.pvd * h * 4294967296.0);
+                long long q = (long long)floor(fma(sd_row_v(gv, win.r0 + rs), h, zrel0) * 4294967296.0);
+                const long long dq = (long long)rint(gv.pvd * h * 4294967296.0);
                 unsigned ofs = (unsigned)(rs * PS + wc);
                 for (int row = rs; row < re; ++row) {
                     int slot = (int)(q >> 32);
@@ -198,8 +223,8 @@ __global__ __launch_bounds__(256) void sd_backproject_tiled(SfGeom g, const SfVi
         }
 
         if (a + 1 < g.nviews)
-            sd_store_view<PW, PH, NSTAGE>(g, rays + (size_t)(a + 1) * g.ncols, sc, sr, win_next, stage, patch[(a + 1) & 1],
-                                          rinv[(a + 1) & 1]);
+            sd_store_view<PW, PH, NSTAGE>(geom_of(a + 1), rays + (size_t)(a + 1) * g.ncols, sc, sr, win_next, stage,
+                                          patch[(a + 1) & 1], rinv[(a + 1) & 1]);
         win = win_next;
         __syncthreads();
     }

@@ -17,11 +17,14 @@
 
 #if defined(__HIPCC__) && !defined(SF_NO_KERNELS)
 
-template <int RG, int SD_WAVES>
-__global__ __launch_bounds__(SD_WAVES * 64) void sd_project_columns(SfGeom g, const SdRayCol *__restrict__ rays,
+// MOD: modular geometry with upright modules: the wave's view brings its own parameter block geoms[a] (the scene
+// translated so that the view is a circular cone-beam view; gk holds the sizes, which all views share).
+template <int RG, int SD_WAVES, bool MOD>
+__global__ __launch_bounds__(SD_WAVES * 64) void sd_project_columns(SfGeom gk, const SdRayCol *__restrict__ rays,
                                                                     const float *__restrict__ volz, float *__restrict__ sino,
                                                                     int nzp, unsigned zero_col, int col_tiles, int bands,
-                                                                    int vb, int tb, int views_pad, int tiles_per_xcd_pad)
+                                                                    int vb, int tb, int views_pad, int tiles_per_xcd_pad,
+                                                                    const SfGeom *__restrict__ geoms)
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -38,10 +41,11 @@ __global__ __launch_bounds__(SD_WAVES * 64) void sd_project_columns(SfGeom g, co
         band = chunk / tchunks;
         ct = ((chunk - band * tchunks) * tb + tloc) * 8 + xcd;
         a = vblk * vb + v_in;
-        if (ct >= col_tiles || a >= g.nviews || band >= bands) return;   // padding blocks (no barrier follows)
+        if (ct >= col_tiles || a >= gk.nviews || band >= bands) return;   // padding blocks (no barrier follows)
     }
     const int c = ct * SD_WAVES + wave;
-    if (c >= g.ncols) return;
+    if (c >= gk.ncols) return;
+    const SfGeom &g = MOD ? geoms[a] : gk;
     const int band0 = band * (RG * 64);
 
     const SdRayCol R = rays[(size_t)a * g.ncols + c];

@@ -215,7 +215,8 @@ extern "C" long host_project_columns(const leap_geometry *G, const float *vol, f
 // Returns -1 when the handle does not use that kernel, else the number of reads that would leave the scratch array.
 extern "C" long host_sd_project_columns(const leap_geometry *G, const float *vol, float *sino)
 {
-    const SfGeom &g = G->g;
+    const SfGeom &gk = G->g;
+    const SfGeom &g = gk;
     if (!G->sd_columns) return -1;
     const int nzp = g.nz + 2 * FP_PAD, kmax = nzp - 2;
     const size_t total = ((size_t)g.nx * g.ny + 1) * nzp;
@@ -228,6 +229,7 @@ extern "C" long host_sd_project_columns(const leap_geometry *G, const float *vol
 #pragma omp parallel for collapse(2) reduction(+ : bad)
     for (int a = 0; a < g.nviews; ++a)
         for (int c = 0; c < g.ncols; ++c) {
+            const SfGeom &g = G->geoms.empty() ? gk : G->geoms[a];        // modular: the view's own parameter block
             const SdRayCol R = G->raycols[(size_t)a * g.ncols + c];
             const int n_major = R.xmajor ? g.nx : g.ny, n_minor = R.xmajor ? g.ny : g.nx;
             for (int r = 0; r < g.nrows; ++r) {

@@ -260,6 +260,47 @@ MODULAR_CASES = [
 ]
 
 
+UPRIGHT_MODULAR_CASES = [
+    ("cone_as_modular", lambda: modular_from(reduced(config(3), 8, nviews=12).replace(shift_u=0.123))),
+    ("shifted_upright_modules", lambda: perturbed_poses(
+        reduced(config(3), 8, nviews=16).replace(nx=67, ny=70, nz=45, nrows=61, ncols=77), 3, shift_mm=25.0, tilt_rad=0.3,
+        upright=True)),
+    ("wobbly_upright_orbit", lambda: perturbed_poses(reduced(config(5), 16, nviews=24), 11, shift_mm=10.0, tilt_rad=0.1,
+                                                     upright=True)),
+]
+
+
+@pytest.mark.parametrize("name,make", UPRIGHT_MODULAR_CASES, ids=[c[0] for c in UPRIGHT_MODULAR_CASES])
+def test_upright_modules_take_the_fast_kernels(torch_mod, oracle_mod, monkeypatch, name, make):
+    """Upright modules run the column / tiled Siddon kernels on per-view parameter blocks; they must agree with the
+    oracle and with the general modular kernels."""
+    from paper_2307_05801_amd import Geometry
+    cfg = make()
+    sd = oracle_mod.siddon
+    x = standard_volume(3, cfg)
+    y = uniform_sinogram(cfg, 6)[0]
+    geo = Geometry(cfg, model="siddon")
+    desc = geo.describe()
+    print(f"[gpu] {name}: {desc}", flush=True)
+    assert "A=columns" in desc and "AT=tiled" in desc and "upright" in desc, desc
+    ax = geo.project(torch_mod.from_numpy(x).cuda()).cpu().numpy()
+    aty = geo.backproject(torch_mod.from_numpy(y).cuda()).cpu().numpy()
+    geo.close()
+    monkeypatch.setenv("LEAP_FORCE_GENERAL", "1")
+    gen = Geometry(cfg, model="siddon")
+    assert "A=general" in gen.describe() and "AT=general" in gen.describe(), gen.describe()
+    ax_g = gen.project(torch_mod.from_numpy(x).cuda()).cpu().numpy()
+    aty_g = gen.backproject(torch_mod.from_numpy(y).cuda()).cpu().numpy()
+    gen.close()
+    e_a, e_t = rel_l2(ax, sd.project(cfg, x)), rel_l2(aty, sd.backproject(cfg, y))
+    print(f"{name}: A {e_a:.2e}  A^T {e_t:.2e}  vs general {rel_l2(ax, ax_g):.2e} {rel_l2(aty, aty_g):.2e}", flush=True)
+    assert e_a <= TOL and e_t <= TOL
+    assert rel_l2(ax, ax_g) <= TOL and rel_l2(aty, aty_g) <= TOL
+    lhs = float((ax.astype(np.float64) * y).sum())
+    rhs = float((aty.astype(np.float64) * x).sum())
+    assert abs(lhs - rhs) <= TOL * abs(lhs)
+
+
 @pytest.mark.parametrize("name,make", MODULAR_CASES, ids=[c[0] for c in MODULAR_CASES])
 def test_modular_geometry_matches_oracle(torch_mod, oracle_mod, name, make):
     """Per-view source position, detector centre and detector orientation (Siddon model)."""

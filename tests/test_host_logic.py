@@ -283,6 +283,22 @@ def test_modular_footprint_bodies_match_oracle_on_cpu(host, oracle_mod, name):
         assert rel_l2(fast, ref) <= TOL, desc
 
 
+@pytest.mark.parametrize("name", list(UPRIGHT_CASES))
+def test_upright_modular_siddon_uses_the_ray_table(host, oracle_mod, name):
+    """Upright modules get the Siddon model's per-column ray table, built on each view's own parameter block: the
+    column kernel's host re-enactment must reproduce the oracle and stay inside the scratch volume."""
+    cfg = UPRIGHT_CASES[name]()
+    x = standard_volume(3, cfg)
+    h = handle(host, cfg, B.LEAP_MODEL_SIDDON)
+    fast = np.zeros(cfg.sino_shape, np.float32)
+    bad = host.host_sd_project_columns(h, x.ctypes.data, fast.ctypes.data)
+    desc = B.leap_geometry_describe(h, host)
+    B.leap_geometry_destroy(h, host)
+    assert "upright" in desc and "AT=tiled" in desc, desc
+    assert "A=columns" in desc and bad == 0, (bad, desc)
+    assert rel_l2(fast, oracle_mod.siddon.project(cfg, x)) <= TOL, desc
+
+
 def test_modular_argument_checks(host):
     cfg = MODULAR_CASES["looking_down"]()
     d, keep = B.desc_from_config(cfg, B.LEAP_MODEL_SF)
