@@ -222,9 +222,13 @@ __global__ __launch_bounds__(256, GT == 1 ? 3 : 4) void sf_backproject_tiled(SfG
                 return s;
             };
             // f: where the voxel's lower face lies inside its first row, in [0,1); the face moves up by av per voxel.
+            // The voxel's first row is carried as a byte offset into the patch array (both buffers), so that every
+            // LDS read is that register plus an immediate and a row crossing costs one select and one add.
             float f = ax.phi0;
-            unsigned row = ofs;                                  // LDS index of the voxel's first row, at this thread's column
-            float s_cur = row_sum(buf + row), s_next = row_sum(buf + row + BP_PS);
+            const char *const lds0 = reinterpret_cast<const char *>(&patch[0][0]);
+            unsigned pb = (unsigned)((a & 1) * (BP_PH * BP_PS) + (int)ofs) * 4u;
+            auto at = [&](unsigned byte_ofs) { return reinterpret_cast<const float *>(lds0 + byte_ofs); };
+            float s_cur = row_sum(at(pb)), s_next = row_sum(at(pb + 4u * BP_PS));
 #pragma unroll
             for (int kk = 0; kk < BP_ZC; ++kk) {
                 const float t = f + ax.av;                        // upper face, still measured from the first row
@@ -233,14 +237,14 @@ __global__ __launch_bounds__(256, GT == 1 ? 3 : 4) void sf_backproject_tiled(SfG
                 acc[kk] = fmaf(w1, s_next, fmaf(w0, s_cur, acc[kk]));
                 if (kk + 1 < BP_ZC) {
                     const bool cross = t >= 1.0f;                 // the next voxel starts in the next row
-                    row += cross ? (unsigned)BP_PS : 0u;
-                    const float s_new = row_sum(buf + row + BP_PS);   // equals s_next when no row was crossed
+                    pb += cross ? 4u * BP_PS : 0u;
+                    const float s_new = row_sum(at(pb + 4u * BP_PS));   // equals s_next when no row was crossed
                     s_cur = cross ? s_next : s_cur;
                     s_next = s_new;
-                    f = t - (cross ? 1.0f : 0.0f);
+                    f = cross ? w1 : t;                           // t - 1 where a row was crossed
                 }
                 if ((kk & 3) == 3)
-                    asm volatile("" : "+v"(row), "+v"(acc[kk - 3]), "+v"(acc[kk - 2]), "+v"(acc[kk - 1]), "+v"(acc[kk]));
+                    asm volatile("" : "+v"(pb), "+v"(acc[kk - 3]), "+v"(acc[kk - 2]), "+v"(acc[kk - 1]), "+v"(acc[kk]));
             }
         } else {
         float lo = ax.phi0;
