@@ -217,6 +217,9 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom gk, c
             const unsigned s_base = (unsigned)__builtin_amdgcn_readlane((int)colbase, e);
             const double s_mu = __hiloint2double(__builtin_amdgcn_readlane(mu_hi, e), __builtin_amdgcn_readlane(mu_lo, e));
             const float step = (float)s_mu;
+            float step_minus[NK];
+#pragma unroll
+            for (int t = 1; t < NK; ++t) step_minus[t] = step - (float)t;
             const char *__restrict__ col = reinterpret_cast<const char *>(volz + s_base);   // wave-uniform base address
 #pragma unroll
             for (int gq = 0; gq < RG; ++gq) {
@@ -226,14 +229,12 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom gk, c
                 int kf = (int)kap;                                 // truncation = floor wherever the clamp leaves it alone
                 asm("v_med3_i32 %0, %1, 0, %2" : "=v"(kf) : "v"(kf), "s"(kmax));   // clamp to [0, kmax] in one op
                 const float *__restrict__ x = reinterpret_cast<const float *>(col + ((unsigned)kf << 2));
-                // overlaps of [kap, kap + step) with voxels kf, kf+1, ...
-                float rem = step, s = 0.0f, w = fminf(1.0f - fr, step);
+                // Overlaps of [kap, kap + step) with voxels kf, kf+1, ...: voxel kf+t, t >= 1, gets clamp(fr + step - t)
+                // and voxel kf the rest of step, so the sum is step * x[0] plus the differences to x[0] times those
+                // overlaps (additions with the clamp modifier issue at twice the rate of min / max).
+                float s = step * x[0];
 #pragma unroll
-                for (int t = 0; t < NK; ++t) {
-                    s = fmaf(w, x[t], s);
-                    rem -= w;
-                    w = (t == NK - 2) ? rem : fminf(rem, 1.0f);
-                }
+                for (int t = 1; t < NK; ++t) s = fmaf(sf_clamp(fr + step_minus[t], 0.0f, 1.0f), x[t] - x[0], s);
 #pragma unroll
                 for (int cw = 0; cw < CW; ++cw) acc[cw][gq] = fmaf(s_fa[cw], s, acc[cw][gq]);
             }
