@@ -560,6 +560,13 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
             // one spare row and column: host and device floats may round apart
             G->bp_tiled = need_w <= BP_SHAPES[sh].pw - 1 && need_h <= BP_SHAPES[sh].ph - 1;
         }
+        // Cylinder: the tiled kernel takes the angle between a voxel's centre and its corners from a short series,
+        // good to 3e-9 rad below 0.08 rad.
+        if (d->type == LEAP_CONE_CURVED) {
+            const double rx = std::fabs(d->center_x) + 0.5 * d->nx * d->voxel_xy, ry = std::fabs(d->center_y) + 0.5 * d->ny * d->voxel_xy;
+            const double nearest = d->sod - std::sqrt(rx * rx + ry * ry);
+            if (!(0.7072 * d->voxel_xy <= 0.08 * nearest)) G->bp_tiled = false;
+        }
     }
 
     // Column-wise forward projection: static limits, then its scratch copy of the volume.
@@ -641,7 +648,37 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         e = hipMalloc((void **)&G->d_raycols, bytes);
         if (e == hipSuccess) e = hipMemcpy(G->d_raycols, G->raycols.data(), bytes, hipMemcpyHostToDevice);
     }
+    if (e == hipSuccess && d->type == LEAP_CONE_CURVED && d->model == LEAP_MODEL_SF && G->bp_tiled) {
+        // For the tiled back projection: cosine and sine of every detector column's fan angle (ray amplitudes), then
+        // per (tile, view) the tile centre's fan angle and the tile's window bounds.
+        const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T;
+        const size_t head = 2 * sizeof(float) * (size_t)d->ncols;
+        const size_t bytes = head + sizeof(SfCurvedBounds) * (size_t)tiles_x * tiles_y * d->nviews;
+        std::vector<unsigned char> blob(bytes);
+        float *cs = reinterpret_cast<float *>(blob.data());
+        for (int c = 0; c < d->ncols; ++c) {
+            const double gam = ((double)c - g.col_offd) * d->pixel_u / d->sdd;
+            cs[2 * (size_t)c] = (float)std::cos(gam);
+            cs[2 * (size_t)c + 1] = (float)std::sin(gam);
+        }
+        SfCurvedBounds *tab = reinterpret_cast<SfCurvedBounds *>(blob.data() + head);
+        const float hx = 0.5f * (float)(BP_T - 1) * g.T;
+        for (int ty = 0; ty < tiles_y; ++ty)
+            for (int tx = 0; tx < tiles_x; ++tx) {
+                const double xcd = g.x0d + ((double)(tx * BP_T) + 0.5 * (BP_T - 1)) * g.Td;
+                const double ycd = g.y0d + ((double)(ty * BP_T) + 0.5 * (BP_T - 1)) * g.Td;
+                SfCurvedBounds *row = tab + ((size_t)ty * tiles_x + tx) * d->nviews;
+                for (int a = 0; a < d->nviews; ++a) {
+                    const SfView &v = G->views[a];
+                    row[a].gref = std::atan2(std::fma(ycd, v.cd, -xcd * v.sd), g.sodd - std::fma(xcd, v.cd, ycd * v.sd));
+                    sf_curved_tile_bounds(g, v, (float)xcd, (float)ycd, hx, row[a].xi_lo, row[a].xi_hi, row[a].ilo, row[a].ihi);
+                }
+            }
+        e = hipMalloc((void **)&G->d_colcs, bytes);
+        if (e == hipSuccess) e = hipMemcpy(G->d_colcs, blob.data(), bytes, hipMemcpyHostToDevice);
+    }
     if (e != hipSuccess) {
+        if (G->d_colcs) (void)hipFree(G->d_colcs);
         if (G->d_views) (void)hipFree(G->d_views);
         if (G->d_volz) (void)hipFree(G->d_volz);
         if (G->d_raycols) (void)hipFree(G->d_raycols);
@@ -660,6 +697,7 @@ extern "C" void leap_geometry_destroy(leap_geometry *G)
     if (G->d_raycols) (void)hipFree(G->d_raycols);
     if (G->d_poses) (void)hipFree(G->d_poses);
     if (G->d_geoms) (void)hipFree(G->d_geoms);
+    if (G->d_colcs) (void)hipFree(G->d_colcs);
     delete G;
 }
 

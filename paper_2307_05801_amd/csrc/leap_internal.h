@@ -43,6 +43,7 @@ struct leap_geometry {
     // footprint model on upright modules: every view is a cone-beam view with its own parameter block
     std::vector<SfGeom> geoms;
     SfGeom *d_geoms = nullptr;
+    void *d_colcs = nullptr;            // cylinder, tiled back projection: (cos, sin) of every column's fan angle, then the (tile, view) table
     bool sd_columns = false;            // wave-per-column forward kernel (needs the scratch copy and slope <= 1)
 };
 

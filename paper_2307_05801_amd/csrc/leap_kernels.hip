@@ -347,7 +347,7 @@ static void launch_bp_tiled_gt(const leap_geometry *G, const float *d_sino, floa
     const unsigned tiles_x = cdiv(g.nx, BP_T), tiles_y = cdiv(g.ny, BP_T);
     dim3 grid(tiles_x * tiles_y, cdiv(g.nz, S.zc), 1);
     hipLaunchKernelGGL((sf_backproject_tiled<NC, NV, S.zc, S.pw, S.ph, GT>), grid, dim3(256, 1, 1), 0, stream, g, G->d_views,
-                       d_sino, d_vol, (int)tiles_x, G->bp_wh, (const SfGeom *)G->d_geoms);
+                       d_sino, d_vol, (int)tiles_x, G->bp_wh, GT == 1 ? (const void *)G->d_colcs : (const void *)G->d_geoms);
 }
 
 template <int NC, int NV, int SH>

@@ -55,9 +55,16 @@ SF_HD void sf_curved_tile_bounds(const SfGeom &g, const SfView &v, float xc, flo
 // xc, yc: tile centre (mm); hx: half extent of the voxel centres in x and y (mm); z0, z1: lower / upper face
 // of the chunk (mm); wh: half of the widest transaxial footprint (pixels); nc, nv: columns / rows a thread reads
 // per voxel (starting at the first one its footprint touches).
+// Cylinder: what depends on (tile, view) only, worked out once per geometry on the host: the fan angle of the tile's
+// centre in double and sf_curved_tile_bounds of the tile.  Stored [tile][view].
+struct SfCurvedBounds {
+    double gref;
+    float xi_lo, xi_hi, ilo, ihi;
+};
+
 template <int GT = -1>
 SF_HD SfWindow sf_bp_window(const SfGeom &g, const SfView &v, float xc, float yc, float hx, float z0, float z1, float wh,
-                            int nc, int nv)
+                            int nc, int nv, const SfCurvedBounds *pre = nullptr)
 {
     SfWindow w;
     const float tc = fmaf(yc, v.c, -xc * v.s);
@@ -66,7 +73,11 @@ SF_HD SfWindow sf_bp_window(const SfGeom &g, const SfView &v, float xc, float yc
     float ilo = 1.0f, ihi = 1.0f;       // smallest / largest 1/den over the tile
     float xi_lo, xi_hi;
     if (sf_is_curved<GT>(g)) {
-        sf_curved_tile_bounds(g, v, xc, yc, hx, xi_lo, xi_hi, ilo, ihi);
+        if (pre) {
+            xi_lo = pre->xi_lo; xi_hi = pre->xi_hi; ilo = pre->ilo; ihi = pre->ihi;
+        } else {
+            sf_curved_tile_bounds(g, v, xc, yc, hx, xi_lo, xi_hi, ilo, ihi);
+        }
     } else {
         if (g.type != SF_PARALLEL) {
             const float lc = fmaf(xc, v.c, yc * v.s);
@@ -92,10 +103,10 @@ SF_HD SfWindow sf_bp_window(const SfGeom &g, const SfView &v, float xc, float yc
 template <int NC, int NV, int PW, int PH, int NSTAGE, int GT>
 __device__ __forceinline__ void bp_load_view(const SfGeom &g, const SfView v, const float *__restrict__ ya, float xc, float yc,
                                              float hx, float z0, float z1, float wh, int sc, int sr, SfWindow &w,
-                                             float (&stage)[NSTAGE])
+                                             float (&stage)[NSTAGE], const SfCurvedBounds *pre = nullptr)
 {
     constexpr int RSTEP = 256 / PW;
-    w = sf_bp_window<GT>(g, v, xc, yc, hx, z0, z1, wh, NC, NV);
+    w = sf_bp_window<GT>(g, v, xc, yc, hx, z0, z1, wh, NC, NV, pre);
     const int c = w.c0 + sc;
     const bool cin = c >= 0 && c < g.ncols;
     ya += cin ? c : 0;
@@ -110,10 +121,19 @@ __device__ __forceinline__ void bp_load_view(const SfGeom &g, const SfView v, co
 // Staging, second half: scale by the ray amplitude and write to LDS.
 template <int PW, int PH, int NSTAGE, int GT>
 __device__ __forceinline__ void bp_store_view(const SfGeom &g, const SfView v, int sc, int sr, const SfWindow &w,
-                                              const float (&stage)[NSTAGE], float *__restrict__ buf)
+                                              const float (&stage)[NSTAGE], float *__restrict__ buf,
+                                              const float2 *__restrict__ colcs = nullptr)
 {
     constexpr int RSTEP = 256 / PW, PS = PW + BP_ROW_PAD;
-    const SfAmpCol ac = sf_amp_col<GT>(g, v, w.c0 + sc);
+    SfAmpCol ac;
+    if (GT == 1 && colcs) {      // cylinder: cosine and sine of the column's fan angle from the per-column table
+        int c = w.c0 + sc;
+        c = c < 0 ? 0 : (c > g.ncols - 1 ? g.ncols - 1 : c);    // columns off the detector were staged as zeros
+        const float2 cs = colcs[c];
+        ac = sf_amp_col_curved(g, v, cs.x, cs.y);
+    } else {
+        ac = sf_amp_col<GT>(g, v, w.c0 + sc);
+    }
 #pragma unroll
     for (int s = 0; s < NSTAGE; ++s) {
         const int row = sr + RSTEP * s;
@@ -142,10 +162,17 @@ SF_HD SfBpScene sf_bp_scene(const SfGeom &g, int i0, int j0, int k0)
 // GT: 0 flat or parallel, 1 cylindrical detector, 2 modular geometry with upright modules (every view brings its own
 // parameter block geoms[a]: the scene translated so that the view is a circular cone-beam view; g holds the sizes).
 template <int NC, int NV, int BP_ZC, int BP_PW, int BP_PH, int GT>
-__global__ __launch_bounds__(256, GT == 1 ? 3 : 4) void sf_backproject_tiled(SfGeom g, const SfView *__restrict__ views,
+__global__ __launch_bounds__(256, 4) void sf_backproject_tiled(SfGeom g, const SfView *__restrict__ views,
                                                             const float *__restrict__ sino, float *__restrict__ vol,
-                                                            int tiles_x, float wh, const SfGeom *__restrict__ geoms)
+                                                            int tiles_x, float wh, const void *__restrict__ aux)
 {
+    // aux: GT == 2: the per-view parameter blocks; GT == 1: cosine and sine of every detector column's fan angle
+    // (ncols pairs of floats), followed by the per-(tile, view) table
+    const SfGeom *__restrict__ geoms = GT == 2 ? static_cast<const SfGeom *>(aux) : nullptr;
+    const float2 *__restrict__ colcs = GT == 1 ? static_cast<const float2 *>(aux) : nullptr;
+    const SfCurvedBounds *__restrict__ cvt =
+        GT == 1 ? reinterpret_cast<const SfCurvedBounds *>(static_cast<const float2 *>(aux) + g.ncols) + (size_t)blockIdx.x * g.nviews
+                : nullptr;
     constexpr int BP_PS = BP_PW + BP_ROW_PAD;      // LDS row stride (floats)
     __shared__ float patch[2][BP_PH * BP_PS];
 
@@ -176,25 +203,38 @@ __global__ __launch_bounds__(256, GT == 1 ? 3 : 4) void sf_backproject_tiled(SfG
     float stage[NSTAGE];
     SfWindow win_next;
 
+    // tile centre in double (cylinder only)
+    const double xcd = g.x0d + ((double)i0 + 0.5 * (BP_T - 1)) * g.Td, ycd = g.y0d + ((double)j0 + 0.5 * (BP_T - 1)) * g.Td;
+    auto cv_pre = [&](int a) -> const SfCurvedBounds * {
+        if constexpr (GT == 1) return cvt + a;
+        else return nullptr;
+    };
+
     SfWindow win;
     bp_load_view<NC, NV, BP_PW, BP_PH, NSTAGE, GT>(geom_of(0), views[0], sino, scene0.xc, scene0.yc, hx, scene0.z0, scene0.z1, wh,
-                                                   sc, sr, win, stage);
+                                                   sc, sr, win, stage, cv_pre(0));
     win_next = win;
-    bp_store_view<BP_PW, BP_PH, NSTAGE, GT>(geom_of(0), views[0], sc, sr, win, stage, patch[0]);
+    bp_store_view<BP_PW, BP_PH, NSTAGE, GT>(geom_of(0), views[0], sc, sr, win, stage, patch[0], colcs);
     __syncthreads();
 
     for (int a = 0; a < g.nviews; ++a) {
         const float *buf = patch[a & 1];
+        double gref = 0.0;
+        if constexpr (GT == 1) gref = cvt[a].gref;
         if (a + 1 < g.nviews) {    // global loads in flight during the gather
             const SfBpScene sn = GT == 2 ? sf_bp_scene<BP_ZC>(geom_of(a + 1), i0, j0, k0) : scene0;
             bp_load_view<NC, NV, BP_PW, BP_PH, NSTAGE, GT>(geom_of(a + 1), views[a + 1], sino + (size_t)(a + 1) * view_stride, sn.xc,
-                                                           sn.yc, hx, sn.z0, sn.z1, wh, sc, sr, win_next, stage);
+                                                           sn.yc, hx, sn.z0, sn.z1, wh, sc, sr, win_next, stage, cv_pre(a + 1));
         }
         const SfGeom &gv = geom_of(a);
         const double zlo_k0 = GT == 2 ? fma((double)k0, gv.Tzd, gv.zlo0d) : scene0.zlo_k0;
 
         const SfView v = views[a];
-        const SfColumn f = sf_column<GT>(gv, v, ic, jc);
+        SfColumn f;
+        if constexpr (GT == 1)
+            f = sf_column_curved_ref(gv, v, ic, jc, fma(ycd, v.cd, -xcd * v.sd), gv.sodd - fma(xcd, v.cd, ycd * v.sd), gref);
+        else
+            f = sf_column<GT>(gv, v, ic, jc);
         int cf, cl;
         sf_col_range(f, cf, cl);
         float fu[NC];
@@ -277,7 +317,7 @@ __global__ __launch_bounds__(256, GT == 1 ? 3 : 4) void sf_backproject_tiled(SfG
         }
 
         if (a + 1 < g.nviews)
-            bp_store_view<BP_PW, BP_PH, NSTAGE, GT>(geom_of(a + 1), views[a + 1], sc, sr, win_next, stage, patch[(a + 1) & 1]);
+            bp_store_view<BP_PW, BP_PH, NSTAGE, GT>(geom_of(a + 1), views[a + 1], sc, sr, win_next, stage, patch[(a + 1) & 1], colcs);
         win = win_next;
         __syncthreads();
     }
