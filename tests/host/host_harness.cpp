@@ -121,7 +121,16 @@ extern "C" int host_check_backproject_windows(const leap_geometry *G, int64_t *r
                     for (int tj = 0; tj < BP_T; ++tj)
                         for (int ti = 0; ti < BP_T; ++ti) {
                             const int i = std::min(i0 + ti, g.nx - 1), j = std::min(j0 + tj, g.ny - 1);
-                            const SfColumn f = sf_column(g, G->views[a], i, j);
+                            SfColumn f;
+                            if (g.type == SF_CONE_CURVED) {      // as the kernel: relative to the tile centre
+                                const double xcd = g.x0d + ((double)i0 + 0.5 * (BP_T - 1)) * g.Td;
+                                const double ycd = g.y0d + ((double)j0 + 0.5 * (BP_T - 1)) * g.Td;
+                                const SfView &v = G->views[a];
+                                const double tref = fma(ycd, v.cd, -xcd * v.sd), dnref = g.sodd - fma(xcd, v.cd, ycd * v.sd);
+                                f = sf_column_curved_ref(g, v, i, j, tref, dnref, atan2(tref, dnref));
+                            } else {
+                                f = sf_column(g, G->views[a], i, j);
+                            }
                             int cf, cl;
                             sf_col_range(f, cf, cl);
                             const SfRowsOfVoxels ax = sf_rows_of_voxels(g, f, zlo);
@@ -139,6 +148,39 @@ extern "C" int host_check_backproject_windows(const leap_geometry *G, int64_t *r
                 }
     report[1] = NC; report[2] = NV; report[3] = S.zc; report[4] = maxc; report[5] = maxr; report[6] = maxspan; report[7] = bad;
     return bad != 0;
+}
+
+// ---- cylinder: the tile-relative column function of the tiled kernel against the general one ------------------------
+// out[0] = largest |difference| of the column coordinate (pixels), out[1] = of the four knot offsets, over every view,
+// tile and voxel column; out[2] = largest corner angle met (rad).
+extern "C" int host_curved_column_deviation(const leap_geometry *G, double *out)
+{
+    const SfGeom &g = G->g;
+    out[0] = out[1] = out[2] = 0.0;
+    if (g.type != SF_CONE_CURVED) return -1;
+    const int tiles_x = (g.nx + BP_T - 1) / BP_T, tiles_y = (g.ny + BP_T - 1) / BP_T;
+    double dxi = 0.0, dof = 0.0, ang = 0.0;
+#pragma omp parallel for collapse(2) reduction(max : dxi, dof, ang)
+    for (int a = 0; a < g.nviews; ++a)
+        for (int ty = 0; ty < tiles_y; ++ty)
+            for (int tx = 0; tx < tiles_x; ++tx) {
+                const SfView &v = G->views[a];
+                const double xcd = g.x0d + ((double)(tx * BP_T) + 0.5 * (BP_T - 1)) * g.Td;
+                const double ycd = g.y0d + ((double)(ty * BP_T) + 0.5 * (BP_T - 1)) * g.Td;
+                const double tref = fma(ycd, v.cd, -xcd * v.sd), dnref = g.sodd - fma(xcd, v.cd, ycd * v.sd);
+                const double gref = atan2(tref, dnref);
+                for (int tj = 0; tj < BP_T; ++tj)
+                    for (int ti = 0; ti < BP_T; ++ti) {
+                        const int i = std::min(tx * BP_T + ti, g.nx - 1), j = std::min(ty * BP_T + tj, g.ny - 1);
+                        const SfColumn p = sf_column(g, v, i, j), q = sf_column_curved_ref(g, v, i, j, tref, dnref, gref);
+                        dxi = std::max(dxi, std::fabs(p.xi - q.xi));
+                        dof = std::max(dof, (double)std::max(std::max(std::fabs(p.o0 - q.o0), std::fabs(p.o1 - q.o1)),
+                                                             std::max(std::fabs(p.o2 - q.o2), std::fabs(p.o3 - q.o3))));
+                        ang = std::max(ang, (double)std::max(std::fabs(p.o0), std::fabs(p.o3)) / g.ku);
+                    }
+            }
+    out[0] = dxi; out[1] = dof; out[2] = ang;
+    return 0;
 }
 
 // ---- column-wise forward projection: its arithmetic, serially ---------------------------------------------------

@@ -41,6 +41,7 @@ def host():
     lib.host_check_backproject_windows.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
     lib.host_project_columns.restype = C.c_long
     lib.host_project_columns.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.host_curved_column_deviation.argtypes = [C.c_void_p, C.POINTER(C.c_double)]
     lib.host_sd_project_columns.restype = C.c_long
     lib.host_sd_project_columns.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     return lib
@@ -165,6 +166,32 @@ def test_tiled_backprojection_reads_stay_inside_the_staged_window(host, name):
     rep, desc = window_report(host, CASES[name][1]())
     assert rep[0] == 1, desc
     assert rep[7] == 0, (rep, desc)
+
+
+@pytest.mark.parametrize("name", ["curved_c3_div8", "curved_wide_fan"])
+def test_curved_tile_relative_columns_agree_with_the_general_function(host, name):
+    """The tiled back projection takes a voxel column's fan angle relative to its tile's centre and the corner angles
+    from a short series.  Against the general function (double atan2, atanf) the column coordinate may move by the
+    float roundings of the small angle (four of them: about 2.4e-7 x angle x pixels per radian, a few 1e-6 pixel on
+    these cases), the knot offsets by less."""
+    h = handle(host, CASES[name][1]())
+    out = (C.c_double * 3)()
+    assert host.host_curved_column_deviation(h, out) == 0
+    desc = B.leap_geometry_describe(h, host)
+    B.leap_geometry_destroy(h, host)
+    assert "AT=tiled" in desc, desc
+    assert out[0] < 4e-6 and out[1] < 1e-6, list(out)
+    assert out[2] < 0.08, list(out)
+
+
+def test_curved_source_too_close_for_the_series(host):
+    """Corner angles above 0.08 rad: the tiled curved kernel is not chosen."""
+    cfg = CTConfig("curved_close", CONE_CURVED, nviews=8, arc_deg=360.0, nrows=40, ncols=64, pixel_v=2.5, pixel_u=2.5,
+                   nx=16, ny=16, nz=16, voxel_xy=2.0, voxel_z=2.0, sod=28.0, sdd=60.0)
+    h = handle(host, cfg)
+    desc = B.leap_geometry_describe(h, host)
+    B.leap_geometry_destroy(h, host)
+    assert "AT=general" in desc, desc
 
 
 def test_window_limits_at_full_benchmark_sizes(host):
