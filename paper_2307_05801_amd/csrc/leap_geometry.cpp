@@ -674,8 +674,14 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
                     sf_curved_tile_bounds(g, v, (float)xcd, (float)ycd, hx, row[a].xi_lo, row[a].xi_hi, row[a].ilo, row[a].ihi);
                 }
             }
-        e = hipMalloc((void **)&G->d_colcs, bytes);
-        if (e == hipSuccess) e = hipMemcpy(G->d_colcs, blob.data(), bytes, hipMemcpyHostToDevice);
+        hipError_t et = hipMalloc((void **)&G->d_colcs, bytes);
+        if (et == hipSuccess) et = hipMemcpy(G->d_colcs, blob.data(), bytes, hipMemcpyHostToDevice);
+        if (et != hipSuccess) {                       // no room for the tables: the general kernel needs none
+            if (G->d_colcs) (void)hipFree(G->d_colcs);
+            G->d_colcs = nullptr;
+            G->bp_tiled = false;
+            (void)hipGetLastError();
+        }
     }
     if (e != hipSuccess) {
         if (G->d_colcs) (void)hipFree(G->d_colcs);
