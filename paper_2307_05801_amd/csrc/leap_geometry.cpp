@@ -156,18 +156,30 @@ static void select_modular_fast_kernels(leap_geometry *G)
     }
     if (d->nrows >= 32 && std::isfinite(vpr) && vpr <= 3.0 && (double)d->nx * d->ny * (d->nz + 2.0 * FP_PAD) < 4294967296.0 &&
         d->ny <= 65535) {
-        G->fp_cw = 2;
-        int need = 0;
-        for (int a = 0; a < d->nviews && need <= 16; ++a)
-            for (int c = 0; c < d->ncols; c += 2) {
-                const SfRayLines L = sf_ray_lines(G->geoms[a], G->views[a], c, 2);
-                const int n_major = L.xmajor ? d->nx : d->ny;
-                const float d0 = std::fabs(L.b0 - L.b1);
-                const float d1 = std::fabs(fmaf(L.m0 - L.m1, (float)(n_major - 1), L.b0 - L.b1));
-                const float dm = d0 > d1 ? d0 : d1;
-                if (!(dm < 1e6f)) { need = 1 << 20; break; }
-                need = std::max(need, (int)std::floor(dm + 2.0f * L.spread + 1e-3f) + 2);
-            }
+        auto slots_needed = [&](int cw) {
+            int need = 0;
+            for (int a = 0; a < d->nviews && need <= 16; ++a)
+                for (int c = 0; c < d->ncols; c += cw) {
+                    const SfRayLines L = sf_ray_lines(G->geoms[a], G->views[a], c, cw);
+                    const int n_major = L.xmajor ? d->nx : d->ny;
+                    const float d0 = std::fabs(L.b0 - L.b1);
+                    const float d1 = std::fabs(fmaf(L.m0 - L.m1, (float)(n_major - 1), L.b0 - L.b1));
+                    const float dm = d0 > d1 ? d0 : d1;
+                    if (!(dm < 1e6f)) return 1 << 20;
+                    need = std::max(need, (int)std::floor(dm + 2.0f * L.spread + 1e-3f) + 2);
+                }
+            return need;
+        };
+        G->fp_cw = 4;                              // the modular instances exist for bundles of 4 and 2 columns
+        if (const char *env = std::getenv("LEAP_FP_CW")) {
+            const int v = std::atoi(env);
+            if (v == 2 || v == 4) G->fp_cw = v;
+        }
+        int need = slots_needed(G->fp_cw);
+        if (need > 16 && G->fp_cw == 4) {
+            G->fp_cw = 2;
+            need = slots_needed(2);
+        }
         G->fp_need_q = need;
         G->fp_nq = need <= 4 ? 4 : (need <= 8 ? 8 : 16);
         G->fp_nk = std::max(2, (int)std::ceil(vpr - 1e-6) + 1);
@@ -577,7 +589,7 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
             const int v = std::atoi(env);
             if (v == 1 || v == 2 || v == 4) G->fp_cw = v;
         }
-        if (d->type == LEAP_CONE_CURVED) G->fp_cw = 2;      // the cylinder has one instance per shape
+        if (d->type == LEAP_CONE_CURVED) G->fp_cw = 2;      // the cylinder has one instance per shape (with 4 columns it spills: 209 ms)
         // candidate slots per slab: widest range of voxel columns any bundle of cw detector columns can see
         auto slots_needed = [&](int cw) {
             int need = 0;

@@ -29,7 +29,7 @@ struct leap_geometry {
     bool bp_tiled = false;
     int bp_need_w = 0, bp_need_h = 0;   // largest staged window any (view, tile, chunk) asks for
     // column-wise forward projection: candidate slots per slab, voxels per detector row, row groups per wave
-    int fp_nq = 0, fp_nk = 0, fp_rg = 0, fp_need_q = 0, fp_waves = 4, fp_cw = 2, fp_wv = 1, fp_vb = 128, fp_tb = 1;
+    int fp_nq = 0, fp_nk = 0, fp_rg = 0, fp_need_q = 0, fp_waves = 4, fp_cw = 4, fp_wv = 1, fp_vb = 128, fp_tb = 1;
     bool fp_columns = false;
     float *d_volz = nullptr;            // z-fastest padded copy of one volume (scratch)
     int nzp = 0;

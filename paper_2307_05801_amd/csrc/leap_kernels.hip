@@ -267,10 +267,15 @@ static void launch_fp_columns(const leap_geometry *G, float *d_sino, hipStream_t
 template <int NQ, int NK, int RG>
 static bool launch_fp_w(const leap_geometry *G, float *d_sino, hipStream_t stream)
 {
-    if (G->g.type == SF_CONE_CURVED || G->g.type == SF_MODULAR) {     // the default bundle width only
+    if (G->g.type == SF_CONE_CURVED) {     // bundles of 2 columns only
         if (G->fp_cw != 2) return false;
-        if (G->g.type == SF_MODULAR) launch_fp_columns<NQ, NK, RG, 2, 2>(G, d_sino, stream);
-        else launch_fp_columns<NQ, NK, RG, 2, 1>(G, d_sino, stream);
+        launch_fp_columns<NQ, NK, RG, 2, 1>(G, d_sino, stream);
+        return true;
+    }
+    if (G->g.type == SF_MODULAR) {
+        if (G->fp_cw == 4) launch_fp_columns<NQ, NK, RG, 4, 2>(G, d_sino, stream);
+        else if (G->fp_cw == 2) launch_fp_columns<NQ, NK, RG, 2, 2>(G, d_sino, stream);
+        else return false;
         return true;
     }
     switch (G->fp_cw) {

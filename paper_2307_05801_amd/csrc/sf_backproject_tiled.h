@@ -162,7 +162,7 @@ SF_HD SfBpScene sf_bp_scene(const SfGeom &g, int i0, int j0, int k0)
 // GT: 0 flat or parallel, 1 cylindrical detector, 2 modular geometry with upright modules (every view brings its own
 // parameter block geoms[a]: the scene translated so that the view is a circular cone-beam view; g holds the sizes).
 template <int NC, int NV, int BP_ZC, int BP_PW, int BP_PH, int GT>
-__global__ __launch_bounds__(256, 4) void sf_backproject_tiled(SfGeom g, const SfView *__restrict__ views,
+__global__ __launch_bounds__(256, (GT == 1 && NV > 2 && BP_ZC > 32) ? 3 : 4) void sf_backproject_tiled(SfGeom g, const SfView *__restrict__ views,
                                                             const float *__restrict__ sino, float *__restrict__ vol,
                                                             int tiles_x, float wh, const void *__restrict__ aux)
 {

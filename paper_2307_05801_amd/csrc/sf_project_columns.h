@@ -248,6 +248,7 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom gk, c
 #pragma unroll
     for (int cw = 0; cw < CW; ++cw) ac[cw] = sf_amp_col<GT>(g, v, c0 + cw < g.ncols ? c0 + cw : g.ncols - 1);
     struct __attribute__((packed, aligned(4))) Pair { float lo, hi; };
+    struct __attribute__((packed, aligned(4))) Quad { float a, b, c, d; };
 #pragma unroll
     for (int gq = 0; gq < RG; ++gq) {
         const int r = band0 + 64 * gq + lane;
@@ -261,6 +262,14 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom gk, c
                 Pair pr;
                 pr.lo = out[0]; pr.hi = out[1];
                 *reinterpret_cast<Pair *>(dst) = pr;
+                continue;
+            }
+        }
+        if constexpr (CW == 4) {
+            if (c0 + 3 < g.ncols) {
+                Quad qd;
+                qd.a = out[0]; qd.b = out[1]; qd.c = out[2]; qd.d = out[3];
+                *reinterpret_cast<Quad *>(dst) = qd;
                 continue;
             }
         }
