@@ -106,6 +106,26 @@ def test_forward_and_adjoint_match_oracle(torch_mod, oracle_mod, name, number, m
         assert rel_l2(gpu_backproject(torch_mod, cfg, ax32), oracle_mod.backproject(cfg, ax32)) <= TOL
 
 
+@pytest.mark.parametrize("cw", ["1", "2", "4"])
+@pytest.mark.parametrize("name,number,make", [c for c in SMALL_CASES if c[0] in ("c2_div4_ragged", "c3_div8_ragged")],
+                         ids=["c2_div4_ragged", "c3_div8_ragged"])
+def test_forward_bundle_widths_on_ragged_detectors(torch_mod, oracle_mod, monkeypatch, name, number, make, cw):
+    """Every bundle width of the column-wise forward kernel on detectors whose column count is odd: the last bundle is
+    partial and the 8- and 16-byte stores of whole bundles are only 4-byte aligned."""
+    from paper_2307_05801_amd import Geometry
+    cfg = make()
+    assert cfg.ncols % 2 == 1
+    x = standard_volume(number, cfg)
+    monkeypatch.setenv("LEAP_FP_CW", cw)
+    geo = Geometry(cfg)
+    desc = geo.describe()
+    print(f"[gpu] {name} cw={cw}: {desc}", flush=True)
+    assert f"cw={cw}" in desc and "A=columns" in desc, desc
+    ax = geo.project(torch_mod.from_numpy(x).cuda()).cpu().numpy()
+    geo.close()
+    assert rel_l2(ax, oracle_mod.project(cfg, x)) <= TOL
+
+
 @pytest.mark.parametrize("geom", [PARALLEL, FAN, CONE])
 def test_columns_of_A_match_the_dense_oracle_matrix(torch_mod, oracle_mod, geom):
     """Every entry of A and of A^T on a tiny grid with shifts and centre offsets, by unit vectors in a batch."""
