@@ -22,11 +22,14 @@
  *   - Calls are asynchronous on the given HIP stream (hipStream_t passed as void*, NULL =
  *     the default stream) and allocate nothing.  Per-view tables are uploaded once, in
  *     leap_geometry_create.  Device memory beyond the caller's arrays ("Performance and
- *     Memory Usage" asks for one copy of each array only): the handle owns ONE scratch
- *     array of nx*ny*(nz+8) floats, a z-fastest copy of the volume that leap_project
- *     rewrites on every call; when it cannot be allocated the handle works without it
- *     (slower kernels).  A LEAP_MODEL_SIDDON handle also keeps a table of 48 bytes per
- *     (view, detector column): the constants of each ray's line.  Because of the scratch copy, calls that use the same handle must be
+ *     Memory Usage" asks for one copy of each array only): the handle owns a scratch
+ *     array of (nx*ny+1)*(nz+8) floats, a z-fastest copy of the volume that leap_project
+ *     rewrites on every call (small volumes: up to 16 such copies, as many as fit in
+ *     1 GiB, so that a batch is projected in one launch); when it cannot be allocated
+ *     the handle works without it (slower kernels).  A LEAP_MODEL_SIDDON handle also
+ *     keeps a table of 48 bytes per (view, detector column): the constants of each
+ *     ray's line; a LEAP_CONE_CURVED footprint handle 24 bytes per (16x16 voxel-column
+ *     tile, view).  Because of the scratch copy, calls that use the same handle must be
  *     ordered (one stream at a time, or events between streams); distinct handles are
  *     independent.
  *   - World frame: voxel centres x_i = center_x + (i-(nx-1)/2) voxel_xy (y, z alike); view

@@ -652,8 +652,21 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
     if (e == hipSuccess && (G->fp_columns || G->sd_columns)) {
         G->nzp = d->nz + 2 * FP_PAD;
         // one more column than the volume has: it stays zero and stands for cells outside the volume (Siddon kernel)
-        const size_t bytes = sizeof(float) * ((size_t)d->nx * d->ny + 1) * G->nzp;
+        const size_t item_bytes = sizeof(float) * ((size_t)d->nx * d->ny + 1) * G->nzp;
+        // Small volumes (a batch of training volumes): up to 16 scratch copies within 1 GiB, so that the footprint
+        // kernel can take that many items of a batch in one launch.
+        if (G->fp_columns) {
+            const size_t fit = ((size_t)1 << 30) / item_bytes;
+            G->volz_items = (int)(fit < 1 ? 1 : (fit > 16 ? 16 : fit));
+        }
+        size_t bytes = item_bytes * (size_t)G->volz_items;
         hipError_t es = hipMalloc((void **)&G->d_volz, bytes);
+        if (es != hipSuccess && G->volz_items > 1) {                      // one copy at least
+            (void)hipGetLastError();
+            G->volz_items = 1;
+            bytes = item_bytes;
+            es = hipMalloc((void **)&G->d_volz, bytes);
+        }
         if (es == hipSuccess) es = hipMemset(G->d_volz, 0, bytes);       // the pads stay zero for the handle's life
         if (es == hipSuccess) es = hipDeviceSynchronize();
         if (es != hipSuccess) {                                           // no room for the copy: use the general kernel
@@ -772,11 +785,8 @@ extern "C" int leap_project(const leap_geometry *G, const float *d_vol, float *d
     int rc = check_call(G, d_vol, d_sino, batch);
     if (rc != LEAP_OK) return rc;
     const size_t nvol = (size_t)G->g.nx * G->g.ny * G->g.nz, nsino = (size_t)G->g.nviews * G->g.nrows * G->g.ncols;
-    for (int32_t b = 0; b < batch; ++b) {
-        rc = leap_launch_project(G, d_vol + b * nvol, d_sino + b * nsino, (hipStream_t)hip_stream);
-        if (rc != LEAP_OK) return rc;
-    }
-    return LEAP_OK;
+    (void)nvol; (void)nsino;
+    return leap_launch_project_batch(G, d_vol, d_sino, batch, (hipStream_t)hip_stream);
 }
 
 extern "C" int leap_backproject(const leap_geometry *G, const float *d_sino, float *d_vol, int32_t batch, void *hip_stream)
@@ -784,9 +794,6 @@ extern "C" int leap_backproject(const leap_geometry *G, const float *d_sino, flo
     int rc = check_call(G, d_sino, d_vol, batch);
     if (rc != LEAP_OK) return rc;
     const size_t nvol = (size_t)G->g.nx * G->g.ny * G->g.nz, nsino = (size_t)G->g.nviews * G->g.nrows * G->g.ncols;
-    for (int32_t b = 0; b < batch; ++b) {
-        rc = leap_launch_backproject(G, d_sino + b * nsino, d_vol + b * nvol, (hipStream_t)hip_stream);
-        if (rc != LEAP_OK) return rc;
-    }
-    return LEAP_OK;
+    (void)nvol; (void)nsino;
+    return leap_launch_backproject_batch(G, d_sino, d_vol, batch, (hipStream_t)hip_stream);
 }

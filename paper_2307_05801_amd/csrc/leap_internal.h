@@ -44,6 +44,7 @@ struct leap_geometry {
     std::vector<SfGeom> geoms;
     SfGeom *d_geoms = nullptr;
     void *d_colcs = nullptr;            // cylinder, tiled back projection: (cos, sin) of every column's fan angle, then the (tile, view) table
+    int volz_items = 1;                 // scratch copies of the volume (items of a batch per forward launch)
     bool sd_columns = false;            // wave-per-column forward kernel (needs the scratch copy and slope <= 1)
 };
 
@@ -58,4 +59,6 @@ int leap_hip_fail(hipError_t e, const char *what);
 
 // kernel launchers (leap_kernels.hip); one batch item per call
 int leap_launch_project(const leap_geometry *geom, const float *d_vol, float *d_sino, hipStream_t stream);
+int leap_launch_project_batch(const leap_geometry *geom, const float *d_vol, float *d_sino, int batch, hipStream_t stream);
 int leap_launch_backproject(const leap_geometry *geom, const float *d_sino, float *d_vol, hipStream_t stream);
+int leap_launch_backproject_batch(const leap_geometry *geom, const float *d_sino, float *d_vol, int batch, hipStream_t stream);

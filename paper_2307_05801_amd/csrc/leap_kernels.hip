@@ -249,7 +249,7 @@ static int launch_sd_backproject(const leap_geometry *G, const float *d_sino, fl
 }
 
 template <int NQ, int NK, int RG, int CW, int GT>
-static void launch_fp_columns(const leap_geometry *G, float *d_sino, hipStream_t stream)
+static void launch_fp_columns(const leap_geometry *G, float *d_sino, hipStream_t stream, int items)
 {
     constexpr int W = 4;          // waves per workgroup (8 and 16 measured slower)
     const SfGeom &g = G->g;
@@ -258,39 +258,39 @@ static void launch_fp_columns(const leap_geometry *G, float *d_sino, hipStream_t
     const int vb = G->fp_vb, tb = G->fp_tb;
     const int vgroups_pad = (int)cdiv(g.nviews, vb) * vb;
     const int tiles_per_xcd_pad = (int)cdiv(cdiv(col_tiles, 8), tb) * tb;
-    dim3 grid((unsigned)(8 * tiles_per_xcd_pad * vgroups_pad * bands), 1, 1);
+    dim3 grid((unsigned)(8 * tiles_per_xcd_pad * vgroups_pad * bands), (unsigned)items, 1);
     hipLaunchKernelGGL((sf_project_columns<NQ, NK, RG, W, CW, 1, GT>), grid, dim3(W * 64, 1, 1), 0, stream, g, G->d_views,
                        G->d_volz, d_sino, G->nzp, col_tiles, bands, vb, tb, vgroups_pad, tiles_per_xcd_pad,
                        (const SfGeom *)G->d_geoms);
 }
 
 template <int NQ, int NK, int RG>
-static bool launch_fp_w(const leap_geometry *G, float *d_sino, hipStream_t stream)
+static bool launch_fp_w(const leap_geometry *G, float *d_sino, hipStream_t stream, int items)
 {
     if (G->g.type == SF_CONE_CURVED) {     // bundles of 2 columns only
         if (G->fp_cw != 2) return false;
-        launch_fp_columns<NQ, NK, RG, 2, 1>(G, d_sino, stream);
+        launch_fp_columns<NQ, NK, RG, 2, 1>(G, d_sino, stream, items);
         return true;
     }
     // four columns with four voxels per row and eight row groups: never selected (that instance serialises its loads)
     constexpr bool has4 = !(NK == 4 && RG == 8);
     if (G->g.type == SF_MODULAR) {
         if (G->fp_cw == 4) {
-            if constexpr (has4) launch_fp_columns<NQ, NK, RG, 4, 2>(G, d_sino, stream);
+            if constexpr (has4) launch_fp_columns<NQ, NK, RG, 4, 2>(G, d_sino, stream, items);
             else return false;
         } else if (G->fp_cw == 2) {
-            launch_fp_columns<NQ, NK, RG, 2, 2>(G, d_sino, stream);
+            launch_fp_columns<NQ, NK, RG, 2, 2>(G, d_sino, stream, items);
         } else {
             return false;
         }
         return true;
     }
     switch (G->fp_cw) {
-    case 1: launch_fp_columns<NQ, NK, RG, 1, 0>(G, d_sino, stream); return true;
-    case 2: launch_fp_columns<NQ, NK, RG, 2, 0>(G, d_sino, stream); return true;
+    case 1: launch_fp_columns<NQ, NK, RG, 1, 0>(G, d_sino, stream, items); return true;
+    case 2: launch_fp_columns<NQ, NK, RG, 2, 0>(G, d_sino, stream, items); return true;
     case 4:
         if constexpr (has4) {
-            launch_fp_columns<NQ, NK, RG, 4, 0>(G, d_sino, stream);
+            launch_fp_columns<NQ, NK, RG, 4, 0>(G, d_sino, stream, items);
             return true;
         } else {
             return false;
@@ -300,49 +300,77 @@ static bool launch_fp_w(const leap_geometry *G, float *d_sino, hipStream_t strea
 }
 
 template <int NQ, int NK>
-static bool launch_fp_rg(const leap_geometry *G, float *d_sino, hipStream_t stream)
+static bool launch_fp_rg(const leap_geometry *G, float *d_sino, hipStream_t stream, int items)
 {
     switch (G->fp_rg) {
-    case 1: return launch_fp_w<NQ, NK, 1>(G, d_sino, stream);
-    case 2: return launch_fp_w<NQ, NK, 2>(G, d_sino, stream);
-    case 4: return launch_fp_w<NQ, NK, 4>(G, d_sino, stream);
-    case 8: return launch_fp_w<NQ, NK, 8>(G, d_sino, stream);
+    case 1: return launch_fp_w<NQ, NK, 1>(G, d_sino, stream, items);
+    case 2: return launch_fp_w<NQ, NK, 2>(G, d_sino, stream, items);
+    case 4: return launch_fp_w<NQ, NK, 4>(G, d_sino, stream, items);
+    case 8: return launch_fp_w<NQ, NK, 8>(G, d_sino, stream, items);
     default: return false;
     }
 }
 
 template <int NQ>
-static bool launch_fp_nk(const leap_geometry *G, float *d_sino, hipStream_t stream)
+static bool launch_fp_nk(const leap_geometry *G, float *d_sino, hipStream_t stream, int items)
 {
     switch (G->fp_nk) {
-    case 2: return launch_fp_rg<NQ, 2>(G, d_sino, stream);
-    case 3: return launch_fp_rg<NQ, 3>(G, d_sino, stream);
-    case 4: return launch_fp_rg<NQ, 4>(G, d_sino, stream);
+    case 2: return launch_fp_rg<NQ, 2>(G, d_sino, stream, items);
+    case 3: return launch_fp_rg<NQ, 3>(G, d_sino, stream, items);
+    case 4: return launch_fp_rg<NQ, 4>(G, d_sino, stream, items);
     default: return false;
     }
+}
+
+// The column-wise footprint kernel on `items` consecutive volumes of a batch (at most G->volz_items: one scratch copy each).
+static int launch_fp_items(const leap_geometry *G, const float *d_vol, float *d_sino, int items, hipStream_t stream)
+{
+    const SfGeom &g = G->g;
+    dim3 tgrid(cdiv(g.nx, 32), cdiv(g.nz, 32), (unsigned)(g.ny * items));
+    hipLaunchKernelGGL(sf_volume_to_columns, tgrid, dim3(32, 8, 1), 0, stream, d_vol, G->d_volz, g.nx, g.ny, g.nz, G->nzp);
+    bool ok = false;
+    switch (G->fp_nq) {
+    case 4: ok = launch_fp_nk<4>(G, d_sino, stream, items); break;
+    case 8: ok = launch_fp_nk<8>(G, d_sino, stream, items); break;
+    case 16: ok = launch_fp_nk<16>(G, d_sino, stream, items); break;
+    default: break;
+    }
+    if (!ok) {
+        leap_set_error("internal: no column-wise forward instance for this footprint");
+        return LEAP_UNSUPPORTED;
+    }
+    LEAP_HIP_CHECK(hipGetLastError());
+    return LEAP_OK;
+}
+
+int leap_launch_project_batch(const leap_geometry *G, const float *d_vol, float *d_sino, int batch, hipStream_t stream)
+{
+    const SfGeom &g = G->g;
+    const size_t nvol = (size_t)g.nx * g.ny * g.nz, nsino = (size_t)g.nviews * g.nrows * g.ncols;
+    if (g.model != SF_MODEL_SIDDON && G->fp_columns) {
+        // small volumes: several items per launch fill the chip (a batch of training volumes), each in its own scratch copy
+        int per = G->volz_items < 1 ? 1 : G->volz_items;
+        if (per > 65535 / g.ny) per = 65535 / g.ny;
+        if (per < 1) per = 1;
+        for (int b = 0; b < batch; b += per) {
+            const int items = batch - b < per ? batch - b : per;
+            const int rc = launch_fp_items(G, d_vol + b * nvol, d_sino + b * nsino, items, stream);
+            if (rc != LEAP_OK) return rc;
+        }
+        return LEAP_OK;
+    }
+    for (int b = 0; b < batch; ++b) {
+        const int rc = leap_launch_project(G, d_vol + b * nvol, d_sino + b * nsino, stream);
+        if (rc != LEAP_OK) return rc;
+    }
+    return LEAP_OK;
 }
 
 int leap_launch_project(const leap_geometry *G, const float *d_vol, float *d_sino, hipStream_t stream)
 {
     const SfGeom &g = G->g;
     if (g.model == SF_MODEL_SIDDON) return launch_sd_project(G, d_vol, d_sino, stream);
-    if (G->fp_columns) {
-        dim3 tgrid(cdiv(g.nx, 32), cdiv(g.nz, 32), g.ny);
-        hipLaunchKernelGGL(sf_volume_to_columns, tgrid, dim3(32, 8, 1), 0, stream, d_vol, G->d_volz, g.nx, g.ny, g.nz, G->nzp);
-        bool ok = false;
-        switch (G->fp_nq) {
-        case 4: ok = launch_fp_nk<4>(G, d_sino, stream); break;
-        case 8: ok = launch_fp_nk<8>(G, d_sino, stream); break;
-        case 16: ok = launch_fp_nk<16>(G, d_sino, stream); break;
-        default: break;
-        }
-        if (!ok) {
-            leap_set_error("internal: no column-wise forward instance for this footprint");
-            return LEAP_UNSUPPORTED;
-        }
-        LEAP_HIP_CHECK(hipGetLastError());
-        return LEAP_OK;
-    }
+    if (G->fp_columns) return launch_fp_items(G, d_vol, d_sino, 1, stream);
     dim3 block(64, 4, 1);
     dim3 grid(cdiv(g.ncols, 64), cdiv(cdiv(g.nrows, GEN_RC), 4), g.nviews);
     if (grid.y > 65535u) {
@@ -358,65 +386,89 @@ int leap_launch_project(const leap_geometry *G, const float *d_vol, float *d_sin
 }
 
 template <int NC, int NV, int SH, int GT>
-static void launch_bp_tiled_gt(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
+static void launch_bp_tiled_gt(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream, int items)
 {
     constexpr SfBpShape S = BP_SHAPES[SH];
     const SfGeom &g = G->g;
     const unsigned tiles_x = cdiv(g.nx, BP_T), tiles_y = cdiv(g.ny, BP_T);
-    dim3 grid(tiles_x * tiles_y, cdiv(g.nz, S.zc), 1);
+    dim3 grid(tiles_x * tiles_y, cdiv(g.nz, S.zc), (unsigned)items);
     hipLaunchKernelGGL((sf_backproject_tiled<NC, NV, S.zc, S.pw, S.ph, GT>), grid, dim3(256, 1, 1), 0, stream, g, G->d_views,
                        d_sino, d_vol, (int)tiles_x, G->bp_wh, GT == 1 ? (const void *)G->d_colcs : (const void *)G->d_geoms);
 }
 
 template <int NC, int NV, int SH>
-static void launch_bp_tiled(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
+static void launch_bp_tiled(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream, int items)
 {
-    if (G->g.type == SF_CONE_CURVED) launch_bp_tiled_gt<NC, NV, SH, 1>(G, d_sino, d_vol, stream);
-    else if (G->g.type == SF_MODULAR) launch_bp_tiled_gt<NC, NV, SH, 2>(G, d_sino, d_vol, stream);
-    else launch_bp_tiled_gt<NC, NV, SH, 0>(G, d_sino, d_vol, stream);
+    if (G->g.type == SF_CONE_CURVED) launch_bp_tiled_gt<NC, NV, SH, 1>(G, d_sino, d_vol, stream, items);
+    else if (G->g.type == SF_MODULAR) launch_bp_tiled_gt<NC, NV, SH, 2>(G, d_sino, d_vol, stream, items);
+    else launch_bp_tiled_gt<NC, NV, SH, 0>(G, d_sino, d_vol, stream, items);
 }
 
 template <int NC, int NV>
-static bool launch_bp_shape(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
+static bool launch_bp_shape(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream, int items)
 {
     switch (G->bp_shape) {
-    case 0: launch_bp_tiled<NC, NV, 0>(G, d_sino, d_vol, stream); return true;
-    case 1: launch_bp_tiled<NC, NV, 1>(G, d_sino, d_vol, stream); return true;
-    case 2: launch_bp_tiled<NC, NV, 2>(G, d_sino, d_vol, stream); return true;
-    case 3: launch_bp_tiled<NC, NV, 3>(G, d_sino, d_vol, stream); return true;
-    case 4: launch_bp_tiled<NC, NV, 4>(G, d_sino, d_vol, stream); return true;
+    case 0: launch_bp_tiled<NC, NV, 0>(G, d_sino, d_vol, stream, items); return true;
+    case 1: launch_bp_tiled<NC, NV, 1>(G, d_sino, d_vol, stream, items); return true;
+    case 2: launch_bp_tiled<NC, NV, 2>(G, d_sino, d_vol, stream, items); return true;
+    case 3: launch_bp_tiled<NC, NV, 3>(G, d_sino, d_vol, stream, items); return true;
+    case 4: launch_bp_tiled<NC, NV, 4>(G, d_sino, d_vol, stream, items); return true;
     default: return false;
     }
+}
+
+// The tiled footprint back projection on `items` consecutive sinograms of a batch in one launch.
+static int launch_bp_items(const leap_geometry *G, const float *d_sino, float *d_vol, int items, hipStream_t stream)
+{
+    bool ok = false;
+    switch (G->bp_nc * 10 + G->bp_nv) {
+    case 22: ok = launch_bp_shape<2, 2>(G, d_sino, d_vol, stream, items); break;
+    case 23: ok = launch_bp_shape<2, 3>(G, d_sino, d_vol, stream, items); break;
+    case 32: ok = launch_bp_shape<3, 2>(G, d_sino, d_vol, stream, items); break;
+    case 33: ok = launch_bp_shape<3, 3>(G, d_sino, d_vol, stream, items); break;
+    case 24: ok = launch_bp_shape<2, 4>(G, d_sino, d_vol, stream, items); break;
+    case 34: ok = launch_bp_shape<3, 4>(G, d_sino, d_vol, stream, items); break;
+    case 42: ok = launch_bp_shape<4, 2>(G, d_sino, d_vol, stream, items); break;
+    case 43: ok = launch_bp_shape<4, 3>(G, d_sino, d_vol, stream, items); break;
+    case 44: ok = launch_bp_shape<4, 4>(G, d_sino, d_vol, stream, items); break;
+    case 52: ok = launch_bp_shape<5, 2>(G, d_sino, d_vol, stream, items); break;
+    case 53: ok = launch_bp_shape<5, 3>(G, d_sino, d_vol, stream, items); break;
+    case 54: ok = launch_bp_shape<5, 4>(G, d_sino, d_vol, stream, items); break;
+    default: break;
+    }
+    if (!ok) {
+        leap_set_error("internal: no tiled back-projection instance for this footprint");
+        return LEAP_UNSUPPORTED;
+    }
+    LEAP_HIP_CHECK(hipGetLastError());
+    return LEAP_OK;
+}
+
+int leap_launch_backproject_batch(const leap_geometry *G, const float *d_sino, float *d_vol, int batch, hipStream_t stream)
+{
+    const SfGeom &g = G->g;
+    const size_t nvol = (size_t)g.nx * g.ny * g.nz, nsino = (size_t)g.nviews * g.nrows * g.ncols;
+    if (g.model != SF_MODEL_SIDDON && G->bp_tiled) {
+        // up to 16 items per launch (a batch of small training volumes fills the chip better that way)
+        for (int b = 0; b < batch; b += 16) {
+            const int items = batch - b < 16 ? batch - b : 16;
+            const int rc = launch_bp_items(G, d_sino + b * nsino, d_vol + b * nvol, items, stream);
+            if (rc != LEAP_OK) return rc;
+        }
+        return LEAP_OK;
+    }
+    for (int b = 0; b < batch; ++b) {
+        const int rc = leap_launch_backproject(G, d_sino + b * nsino, d_vol + b * nvol, stream);
+        if (rc != LEAP_OK) return rc;
+    }
+    return LEAP_OK;
 }
 
 int leap_launch_backproject(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
 {
     const SfGeom &g = G->g;
     if (g.model == SF_MODEL_SIDDON) return launch_sd_backproject(G, d_sino, d_vol, stream);
-    if (G->bp_tiled) {
-        bool ok = false;
-        switch (G->bp_nc * 10 + G->bp_nv) {
-        case 22: ok = launch_bp_shape<2, 2>(G, d_sino, d_vol, stream); break;
-        case 23: ok = launch_bp_shape<2, 3>(G, d_sino, d_vol, stream); break;
-        case 32: ok = launch_bp_shape<3, 2>(G, d_sino, d_vol, stream); break;
-        case 33: ok = launch_bp_shape<3, 3>(G, d_sino, d_vol, stream); break;
-        case 24: ok = launch_bp_shape<2, 4>(G, d_sino, d_vol, stream); break;
-        case 34: ok = launch_bp_shape<3, 4>(G, d_sino, d_vol, stream); break;
-        case 42: ok = launch_bp_shape<4, 2>(G, d_sino, d_vol, stream); break;
-        case 43: ok = launch_bp_shape<4, 3>(G, d_sino, d_vol, stream); break;
-        case 44: ok = launch_bp_shape<4, 4>(G, d_sino, d_vol, stream); break;
-        case 52: ok = launch_bp_shape<5, 2>(G, d_sino, d_vol, stream); break;
-        case 53: ok = launch_bp_shape<5, 3>(G, d_sino, d_vol, stream); break;
-        case 54: ok = launch_bp_shape<5, 4>(G, d_sino, d_vol, stream); break;
-        default: break;
-        }
-        if (!ok) {
-            leap_set_error("internal: no tiled back-projection instance for this footprint");
-            return LEAP_UNSUPPORTED;
-        }
-        LEAP_HIP_CHECK(hipGetLastError());
-        return LEAP_OK;
-    }
+    if (G->bp_tiled) return launch_bp_items(G, d_sino, d_vol, 1, stream);
     dim3 block(64, 4, 1);
     dim3 grid(cdiv(g.nx, 64), cdiv(g.ny, 4), cdiv(g.nz, GEN_ZC));
     if (grid.y > 65535u || grid.z > 65535u) {

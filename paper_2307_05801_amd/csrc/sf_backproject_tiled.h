@@ -175,6 +175,9 @@ __global__ __launch_bounds__(256, (GT == 1 && NV > 2 && BP_ZC > 32) ? 3 : 4) voi
                 : nullptr;
     constexpr int BP_PS = BP_PW + BP_ROW_PAD;      // LDS row stride (floats)
     __shared__ float patch[2][BP_PH * BP_PS];
+    // blockIdx.z: item of a batch
+    sino += (size_t)blockIdx.z * g.nviews * g.nrows * g.ncols;
+    vol += (size_t)blockIdx.z * g.nx * g.ny * g.nz;
 
     const int tid = threadIdx.x;
     const int ti = tid & (BP_T - 1), tj = tid >> 4;

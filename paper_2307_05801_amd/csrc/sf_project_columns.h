@@ -95,7 +95,10 @@ __global__ __launch_bounds__(256) void sf_volume_to_columns(const float *__restr
                                                             int ny, int nz, int nzp)
 {
     __shared__ float tile[32][33];
-    const int j = blockIdx.z;
+    // blockIdx.z = j + ny * item: several volumes of a batch go into consecutive scratch copies in one launch
+    const int item = blockIdx.z / ny, j = blockIdx.z - item * ny;
+    vol += (size_t)item * nx * ny * nz;
+    volz += (size_t)item * ((size_t)nx * ny + 1) * nzp;
     const int i0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
     const int tx = threadIdx.x, ty = threadIdx.y;
 #pragma unroll
@@ -124,6 +127,9 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom gk, c
     // GT == 2 (modular geometry, upright modules): the wave's view brings its own parameter block, the scene
     // translated so that the view is a circular cone-beam view; gk holds the sizes, which all views share.
     const SfGeom &gsz = gk;
+    // blockIdx.y: item of a batch (its scratch copy and its sinogram)
+    volz += (size_t)blockIdx.y * ((size_t)gk.nx * gk.ny + 1) * nzp;
+    sino += (size_t)blockIdx.y * gk.nviews * gk.nrows * gk.ncols;
     constexpr int SB = 64 / NQ;                       // slabs per record block
     constexpr int WC = FP_WAVES / WV;                 // column bundles per workgroup
     static_assert(WC * WV == FP_WAVES, "waves = column bundles x views");

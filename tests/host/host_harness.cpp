@@ -62,6 +62,17 @@ int leap_launch_project(const leap_geometry *G, const float *vol, float *sino, h
     return LEAP_OK;
 }
 
+int leap_launch_project_batch(const leap_geometry *G, const float *vol, float *sino, int batch, hipStream_t st)
+{
+    const SfGeom &g = G->g;
+    const size_t nvol = (size_t)g.nx * g.ny * g.nz, nsino = (size_t)g.nviews * g.nrows * g.ncols;
+    for (int b = 0; b < batch; ++b) {
+        const int rc = leap_launch_project(G, vol + b * nvol, sino + b * nsino, st);
+        if (rc != LEAP_OK) return rc;
+    }
+    return LEAP_OK;
+}
+
 int leap_launch_backproject(const leap_geometry *G, const float *sino, float *vol, hipStream_t)
 {
     const SfGeom &g = G->g;
@@ -89,6 +100,17 @@ int leap_launch_backproject(const leap_geometry *G, const float *sino, float *vo
                 sf_backproject_column_chunk<ZC>(g, G->d_views, sino, i, j, k0, acc, G->d_geoms);
                 for (int kk = 0; kk < ZC && k0 + kk < g.nz; ++kk) vol[((size_t)(k0 + kk) * g.ny + j) * g.nx + i] = acc[kk];
             }
+    return LEAP_OK;
+}
+
+int leap_launch_backproject_batch(const leap_geometry *G, const float *sino, float *vol, int batch, hipStream_t st)
+{
+    const SfGeom &g = G->g;
+    const size_t nvol = (size_t)g.nx * g.ny * g.nz, nsino = (size_t)g.nviews * g.nrows * g.ncols;
+    for (int b = 0; b < batch; ++b) {
+        const int rc = leap_launch_backproject(G, sino + b * nsino, vol + b * nvol, st);
+        if (rc != LEAP_OK) return rc;
+    }
     return LEAP_OK;
 }
 

@@ -225,6 +225,22 @@ def test_batch_equals_item_by_item_and_is_reproducible(torch_mod):
     geo.close()
 
 
+def test_long_batch_is_split_over_several_launches(torch_mod):
+    """The fast kernels take up to 16 items of a batch per launch (one scratch copy of the volume each); a batch of 19
+    needs two launches, and every item must come out as if projected alone."""
+    from paper_2307_05801_amd import Geometry
+    cfg = reduced(config(4), 8, nviews=6, batch=19)
+    geo = Geometry(cfg)
+    assert "A=columns" in geo.describe() and "AT=tiled" in geo.describe(), geo.describe()
+    xs = torch_mod.from_numpy(uniform_volume(cfg, 3, batch=19)).cuda()
+    ys = torch_mod.from_numpy(uniform_sinogram(cfg, 4, batch=19)).cuda()
+    a_all, at_all = geo.project(xs), geo.backproject(ys)
+    for b in (0, 7, 15, 16, 18):
+        assert torch_mod.equal(a_all[b], geo.project(xs[b].contiguous())), b
+        assert torch_mod.equal(at_all[b], geo.backproject(ys[b].contiguous())), b
+    geo.close()
+
+
 def test_autograd_gradient_is_the_matched_transpose(torch_mod, oracle_mod):
     """d/dx 1/2 |Ax - y|^2 = A^T (Ax - y) (the paper's least-squares example), and A^T differentiates to A."""
     from paper_2307_05801_amd import Projector
