@@ -178,7 +178,6 @@ static void select_modular_fast_kernels(leap_geometry *G)
         G->fp_nk = std::max(2, (int)std::ceil(vpr - 1e-6) + 1);
         const int groups = (d->nrows + 63) / 64;
         G->fp_rg = groups >= 8 ? 8 : (groups >= 4 ? 4 : (groups >= 2 ? 2 : 1));
-        if (G->fp_nk == 4 && G->fp_rg == 8) G->fp_cw = 2;      // see leap_geometry_create: that instance serialises its loads
         if (G->fp_rg < 4 && !std::getenv("LEAP_FP_CW")) G->fp_cw = 2;      // short detectors: see leap_geometry_create
         int need = slots_needed(G->fp_cw);
         if (need > 16 && G->fp_cw == 4) {
@@ -591,7 +590,7 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
             const int v = std::atoi(env);
             if (v == 1 || v == 2 || v == 4) G->fp_cw = v;
         }
-        if (d->type == LEAP_CONE_CURVED) G->fp_cw = 2;      // the cylinder has one instance per shape (with 4 columns it spills: 209 ms)
+        if (d->type == LEAP_CONE_CURVED && G->fp_cw == 1) G->fp_cw = 2;      // the cylinder has instances for 4 and 2 columns
         // candidate slots per slab: widest range of voxel columns any bundle of cw detector columns can see
         auto slots_needed = [&](int cw) {
             int need = 0;
@@ -616,12 +615,11 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
             const int v = std::atoi(env);
             if (v == 1 || v == 2 || v == 4 || v == 8) G->fp_rg = v;
         }
-        // The instance with four columns, four voxels per row and eight row groups does not keep its loads in flight
-        // (the compiler settles on 95 registers and serialises them: 140 against 67 ms measured): two columns there.
-        if (G->fp_cw == 4 && G->fp_nk == 4 && G->fp_rg == 8) G->fp_cw = 2;
         // Short detectors (fewer than 256 rows) have too few bundles of four to fill the chip: two columns measured
         // 5 to 12 % faster there, four columns 5 to 10 % faster from 256 rows on.
         if (G->fp_cw == 4 && G->fp_rg < 4 && !std::getenv("LEAP_FP_CW")) G->fp_cw = 2;
+        // the cylinder's record phase is heavier: four columns only pay off from 512 rows on (64.4 against 70.5 ms at 512^3)
+        if (G->fp_cw == 4 && d->type == LEAP_CONE_CURVED && G->fp_rg < 8 && !std::getenv("LEAP_FP_CW")) G->fp_cw = 2;
         int need = slots_needed(G->fp_cw);
         while (need > 16 && G->fp_cw > 1) {
             G->fp_cw /= 2;
@@ -629,7 +627,7 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         }
         G->fp_need_q = need;
         G->fp_nq = need <= 4 ? 4 : (need <= 8 ? 8 : 16);
-        G->fp_columns = need <= 16 && G->fp_nk <= 4 && (d->type != LEAP_CONE_CURVED || G->fp_cw == 2);
+        G->fp_columns = need <= 16 && G->fp_nk <= 4 && (d->type != LEAP_CONE_CURVED || G->fp_cw >= 2);
         if (const char *env = std::getenv("LEAP_FP_VB")) {
             const int v = std::atoi(env);
             if (v >= 1 && v <= 1024) G->fp_vb = v;

@@ -267,34 +267,22 @@ static void launch_fp_columns(const leap_geometry *G, float *d_sino, hipStream_t
 template <int NQ, int NK, int RG>
 static bool launch_fp_w(const leap_geometry *G, float *d_sino, hipStream_t stream, int items)
 {
-    if (G->g.type == SF_CONE_CURVED) {     // bundles of 2 columns only
-        if (G->fp_cw != 2) return false;
-        launch_fp_columns<NQ, NK, RG, 2, 1>(G, d_sino, stream, items);
+    if (G->g.type == SF_CONE_CURVED) {     // bundles of 4 or 2 columns
+        if (G->fp_cw == 4) launch_fp_columns<NQ, NK, RG, 4, 1>(G, d_sino, stream, items);
+        else if (G->fp_cw == 2) launch_fp_columns<NQ, NK, RG, 2, 1>(G, d_sino, stream, items);
+        else return false;
         return true;
     }
-    // four columns with four voxels per row and eight row groups: never selected (that instance serialises its loads)
-    constexpr bool has4 = !(NK == 4 && RG == 8);
     if (G->g.type == SF_MODULAR) {
-        if (G->fp_cw == 4) {
-            if constexpr (has4) launch_fp_columns<NQ, NK, RG, 4, 2>(G, d_sino, stream, items);
-            else return false;
-        } else if (G->fp_cw == 2) {
-            launch_fp_columns<NQ, NK, RG, 2, 2>(G, d_sino, stream, items);
-        } else {
-            return false;
-        }
+        if (G->fp_cw == 4) launch_fp_columns<NQ, NK, RG, 4, 2>(G, d_sino, stream, items);
+        else if (G->fp_cw == 2) launch_fp_columns<NQ, NK, RG, 2, 2>(G, d_sino, stream, items);
+        else return false;
         return true;
     }
     switch (G->fp_cw) {
     case 1: launch_fp_columns<NQ, NK, RG, 1, 0>(G, d_sino, stream, items); return true;
     case 2: launch_fp_columns<NQ, NK, RG, 2, 0>(G, d_sino, stream, items); return true;
-    case 4:
-        if constexpr (has4) {
-            launch_fp_columns<NQ, NK, RG, 4, 0>(G, d_sino, stream, items);
-            return true;
-        } else {
-            return false;
-        }
+    case 4: launch_fp_columns<NQ, NK, RG, 4, 0>(G, d_sino, stream, items); return true;
     default: return false;
     }
 }

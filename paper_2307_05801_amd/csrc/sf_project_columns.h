@@ -227,20 +227,37 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom gk, c
 #pragma unroll
             for (int t = 1; t < NK; ++t) step_minus[t] = step - (float)t;
             const char *__restrict__ col = reinterpret_cast<const char *>(volz + s_base);   // wave-uniform base address
+            // Addresses, loads, arithmetic.  Left alone, the compiler schedules a few instances as load - wait - use,
+            // load - wait - use (its register-pressure heuristics give up on keeping RG loads in flight), and they run
+            // at a third of the speed: those get scheduling barriers between the three phases.  The others are faster
+            // without (1 to 2 % at 512^3), so they keep the compiler's own schedule.
+            constexpr bool PIN = (GT == 1 && CW == 4) || (NK == 4 && RG == 8 && CW == 4);
+            float fr[RG];
+            const float *xp[RG];
 #pragma unroll
             for (int gq = 0; gq < RG; ++gq) {
                 // kappa measured from the start of the padded column; negative values only occur inside the pad
                 const double kap = fma(rd[gq], s_mu, zkp);
-                const float fr = (float)__builtin_amdgcn_fract(kap);
+                fr[gq] = (float)__builtin_amdgcn_fract(kap);
                 int kf = (int)kap;                                 // truncation = floor wherever the clamp leaves it alone
                 asm("v_med3_i32 %0, %1, 0, %2" : "=v"(kf) : "v"(kf), "s"(kmax));   // clamp to [0, kmax] in one op
-                const float *__restrict__ x = reinterpret_cast<const float *>(col + ((unsigned)kf << 2));
+                xp[gq] = reinterpret_cast<const float *>(col + ((unsigned)kf << 2));
+            }
+            if constexpr (PIN) __builtin_amdgcn_sched_barrier(0);
+            float xv[RG][NK];
+#pragma unroll
+            for (int gq = 0; gq < RG; ++gq)
+#pragma unroll
+                for (int t = 0; t < NK; ++t) xv[gq][t] = xp[gq][t];
+            if constexpr (PIN) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int gq = 0; gq < RG; ++gq) {
                 // Overlaps of [kap, kap + step) with voxels kf, kf+1, ...: voxel kf+t, t >= 1, gets clamp(fr + step - t)
                 // and voxel kf the rest of step, so the sum is step * x[0] plus the differences to x[0] times those
                 // overlaps (additions with the clamp modifier issue at twice the rate of min / max).
-                float s = step * x[0];
+                float s = step * xv[gq][0];
 #pragma unroll
-                for (int t = 1; t < NK; ++t) s = fmaf(sf_clamp(fr + step_minus[t], 0.0f, 1.0f), x[t] - x[0], s);
+                for (int t = 1; t < NK; ++t) s = fmaf(sf_clamp(fr[gq] + step_minus[t], 0.0f, 1.0f), xv[gq][t] - xv[gq][0], s);
 #pragma unroll
                 for (int cw = 0; cw < CW; ++cw) acc[cw][gq] = fmaf(s_fa[cw], s, acc[cw][gq]);
             }
