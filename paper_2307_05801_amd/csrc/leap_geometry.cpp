@@ -653,7 +653,7 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         const size_t item_bytes = sizeof(float) * ((size_t)d->nx * d->ny + 1) * G->nzp;
         // Small volumes (a batch of training volumes): up to 16 scratch copies within 1 GiB, so that the footprint
         // kernel can take that many items of a batch in one launch.
-        if (G->fp_columns) {
+        {
             const size_t fit = ((size_t)1 << 30) / item_bytes;
             G->volz_items = (int)(fit < 1 ? 1 : (fit > 16 ? 16 : fit));
         }

@@ -137,7 +137,7 @@ static inline unsigned cdiv(unsigned a, unsigned b) { return (a + b - 1) / b; }
 constexpr int SD_WAVES = 4;   // adjacent detector columns per workgroup of the Siddon forward kernel
 
 template <int RG>
-static void launch_sd_columns(const leap_geometry *G, float *d_sino, hipStream_t stream)
+static void launch_sd_columns(const leap_geometry *G, float *d_sino, hipStream_t stream, int items)
 {
     const SfGeom &g = G->g;
     const int col_tiles = (int)cdiv(g.ncols, SD_WAVES), bands = (int)cdiv(g.nrows, RG * 64);
@@ -145,7 +145,7 @@ static void launch_sd_columns(const leap_geometry *G, float *d_sino, hipStream_t
     const int views_pad = (int)cdiv(g.nviews, vb) * vb;
     const int tiles_per_xcd_pad = (int)cdiv(cdiv(col_tiles, 8), tb) * tb;
     const unsigned zero_col = (unsigned)g.nx * (unsigned)g.ny * (unsigned)G->nzp;
-    dim3 grid((unsigned)(8 * tiles_per_xcd_pad * views_pad * bands), 1, 1);
+    dim3 grid((unsigned)(8 * tiles_per_xcd_pad * views_pad * bands), (unsigned)items, 1);
     if (g.type == SF_MODULAR)
         hipLaunchKernelGGL((sd_project_columns<RG, SD_WAVES, true>), grid, dim3(SD_WAVES * 64, 1, 1), 0, stream, g, G->d_raycols,
                            G->d_volz, d_sino, G->nzp, zero_col, col_tiles, bands, vb, tb, views_pad, tiles_per_xcd_pad,
@@ -154,6 +154,22 @@ static void launch_sd_columns(const leap_geometry *G, float *d_sino, hipStream_t
         hipLaunchKernelGGL((sd_project_columns<RG, SD_WAVES, false>), grid, dim3(SD_WAVES * 64, 1, 1), 0, stream, g, G->d_raycols,
                            G->d_volz, d_sino, G->nzp, zero_col, col_tiles, bands, vb, tb, views_pad, tiles_per_xcd_pad,
                            (const SfGeom *)nullptr);
+}
+
+// The column-wise Siddon kernel on `items` consecutive volumes of a batch (at most G->volz_items: one scratch copy each).
+static int launch_sd_items(const leap_geometry *G, const float *d_vol, float *d_sino, int items, hipStream_t stream)
+{
+    const SfGeom &g = G->g;
+    dim3 tgrid(cdiv(g.nx, 32), cdiv(g.nz, 32), (unsigned)(g.ny * items));
+    hipLaunchKernelGGL(sf_volume_to_columns, tgrid, dim3(32, 8, 1), 0, stream, d_vol, G->d_volz, g.nx, g.ny, g.nz, G->nzp);
+    switch (G->fp_rg) {
+    case 1: launch_sd_columns<1>(G, d_sino, stream, items); break;
+    case 2: launch_sd_columns<2>(G, d_sino, stream, items); break;
+    case 4: launch_sd_columns<4>(G, d_sino, stream, items); break;
+    default: launch_sd_columns<8>(G, d_sino, stream, items); break;
+    }
+    LEAP_HIP_CHECK(hipGetLastError());
+    return LEAP_OK;
 }
 
 static int launch_sd_project(const leap_geometry *G, const float *d_vol, float *d_sino, hipStream_t stream)
@@ -165,18 +181,7 @@ static int launch_sd_project(const leap_geometry *G, const float *d_vol, float *
         LEAP_HIP_CHECK(hipGetLastError());
         return LEAP_OK;
     }
-    if (G->sd_columns) {
-        dim3 tgrid(cdiv(g.nx, 32), cdiv(g.nz, 32), g.ny);
-        hipLaunchKernelGGL(sf_volume_to_columns, tgrid, dim3(32, 8, 1), 0, stream, d_vol, G->d_volz, g.nx, g.ny, g.nz, G->nzp);
-        switch (G->fp_rg) {
-        case 1: launch_sd_columns<1>(G, d_sino, stream); break;
-        case 2: launch_sd_columns<2>(G, d_sino, stream); break;
-        case 4: launch_sd_columns<4>(G, d_sino, stream); break;
-        default: launch_sd_columns<8>(G, d_sino, stream); break;
-        }
-        LEAP_HIP_CHECK(hipGetLastError());
-        return LEAP_OK;
-    }
+    if (G->sd_columns) return launch_sd_items(G, d_vol, d_sino, 1, stream);
     dim3 grid(cdiv(g.ncols, 64), cdiv(g.nrows, 4), g.nviews);
     if (grid.y > 65535u) {
         leap_set_error("detector has too many rows for one launch");
@@ -188,12 +193,12 @@ static int launch_sd_project(const leap_geometry *G, const float *d_vol, float *
 }
 
 template <int NCS, int SH>
-static void launch_sd_tiled(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
+static void launch_sd_tiled(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream, int items)
 {
     constexpr SfBpShape S = BP_SHAPES[SH];
     const SfGeom &g = G->g;
     const unsigned tiles_x = cdiv(g.nx, BP_T), tiles_y = cdiv(g.ny, BP_T);
-    dim3 grid(tiles_x * tiles_y, cdiv(g.nz, S.zc), 1);
+    dim3 grid(tiles_x * tiles_y, cdiv(g.nz, S.zc), (unsigned)items);
     if (g.type == SF_MODULAR)
         hipLaunchKernelGGL((sd_backproject_tiled<NCS, S.zc, S.pw, S.ph, true>), grid, dim3(256, 1, 1), 0, stream, g, G->d_views,
                            G->d_raycols, d_sino, d_vol, (int)tiles_x, (const SfGeom *)G->d_geoms);
@@ -203,15 +208,33 @@ static void launch_sd_tiled(const leap_geometry *G, const float *d_sino, float *
 }
 
 template <int NCS>
-static bool launch_sd_shape(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
+static bool launch_sd_shape(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream, int items)
 {
     switch (G->bp_shape) {
-    case 1: launch_sd_tiled<NCS, 1>(G, d_sino, d_vol, stream); return true;
-    case 2: launch_sd_tiled<NCS, 2>(G, d_sino, d_vol, stream); return true;
-    case 3: launch_sd_tiled<NCS, 3>(G, d_sino, d_vol, stream); return true;
-    case 4: launch_sd_tiled<NCS, 4>(G, d_sino, d_vol, stream); return true;
+    case 1: launch_sd_tiled<NCS, 1>(G, d_sino, d_vol, stream, items); return true;
+    case 2: launch_sd_tiled<NCS, 2>(G, d_sino, d_vol, stream, items); return true;
+    case 3: launch_sd_tiled<NCS, 3>(G, d_sino, d_vol, stream, items); return true;
+    case 4: launch_sd_tiled<NCS, 4>(G, d_sino, d_vol, stream, items); return true;
     default: return false;
     }
+}
+
+// The tiled Siddon back projection on `items` consecutive sinograms of a batch in one launch.
+static int launch_sd_bp_items(const leap_geometry *G, const float *d_sino, float *d_vol, int items, hipStream_t stream)
+{
+    bool ok = false;
+    switch (G->bp_nc) {
+    case 2: ok = launch_sd_shape<2>(G, d_sino, d_vol, stream, items); break;
+    case 3: ok = launch_sd_shape<3>(G, d_sino, d_vol, stream, items); break;
+    case 4: ok = launch_sd_shape<4>(G, d_sino, d_vol, stream, items); break;
+    default: break;
+    }
+    if (!ok) {
+        leap_set_error("internal: no tiled Siddon back-projection instance for this geometry");
+        return LEAP_UNSUPPORTED;
+    }
+    LEAP_HIP_CHECK(hipGetLastError());
+    return LEAP_OK;
 }
 
 static int launch_sd_backproject(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream)
@@ -223,21 +246,7 @@ static int launch_sd_backproject(const leap_geometry *G, const float *d_sino, fl
         LEAP_HIP_CHECK(hipGetLastError());
         return LEAP_OK;
     }
-    if (G->bp_tiled) {
-        bool ok = false;
-        switch (G->bp_nc) {
-        case 2: ok = launch_sd_shape<2>(G, d_sino, d_vol, stream); break;
-        case 3: ok = launch_sd_shape<3>(G, d_sino, d_vol, stream); break;
-        case 4: ok = launch_sd_shape<4>(G, d_sino, d_vol, stream); break;
-        default: break;
-        }
-        if (!ok) {
-            leap_set_error("internal: no tiled Siddon back-projection instance for this geometry");
-            return LEAP_UNSUPPORTED;
-        }
-        LEAP_HIP_CHECK(hipGetLastError());
-        return LEAP_OK;
-    }
+    if (G->bp_tiled) return launch_sd_bp_items(G, d_sino, d_vol, 1, stream);
     dim3 grid(cdiv(g.nx, 64), cdiv(g.ny, 4), g.nz);
     if (grid.y > 65535u || grid.z > 65535u) {
         leap_set_error("volume has too many voxels along y or z for one launch");
@@ -335,14 +344,17 @@ int leap_launch_project_batch(const leap_geometry *G, const float *d_vol, float 
 {
     const SfGeom &g = G->g;
     const size_t nvol = (size_t)g.nx * g.ny * g.nz, nsino = (size_t)g.nviews * g.nrows * g.ncols;
-    if (g.model != SF_MODEL_SIDDON && G->fp_columns) {
+    const bool footprint_fast = g.model != SF_MODEL_SIDDON && G->fp_columns;
+    const bool siddon_fast = g.model == SF_MODEL_SIDDON && G->sd_columns;
+    if (footprint_fast || siddon_fast) {
         // small volumes: several items per launch fill the chip (a batch of training volumes), each in its own scratch copy
         int per = G->volz_items < 1 ? 1 : G->volz_items;
         if (per > 65535 / g.ny) per = 65535 / g.ny;
         if (per < 1) per = 1;
         for (int b = 0; b < batch; b += per) {
             const int items = batch - b < per ? batch - b : per;
-            const int rc = launch_fp_items(G, d_vol + b * nvol, d_sino + b * nsino, items, stream);
+            const int rc = footprint_fast ? launch_fp_items(G, d_vol + b * nvol, d_sino + b * nsino, items, stream)
+                                          : launch_sd_items(G, d_vol + b * nvol, d_sino + b * nsino, items, stream);
             if (rc != LEAP_OK) return rc;
         }
         return LEAP_OK;
@@ -436,11 +448,12 @@ int leap_launch_backproject_batch(const leap_geometry *G, const float *d_sino, f
 {
     const SfGeom &g = G->g;
     const size_t nvol = (size_t)g.nx * g.ny * g.nz, nsino = (size_t)g.nviews * g.nrows * g.ncols;
-    if (g.model != SF_MODEL_SIDDON && G->bp_tiled) {
+    if (G->bp_tiled) {
         // up to 16 items per launch (a batch of small training volumes fills the chip better that way)
         for (int b = 0; b < batch; b += 16) {
             const int items = batch - b < 16 ? batch - b : 16;
-            const int rc = launch_bp_items(G, d_sino + b * nsino, d_vol + b * nvol, items, stream);
+            const int rc = g.model != SF_MODEL_SIDDON ? launch_bp_items(G, d_sino + b * nsino, d_vol + b * nvol, items, stream)
+                                                      : launch_sd_bp_items(G, d_sino + b * nsino, d_vol + b * nvol, items, stream);
             if (rc != LEAP_OK) return rc;
         }
         return LEAP_OK;

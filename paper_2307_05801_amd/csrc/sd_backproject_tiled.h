@@ -128,6 +128,9 @@ __global__ __launch_bounds__(256) void sd_backproject_tiled(SfGeom g, const SfVi
     __shared__ float rinv[2][PH];
     __shared__ float sums[NSLOT * 256];
 
+    // blockIdx.z: item of a batch
+    sino += (size_t)blockIdx.z * g.nviews * g.nrows * g.ncols;
+    vol += (size_t)blockIdx.z * g.nx * g.ny * g.nz;
     const int tid = threadIdx.x;
     const int ti = tid & (BP_T - 1), tj = tid >> 4;
     const int tx = blockIdx.x % tiles_x, ty = blockIdx.x / tiles_x;

@@ -26,6 +26,9 @@ __global__ __launch_bounds__(SD_WAVES * 64) void sd_project_columns(SfGeom gk, c
                                                                     int vb, int tb, int views_pad, int tiles_per_xcd_pad,
                                                                     const SfGeom *__restrict__ geoms)
 {
+    // blockIdx.y: item of a batch (its scratch copy and its sinogram)
+    volz += (size_t)blockIdx.y * ((size_t)gk.nx * gk.ny + 1) * nzp;
+    sino += (size_t)blockIdx.y * gk.nviews * gk.nrows * gk.ncols;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // Block -> (view, band, column tile), in the XCD-aware order of the footprint kernel: index = 8 s + xcd, and

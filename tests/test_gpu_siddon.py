@@ -136,6 +136,22 @@ def test_rays_inside_face_planes_keep_the_total_chord(torch_mod, oracle_mod):
     assert rel_l2(ax[:, :, keep], ref[:, :, keep]) <= TOL
 
 
+def test_long_batch_is_split_over_several_launches(torch_mod):
+    """Up to 16 items of a batch go into one launch of the fast kernels (one scratch copy of the volume each); a batch
+    of 19 needs two, and every item must come out as if projected alone."""
+    from paper_2307_05801_amd import Geometry
+    cfg = off_face(reduced(config(4), 8, nviews=6)).replace(batch=19)
+    geo = Geometry(cfg, model="siddon")
+    assert "A=columns" in geo.describe() and "AT=tiled" in geo.describe(), geo.describe()
+    xs = torch_mod.from_numpy(uniform_volume(cfg, 3, batch=19)).cuda()
+    ys = torch_mod.from_numpy(uniform_sinogram(cfg, 4, batch=19)).cuda()
+    a_all, at_all = geo.project(xs), geo.backproject(ys)
+    for b in (0, 7, 15, 16, 18):
+        assert torch_mod.equal(a_all[b], geo.project(xs[b].contiguous())), b
+        assert torch_mod.equal(at_all[b], geo.backproject(ys[b].contiguous())), b
+    geo.close()
+
+
 def test_batch_autograd_and_overwrite(torch_mod, oracle_mod):
     from paper_2307_05801_amd import Projector
     torch = torch_mod
