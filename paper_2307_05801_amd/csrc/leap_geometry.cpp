@@ -129,7 +129,7 @@ static void select_modular_fast_kernels(leap_geometry *G)
     if (const char *env = std::getenv("LEAP_FORCE_GENERAL"))
         if (env[0] == '1') return;
 
-    if (d->nz >= 8 && std::isfinite(cols) && cols <= 4.0 && rows <= 3.0) {
+    if (d->nz >= 8 && std::isfinite(cols) && cols <= 4.0 && rows <= 3.0 && (double)d->nrows * d->ncols < 1073741824.0) {
         G->bp_nc = std::max(2, (int)std::ceil(cols) + 1);
         G->bp_nv = std::max(2, (int)std::ceil(rows - 1e-6) + 1);
         G->bp_wh = (float)(0.5 * cols);
@@ -221,7 +221,8 @@ static void select_siddon_fast_kernels(leap_geometry *G)
 
     // tiled back projection: at most 4 pixel centres inside a voxel's footprint, and the staged window of every
     // (view, tile, z-chunk) must fit the instance (checked with the kernel's own function)
-    if (d->nz >= 8 && std::isfinite(G->max_cols_per_voxel) && G->max_cols_per_voxel > 0.0 && G->max_cols_per_voxel < 3.9) {
+    if (d->nz >= 8 && std::isfinite(G->max_cols_per_voxel) && G->max_cols_per_voxel > 0.0 && G->max_cols_per_voxel < 3.9 &&
+        (double)d->nrows * d->ncols < 1073741824.0) {      // the staging loads use 32-bit byte offsets within a view
         G->bp_nc = (int)std::floor(G->max_cols_per_voxel + 0.01) + 1;
         if (G->bp_nc < 2) G->bp_nc = 2;
         const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T;
@@ -541,7 +542,7 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
     // Tiled back projection: pick the template instance and verify its staged window against every
     // (view, tile, z-chunk) with the very function the kernel evaluates.
     if (d->model == LEAP_MODEL_SF && d->type != LEAP_FAN && d->nz >= 8 && std::isfinite(G->max_cols_per_voxel) && G->max_cols_per_voxel <= 4.0 &&
-        G->max_rows_per_voxel <= 3.0) {
+        G->max_rows_per_voxel <= 3.0 && (double)d->nrows * d->ncols < 1073741824.0) {     // 32-bit byte offsets within a view
         G->bp_nc = (int)std::ceil(G->max_cols_per_voxel) + 1;
         if (G->bp_nc < 2) G->bp_nc = 2;
         G->bp_nv = (int)std::ceil(G->max_rows_per_voxel - 1e-6) + 1;

@@ -60,13 +60,17 @@ __device__ __forceinline__ void sd_load_view(const SfGeom &g, const SfView v, co
     constexpr int RSTEP = 256 / PW;
     w = sd_bp_window(g, v, xc, yc, hx, z0, z1);
     const int c = w.c0 + sc;
-    const bool cin = c >= 0 && c < g.ncols;
-    ya += cin ? c : 0;
+    const bool cin = (unsigned)c < (unsigned)g.ncols;
+    // 32-bit byte offsets from the view's first element (a view has fewer than 2^30 pixels where this kernel is chosen)
+    const char *__restrict__ yb = reinterpret_cast<const char *>(ya);
+    unsigned off = (unsigned)(((w.r0 + sr) * g.ncols + (cin ? c : 0)) * 4);
+    const unsigned step = (unsigned)(RSTEP * g.ncols * 4);
 #pragma unroll
     for (int s = 0; s < NSTAGE; ++s) {
         const int r = w.r0 + sr + RSTEP * s;
-        const bool in = cin && r >= 0 && r < g.nrows && (sr + RSTEP * s) < PH;
-        stage[s] = in ? ya[(size_t)r * g.ncols] : 0.0f;
+        const bool in = cin && (unsigned)r < (unsigned)g.nrows && (sr + RSTEP * s) < PH;
+        stage[s] = in ? *reinterpret_cast<const float *>(yb + off) : 0.0f;
+        off += step;
     }
 }
 

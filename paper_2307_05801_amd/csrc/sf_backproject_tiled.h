@@ -108,13 +108,18 @@ __device__ __forceinline__ void bp_load_view(const SfGeom &g, const SfView v, co
     constexpr int RSTEP = 256 / PW;
     w = sf_bp_window<GT>(g, v, xc, yc, hx, z0, z1, wh, NC, NV, pre);
     const int c = w.c0 + sc;
-    const bool cin = c >= 0 && c < g.ncols;
-    ya += cin ? c : 0;
+    const bool cin = (unsigned)c < (unsigned)g.ncols;
+    // 32-bit byte offsets from the view's first element (a view has fewer than 2^30 pixels where this kernel is
+    // chosen): one add per row instead of a 64-bit multiply; offsets of rows off the detector are never used
+    const char *__restrict__ yb = reinterpret_cast<const char *>(ya);
+    unsigned off = (unsigned)(((w.r0 + sr) * g.ncols + (cin ? c : 0)) * 4);
+    const unsigned step = (unsigned)(RSTEP * g.ncols * 4);
 #pragma unroll
     for (int s = 0; s < NSTAGE; ++s) {
         const int r = w.r0 + sr + RSTEP * s;
-        const bool in = cin && r >= 0 && r < g.nrows && (sr + RSTEP * s) < PH;
-        stage[s] = in ? ya[(size_t)r * g.ncols] : 0.0f;
+        const bool in = cin && (unsigned)r < (unsigned)g.nrows && (sr + RSTEP * s) < PH;
+        stage[s] = in ? *reinterpret_cast<const float *>(yb + off) : 0.0f;
+        off += step;
     }
 }
 
@@ -134,10 +139,13 @@ __device__ __forceinline__ void bp_store_view(const SfGeom &g, const SfView v, i
     } else {
         ac = sf_amp_col<GT>(g, v, w.c0 + sc);
     }
+    float vv = fmaf((float)(w.r0 + sr), g.pv, g.v0);      // this thread's first row; RSTEP rows further per element
+    const float dv = (float)RSTEP * g.pv;
 #pragma unroll
     for (int s = 0; s < NSTAGE; ++s) {
         const int row = sr + RSTEP * s;
-        if (row < PH) buf[row * PS + sc] = stage[s] * sf_amp(g, v, ac, w.r0 + row);
+        if (row < PH) buf[row * PS + sc] = stage[s] * sf_amp_at(g, v, ac, vv);
+        vv += dv;
     }
 }
 

@@ -311,3 +311,11 @@ SF_HD float sf_amp(const SfGeom &g, const SfView &v, const SfAmpCol &a, int r)
     const float vv = (g.type == SF_FAN) ? 0.0f : fmaf((float)r, g.pv, g.v0);
     return a.gcol * sf_sqrt(fmaf(vv, vv, a.wcol));
 }
+
+// The same with the row's detector coordinate v given (callers that walk rows in equal steps add the step).
+SF_HD float sf_amp_at(const SfGeom &g, const SfView &v, const SfAmpCol &a, float vv)
+{
+    if (g.type == SF_PARALLEL) return v.par_amp;
+    if (g.type == SF_FAN) vv = 0.0f;
+    return a.gcol * sf_sqrt(fmaf(vv, vv, a.wcol));
+}
