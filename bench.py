@@ -27,8 +27,8 @@ PEAK_HBM_GBPS = 8000.0
 # device copy in the same run (FETCH_SIZE x 2 KiB, WRITE_SIZE x 1 KiB); summaries under profiles/.  Keyed by workload
 # and operator; None when a workload has not been profiled.
 MEASURED_TRAFFIC_BYTES = {
-    ("c3_cone_512", "A"): 1.5638e8 * 2048 + 1.49468e6 * 1024,
-    ("c3_cone_512", "AT"): 8.48129e6 * 2048 + 524288 * 1024,
+    ("c3_cone_512", "A"): 1.56067e8 * 2048 + 1.49308e6 * 1024,
+    ("c3_cone_512", "AT"): 8.47904e6 * 2048 + 524288 * 1024,
     ("c3_cone_512:siddon", "A"): 1.06982e8 * 2048 + 2.88743e6 * 1024,
     ("c3_cone_512:siddon", "AT"): 3.54689e7 * 2048 + 524288 * 1024,
 }
