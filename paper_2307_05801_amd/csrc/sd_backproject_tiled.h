@@ -34,7 +34,7 @@ SF_HD SfWindow sd_bp_window(const SfGeom &g, const SfView &v, float xc, float yc
         if (g.type != SF_PARALLEL) {
             const float lc = fmaf(xc, v.c, yc * v.s);
             ilo = sf_rcp(g.sod - lc + rho);
-            ihi = sf_rcp(g.sod - lc - rho);
+            ihi = sf_rcp(fmaxf(g.sod - lc - rho, 1e-6f * g.sod));   // padding voxels of an edge tile may reach the source plane
         }
         xi_lo = fmaf(g.ku * tlo, tlo >= 0.0f ? ilo : ihi, g.col_off);
         xi_hi = fmaf(g.ku * thi, thi >= 0.0f ? ihi : ilo, g.col_off);
@@ -43,10 +43,10 @@ SF_HD SfWindow sd_bp_window(const SfGeom &g, const SfView &v, float xc, float yc
     const float eta_lo = fmaf(kv * z0, z0 >= 0.0f ? ilo : ihi, row_off);
     const float eta_hi = fmaf(kv * z1, z1 >= 0.0f ? ihi : ilo, row_off);
     // pixel c has its centre at xi = c; row r at eta = r + 1/2.  A margin of 0.02 pixels for float rounding.
-    w.c0 = (int)ceilf(xi_lo - 0.02f);
-    w.r0 = (int)ceilf(eta_lo - 0.52f);
-    w.need_w = (int)floorf(xi_hi + 0.02f) - w.c0 + 1;
-    w.need_h = (int)floorf(eta_hi - 0.48f) - w.r0 + 1;
+    w.c0 = sf_f2i(ceilf(xi_lo - 0.02f));
+    w.r0 = sf_f2i(ceilf(eta_lo - 0.52f));
+    w.need_w = sf_f2i(floorf(xi_hi + 0.02f)) - w.c0 + 1;
+    w.need_h = sf_f2i(floorf(eta_hi - 0.48f)) - w.r0 + 1;
     return w;
 }
 
@@ -63,8 +63,8 @@ __device__ __forceinline__ void sd_load_view(const SfGeom &g, const SfView v, co
     const bool cin = (unsigned)c < (unsigned)g.ncols;
     // 32-bit byte offsets from the view's first element (a view has fewer than 2^30 pixels where this kernel is chosen)
     const char *__restrict__ yb = reinterpret_cast<const char *>(ya);
-    unsigned off = (unsigned)(((w.r0 + sr) * g.ncols + (cin ? c : 0)) * 4);
-    const unsigned step = (unsigned)(RSTEP * g.ncols * 4);
+    unsigned off = ((unsigned)(w.r0 + sr) * (unsigned)g.ncols + (unsigned)(cin ? c : 0)) * 4u;
+    const unsigned step = (unsigned)RSTEP * (unsigned)g.ncols * 4u;
 #pragma unroll
     for (int s = 0; s < NSTAGE; ++s) {
         const int r = w.r0 + sr + RSTEP * s;

@@ -81,8 +81,10 @@ SF_HD SfWindow sf_bp_window(const SfGeom &g, const SfView &v, float xc, float yc
     } else {
         if (g.type != SF_PARALLEL) {
             const float lc = fmaf(xc, v.c, yc * v.s);
+            // a ragged edge tile's padding voxels may reach the source plane: keep the distance positive (the window then
+            // comes out huge and the host rejects the kernel)
             ilo = sf_rcp(g.sod - lc + rho);
-            ihi = sf_rcp(g.sod - lc - rho);
+            ihi = sf_rcp(fmaxf(g.sod - lc - rho, 1e-6f * g.sod));
         }
         xi_lo = fmaf(g.ku * tlo, tlo >= 0.0f ? ilo : ihi, g.col_off);
         xi_hi = fmaf(g.ku * thi, thi >= 0.0f ? ihi : ilo, g.col_off);
@@ -90,10 +92,10 @@ SF_HD SfWindow sf_bp_window(const SfGeom &g, const SfView &v, float xc, float yc
     const float kv = (float)g.kvd, row_off = (float)g.row_offd;
     const float eta_lo = fmaf(kv * z0, z0 >= 0.0f ? ilo : ihi, row_off);
     const float eta_hi = fmaf(kv * z1, z1 >= 0.0f ? ihi : ilo, row_off);
-    w.c0 = (int)floorf(xi_lo - wh + 0.48f);
-    w.r0 = (int)floorf(eta_lo - 0.02f);
-    w.need_w = (int)floorf(xi_hi + 0.52f) + nc - w.c0;       // a thread reads nc columns from its first one
-    w.need_h = (int)floorf(eta_hi + 0.02f) + nv - w.r0;      // and nv rows from the first row of each voxel
+    w.c0 = sf_f2i(floorf(xi_lo - wh + 0.48f));
+    w.r0 = sf_f2i(floorf(eta_lo - 0.02f));
+    w.need_w = sf_f2i(floorf(xi_hi + 0.52f)) + nc - w.c0;    // a thread reads nc columns from its first one
+    w.need_h = sf_f2i(floorf(eta_hi + 0.02f)) + nv - w.r0;   // and nv rows from the first row of each voxel
     return w;
 }
 
@@ -112,8 +114,9 @@ __device__ __forceinline__ void bp_load_view(const SfGeom &g, const SfView v, co
     // 32-bit byte offsets from the view's first element (a view has fewer than 2^30 pixels where this kernel is
     // chosen): one add per row instead of a 64-bit multiply; offsets of rows off the detector are never used
     const char *__restrict__ yb = reinterpret_cast<const char *>(ya);
-    unsigned off = (unsigned)(((w.r0 + sr) * g.ncols + (cin ? c : 0)) * 4);
-    const unsigned step = (unsigned)(RSTEP * g.ncols * 4);
+    // (unsigned arithmetic: offsets of rows off the detector wrap around harmlessly)
+    unsigned off = ((unsigned)(w.r0 + sr) * (unsigned)g.ncols + (unsigned)(cin ? c : 0)) * 4u;
+    const unsigned step = (unsigned)RSTEP * (unsigned)g.ncols * 4u;
 #pragma unroll
     for (int s = 0; s < NSTAGE; ++s) {
         const int r = w.r0 + sr + RSTEP * s;

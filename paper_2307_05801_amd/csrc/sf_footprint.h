@@ -63,6 +63,11 @@ SF_HD float sf_clamp(float x, float lo, float hi)
 #endif
 }
 
+// float -> int for window bounds: clamped first, so that an infinite or absurd bound (a ragged edge tile whose padding
+// voxels reach past the source) converts to a defined value; the host then sees an oversized window and picks
+// another kernel.  NaN becomes the lower bound.
+SF_HD int sf_f2i(float x) { return (int)fminf(fmaxf(x, -1.0e9f), 1.0e9f); }
+
 // Transaxial footprint of one voxel column in one view.
 struct SfColumn {
     double xi;            // detector column coordinate of the voxel centre

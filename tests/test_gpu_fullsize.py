@@ -158,3 +158,105 @@ def test_c5_full_size_all_views(oracle_mod):
     assert abs(lhs - rhs) <= TOL * abs(lhs)
     assert rel_l2(ax_s, oracle_mod.project_rays(cfg, x, rays)) <= TOL
     assert rel_l2(aty_s, oracle_mod.backproject_voxels(cfg, y, vox)) <= TOL
+
+
+def max_abs_ok(got, ref, factor):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.abs(got - ref).max()) <= factor * float(np.abs(ref).max())
+
+
+def test_c2_full_size_whole_arrays(oracle_mod):
+    """The 3-D parallel-beam case at its stated size (256^3 voxels, 180 views, 256x256 detector): the whole sinogram
+    and the whole back projection of it, element by element, in the kernel instances the benchmark times."""
+    import torch
+    from paper_2307_05801_amd import Geometry
+    cfg = config(2)
+    print("[gpu] full-size C2: phantom", flush=True)
+    x = standard_volume(2, cfg)
+    geo = Geometry(cfg)
+    desc = geo.describe()
+    print(f"[gpu] full-size C2: {desc}", flush=True)
+    assert "A=columns" in desc and "AT=tiled" in desc, desc
+    ax = geo.project(torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    print("[gpu] full-size C2: backproject of the projection", flush=True)
+    atax = geo.backproject(ax)
+    torch.cuda.synchronize()
+    ax, atax = ax.cpu().numpy(), atax.cpu().numpy()
+    geo.close()
+    print("[gpu] full-size C2: oracle A", flush=True)
+    ax_ref = oracle_mod.project(cfg, x)
+    e = rel_l2(ax, ax_ref)
+    print(f"C2 full: A rel-L2 {e:.2e}", flush=True)
+    assert e <= TOL
+    for a in range(cfg.nviews):
+        assert rel_l2(ax[a], ax_ref[a]) <= TOL, a
+    assert max_abs_ok(ax, ax_ref, 2e-5)
+    print("[gpu] full-size C2: oracle A^T", flush=True)
+    atax_ref = oracle_mod.backproject(cfg, ax)
+    e = rel_l2(atax, atax_ref)
+    print(f"C2 full: A^T rel-L2 {e:.2e}", flush=True)
+    assert e <= TOL
+    assert max_abs_ok(atax, atax_ref, 2e-5)
+    lhs = float((ax.astype(np.float64) ** 2).sum())                     # <A x, A x> = <x, A^T A x>
+    rhs = float((atax.astype(np.float64) * x).sum())
+    assert abs(lhs - rhs) <= TOL * abs(lhs)
+
+
+def test_c4_full_size_training_batch_in_one_call(oracle_mod):
+    """The training-step case at its stated size: eight 256^3 volumes through ONE leap_project call and eight
+    384x384x60 residual sinograms through ONE leap_backproject call.  The oracle recomputes two items whole and
+    sampled rays and voxels of the other six; every item must also equal a call on it alone, bit for bit."""
+    import torch
+    from paper_2307_05801_amd import Geometry
+    from synthetic import measured_sinogram, perturbed_volume
+    cfg = config(4)
+    assert cfg.batch == 8
+    print("[gpu] full-size C4: phantoms", flush=True)
+    truth = np.stack([standard_volume(4, cfg, item=b) for b in range(cfg.batch)])
+    x = np.stack([perturbed_volume(truth[b], 1004 + b) for b in range(cfg.batch)])
+    geo = Geometry(cfg)
+    desc = geo.describe()
+    print(f"[gpu] full-size C4: {desc}", flush=True)
+    assert "A=columns" in desc and "AT=tiled" in desc, desc
+    xt = torch.from_numpy(x).cuda()
+    # measurement: photon noise on the projection of the true volumes (input preparation; A of the truth is checked too)
+    ideal = geo.project(torch.from_numpy(truth).cuda()).cpu().numpy()
+    y_meas = np.stack([measured_sinogram(ideal[b], 1004 + b) for b in range(cfg.batch)])
+    yt = torch.from_numpy(y_meas).cuda()
+    print("[gpu] full-size C4: step", flush=True)
+    ax = geo.project(xt)                       # one call, eight items
+    r = ax - yt
+    g = geo.backproject(r)                     # one call, eight items
+    torch.cuda.synchronize()
+    for b in (0, 3, 7):                        # batched == alone, bit for bit
+        assert torch.equal(ax[b], geo.project(xt[b].contiguous())), b
+        assert torch.equal(g[b], geo.backproject(r[b].contiguous())), b
+    ax_np, r_np, g_np = ax.cpu().numpy(), r.cpu().numpy(), g.cpu().numpy()
+    geo.close()
+    nray, nvox = cfg.nviews * cfg.nrows * cfg.ncols, cfg.nx * cfg.ny * cfg.nz
+    rs = np.random.default_rng(46)
+    for b in range(cfg.batch):
+        if b in (1, 6):
+            print(f"[gpu] full-size C4: oracle, item {b} whole", flush=True)
+            ax_ref = oracle_mod.project(cfg, x[b])
+            e_a = rel_l2(ax_np[b], ax_ref)
+            assert e_a <= TOL and max_abs_ok(ax_np[b], ax_ref, 2e-5)
+            for a in range(cfg.nviews):
+                assert rel_l2(ax_np[b][a], ax_ref[a]) <= TOL, (b, a)
+            g_ref = oracle_mod.backproject(cfg, r_np[b])
+            e_g = rel_l2(g_np[b], g_ref)
+            assert e_g <= TOL and max_abs_ok(g_np[b], g_ref, 5e-5)
+            assert rel_l2(ideal[b], oracle_mod.project(cfg, truth[b])) <= TOL
+        else:
+            print(f"[gpu] full-size C4: oracle, item {b} sampled", flush=True)
+            rays = np.unique(np.concatenate([rs.integers(0, nray, 3000), np.array([0, nray - 1])]))
+            vox = np.unique(np.concatenate([rs.integers(0, nvox, 30000), np.array([0, nvox - 1, cfg.nx - 1])]))
+            e_a = rel_l2(ax_np[b].ravel()[rays], oracle_mod.project_rays(cfg, x[b], rays))
+            e_g = rel_l2(g_np[b].ravel()[vox], oracle_mod.backproject_voxels(cfg, r_np[b], vox))
+            assert e_a <= TOL and e_g <= TOL
+        print(f"C4 full item {b}: A {e_a:.2e}  A^T r {e_g:.2e}", flush=True)
+        lhs = float((ax_np[b].astype(np.float64) * r_np[b]).sum())     # <A x, r> = <x, A^T r>
+        rhs = float((g_np[b].astype(np.float64) * x[b]).sum())
+        assert abs(lhs - rhs) <= TOL * abs(lhs)

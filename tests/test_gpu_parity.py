@@ -95,6 +95,9 @@ def test_forward_and_adjoint_match_oracle(torch_mod, oracle_mod, name, number, m
     e_a, e_at = rel_l2(ax, ax_ref), rel_l2(aty, aty_ref)
     print(f"{name}: rel-L2 A {e_a:.2e}  A^T {e_at:.2e}")
     assert e_a <= TOL and e_at <= TOL
+    # no single element far off either (rounding errors of float32 sums stay well inside this bound)
+    assert np.abs(ax - ax_ref).max() <= 2e-5 * np.abs(ax_ref).max()
+    assert np.abs(aty - aty_ref).max() <= 2e-5 * np.abs(aty_ref).max()
     for a in range(cfg.nviews):                       # per view as well: no view may hide behind the others
         assert rel_l2(ax[a], ax_ref[a]) <= TOL
     lhs = float((ax.astype(np.float64) * y).sum())
