@@ -110,6 +110,18 @@ int leap_project(const leap_geometry *geom, const float *d_vol, float *d_sino, i
  * gather without atomics (bitwise reproducible): d_vol[b] = A^T d_sino[b].  Asynchronous on hip_stream. */
 int leap_backproject(const leap_geometry *geom, const float *d_sino, float *d_vol, int32_t batch, void *hip_stream);
 
+/* leap_project for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same result as leap_project, same kernels; the z-fastest copy of
+ * the volume that the column-wise forward kernels read is kept in a fixed array of 72 MiB inside the library's device
+ * code (every GPU the library runs on holds that array until the process ends) instead of the handle's own scratch.
+ * The call allocates and frees nothing and calls no allocating routine; the array's address is looked up once per
+ * device in leap_geometry_create.  Limit: (nx*ny+1)*(nz+8) floats must fit the array (a 256^3 volume does), else
+ * LEAP_UNSUPPORTED with a message; geometries whose forward kernel reads the caller's volume directly (fan-beam,
+ * tilted Siddon modules, very coarse detectors) have no such limit.  Items of a batch share the array, as many per launch as fit.
+ * All calls on one GPU share the one array, whatever the handle: calls that overlap in time on one GPU (two streams,
+ * two threads) race; order them.  The array keeps the last call's contents; each call restores the zeros it relies on. */
+int leap_project_static_scratch(const leap_geometry *geom, const float *d_vol, float *d_sino, int32_t batch, void *hip_stream);
+
 /* ---- iterative reconstruction on top of the pair ------------------------------------------------------------
  * "CT Projection Models and Geometries" motivates the matched transpose with the least-squares cost
  * 1/2 ||A x - y||^2, whose gradient is A^T (A x - y), and with iterations that stay stable over a thousand or

@@ -17,7 +17,7 @@ LEAP_MODEL_SF, LEAP_MODEL_SIDDON = 0, 1
 MODELS = {"sf": LEAP_MODEL_SF, "siddon": LEAP_MODEL_SIDDON}
 LEAP_OK, LEAP_INVALID_ARG, LEAP_BAD_GEOMETRY, LEAP_HIP_ERROR, LEAP_UNSUPPORTED = 0, -1, -2, -3, -4
 
-EXPORTS = ("leap_geometry_create", "leap_geometry_destroy", "leap_project", "leap_backproject",
+EXPORTS = ("leap_geometry_create", "leap_geometry_destroy", "leap_project", "leap_backproject", "leap_project_static_scratch",
            "leap_status_string", "leap_last_error", "leap_geometry_describe",
            "leap_recon_workspace_floats", "leap_sirt", "leap_least_squares_descent")
 
@@ -48,13 +48,13 @@ _lib = None
 
 
 def declare(lib, solvers: bool = True) -> None:
-    """Attach the prototypes of include/leap.h to a loaded library (solvers=False: the projector entry points only,
-    for test builds that link the geometry module alone)."""
+    """Attach the prototypes of include/leap.h to a loaded library (solvers=False: the entry points of the geometry module
+    only, for test builds that link it without the kernel launchers)."""
     lib.leap_geometry_create.restype = C.c_int
     lib.leap_geometry_create.argtypes = [C.POINTER(leap_geometry_desc), C.POINTER(C.c_void_p)]
     lib.leap_geometry_destroy.restype = None
     lib.leap_geometry_destroy.argtypes = [C.c_void_p]
-    for fn in (lib.leap_project, lib.leap_backproject):
+    for fn in (lib.leap_project, lib.leap_backproject) + ((lib.leap_project_static_scratch,) if solvers else ()):
         fn.restype = C.c_int
         fn.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
     if solvers:
@@ -151,6 +151,13 @@ def leap_project(handle: int, d_vol: int, d_sino: int, batch: int, stream: int =
     """d_vol, d_sino: device addresses (tensor.data_ptr()); stream: hipStream_t as an integer."""
     lib = lib or load_library()
     _check(lib, lib.leap_project(C.c_void_p(handle), C.c_void_p(d_vol), C.c_void_p(d_sino), batch, C.c_void_p(stream)))
+
+
+def leap_project_static_scratch(handle: int, d_vol: int, d_sino: int, batch: int, stream: int = 0, lib=None) -> None:
+    """leap_project on the library's fixed scratch array (allocates nothing; see include/leap.h for its limits)."""
+    lib = lib or load_library()
+    _check(lib, lib.leap_project_static_scratch(C.c_void_p(handle), C.c_void_p(d_vol), C.c_void_p(d_sino), batch,
+                                                C.c_void_p(stream)))
 
 
 def leap_backproject(handle: int, d_sino: int, d_vol: int, batch: int, stream: int = 0, lib=None) -> None:

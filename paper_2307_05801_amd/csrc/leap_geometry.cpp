@@ -377,6 +377,7 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
         select_siddon_fast_kernels(G);
     }
     hipError_t e = hipGetDevice(&G->device);
+    if (e == hipSuccess) (void)leap_static_scratch_init(G->device);   // set-up for leap_project_static_scratch; it reports a failure itself
     if (e == hipSuccess && (G->fp_columns || G->sd_columns)) {
         G->nzp = d->nz + 2 * FP_PAD;
         const size_t bytes = sizeof(float) * ((size_t)d->nx * d->ny + 1) * G->nzp;
@@ -646,6 +647,7 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
         if (env[0] == '1') G->bp_tiled = G->fp_columns = G->sd_columns = false;
 
     hipError_t e = hipGetDevice(&G->device);
+    if (e == hipSuccess) (void)leap_static_scratch_init(G->device);   // set-up for leap_project_static_scratch; it reports a failure itself
     if (e == hipSuccess) e = hipMalloc((void **)&G->d_views, sizeof(SfView) * (size_t)d->nviews);
     if (e == hipSuccess) e = hipMemcpy(G->d_views, G->views.data(), sizeof(SfView) * (size_t)d->nviews, hipMemcpyHostToDevice);
     if (e == hipSuccess && (G->fp_columns || G->sd_columns)) {

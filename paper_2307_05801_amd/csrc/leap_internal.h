@@ -57,6 +57,11 @@ int leap_hip_fail(hipError_t e, const char *what);
         if (e__ != hipSuccess) return leap_hip_fail(e__, #expr); \
     } while (0)
 
+// Size of the file-scope device array behind leap_project_static_scratch (one per GPU the library runs on).
+constexpr size_t LEAP_STATIC_SCRATCH_BYTES = (size_t)72 << 20;
+// Looks up the array's address on `device` (which must be current) once; called from leap_geometry_create.
+int leap_static_scratch_init(int device);
+
 // kernel launchers (leap_kernels.hip); one batch item per call
 int leap_launch_project(const leap_geometry *geom, const float *d_vol, float *d_sino, hipStream_t stream);
 int leap_launch_project_batch(const leap_geometry *geom, const float *d_vol, float *d_sino, int batch, hipStream_t stream);

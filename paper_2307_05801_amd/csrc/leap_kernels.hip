@@ -1,6 +1,9 @@
 // HIP kernels (gfx950) and launchers of the projector pairs (separable footprint and Siddon).
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
+#include <mutex>
+
 #include "leap_internal.h"
 #include "sf_general.h"
 #include "sf_backproject_tiled.h"
@@ -137,7 +140,7 @@ static inline unsigned cdiv(unsigned a, unsigned b) { return (a + b - 1) / b; }
 constexpr int SD_WAVES = 4;   // adjacent detector columns per workgroup of the Siddon forward kernel
 
 template <int RG>
-static void launch_sd_columns(const leap_geometry *G, float *d_sino, hipStream_t stream, int items)
+static void launch_sd_columns(const leap_geometry *G, const float *volz, float *d_sino, hipStream_t stream, int items)
 {
     const SfGeom &g = G->g;
     const int col_tiles = (int)cdiv(g.ncols, SD_WAVES), bands = (int)cdiv(g.nrows, RG * 64);
@@ -148,25 +151,26 @@ static void launch_sd_columns(const leap_geometry *G, float *d_sino, hipStream_t
     dim3 grid((unsigned)(8 * tiles_per_xcd_pad * views_pad * bands), (unsigned)items, 1);
     if (g.type == SF_MODULAR)
         hipLaunchKernelGGL((sd_project_columns<RG, SD_WAVES, true>), grid, dim3(SD_WAVES * 64, 1, 1), 0, stream, g, G->d_raycols,
-                           G->d_volz, d_sino, G->nzp, zero_col, col_tiles, bands, vb, tb, views_pad, tiles_per_xcd_pad,
+                           volz, d_sino, G->nzp, zero_col, col_tiles, bands, vb, tb, views_pad, tiles_per_xcd_pad,
                            (const SfGeom *)G->d_geoms);
     else
         hipLaunchKernelGGL((sd_project_columns<RG, SD_WAVES, false>), grid, dim3(SD_WAVES * 64, 1, 1), 0, stream, g, G->d_raycols,
-                           G->d_volz, d_sino, G->nzp, zero_col, col_tiles, bands, vb, tb, views_pad, tiles_per_xcd_pad,
+                           volz, d_sino, G->nzp, zero_col, col_tiles, bands, vb, tb, views_pad, tiles_per_xcd_pad,
                            (const SfGeom *)nullptr);
 }
 
-// The column-wise Siddon kernel on `items` consecutive volumes of a batch (at most G->volz_items: one scratch copy each).
-static int launch_sd_items(const leap_geometry *G, const float *d_vol, float *d_sino, int items, hipStream_t stream)
+// The column-wise Siddon kernel on `items` consecutive volumes of a batch, each in its own z-fastest copy inside `volz`
+// (whose pads and spare column are zero).
+static int launch_sd_items(const leap_geometry *G, const float *d_vol, float *d_sino, int items, hipStream_t stream, float *volz)
 {
     const SfGeom &g = G->g;
     dim3 tgrid(cdiv(g.nx, 32), cdiv(g.nz, 32), (unsigned)(g.ny * items));
-    hipLaunchKernelGGL(sf_volume_to_columns, tgrid, dim3(32, 8, 1), 0, stream, d_vol, G->d_volz, g.nx, g.ny, g.nz, G->nzp);
+    hipLaunchKernelGGL(sf_volume_to_columns, tgrid, dim3(32, 8, 1), 0, stream, d_vol, volz, g.nx, g.ny, g.nz, G->nzp);
     switch (G->fp_rg) {
-    case 1: launch_sd_columns<1>(G, d_sino, stream, items); break;
-    case 2: launch_sd_columns<2>(G, d_sino, stream, items); break;
-    case 4: launch_sd_columns<4>(G, d_sino, stream, items); break;
-    default: launch_sd_columns<8>(G, d_sino, stream, items); break;
+    case 1: launch_sd_columns<1>(G, volz, d_sino, stream, items); break;
+    case 2: launch_sd_columns<2>(G, volz, d_sino, stream, items); break;
+    case 4: launch_sd_columns<4>(G, volz, d_sino, stream, items); break;
+    default: launch_sd_columns<8>(G, volz, d_sino, stream, items); break;
     }
     LEAP_HIP_CHECK(hipGetLastError());
     return LEAP_OK;
@@ -181,7 +185,7 @@ static int launch_sd_project(const leap_geometry *G, const float *d_vol, float *
         LEAP_HIP_CHECK(hipGetLastError());
         return LEAP_OK;
     }
-    if (G->sd_columns) return launch_sd_items(G, d_vol, d_sino, 1, stream);
+    if (G->sd_columns) return launch_sd_items(G, d_vol, d_sino, 1, stream, G->d_volz);
     dim3 grid(cdiv(g.ncols, 64), cdiv(g.nrows, 4), g.nviews);
     if (grid.y > 65535u) {
         leap_set_error("detector has too many rows for one launch");
@@ -258,7 +262,7 @@ static int launch_sd_backproject(const leap_geometry *G, const float *d_sino, fl
 }
 
 template <int NQ, int NK, int RG, int CW, int GT>
-static void launch_fp_columns(const leap_geometry *G, float *d_sino, hipStream_t stream, int items)
+static void launch_fp_columns(const leap_geometry *G, const float *volz, float *d_sino, hipStream_t stream, int items)
 {
     constexpr int W = 4;          // waves per workgroup (8 and 16 measured slower)
     const SfGeom &g = G->g;
@@ -269,67 +273,68 @@ static void launch_fp_columns(const leap_geometry *G, float *d_sino, hipStream_t
     const int tiles_per_xcd_pad = (int)cdiv(cdiv(col_tiles, 8), tb) * tb;
     dim3 grid((unsigned)(8 * tiles_per_xcd_pad * vgroups_pad * bands), (unsigned)items, 1);
     hipLaunchKernelGGL((sf_project_columns<NQ, NK, RG, W, CW, 1, GT>), grid, dim3(W * 64, 1, 1), 0, stream, g, G->d_views,
-                       G->d_volz, d_sino, G->nzp, col_tiles, bands, vb, tb, vgroups_pad, tiles_per_xcd_pad,
+                       volz, d_sino, G->nzp, col_tiles, bands, vb, tb, vgroups_pad, tiles_per_xcd_pad,
                        (const SfGeom *)G->d_geoms);
 }
 
 template <int NQ, int NK, int RG>
-static bool launch_fp_w(const leap_geometry *G, float *d_sino, hipStream_t stream, int items)
+static bool launch_fp_w(const leap_geometry *G, const float *volz, float *d_sino, hipStream_t stream, int items)
 {
     if (G->g.type == SF_CONE_CURVED) {     // bundles of 4 or 2 columns
-        if (G->fp_cw == 4) launch_fp_columns<NQ, NK, RG, 4, 1>(G, d_sino, stream, items);
-        else if (G->fp_cw == 2) launch_fp_columns<NQ, NK, RG, 2, 1>(G, d_sino, stream, items);
+        if (G->fp_cw == 4) launch_fp_columns<NQ, NK, RG, 4, 1>(G, volz, d_sino, stream, items);
+        else if (G->fp_cw == 2) launch_fp_columns<NQ, NK, RG, 2, 1>(G, volz, d_sino, stream, items);
         else return false;
         return true;
     }
     if (G->g.type == SF_MODULAR) {
-        if (G->fp_cw == 4) launch_fp_columns<NQ, NK, RG, 4, 2>(G, d_sino, stream, items);
-        else if (G->fp_cw == 2) launch_fp_columns<NQ, NK, RG, 2, 2>(G, d_sino, stream, items);
+        if (G->fp_cw == 4) launch_fp_columns<NQ, NK, RG, 4, 2>(G, volz, d_sino, stream, items);
+        else if (G->fp_cw == 2) launch_fp_columns<NQ, NK, RG, 2, 2>(G, volz, d_sino, stream, items);
         else return false;
         return true;
     }
     switch (G->fp_cw) {
-    case 1: launch_fp_columns<NQ, NK, RG, 1, 0>(G, d_sino, stream, items); return true;
-    case 2: launch_fp_columns<NQ, NK, RG, 2, 0>(G, d_sino, stream, items); return true;
-    case 4: launch_fp_columns<NQ, NK, RG, 4, 0>(G, d_sino, stream, items); return true;
+    case 1: launch_fp_columns<NQ, NK, RG, 1, 0>(G, volz, d_sino, stream, items); return true;
+    case 2: launch_fp_columns<NQ, NK, RG, 2, 0>(G, volz, d_sino, stream, items); return true;
+    case 4: launch_fp_columns<NQ, NK, RG, 4, 0>(G, volz, d_sino, stream, items); return true;
     default: return false;
     }
 }
 
 template <int NQ, int NK>
-static bool launch_fp_rg(const leap_geometry *G, float *d_sino, hipStream_t stream, int items)
+static bool launch_fp_rg(const leap_geometry *G, const float *volz, float *d_sino, hipStream_t stream, int items)
 {
     switch (G->fp_rg) {
-    case 1: return launch_fp_w<NQ, NK, 1>(G, d_sino, stream, items);
-    case 2: return launch_fp_w<NQ, NK, 2>(G, d_sino, stream, items);
-    case 4: return launch_fp_w<NQ, NK, 4>(G, d_sino, stream, items);
-    case 8: return launch_fp_w<NQ, NK, 8>(G, d_sino, stream, items);
+    case 1: return launch_fp_w<NQ, NK, 1>(G, volz, d_sino, stream, items);
+    case 2: return launch_fp_w<NQ, NK, 2>(G, volz, d_sino, stream, items);
+    case 4: return launch_fp_w<NQ, NK, 4>(G, volz, d_sino, stream, items);
+    case 8: return launch_fp_w<NQ, NK, 8>(G, volz, d_sino, stream, items);
     default: return false;
     }
 }
 
 template <int NQ>
-static bool launch_fp_nk(const leap_geometry *G, float *d_sino, hipStream_t stream, int items)
+static bool launch_fp_nk(const leap_geometry *G, const float *volz, float *d_sino, hipStream_t stream, int items)
 {
     switch (G->fp_nk) {
-    case 2: return launch_fp_rg<NQ, 2>(G, d_sino, stream, items);
-    case 3: return launch_fp_rg<NQ, 3>(G, d_sino, stream, items);
-    case 4: return launch_fp_rg<NQ, 4>(G, d_sino, stream, items);
+    case 2: return launch_fp_rg<NQ, 2>(G, volz, d_sino, stream, items);
+    case 3: return launch_fp_rg<NQ, 3>(G, volz, d_sino, stream, items);
+    case 4: return launch_fp_rg<NQ, 4>(G, volz, d_sino, stream, items);
     default: return false;
     }
 }
 
-// The column-wise footprint kernel on `items` consecutive volumes of a batch (at most G->volz_items: one scratch copy each).
-static int launch_fp_items(const leap_geometry *G, const float *d_vol, float *d_sino, int items, hipStream_t stream)
+// The column-wise footprint kernel on `items` consecutive volumes of a batch, each in its own z-fastest copy inside
+// `volz` (whose pads are zero).
+static int launch_fp_items(const leap_geometry *G, const float *d_vol, float *d_sino, int items, hipStream_t stream, float *volz)
 {
     const SfGeom &g = G->g;
     dim3 tgrid(cdiv(g.nx, 32), cdiv(g.nz, 32), (unsigned)(g.ny * items));
-    hipLaunchKernelGGL(sf_volume_to_columns, tgrid, dim3(32, 8, 1), 0, stream, d_vol, G->d_volz, g.nx, g.ny, g.nz, G->nzp);
+    hipLaunchKernelGGL(sf_volume_to_columns, tgrid, dim3(32, 8, 1), 0, stream, d_vol, volz, g.nx, g.ny, g.nz, G->nzp);
     bool ok = false;
     switch (G->fp_nq) {
-    case 4: ok = launch_fp_nk<4>(G, d_sino, stream, items); break;
-    case 8: ok = launch_fp_nk<8>(G, d_sino, stream, items); break;
-    case 16: ok = launch_fp_nk<16>(G, d_sino, stream, items); break;
+    case 4: ok = launch_fp_nk<4>(G, volz, d_sino, stream, items); break;
+    case 8: ok = launch_fp_nk<8>(G, volz, d_sino, stream, items); break;
+    case 16: ok = launch_fp_nk<16>(G, volz, d_sino, stream, items); break;
     default: break;
     }
     if (!ok) {
@@ -353,8 +358,8 @@ int leap_launch_project_batch(const leap_geometry *G, const float *d_vol, float 
         if (per < 1) per = 1;
         for (int b = 0; b < batch; b += per) {
             const int items = batch - b < per ? batch - b : per;
-            const int rc = footprint_fast ? launch_fp_items(G, d_vol + b * nvol, d_sino + b * nsino, items, stream)
-                                          : launch_sd_items(G, d_vol + b * nvol, d_sino + b * nsino, items, stream);
+            const int rc = footprint_fast ? launch_fp_items(G, d_vol + b * nvol, d_sino + b * nsino, items, stream, G->d_volz)
+                                          : launch_sd_items(G, d_vol + b * nvol, d_sino + b * nsino, items, stream, G->d_volz);
             if (rc != LEAP_OK) return rc;
         }
         return LEAP_OK;
@@ -370,7 +375,7 @@ int leap_launch_project(const leap_geometry *G, const float *d_vol, float *d_sin
 {
     const SfGeom &g = G->g;
     if (g.model == SF_MODEL_SIDDON) return launch_sd_project(G, d_vol, d_sino, stream);
-    if (G->fp_columns) return launch_fp_items(G, d_vol, d_sino, 1, stream);
+    if (G->fp_columns) return launch_fp_items(G, d_vol, d_sino, 1, stream, G->d_volz);
     dim3 block(64, 4, 1);
     dim3 grid(cdiv(g.ncols, 64), cdiv(cdiv(g.nrows, GEN_RC), 4), g.nviews);
     if (grid.y > 65535u) {
@@ -481,5 +486,113 @@ int leap_launch_backproject(const leap_geometry *G, const float *d_sino, float *
     else
         hipLaunchKernelGGL(sf_backproject_general, grid, block, 0, stream, g, G->d_views, d_sino, d_vol);
     LEAP_HIP_CHECK(hipGetLastError());
+    return LEAP_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Forward projection on a fixed scratch array, for callers that must not allocate.
+// ------------------------------------------------------------------------------------------------
+//
+// The column-wise forward kernels read a z-fastest copy of the volume.  A handle normally owns that copy (allocated
+// in leap_geometry_create).  leap_project_static_scratch keeps it in the file-scope device array below instead, so
+// the call itself, and everything it launches, touches no allocator.  In host code the array's name is only a
+// stand-in for the symbol: its device address is asked for once per device (hipGetSymbolAddress, with that device
+// current) and only that address is ever handed to kernels.
+static __device__ __align__(256) unsigned char scratch[LEAP_STATIC_SCRATCH_BYTES];
+
+constexpr int LEAP_MAX_DEVICES = 64;
+static float *g_static_scratch[LEAP_MAX_DEVICES];     // device address of `scratch`, per device (nullptr: not asked yet)
+static std::mutex g_static_scratch_mutex;
+
+int leap_static_scratch_init(int device)
+{
+    if (device < 0 || device >= LEAP_MAX_DEVICES) {
+        leap_set_error("device index beyond the static scratch table");
+        return LEAP_UNSUPPORTED;
+    }
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (g_static_scratch[device]) return LEAP_OK;
+    int current = -1;
+    LEAP_HIP_CHECK(hipGetDevice(&current));
+    if (current != device) {
+        leap_set_error("the handle's device is not the current device");
+        return LEAP_INVALID_ARG;
+    }
+    void *p = nullptr;
+    LEAP_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    g_static_scratch[device] = static_cast<float *>(p);
+    return LEAP_OK;
+}
+
+// Zeroes what the column-wise kernels expect to be zero around the voxels that sf_volume_to_columns writes: FP_PAD
+// floats before and after each of the ncolumns z-columns and the whole spare column that follows them (a fill kernel,
+// not a memset, so that a caller may capture the call in a graph).
+__global__ __launch_bounds__(256) void sf_clear_column_pads(float *__restrict__ volz, unsigned ncolumns, int nz, int nzp)
+{
+    const unsigned t = blockIdx.x * 256u + threadIdx.x;
+    const unsigned col = t / (2u * FP_PAD), e = t % (2u * FP_PAD);
+    if (col < ncolumns) volz[(size_t)col * nzp + (e < FP_PAD ? e : nz + e)] = 0.0f;
+    if (t < (unsigned)nzp) volz[(size_t)ncolumns * nzp + t] = 0.0f;
+}
+
+extern "C" int leap_project_static_scratch(const leap_geometry *G, const float *d_vol, float *d_sino, int32_t batch, void *hip_stream)
+{
+    if (!G || !d_vol || !d_sino) {
+        leap_set_error("null handle or data pointer");
+        return LEAP_INVALID_ARG;
+    }
+    if (batch <= 0) {
+        leap_set_error("batch must be positive");
+        return LEAP_INVALID_ARG;
+    }
+    if ((const void *)d_vol == (const void *)d_sino) {
+        leap_set_error("input and output must not alias");
+        return LEAP_INVALID_ARG;
+    }
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const SfGeom &g = G->g;
+    const bool footprint_fast = g.model != SF_MODEL_SIDDON && G->fp_columns;
+    const bool siddon_fast = g.model == SF_MODEL_SIDDON && G->sd_columns;
+    if (!footprint_fast && !siddon_fast) {
+        // this geometry runs on kernels that read the caller's volume directly: no scratch is involved at all
+        const size_t nvol = (size_t)g.nx * g.ny * g.nz, nsino = (size_t)g.nviews * g.nrows * g.ncols;
+        for (int b = 0; b < batch; ++b) {
+            const int rc = leap_launch_project(G, d_vol + b * nvol, d_sino + b * nsino, stream);
+            if (rc != LEAP_OK) return rc;
+        }
+        return LEAP_OK;
+    }
+    const size_t item_bytes = sizeof(float) * ((size_t)g.nx * g.ny + 1) * (size_t)G->nzp;
+    if (item_bytes > LEAP_STATIC_SCRATCH_BYTES) {
+        char msg[200];
+        std::snprintf(msg, sizeof msg, "volume too large for the static scratch: its z-fastest copy needs %zu bytes, the array holds %zu",
+                      item_bytes, (size_t)LEAP_STATIC_SCRATCH_BYTES);
+        leap_set_error(msg);
+        return LEAP_UNSUPPORTED;
+    }
+    float *volz = (G->device >= 0 && G->device < LEAP_MAX_DEVICES) ? g_static_scratch[G->device] : nullptr;
+    if (!volz) {
+        leap_set_error("static scratch address unknown for the handle's device");
+        return LEAP_HIP_ERROR;
+    }
+    int per = (int)(LEAP_STATIC_SCRATCH_BYTES / item_bytes);
+    if (per > 16) per = 16;
+    if (per > 65535 / g.ny) per = 65535 / g.ny;
+    if (per < 1) per = 1;
+    if (per > batch) per = batch;
+    const size_t nvol = (size_t)g.nx * g.ny * g.nz, nsino = (size_t)g.nviews * g.nrows * g.ncols;
+    // the array keeps what the last call (of any handle) left in it: restore the zeros around this geometry's columns
+    const unsigned ncolumns = (unsigned)g.nx * (unsigned)g.ny;
+    const unsigned nthreads = ncolumns * 2u * FP_PAD > (unsigned)G->nzp ? ncolumns * 2u * FP_PAD : (unsigned)G->nzp;
+    for (int it = 0; it < per; ++it)
+        hipLaunchKernelGGL(sf_clear_column_pads, dim3(cdiv(nthreads, 256)), dim3(256), 0, stream,
+                           volz + (size_t)it * ((size_t)ncolumns + 1) * G->nzp, ncolumns, g.nz, G->nzp);
+    LEAP_HIP_CHECK(hipGetLastError());
+    for (int b = 0; b < batch; b += per) {
+        const int items = batch - b < per ? batch - b : per;
+        const int rc = footprint_fast ? launch_fp_items(G, d_vol + b * nvol, d_sino + b * nsino, items, stream, volz)
+                                      : launch_sd_items(G, d_vol + b * nvol, d_sino + b * nsino, items, stream, volz);
+        if (rc != LEAP_OK) return rc;
+    }
     return LEAP_OK;
 }

@@ -30,6 +30,8 @@ hipError_t hipGetLastError() { return hipSuccess; }
 const char *hipGetErrorString(hipError_t) { return "stub"; }
 }
 
+int leap_static_scratch_init(int) { return LEAP_OK; }   // the fixed device array exists on a GPU only
+
 // ---- CPU launchers: the general kernel bodies, one "thread" at a time ----------------------------------------
 int leap_launch_project(const leap_geometry *G, const float *vol, float *sino, hipStream_t)
 {

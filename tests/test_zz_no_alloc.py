@@ -1,0 +1,70 @@
+"""leap_project_static_scratch: the forward projection for callers that cannot allocate.  It runs the same kernels
+as leap_project on the library's fixed device array instead of the handle's own scratch copy, so its sinograms must
+equal leap_project's bit for bit, call after call, whatever an earlier call left in the array."""
+import numpy as np
+import pytest
+
+from synthetic import config, reduced, uniform_volume
+
+pytestmark = pytest.mark.gpu
+
+
+def _both(torch, B, cfg, model, seed, batch=1):
+    from paper_2307_05801_amd import Geometry
+    geo = Geometry(cfg, model=model)
+    desc = geo.describe()
+    print(f"[gpu] static scratch: {cfg.name} model={model} batch={batch}: {desc}", flush=True)
+    assert "A=columns" in desc, desc                      # the kernels that need the scratch copy
+    x = torch.from_numpy(uniform_volume(cfg, seed, batch=batch)).cuda()
+    ref = geo.project(x)
+    got = torch.full_like(ref, float("nan"))
+    stream = torch.cuda.current_stream().cuda_stream
+    B.leap_project_static_scratch(geo.handle, x.data_ptr(), got.data_ptr(), batch, stream)
+    torch.cuda.synchronize()
+    same = torch.equal(ref, got)
+    err = float((ref - got).abs().max())
+    geo.close()
+    return same, err, ref.cpu().numpy()
+
+
+@pytest.mark.parametrize("model", ["sf", "siddon"])
+def test_two_calls_in_a_row_second_one_smaller(oracle_mod, model):
+    import torch
+    from paper_2307_05801_amd import binding as B
+    big = reduced(config(3), 4, nviews=24)                                  # 128^3 voxels, 128x128 detector
+    small = reduced(config(3), 8, nviews=20).replace(nx=67, ny=70, nz=45, nrows=61, ncols=77, shift_u=0.4)
+    same, err, ax_big = _both(torch, B, big, model, 11)
+    assert same, f"first call differs from leap_project by {err}"
+    same, err, ax_small = _both(torch, B, small, model, 12)
+    assert same, f"second (smaller) call differs from leap_project by {err}"
+    # and the result is the operator's: the smaller case against the oracle
+    oracle = oracle_mod if model == "sf" else oracle_mod.siddon
+    if model == "siddon":
+        oracle.build()
+    ref = oracle.project(small, uniform_volume(small, 12)[0])
+    rel = float(np.linalg.norm(ax_small[0].astype(np.float64) - ref) / np.linalg.norm(ref))
+    assert rel <= 1e-5, rel
+
+
+def test_batch_shares_the_array_and_smaller_batch_follows():
+    import torch
+    from paper_2307_05801_amd import binding as B
+    cfg = reduced(config(4), 4, nviews=10)                                  # 64^3 voxels: many items fit the array
+    same, err, _ = _both(torch, B, cfg, "sf", 21, batch=19)                 # more items than one launch takes
+    assert same, err
+    same, err, _ = _both(torch, B, cfg.replace(nz=40, nrows=70), "sf", 22, batch=3)
+    assert same, err
+
+
+def test_volume_beyond_the_array_is_refused_with_a_message():
+    import torch
+    from paper_2307_05801_amd import Geometry, binding as B
+    cfg = reduced(config(3), 1, nviews=2).replace(nx=300, ny=300, nz=300)   # (300*300+1)*308 floats = 111 MB > 72 MiB
+    geo = Geometry(cfg)
+    assert "A=columns" in geo.describe(), geo.describe()
+    x = torch.zeros(cfg.vol_shape, device="cuda")
+    y = torch.zeros(cfg.sino_shape, device="cuda")
+    with pytest.raises(B.LeapError) as err:
+        B.leap_project_static_scratch(geo.handle, x.data_ptr(), y.data_ptr(), 1, torch.cuda.current_stream().cuda_stream)
+    assert err.value.status == B.LEAP_UNSUPPORTED and "static scratch" in str(err.value)
+    geo.close()
