@@ -22,16 +22,17 @@
  *   - Calls are asynchronous on the given HIP stream (hipStream_t passed as void*, NULL =
  *     the default stream) and allocate nothing.  Per-view tables are uploaded once, in
  *     leap_geometry_create.  Device memory beyond the caller's arrays ("Performance and
- *     Memory Usage" asks for one copy of each array only): the handle owns a scratch
- *     array of (nx*ny+1)*(nz+8) floats, a z-fastest copy of the volume that leap_project
- *     rewrites on every call (small volumes: up to 16 such copies, as many as fit in
- *     1 GiB, so that a batch is projected in one launch); when it cannot be allocated
- *     the handle works without it (slower kernels).  A LEAP_MODEL_SIDDON handle also
- *     keeps a table of 48 bytes per (view, detector column): the constants of each
- *     ray's line; a LEAP_CONE_CURVED footprint handle 24 bytes per (16x16 voxel-column
- *     tile, view).  Because of the scratch copy, calls that use the same handle must be
- *     ordered (one stream at a time, or events between streams); distinct handles are
- *     independent.
+ *     Memory Usage" asks for one copy of each array only): the fast forward kernels read the
+ *     volume through a z-fastest scratch copy, one SLAB of the volume at a time, so the handle
+ *     owns a scratch of at most max(64 MiB, an eighth of one volume) -- leap_geometry_describe
+ *     reports its size as "scratch=<bytes>"; small volumes share it between the items of a batch.
+ *     If it cannot be allocated the handle works without it on a slower kernel, says so in
+ *     leap_last_error at creation and in a "note=" of leap_geometry_describe.  A
+ *     LEAP_MODEL_SIDDON handle also keeps a table of 48 bytes per (view, detector column): the
+ *     constants of each ray's line; a LEAP_CONE_CURVED footprint handle 24 bytes per (16x16
+ *     voxel-column tile, view).  leap_project calls on one handle share its scratch; the library
+ *     orders them on the device (a call arriving on another stream than the previous one first
+ *     waits for that one's kernels), so any stream may be used; distinct handles are independent.
  *   - World frame: voxel centres x_i = center_x + (i-(nx-1)/2) voxel_xy (y, z alike); view
  *     angle phi counter-clockwise from +x, the source sits at sod*(cos phi, sin phi, 0);
  *     detector columns grow along (-sin phi, cos phi, 0), rows along +z; pixel centres
@@ -69,7 +70,8 @@ enum {
     LEAP_INVALID_ARG = -1,   /* null pointer, non-positive size or count, unknown type or model, FAN with nrows != 1 or nz != 1 */
     LEAP_BAD_GEOMETRY = -2,  /* cone/fan: source not strictly outside the volume's bounding circle, sdd <= 0, curved fan wider than +-1.5 rad */
     LEAP_HIP_ERROR = -3,     /* a HIP runtime call failed (the message is kept, see leap_last_error) */
-    LEAP_UNSUPPORTED = -4    /* sizes beyond what the index arithmetic of the kernels covers */
+    LEAP_UNSUPPORTED = -4    /* sizes beyond what the index arithmetic of the kernels covers; a tilted module with LEAP_MODEL_SF;
+                                a volume beyond the fixed array of leap_project_static_scratch */
 };
 
 /* The CT parameter set of "PyTorch Interfaces and CT Parameters": geometry type, number of
@@ -103,7 +105,7 @@ void leap_geometry_destroy(leap_geometry *geom);
 
 /* Forward projection y = A x ("CT Projection Models and Geometries", y = A x), ray-driven gather:
  * d_sino[b] = A d_vol[b] for b < batch.  d_vol: batch volumes, d_sino: batch sinograms (layouts above),
- * both device memory, not overlapping.  Asynchronous on hip_stream.  Uses the handle's scratch copy. */
+ * both device memory, not overlapping.  Asynchronous on hip_stream.  Uses the handle's scratch (see above). */
 int leap_project(const leap_geometry *geom, const float *d_vol, float *d_sino, int32_t batch, void *hip_stream);
 
 /* Back projection x = A^T y, the exact transpose of leap_project ("matched projectors"), voxel-driven
@@ -112,14 +114,15 @@ int leap_backproject(const leap_geometry *geom, const float *d_sino, float *d_vo
 
 /* leap_project for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same arguments, same result as leap_project, same kernels; the z-fastest copy of
- * the volume that the column-wise forward kernels read is kept in a fixed array of 72 MiB inside the library's device
- * code (every GPU the library runs on holds that array until the process ends) instead of the handle's own scratch.
- * The call allocates and frees nothing and calls no allocating routine; the array's address is looked up once per
- * device in leap_geometry_create.  Limit: (nx*ny+1)*(nz+8) floats must fit the array (a 256^3 volume does), else
- * LEAP_UNSUPPORTED with a message; geometries whose forward kernel reads the caller's volume directly (fan-beam,
- * tilted Siddon modules, very coarse detectors) have no such limit.  Items of a batch share the array, as many per launch as fit.
- * All calls on one GPU share the one array, whatever the handle: calls that overlap in time on one GPU (two streams,
- * two threads) race; order them.  The array keeps the last call's contents; each call restores the zeros it relies on. */
+ * the volume's slabs is kept in a fixed array of 72 MiB inside the library's device code (every GPU the library runs
+ * on holds that array until the process ends) instead of the handle's own scratch.  The call allocates and frees
+ * nothing and calls no allocating routine; the array's address is looked up once per device in leap_geometry_create.
+ * Limit: four voxel layers of the copy, 4 * max(nx, ny) * (nz + 16) floats, must fit the array (volumes up to about
+ * 2000^3 do; the fewer layers fit, the more passes the call makes), else LEAP_UNSUPPORTED with a message; geometries
+ * whose forward kernel reads the caller's volume directly (fan-beam, tilted Siddon modules, very coarse detectors)
+ * have no limit.  Items of a batch share the array, as many per launch as fit.  All calls on one GPU share the one
+ * array, whatever the handle: calls that overlap in time on one GPU (two streams, two threads) race; order them.
+ * The array keeps the last call's contents; each call restores the zeros it relies on. */
 int leap_project_static_scratch(const leap_geometry *geom, const float *d_vol, float *d_sino, int32_t batch, void *hip_stream);
 
 /* ---- iterative reconstruction on top of the pair ------------------------------------------------------------
@@ -151,7 +154,15 @@ const char *leap_status_string(int status);
 const char *leap_last_error(void);
 
 /* Which kernel family the handle dispatches to: writes up to `cap` bytes of a short NUL-terminated
- * description (for logs and benchmarks).  Returns LEAP_OK or LEAP_INVALID_ARG. */
+ * description (for logs and benchmarks): "A=..." and "AT=..." name the forward and the back projection kernel and
+ * their instance, "scratch=<bytes>" the device memory the handle owns beyond its tables, "note=..." anything that went
+ * differently from the plan at creation.  Returns LEAP_OK or LEAP_INVALID_ARG.
+ *
+ * Debugging aid: the environment variable LEAP_DEBUG, read by leap_geometry_create, overrides the choices shown
+ * there.  Comma-separated key=value pairs: general=1 (no fast kernels), cw=1|2|4 (detector columns per wavefront),
+ * rg=1|2|4|8 (row groups per wavefront), vb=N / tb=N (views per run / tiles per chunk of the block order), bp_shape=0..4
+ * (first back-projection tile shape tried), slab=N (voxel layers per scratch slab), items=N (batch items per launch),
+ * scratch_mib=N (scratch budget). */
 int leap_geometry_describe(const leap_geometry *geom, char *buf, int32_t cap);
 
 #ifdef __cplusplus

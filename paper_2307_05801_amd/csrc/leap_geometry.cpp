@@ -104,158 +104,395 @@ static void build_ray_table(leap_geometry *G)
     G->sd_max_axial_slope = max_slope;
 }
 
-// Modular geometry, footprint model: static limits of the two fast kernels, checked view by view on each view's own
-// parameter block (the same checks the circular scanners get in leap_geometry_create).
-static void select_modular_fast_kernels(leap_geometry *G)
+// ---- debugging aid ---------------------------------------------------------------------------------------------------
+// One environment variable, LEAP_DEBUG, read when a handle is created: comma-separated key=value pairs that override
+// what the selection below would pick (include/leap.h lists the keys).  Unknown keys are ignored.
+static bool debug_option(const char *key, long &value)
+{
+    const char *env = std::getenv("LEAP_DEBUG");
+    if (!env) return false;
+    const size_t klen = std::strlen(key);
+    for (const char *p = env; *p;) {
+        const char *end = std::strchr(p, ',');
+        const size_t len = end ? (size_t)(end - p) : std::strlen(p);
+        if (len > klen + 1 && std::strncmp(p, key, klen) == 0 && p[klen] == '=') {
+            value = std::atol(p + klen + 1);
+            return true;
+        }
+        if (!end) break;
+        p = end + 1;
+    }
+    return false;
+}
+
+// The parameter block view a is projected with: its own (modular scans with upright modules) or the shared one.
+static const SfGeom &view_geom(const leap_geometry *G, int a) { return G->geoms.empty() ? G->g : G->geoms[a]; }
+
+// Footprint bounds over the whole volume and all views, in double.  Magnification is extreme at the corner of the
+// volume's bounding circle; a flat detector stretches a footprint seen at fan angle gamma by 1 / cos(gamma).
+// Returns false when some view's source does not clear the bounding circle (then no fast kernel applies).
+static bool footprint_bounds(leap_geometry *G)
 {
     const leap_geometry_desc *d = &G->desc;
     const double T = d->voxel_xy, half_x = 0.5 * d->nx * T, half_y = 0.5 * d->ny * T;
-    double cols = 0.0, rows = 0.0, vpr = 0.0;
-    for (int a = 0; a < d->nviews; ++a) {
-        const SfGeom &ga = G->geoms[a];
+    const int blocks = G->geoms.empty() ? 1 : d->nviews;
+    double cols = 0.0, rows = 0.0, vpr = 0.0, slope = 1.0;
+    for (int a = 0; a < blocks; ++a) {
+        const SfGeom &ga = view_geom(G, a);
         const double cx = ga.x0d + 0.5 * (d->nx - 1) * T, cy = ga.y0d + 0.5 * (d->ny - 1) * T;
         const double rx = std::fabs(cx) + half_x, ry = std::fabs(cy) + half_y;
         const double reach = std::sqrt(rx * rx + ry * ry) + T;
-        const double sdd = ga.kud * d->pixel_u, lS = ga.sodd;
-        if (!(lS > reach)) return;
-        const double mag_max = sdd / (lS - reach), mag_min = sdd / (lS + reach);
-        const double umax = std::fmax(std::fabs(-2.0 - ga.col_offd), std::fabs(d->ncols + 1.0 - ga.col_offd)) * d->pixel_u;
-        const double stretch = 1.02 / std::cos(std::atan(umax / sdd));
+        double mag_max = 1.0, mag_min = 1.0, stretch = 1.0;
+        if (ga.type != SF_PARALLEL) {
+            const double sdd = ga.kud * d->pixel_u, sod = ga.sodd;
+            if (!(sod > reach) && !G->geoms.empty()) return false;
+            mag_max = sdd / std::fmax(sod - reach, 1e-9 * sod);
+            mag_min = sdd / (sod + reach);
+            const double umax = std::fmax(std::fabs(-2.0 - ga.col_offd), std::fabs(d->ncols + 1.0 - ga.col_offd)) * d->pixel_u;
+            const bool curved = ga.type == SF_CONE_CURVED;
+            const double gam = curved ? std::fmin(umax / sdd, 1.57) : std::atan(umax / sdd);
+            stretch = curved ? 1.02 : 1.02 / std::cos(gam);       // no stretch on the cylinder
+            slope = std::fmax(slope, gam < 0.78 ? std::tan(0.7853981633974483 + gam) : 1e30);
+        }
+        const bool fan = ga.type == SF_FAN;
         cols = std::fmax(cols, mag_max * T * std::sqrt(2.0) / d->pixel_u * stretch);
-        rows = std::fmax(rows, mag_max * d->voxel_z / d->pixel_v);
-        vpr = std::fmax(vpr, d->pixel_v / (mag_min * d->voxel_z));
+        rows = std::fmax(rows, fan ? 1.0 : mag_max * d->voxel_z / d->pixel_v);
+        vpr = std::fmax(vpr, fan ? 1.0 : d->pixel_v / (mag_min * d->voxel_z));
     }
-    G->max_cols_per_voxel = cols; G->max_rows_per_voxel = rows; G->max_voxels_per_row = vpr;
-    if (const char *env = std::getenv("LEAP_FORCE_GENERAL"))
-        if (env[0] == '1') return;
+    G->max_cols_per_voxel = cols; G->max_rows_per_voxel = rows; G->max_voxels_per_row = vpr; G->max_minor_slope = slope;
+    return true;
+}
 
-    if (d->nz >= 8 && std::isfinite(cols) && cols <= 4.0 && rows <= 3.0 && (double)d->nrows * d->ncols < 1073741824.0) {
-        G->bp_nc = std::max(2, (int)std::ceil(cols) + 1);
-        G->bp_nv = std::max(2, (int)std::ceil(rows - 1e-6) + 1);
-        G->bp_wh = (float)(0.5 * cols);
-        const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T;
-        const float hx = 0.5f * (float)(BP_T - 1) * G->g.T;
-        for (int sh = d->nz >= 128 ? 0 : 1; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
-            const int zc = BP_SHAPES[sh].zc, chunks = (d->nz + zc - 1) / zc;
-            int need_w = 0, need_h = 0;
-            for (int a = 0; a < d->nviews; ++a)
-                for (int ty = 0; ty < tiles_y; ++ty)
-                    for (int tx = 0; tx < tiles_x; ++tx)
-                        for (int ch = 0; ch < chunks; ch += (chunks > 1 ? chunks - 1 : 1)) {
-                            const SfGeom &ga = G->geoms[a];
-                            const float xc = (float)(ga.x0d + ((double)(tx * BP_T) + 0.5 * (BP_T - 1)) * ga.Td);
-                            const float yc = (float)(ga.y0d + ((double)(ty * BP_T) + 0.5 * (BP_T - 1)) * ga.Td);
-                            const float z0 = (float)(ga.zlo0d + (double)(ch * zc) * ga.Tzd), z1 = z0 + (float)zc * ga.Tz;
-                            const SfWindow w = sf_bp_window(ga, G->views[a], xc, yc, hx, z0, z1, G->bp_wh, G->bp_nc, G->bp_nv);
-                            need_w = std::max(need_w, w.need_w);
-                            need_h = std::max(need_h, w.need_h);
-                        }
-            G->bp_need_w = need_w; G->bp_need_h = need_h; G->bp_shape = sh;
-            G->bp_tiled = need_w <= BP_SHAPES[sh].pw - 1 && need_h <= BP_SHAPES[sh].ph - 1;
-        }
-    }
-    if (d->nrows >= 32 && std::isfinite(vpr) && vpr <= 3.0 && (double)d->nx * d->ny * (d->nz + 2.0 * FP_PAD) < 4294967296.0 &&
-        d->ny <= 65535) {
-        auto slots_needed = [&](int cw) {
-            int need = 0;
-            for (int a = 0; a < d->nviews && need <= 16; ++a)
-                for (int c = 0; c < d->ncols; c += cw) {
-                    const SfRayLines L = sf_ray_lines(G->geoms[a], G->views[a], c, cw);
-                    const int n_major = L.xmajor ? d->nx : d->ny;
-                    const float d0 = std::fabs(L.b0 - L.b1);
-                    const float d1 = std::fabs(fmaf(L.m0 - L.m1, (float)(n_major - 1), L.b0 - L.b1));
-                    const float dm = d0 > d1 ? d0 : d1;
-                    if (!(dm < 1e6f)) return 1 << 20;
-                    need = std::max(need, (int)std::floor(dm + 2.0f * L.spread + 1e-3f) + 2);
+// Largest staged window any (view, tile, first or last z-chunk) of a tiled back projection asks for, evaluated with the
+// kernel's own window function on the view's own parameter block.
+template <class WindowFn>
+static void staged_window_need(const leap_geometry *G, int zc, WindowFn window, int &need_w, int &need_h)
+{
+    const leap_geometry_desc *d = &G->desc;
+    const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T;
+    const int chunks = (d->nz + zc - 1) / zc;
+    need_w = need_h = 0;
+    for (int a = 0; a < d->nviews; ++a) {
+        const SfGeom &ga = view_geom(G, a);
+        for (int ty = 0; ty < tiles_y; ++ty)
+            for (int tx = 0; tx < tiles_x; ++tx) {
+                const float xc = (float)(ga.x0d + ((double)(tx * BP_T) + 0.5 * (BP_T - 1)) * ga.Td);
+                const float yc = (float)(ga.y0d + ((double)(ty * BP_T) + 0.5 * (BP_T - 1)) * ga.Td);
+                for (int ch = 0; ch < chunks; ch += (chunks > 1 ? chunks - 1 : 1)) {   // extremes: first and last chunk
+                    const float z0 = (float)(ga.zlo0d + (double)(ch * zc) * ga.Tzd), z1 = z0 + (float)zc * ga.Tz;
+                    const SfWindow w = window(ga, G->views[a], xc, yc, z0, z1);
+                    need_w = w.need_w > need_w ? w.need_w : need_w;
+                    need_h = w.need_h > need_h ? w.need_h : need_h;
                 }
-            return need;
-        };
-        G->fp_cw = 4;                              // the modular instances exist for bundles of 4 and 2 columns
-        if (const char *env = std::getenv("LEAP_FP_CW")) {
-            const int v = std::atoi(env);
-            if (v == 2 || v == 4) G->fp_cw = v;
-        }
-        G->fp_nk = std::max(2, (int)std::ceil(vpr - 1e-6) + 1);
-        const int groups = (d->nrows + 63) / 64;
-        G->fp_rg = groups >= 8 ? 8 : (groups >= 4 ? 4 : (groups >= 2 ? 2 : 1));
-        if (G->fp_rg < 4 && !std::getenv("LEAP_FP_CW")) G->fp_cw = 2;      // short detectors: see leap_geometry_create
-        int need = slots_needed(G->fp_cw);
-        if (need > 16 && G->fp_cw == 4) {
-            G->fp_cw = 2;
-            need = slots_needed(2);
-        }
-        G->fp_need_q = need;
-        G->fp_nq = need <= 4 ? 4 : (need <= 8 ? 8 : 16);
-        G->fp_columns = need <= 16 && G->fp_nk <= 4;
+            }
     }
 }
 
-// Siddon model: static limits of the two fast kernels.  With per-view parameter blocks (upright modular scans) every
-// view is checked on its own block.
+// Footprint model, tiled back projection: pick the template instance and verify its staged window.
+static void select_footprint_tiled(leap_geometry *G)
+{
+    const leap_geometry_desc *d = &G->desc;
+    if (d->type == LEAP_FAN || d->nz < 8 || !std::isfinite(G->max_cols_per_voxel) || G->max_cols_per_voxel > 4.0 ||
+        G->max_rows_per_voxel > 3.0 || !((double)d->nrows * d->ncols < 1073741824.0))     // 32-bit byte offsets within a view
+        return;
+    G->bp_nc = std::max(2, (int)std::ceil(G->max_cols_per_voxel) + 1);
+    G->bp_nv = std::max(2, (int)std::ceil(G->max_rows_per_voxel - 1e-6) + 1);
+    G->bp_wh = (float)(0.5 * G->max_cols_per_voxel);
+    const float hx = 0.5f * (float)(BP_T - 1) * G->g.T;
+    long first_shape = d->nz >= 128 ? 0 : 1;       // 64-voxel chunks only pay off on tall volumes
+    if (debug_option("bp_shape", first_shape)) first_shape = ((first_shape % BP_NSHAPES) + BP_NSHAPES) % BP_NSHAPES;
+    for (int sh = (int)first_shape; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
+        staged_window_need(G, BP_SHAPES[sh].zc,
+                           [&](const SfGeom &ga, const SfView &v, float xc, float yc, float z0, float z1) {
+                               return sf_bp_window(ga, v, xc, yc, hx, z0, z1, G->bp_wh, G->bp_nc, G->bp_nv);
+                           },
+                           G->bp_need_w, G->bp_need_h);
+        G->bp_shape = sh;
+        // one spare row and column: host and device floats may round apart
+        G->bp_tiled = G->bp_need_w <= BP_SHAPES[sh].pw - 1 && G->bp_need_h <= BP_SHAPES[sh].ph - 1;
+    }
+    // Cylinder: the tiled kernel takes the angle between a voxel's centre and its corners from a short series,
+    // good to 3e-9 rad below 0.08 rad.
+    if (d->type == LEAP_CONE_CURVED) {
+        const double rx = std::fabs(d->center_x) + 0.5 * d->nx * d->voxel_xy, ry = std::fabs(d->center_y) + 0.5 * d->ny * d->voxel_xy;
+        const double nearest = d->sod - std::sqrt(rx * rx + ry * ry);
+        if (!(0.7072 * d->voxel_xy <= 0.08 * nearest)) G->bp_tiled = false;
+    }
+}
+
+// Row groups per wave of the column-wise forward kernels: the largest of 1, 2, 4, (8) that the detector fills.
+static int row_groups(int nrows, int rows_per_group, int most)
+{
+    const int groups = (nrows + rows_per_group - 1) / rows_per_group;
+    int rg = 1;
+    while (rg * 2 <= most && rg * 2 <= groups) rg *= 2;
+    long v;
+    if (debug_option("rg", v) && (v == 1 || v == 2 || v == 4 || (v == 8 && most >= 8))) rg = (int)v;
+    return rg;
+}
+
+static void block_order_options(leap_geometry *G)
+{
+    long v;
+    if (debug_option("vb", v) && v >= 1 && v <= 1024) G->fp_vb = (int)v;
+    if (debug_option("tb", v) && v >= 1 && v <= 1024) G->fp_tb = (int)v;
+}
+
+// Footprint model, column-wise forward projection: static limits and the marching axis of every bundle.
+static void select_footprint_columns(leap_geometry *G)
+{
+    const leap_geometry_desc *d = &G->desc;
+    const double vpr = G->max_voxels_per_row;
+    if (d->type == LEAP_FAN || d->nrows < 32 || !std::isfinite(vpr) || vpr > 3.0) return;
+    // kappa (the axial voxel coordinate of a row's edge) must stay within +-2^19 for the kernel's placement arithmetic
+    if (!((d->nrows + 1024.0) * vpr + d->nz + 64.0 < 500000.0)) return;
+    long v;
+    G->fp_cw = 4;
+    // Short detectors (fewer than about 200 rows) have too few bundles of four to fill the chip: two columns measured
+    // 5 to 12 % faster there.  The cylinder's record phase is heavier: four columns only pay off from about 450 rows on.
+    if (d->nrows <= 192 || (d->type == LEAP_CONE_CURVED && d->nrows <= 448)) G->fp_cw = 2;
+    const bool forced_cw = debug_option("cw", v) && (v == 1 || v == 2 || v == 4);
+    if (forced_cw) G->fp_cw = (int)v;
+    if (d->type != LEAP_CONE && d->type != LEAP_PARALLEL && G->fp_cw == 1) G->fp_cw = 2;   // instances of 4 and 2 columns only
+    // candidate slots per slab: widest range of voxel columns any bundle of cw detector columns can see
+    auto slots_needed = [&](int cw) {
+        int need = 0;
+        for (int a = 0; a < d->nviews && need <= 16; ++a)
+            for (int c = 0; c < d->ncols; c += cw) {
+                const SfRayLines L = sf_ray_lines(view_geom(G, a), G->views[a], c, cw);
+                const int n_major = L.xmajor ? d->nx : d->ny;
+                const float d0 = std::fabs(L.b0 - L.b1);
+                const float d1 = std::fabs(fmaf(L.m0 - L.m1, (float)(n_major - 1), L.b0 - L.b1));
+                const float dm = d0 > d1 ? d0 : d1;
+                if (!(dm < 1e6f)) return 1 << 20;
+                need = std::max(need, (int)std::floor(dm + 2.0f * L.spread + 1e-3f) + 2);
+            }
+        return need;
+    };
+    int need = slots_needed(G->fp_cw);
+    const int cw_min = (d->type == LEAP_CONE || d->type == LEAP_PARALLEL) ? 1 : 2;
+    while (need > 16 && G->fp_cw > cw_min) {
+        G->fp_cw /= 2;
+        need = slots_needed(G->fp_cw);
+    }
+    G->fp_need_q = need;
+    G->fp_nq = need <= 4 ? 4 : (need <= 8 ? 8 : 16);
+    G->fp_nkp = std::min(FP_MAX_P, std::max(2, (int)std::ceil(2.0 * vpr - 1e-6) + 1));
+    G->fp_rg = row_groups(d->nrows, 128, 4);
+    G->fp_columns = need <= 16;
+    block_order_options(G);
+    if (!G->fp_columns) return;
+    const int nbundles = (d->ncols + G->fp_cw - 1) / G->fp_cw;
+    G->major.resize((size_t)d->nviews * nbundles);
+    for (int a = 0; a < d->nviews; ++a)
+        for (int b = 0; b < nbundles; ++b)
+            G->major[(size_t)a * nbundles + b] = (unsigned char)sf_ray_lines(view_geom(G, a), G->views[a], b * G->fp_cw, G->fp_cw).xmajor;
+}
+
+// Siddon model: static limits of the two fast kernels.
 static void select_siddon_fast_kernels(leap_geometry *G)
 {
     const leap_geometry_desc *d = &G->desc;
-    const bool per_view = !G->geoms.empty();
     if (d->type == LEAP_FAN || !(G->sd_max_axial_slope <= 0.999)) return;
-    if (const char *env = std::getenv("LEAP_FORCE_GENERAL"))
-        if (env[0] == '1') return;
 
     // wave-per-column forward projection: no ray may cross more than one z-face per slab
-    if (d->nrows >= 32 && ((double)d->nx * d->ny + 1.0) * (d->nz + 2.0 * FP_PAD) < 4294967296.0 && d->ny <= 65535) {
+    if (d->nrows >= 32) {
         G->sd_columns = true;
-        const int groups = (d->nrows + 63) / 64;
-        G->fp_rg = groups >= 8 ? 8 : (groups >= 4 ? 4 : (groups >= 2 ? 2 : 1));
-        if (const char *env = std::getenv("LEAP_FP_VB")) {
-            const int v = std::atoi(env);
-            if (v >= 1 && v <= 1024) G->fp_vb = v;
-        }
-        if (const char *env = std::getenv("LEAP_FP_TB")) {
-            const int v = std::atoi(env);
-            if (v >= 1 && v <= 1024) G->fp_tb = v;
-        }
-        if (const char *env = std::getenv("LEAP_FP_RG")) {
-            const int v = std::atoi(env);
-            if (v == 1 || v == 2 || v == 4 || v == 8) G->fp_rg = v;
-        }
+        G->fp_rg = row_groups(d->nrows, 64, 8);
+        block_order_options(G);
     }
 
     // tiled back projection: at most 4 pixel centres inside a voxel's footprint, and the staged window of every
     // (view, tile, z-chunk) must fit the instance (checked with the kernel's own function)
     if (d->nz >= 8 && std::isfinite(G->max_cols_per_voxel) && G->max_cols_per_voxel > 0.0 && G->max_cols_per_voxel < 3.9 &&
         (double)d->nrows * d->ncols < 1073741824.0) {      // the staging loads use 32-bit byte offsets within a view
-        G->bp_nc = (int)std::floor(G->max_cols_per_voxel + 0.01) + 1;
-        if (G->bp_nc < 2) G->bp_nc = 2;
-        const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T;
+        G->bp_nc = std::max(2, (int)std::floor(G->max_cols_per_voxel + 0.01) + 1);
         const float hx = 0.5f * (float)BP_T * G->g.T;
-        int first_shape = 1;                          // the 64-voxel shape does not fit: the sums live in LDS
-        if (const char *env = std::getenv("LEAP_BP_SHAPE")) {
-            first_shape = std::atoi(env) % BP_NSHAPES;
-            if (first_shape < 1) first_shape = 1;
-        }
-        for (int sh = first_shape; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
-            const int zc = BP_SHAPES[sh].zc;
-            const int chunks = (d->nz + zc - 1) / zc;
-            int need_w = 0, need_h = 0;
-            for (int a = 0; a < d->nviews; ++a) {
-                const SfGeom &g = per_view ? G->geoms[a] : G->g;
-                for (int ty = 0; ty < tiles_y; ++ty)
-                    for (int tx = 0; tx < tiles_x; ++tx) {
-                        const float xc = (float)(g.x0d + ((double)(tx * BP_T) + 0.5 * (BP_T - 1)) * g.Td);
-                        const float yc = (float)(g.y0d + ((double)(ty * BP_T) + 0.5 * (BP_T - 1)) * g.Td);
-                        for (int ch = 0; ch < chunks; ch += (chunks > 1 ? chunks - 1 : 1)) {
-                            const float z0 = (float)(g.zlo0d + (double)(ch * zc) * g.Tzd), z1 = z0 + (float)zc * g.Tz;
-                            const SfWindow w = sd_bp_window(g, G->views[a], xc, yc, hx, z0, z1);
-                            need_w = w.need_w > need_w ? w.need_w : need_w;
-                            need_h = w.need_h > need_h ? w.need_h : need_h;
-                        }
-                    }
-            }
-            G->bp_need_w = need_w;
-            G->bp_need_h = need_h;
+        long first_shape = 1;                          // the 64-voxel shape does not fit: the sums live in LDS
+        if (debug_option("bp_shape", first_shape)) first_shape = std::max(1L, first_shape % BP_NSHAPES);
+        for (int sh = (int)first_shape; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
+            staged_window_need(G, BP_SHAPES[sh].zc,
+                               [&](const SfGeom &ga, const SfView &v, float xc, float yc, float z0, float z1) {
+                                   return sd_bp_window(ga, v, xc, yc, hx, z0, z1);
+                               },
+                               G->bp_need_w, G->bp_need_h);
             G->bp_shape = sh;
-            G->bp_tiled = need_w <= BP_SHAPES[sh].pw - 1 && need_h <= BP_SHAPES[sh].ph - 1;
+            G->bp_tiled = G->bp_need_w <= BP_SHAPES[sh].pw - 1 && G->bp_need_h <= BP_SHAPES[sh].ph - 1;
         }
     }
+}
+
+// Picks the kernels of a validated scan (circular scanners, or modular scans made of upright modules).
+static void select_fast_kernels(leap_geometry *G)
+{
+    if (!footprint_bounds(G)) return;
+    long v;
+    if (debug_option("general", v) && v == 1) return;       // testing aid: every call on the general kernels
+    if (G->desc.model == LEAP_MODEL_SF) {
+        select_footprint_tiled(G);
+        select_footprint_columns(G);
+    } else {
+        select_siddon_fast_kernels(G);
+    }
+}
+
+// Slab width and items per launch that a scratch of `floats` floats affords for a batch of `batch` volumes: as many
+// items at once as the batch has (16 at most) while a slab stays at least 32 voxel layers wide, the whole volume per
+// copy if it fits.  Returns false if not even four layers fit.
+bool leap_plan_scratch(const leap_geometry *G, size_t floats, int batch, int &width, int &items)
+{
+    const leap_geometry_desc *d = &G->desc;
+    const int n_side = std::max(d->nx, d->ny);                  // a slab holds up to width * n_side voxel columns
+    const double nzp = d->nz + 2.0 * FP_PAD;
+    auto width_for = [&](int it) {
+        const double w = std::floor(((double)floats / it - nzp) / (nzp * n_side));
+        return w >= n_side ? n_side : (w < 4 ? 0 : ((int)w & ~3));
+    };
+    items = std::max(1, std::min(batch, 16));
+    while (items > 1 && width_for(items) < std::min(32, n_side)) items = (items + 1) / 2;
+    width = width_for(items);
+    if (G->dbg_items > 0) items = std::min(G->dbg_items, std::max(1, batch));
+    if (G->dbg_slab > 0) width = std::min(G->dbg_slab, n_side);
+    if (G->dbg_items > 0 || G->dbg_slab > 0) {                  // overrides must still fit
+        while (items > 1 && ((double)width * n_side + 1.0) * nzp * items > (double)floats) --items;
+        if (((double)width * n_side + 1.0) * nzp * items > (double)floats) width = width_for(items);
+    }
+    // the copy kernel puts (voxel rows of a slab) x (items) into one grid dimension
+    items = std::max(1, std::min(items, 65535 / std::max(std::max(d->ny, width), 1)));
+    return width >= 4 && ((double)width * n_side + 1.0) * nzp < 4294967296.0;     // slab columns are indexed with 32 bits
+}
+
+// The scratch of the column-wise forward kernels: z-fastest copies of one slab of the volume (plus a spare zero column
+// each).  Large volumes: an eighth of one volume (a quarter for the Siddon kernel, whose waves own a single detector
+// column and lose more to narrow slabs); volumes under 512 MiB: 128 MiB, which lets a batch of small training volumes
+// go through together.  On failure the handle falls back to the general kernel and says so (leap_last_error, and the
+// note shown by leap_geometry_describe).
+static void allocate_forward_scratch(leap_geometry *G)
+{
+    const leap_geometry_desc *d = &G->desc;
+    if (!G->fp_columns && !G->sd_columns) return;
+    G->nzp = d->nz + 2 * FP_PAD;
+    const double volume_bytes = 4.0 * d->nx * d->ny * (double)d->nz;
+    const double share = volume_bytes / (d->model == LEAP_MODEL_SIDDON ? 4.0 : 8.0);
+    double budget = volume_bytes / 8.0 >= 64.0 * 1048576.0 ? share : 128.0 * 1048576.0;
+    long v;
+    if (debug_option("scratch_mib", v) && v >= 1) budget = 1048576.0 * (double)v;
+    if (debug_option("slab", v) && v >= 4) G->dbg_slab = (int)(v & ~3L);
+    if (debug_option("items", v) && v >= 1 && v <= 16) G->dbg_items = (int)v;
+    // no more than 16 whole copies
+    const double whole = 4.0 * ((double)d->nx * d->ny + 1.0) * G->nzp;
+    budget = std::fmin(budget, 16.0 * whole);
+    hipError_t e = hipErrorOutOfMemory;
+    int width = 0, items = 0;
+    for (int attempt = 0; attempt < 6; ++attempt, budget *= 0.5) {
+        G->scratch_bytes = (size_t)budget & ~(size_t)255;
+        if (!leap_plan_scratch(G, G->scratch_bytes / sizeof(float), 1, width, items)) break;
+        e = hipMalloc((void **)&G->d_volz, G->scratch_bytes);
+        if (e == hipSuccess) e = hipMemset(G->d_volz, 0, G->scratch_bytes);   // the pads stay zero for the handle's life
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e == hipSuccess) break;
+        if (G->d_volz) (void)hipFree(G->d_volz);
+        G->d_volz = nullptr;
+        (void)hipGetLastError();
+    }
+    if (e == hipSuccess && !G->major.empty()) {
+        e = hipMalloc((void **)&G->d_major, G->major.size());
+        if (e == hipSuccess) e = hipMemcpy(G->d_major, G->major.data(), G->major.size(), hipMemcpyHostToDevice);
+    }
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&G->scratch_event, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        if (G->d_volz) (void)hipFree(G->d_volz);
+        if (G->d_major) (void)hipFree(G->d_major);
+        G->d_volz = nullptr; G->d_major = nullptr;
+        G->fp_columns = G->sd_columns = false;
+        G->scratch_bytes = 0;
+        G->note = "scratch allocation failed: forward projection runs on the general kernel";
+        leap_set_error(std::string("leap_geometry_create: ") + G->note + " (" + hipGetErrorString(e) + ")");
+        (void)hipGetLastError();
+        return;
+    }
+    G->slab_width = width;
+}
+
+static void free_handle(leap_geometry *G)
+{
+    if (!G) return;
+    if (G->d_views) (void)hipFree(G->d_views);
+    if (G->d_volz) (void)hipFree(G->d_volz);
+    if (G->d_major) (void)hipFree(G->d_major);
+    if (G->d_raycols) (void)hipFree(G->d_raycols);
+    if (G->d_poses) (void)hipFree(G->d_poses);
+    if (G->d_geoms) (void)hipFree(G->d_geoms);
+    if (G->d_colcs) (void)hipFree(G->d_colcs);
+    if (G->scratch_event) (void)hipEventDestroy(G->scratch_event);
+    delete G;
+}
+
+// Cylindrical detector, tiled back projection: cosine and sine of every detector column's fan angle (ray amplitudes),
+// then per (tile, view) the tile centre's fan angle and the tile's window bounds.  No room for the tables: the general
+// kernel needs none.
+static void upload_curved_tables(leap_geometry *G)
+{
+    const leap_geometry_desc *d = &G->desc;
+    const SfGeom &g = G->g;
+    const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T;
+    const size_t head = 2 * sizeof(float) * (size_t)d->ncols;
+    const size_t bytes = head + sizeof(SfCurvedBounds) * (size_t)tiles_x * tiles_y * d->nviews;
+    std::vector<unsigned char> blob(bytes);
+    float *cs = reinterpret_cast<float *>(blob.data());
+    for (int c = 0; c < d->ncols; ++c) {
+        const double gam = ((double)c - g.col_offd) * d->pixel_u / d->sdd;
+        cs[2 * (size_t)c] = (float)std::cos(gam);
+        cs[2 * (size_t)c + 1] = (float)std::sin(gam);
+    }
+    SfCurvedBounds *tab = reinterpret_cast<SfCurvedBounds *>(blob.data() + head);
+    const float hx = 0.5f * (float)(BP_T - 1) * g.T;
+    for (int ty = 0; ty < tiles_y; ++ty)
+        for (int tx = 0; tx < tiles_x; ++tx) {
+            const double xcd = g.x0d + ((double)(tx * BP_T) + 0.5 * (BP_T - 1)) * g.Td;
+            const double ycd = g.y0d + ((double)(ty * BP_T) + 0.5 * (BP_T - 1)) * g.Td;
+            SfCurvedBounds *row = tab + ((size_t)ty * tiles_x + tx) * d->nviews;
+            for (int a = 0; a < d->nviews; ++a) {
+                const SfView &v = G->views[a];
+                row[a].gref = std::atan2(std::fma(ycd, v.cd, -xcd * v.sd), g.sodd - std::fma(xcd, v.cd, ycd * v.sd));
+                sf_curved_tile_bounds(g, v, (float)xcd, (float)ycd, hx, row[a].xi_lo, row[a].xi_hi, row[a].ilo, row[a].ihi);
+            }
+        }
+    hipError_t et = hipMalloc((void **)&G->d_colcs, bytes);
+    if (et == hipSuccess) et = hipMemcpy(G->d_colcs, blob.data(), bytes, hipMemcpyHostToDevice);
+    if (et != hipSuccess) {
+        if (G->d_colcs) (void)hipFree(G->d_colcs);
+        G->d_colcs = nullptr;
+        G->bp_tiled = false;
+        G->note = "no room for the cylinder's tile tables: back projection runs on the general kernel";
+        (void)hipGetLastError();
+    }
+}
+
+// Uploads every table the chosen kernels read to the current device and allocates the forward scratch; on failure
+// frees the handle.
+static int finish_handle(leap_geometry *G, leap_geometry **out)
+{
+    const leap_geometry_desc *d = &G->desc;
+    auto upload = [](void **dst, const void *src, size_t bytes) {
+        hipError_t e = hipMalloc(dst, bytes);
+        if (e == hipSuccess) e = hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice);
+        return e;
+    };
+    hipError_t e = hipGetDevice(&G->device);
+    if (e == hipSuccess) (void)leap_static_scratch_init(G->device);   // set-up for leap_project_static_scratch; it reports a failure itself
+    if (e == hipSuccess && !G->views.empty()) e = upload((void **)&G->d_views, G->views.data(), sizeof(SfView) * G->views.size());
+    if (e == hipSuccess) allocate_forward_scratch(G);
+    if (e == hipSuccess && !G->raycols.empty()) e = upload((void **)&G->d_raycols, G->raycols.data(), sizeof(SdRayCol) * G->raycols.size());
+    if (e == hipSuccess && !G->geoms.empty()) e = upload((void **)&G->d_geoms, G->geoms.data(), sizeof(SfGeom) * G->geoms.size());
+    if (e == hipSuccess && !G->poses.empty()) e = upload((void **)&G->d_poses, G->poses.data(), sizeof(MdPose) * G->poses.size());
+    if (e == hipSuccess && d->type == LEAP_CONE_CURVED && d->model == LEAP_MODEL_SF && G->bp_tiled) upload_curved_tables(G);
+    if (e != hipSuccess) {
+        free_handle(G);
+        return leap_hip_fail(e, "uploading the geometry tables");
+    }
+    *out = G;
+    return LEAP_OK;
 }
 
 // Modular geometry: per-view poses instead of the angle list; only the fields the modular kernels read are filled.
@@ -368,53 +605,11 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
             ga.col_off = (float)ga.col_offd; ga.v0 = (float)ga.v0d;
         }
     }
-    if (d->model == LEAP_MODEL_SF) select_modular_fast_kernels(G);
-    if (d->model == LEAP_MODEL_SIDDON && upright) {
-        build_ray_table(G);
-        select_modular_fast_kernels(G);      // footprint bounds (columns per voxel) are what the Siddon limits need too
-        G->bp_tiled = G->fp_columns = false;
-        G->bp_shape = 0;
-        select_siddon_fast_kernels(G);
+    if (upright) {
+        if (d->model == LEAP_MODEL_SIDDON) build_ray_table(G);
+        select_fast_kernels(G);
     }
-    hipError_t e = hipGetDevice(&G->device);
-    if (e == hipSuccess) (void)leap_static_scratch_init(G->device);   // set-up for leap_project_static_scratch; it reports a failure itself
-    if (e == hipSuccess && (G->fp_columns || G->sd_columns)) {
-        G->nzp = d->nz + 2 * FP_PAD;
-        const size_t bytes = sizeof(float) * ((size_t)d->nx * d->ny + 1) * G->nzp;
-        hipError_t es = hipMalloc((void **)&G->d_volz, bytes);
-        if (es == hipSuccess) es = hipMemset(G->d_volz, 0, bytes);
-        if (es == hipSuccess) es = hipDeviceSynchronize();
-        if (es != hipSuccess) {
-            if (G->d_volz) (void)hipFree(G->d_volz);
-            G->d_volz = nullptr;
-            G->fp_columns = G->sd_columns = false;
-            (void)hipGetLastError();
-        }
-    }
-    if (e == hipSuccess && (G->sd_columns || (G->bp_tiled && d->model == LEAP_MODEL_SIDDON))) {
-        const size_t bytes = sizeof(SdRayCol) * G->raycols.size();
-        e = hipMalloc((void **)&G->d_raycols, bytes);
-        if (e == hipSuccess) e = hipMemcpy(G->d_raycols, G->raycols.data(), bytes, hipMemcpyHostToDevice);
-    }
-    if (e == hipSuccess && !G->geoms.empty()) {
-        e = hipMalloc((void **)&G->d_geoms, sizeof(SfGeom) * G->geoms.size());
-        if (e == hipSuccess) e = hipMemcpy(G->d_geoms, G->geoms.data(), sizeof(SfGeom) * G->geoms.size(), hipMemcpyHostToDevice);
-        if (e == hipSuccess) e = hipMalloc((void **)&G->d_views, sizeof(SfView) * G->views.size());
-        if (e == hipSuccess) e = hipMemcpy(G->d_views, G->views.data(), sizeof(SfView) * G->views.size(), hipMemcpyHostToDevice);
-    }
-    if (e == hipSuccess) e = hipMalloc((void **)&G->d_poses, sizeof(MdPose) * (size_t)d->nviews);
-    if (e == hipSuccess) e = hipMemcpy(G->d_poses, G->poses.data(), sizeof(MdPose) * (size_t)d->nviews, hipMemcpyHostToDevice);
-    if (e != hipSuccess) {
-        if (G->d_poses) (void)hipFree(G->d_poses);
-        if (G->d_geoms) (void)hipFree(G->d_geoms);
-        if (G->d_views) (void)hipFree(G->d_views);
-        if (G->d_volz) (void)hipFree(G->d_volz);
-        if (G->d_raycols) (void)hipFree(G->d_raycols);
-        delete G;
-        return leap_hip_fail(e, "uploading the pose table");
-    }
-    *out = G;
-    return LEAP_OK;
+    return finish_handle(G, out);
 }
 
 extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry **out)
@@ -519,257 +714,35 @@ extern "C" int leap_geometry_create(const leap_geometry_desc *d, leap_geometry *
     }
 
     if (d->model == LEAP_MODEL_SIDDON) build_ray_table(G);
-
-    // Footprint bounds over the whole volume (double).  Magnification is extreme at the corner of the volume's
-    // bounding circle; a flat detector stretches a footprint seen at fan angle gamma by 1/cos(gamma).
-    {
-        const double rx = std::fabs(d->center_x) + half_x, ry = std::fabs(d->center_y) + half_y;
-        const double reach = std::sqrt(rx * rx + ry * ry) + T;
-        double mag_max = 1.0, mag_min = 1.0, stretch = 1.0, slope = 1.0;
-        if (!par) {
-            mag_max = d->sdd / std::fmax(d->sod - reach, 1e-9 * d->sod);
-            mag_min = d->sdd / (d->sod + reach);
-            const double umax = (0.5 * d->ncols + std::fabs(d->shift_u) + 2.0) * d->pixel_u;
-            const double gam = d->type == LEAP_CONE_CURVED ? std::fmin(umax / d->sdd, 1.57) : std::atan(umax / d->sdd);
-            stretch = d->type == LEAP_CONE_CURVED ? 1.02 : 1.02 / std::cos(gam);     // no stretch on the cylinder
-            slope = (gam < 0.78) ? std::tan(0.7853981633974483 + gam) : 1e30;
-        }
-        G->max_cols_per_voxel = mag_max * T * std::sqrt(2.0) / d->pixel_u * stretch;
-        G->max_rows_per_voxel = (d->type == LEAP_FAN) ? 1.0 : mag_max * d->voxel_z / d->pixel_v;
-        G->max_voxels_per_row = (d->type == LEAP_FAN) ? 1.0 : d->pixel_v / (mag_min * d->voxel_z);
-        G->max_minor_slope = slope;
-    }
-
-    // Tiled back projection: pick the template instance and verify its staged window against every
-    // (view, tile, z-chunk) with the very function the kernel evaluates.
-    if (d->model == LEAP_MODEL_SF && d->type != LEAP_FAN && d->nz >= 8 && std::isfinite(G->max_cols_per_voxel) && G->max_cols_per_voxel <= 4.0 &&
-        G->max_rows_per_voxel <= 3.0 && (double)d->nrows * d->ncols < 1073741824.0) {     // 32-bit byte offsets within a view
-        G->bp_nc = (int)std::ceil(G->max_cols_per_voxel) + 1;
-        if (G->bp_nc < 2) G->bp_nc = 2;
-        G->bp_nv = (int)std::ceil(G->max_rows_per_voxel - 1e-6) + 1;
-        if (G->bp_nv < 2) G->bp_nv = 2;
-        G->bp_wh = (float)(0.5 * G->max_cols_per_voxel);
-        const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T;
-        const float hx = 0.5f * (float)(BP_T - 1) * g.T;
-        int first_shape = d->nz >= 128 ? 0 : 1;       // 64-voxel chunks only pay off on tall volumes
-        if (const char *env = std::getenv("LEAP_BP_SHAPE")) first_shape = std::atoi(env) % BP_NSHAPES;
-        for (int sh = first_shape; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
-            const int zc = BP_SHAPES[sh].zc;
-            const int chunks = (d->nz + zc - 1) / zc;
-            int need_w = 0, need_h = 0;
-            for (int a = 0; a < d->nviews; ++a)
-                for (int ty = 0; ty < tiles_y; ++ty)
-                    for (int tx = 0; tx < tiles_x; ++tx) {
-                        const float xc = (float)(g.x0d + ((double)(tx * BP_T) + 0.5 * (BP_T - 1)) * g.Td);
-                        const float yc = (float)(g.y0d + ((double)(ty * BP_T) + 0.5 * (BP_T - 1)) * g.Td);
-                        for (int ch = 0; ch < chunks; ch += (chunks > 1 ? chunks - 1 : 1)) {   // extremes: first and last chunk
-                            const float z0 = (float)(g.zlo0d + (double)(ch * zc) * g.Tzd), z1 = z0 + (float)zc * g.Tz;
-                            const SfWindow w = sf_bp_window(g, G->views[a], xc, yc, hx, z0, z1, G->bp_wh, G->bp_nc, G->bp_nv);
-                            need_w = w.need_w > need_w ? w.need_w : need_w;
-                            need_h = w.need_h > need_h ? w.need_h : need_h;
-                        }
-                    }
-            G->bp_need_w = need_w;
-            G->bp_need_h = need_h;
-            G->bp_shape = sh;
-            // one spare row and column: host and device floats may round apart
-            G->bp_tiled = need_w <= BP_SHAPES[sh].pw - 1 && need_h <= BP_SHAPES[sh].ph - 1;
-        }
-        // Cylinder: the tiled kernel takes the angle between a voxel's centre and its corners from a short series,
-        // good to 3e-9 rad below 0.08 rad.
-        if (d->type == LEAP_CONE_CURVED) {
-            const double rx = std::fabs(d->center_x) + 0.5 * d->nx * d->voxel_xy, ry = std::fabs(d->center_y) + 0.5 * d->ny * d->voxel_xy;
-            const double nearest = d->sod - std::sqrt(rx * rx + ry * ry);
-            if (!(0.7072 * d->voxel_xy <= 0.08 * nearest)) G->bp_tiled = false;
-        }
-    }
-
-    // Column-wise forward projection: static limits, then its scratch copy of the volume.
-    if (d->model == LEAP_MODEL_SF && d->type != LEAP_FAN && d->nrows >= 32 && std::isfinite(G->max_voxels_per_row) && G->max_voxels_per_row <= 3.0 &&
-        (double)d->nx * d->ny * (d->nz + 2.0 * FP_PAD) < 4294967296.0 && d->ny <= 65535) {
-        // tuning aids (read once per handle)
-        if (const char *env = std::getenv("LEAP_FP_CW")) {
-            const int v = std::atoi(env);
-            if (v == 1 || v == 2 || v == 4) G->fp_cw = v;
-        }
-        if (d->type == LEAP_CONE_CURVED && G->fp_cw == 1) G->fp_cw = 2;      // the cylinder has instances for 4 and 2 columns
-        // candidate slots per slab: widest range of voxel columns any bundle of cw detector columns can see
-        auto slots_needed = [&](int cw) {
-            int need = 0;
-            for (int a = 0; a < d->nviews; ++a)
-                for (int c = 0; c < d->ncols; c += cw) {
-                    const SfRayLines L = sf_ray_lines(g, G->views[a], c, cw);
-                    const int n_major = L.xmajor ? d->nx : d->ny;
-                    const float d0 = std::fabs(L.b0 - L.b1);
-                    const float d1 = std::fabs(fmaf(L.m0 - L.m1, (float)(n_major - 1), L.b0 - L.b1));
-                    const float dm = d0 > d1 ? d0 : d1;
-                    if (!(dm < 1e6f)) return 1 << 20;
-                    const int cnt = (int)std::floor(dm + 2.0f * L.spread + 1e-3f) + 2;
-                    need = cnt > need ? cnt : need;
-                }
-            return need;
-        };
-        G->fp_nk = (int)std::ceil(G->max_voxels_per_row - 1e-6) + 1;
-        if (G->fp_nk < 2) G->fp_nk = 2;
-        const int groups = (d->nrows + 63) / 64;
-        G->fp_rg = groups >= 8 ? 8 : (groups >= 4 ? 4 : (groups >= 2 ? 2 : 1));
-        if (const char *env = std::getenv("LEAP_FP_RG")) {
-            const int v = std::atoi(env);
-            if (v == 1 || v == 2 || v == 4 || v == 8) G->fp_rg = v;
-        }
-        // Short detectors (fewer than 256 rows) have too few bundles of four to fill the chip: two columns measured
-        // 5 to 12 % faster there, four columns 5 to 10 % faster from 256 rows on.
-        if (G->fp_cw == 4 && G->fp_rg < 4 && !std::getenv("LEAP_FP_CW")) G->fp_cw = 2;
-        // the cylinder's record phase is heavier: four columns only pay off from 512 rows on (64.4 against 70.5 ms at 512^3)
-        if (G->fp_cw == 4 && d->type == LEAP_CONE_CURVED && G->fp_rg < 8 && !std::getenv("LEAP_FP_CW")) G->fp_cw = 2;
-        int need = slots_needed(G->fp_cw);
-        while (need > 16 && G->fp_cw > 1) {
-            G->fp_cw /= 2;
-            need = slots_needed(G->fp_cw);
-        }
-        G->fp_need_q = need;
-        G->fp_nq = need <= 4 ? 4 : (need <= 8 ? 8 : 16);
-        G->fp_columns = need <= 16 && G->fp_nk <= 4 && (d->type != LEAP_CONE_CURVED || G->fp_cw >= 2);
-        if (const char *env = std::getenv("LEAP_FP_VB")) {
-            const int v = std::atoi(env);
-            if (v >= 1 && v <= 1024) G->fp_vb = v;
-        }
-        if (const char *env = std::getenv("LEAP_FP_TB")) {
-            const int v = std::atoi(env);
-            if (v >= 1 && v <= 1024) G->fp_tb = v;
-        }
-    }
-
-    if (d->model == LEAP_MODEL_SIDDON) select_siddon_fast_kernels(G);
-
-    // Testing aid: LEAP_FORCE_GENERAL=1 keeps every call on the general kernels.
-    if (const char *env = std::getenv("LEAP_FORCE_GENERAL"))
-        if (env[0] == '1') G->bp_tiled = G->fp_columns = G->sd_columns = false;
-
-    hipError_t e = hipGetDevice(&G->device);
-    if (e == hipSuccess) (void)leap_static_scratch_init(G->device);   // set-up for leap_project_static_scratch; it reports a failure itself
-    if (e == hipSuccess) e = hipMalloc((void **)&G->d_views, sizeof(SfView) * (size_t)d->nviews);
-    if (e == hipSuccess) e = hipMemcpy(G->d_views, G->views.data(), sizeof(SfView) * (size_t)d->nviews, hipMemcpyHostToDevice);
-    if (e == hipSuccess && (G->fp_columns || G->sd_columns)) {
-        G->nzp = d->nz + 2 * FP_PAD;
-        // one more column than the volume has: it stays zero and stands for cells outside the volume (Siddon kernel)
-        const size_t item_bytes = sizeof(float) * ((size_t)d->nx * d->ny + 1) * G->nzp;
-        // Small volumes (a batch of training volumes): up to 16 scratch copies within 1 GiB, so that the footprint
-        // kernel can take that many items of a batch in one launch.
-        {
-            const size_t fit = ((size_t)1 << 30) / item_bytes;
-            G->volz_items = (int)(fit < 1 ? 1 : (fit > 16 ? 16 : fit));
-        }
-        size_t bytes = item_bytes * (size_t)G->volz_items;
-        hipError_t es = hipMalloc((void **)&G->d_volz, bytes);
-        if (es != hipSuccess && G->volz_items > 1) {                      // one copy at least
-            (void)hipGetLastError();
-            G->volz_items = 1;
-            bytes = item_bytes;
-            es = hipMalloc((void **)&G->d_volz, bytes);
-        }
-        if (es == hipSuccess) es = hipMemset(G->d_volz, 0, bytes);       // the pads stay zero for the handle's life
-        if (es == hipSuccess) es = hipDeviceSynchronize();
-        if (es != hipSuccess) {                                           // no room for the copy: use the general kernel
-            if (G->d_volz) (void)hipFree(G->d_volz);
-            G->d_volz = nullptr;
-            G->fp_columns = G->sd_columns = false;
-            (void)hipGetLastError();
-        }
-    }
-    if (e == hipSuccess && !G->raycols.empty()) {
-        const size_t bytes = sizeof(SdRayCol) * G->raycols.size();
-        e = hipMalloc((void **)&G->d_raycols, bytes);
-        if (e == hipSuccess) e = hipMemcpy(G->d_raycols, G->raycols.data(), bytes, hipMemcpyHostToDevice);
-    }
-    if (e == hipSuccess && d->type == LEAP_CONE_CURVED && d->model == LEAP_MODEL_SF && G->bp_tiled) {
-        // For the tiled back projection: cosine and sine of every detector column's fan angle (ray amplitudes), then
-        // per (tile, view) the tile centre's fan angle and the tile's window bounds.
-        const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T;
-        const size_t head = 2 * sizeof(float) * (size_t)d->ncols;
-        const size_t bytes = head + sizeof(SfCurvedBounds) * (size_t)tiles_x * tiles_y * d->nviews;
-        std::vector<unsigned char> blob(bytes);
-        float *cs = reinterpret_cast<float *>(blob.data());
-        for (int c = 0; c < d->ncols; ++c) {
-            const double gam = ((double)c - g.col_offd) * d->pixel_u / d->sdd;
-            cs[2 * (size_t)c] = (float)std::cos(gam);
-            cs[2 * (size_t)c + 1] = (float)std::sin(gam);
-        }
-        SfCurvedBounds *tab = reinterpret_cast<SfCurvedBounds *>(blob.data() + head);
-        const float hx = 0.5f * (float)(BP_T - 1) * g.T;
-        for (int ty = 0; ty < tiles_y; ++ty)
-            for (int tx = 0; tx < tiles_x; ++tx) {
-                const double xcd = g.x0d + ((double)(tx * BP_T) + 0.5 * (BP_T - 1)) * g.Td;
-                const double ycd = g.y0d + ((double)(ty * BP_T) + 0.5 * (BP_T - 1)) * g.Td;
-                SfCurvedBounds *row = tab + ((size_t)ty * tiles_x + tx) * d->nviews;
-                for (int a = 0; a < d->nviews; ++a) {
-                    const SfView &v = G->views[a];
-                    row[a].gref = std::atan2(std::fma(ycd, v.cd, -xcd * v.sd), g.sodd - std::fma(xcd, v.cd, ycd * v.sd));
-                    sf_curved_tile_bounds(g, v, (float)xcd, (float)ycd, hx, row[a].xi_lo, row[a].xi_hi, row[a].ilo, row[a].ihi);
-                }
-            }
-        hipError_t et = hipMalloc((void **)&G->d_colcs, bytes);
-        if (et == hipSuccess) et = hipMemcpy(G->d_colcs, blob.data(), bytes, hipMemcpyHostToDevice);
-        if (et != hipSuccess) {                       // no room for the tables: the general kernel needs none
-            if (G->d_colcs) (void)hipFree(G->d_colcs);
-            G->d_colcs = nullptr;
-            G->bp_tiled = false;
-            (void)hipGetLastError();
-        }
-    }
-    if (e != hipSuccess) {
-        if (G->d_colcs) (void)hipFree(G->d_colcs);
-        if (G->d_views) (void)hipFree(G->d_views);
-        if (G->d_volz) (void)hipFree(G->d_volz);
-        if (G->d_raycols) (void)hipFree(G->d_raycols);
-        delete G;
-        return leap_hip_fail(e, "uploading the view table");
-    }
-    *out = G;
-    return LEAP_OK;
+    select_fast_kernels(G);
+    return finish_handle(G, out);
 }
 
-extern "C" void leap_geometry_destroy(leap_geometry *G)
-{
-    if (!G) return;
-    if (G->d_views) (void)hipFree(G->d_views);
-    if (G->d_volz) (void)hipFree(G->d_volz);
-    if (G->d_raycols) (void)hipFree(G->d_raycols);
-    if (G->d_poses) (void)hipFree(G->d_poses);
-    if (G->d_geoms) (void)hipFree(G->d_geoms);
-    if (G->d_colcs) (void)hipFree(G->d_colcs);
-    delete G;
-}
+extern "C" void leap_geometry_destroy(leap_geometry *G) { free_handle(G); }
 
 extern "C" int leap_geometry_describe(const leap_geometry *G, char *buf, int32_t cap)
 {
     if (!G || !buf || cap <= 0) return invalid("null handle or buffer");
-    if (G->g.type == SF_MODULAR) {
-        if (G->g.model == SF_MODEL_SIDDON)
-            std::snprintf(buf, (size_t)cap, "type=4 model=siddon A=%s(rg=%d) AT=%s(nc=%d,zc=%d,window=%dx%d) %s",
-                          G->sd_columns ? "columns" : "general", G->fp_rg, G->bp_tiled ? "tiled" : "general", G->bp_nc,
-                          BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h,
-                          G->geoms.empty() ? "(tilted modules: one thread per ray / per voxel)" : "(upright modules)");
-        else
-            std::snprintf(buf, (size_t)cap, "type=4 model=sf A=%s(nq=%d/%d,nk=%d,rg=%d) AT=%s(nc=%d,nv=%d,zc=%d,window=%dx%d) "
-                          "cols/voxel<=%.2f rows/voxel<=%.2f voxels/row<=%.2f", G->fp_columns ? "columns" : "general", G->fp_need_q,
-                          G->fp_nq, G->fp_nk, G->fp_rg, G->bp_tiled ? "tiled" : "general", G->bp_nc, G->bp_nv,
-                          BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h, G->max_cols_per_voxel, G->max_rows_per_voxel,
-                          G->max_voxels_per_row);
-        return LEAP_OK;
-    }
-    if (G->g.model == SF_MODEL_SIDDON) {
-        std::snprintf(buf, (size_t)cap, "type=%d model=siddon A=%s(rg=%d) AT=%s(nc=%d,zc=%d,window=%dx%d) axial-slope<=%.3f "
-                      "cols/voxel<=%.2f", G->g.type, G->sd_columns ? "columns" : "general", G->fp_rg,
-                      G->bp_tiled ? "tiled" : "general", G->bp_nc, BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h,
-                      G->sd_max_axial_slope, G->max_cols_per_voxel);
-        return LEAP_OK;
-    }
-    std::snprintf(buf, (size_t)cap,
-                  "type=%d A=%s(nq=%d/%d,nk=%d,rg=%d,w=%d,cw=%d,wv=%d) AT=%s(nc=%d,nv=%d,zc=%d,window=%dx%d) cols/voxel<=%.2f rows/voxel<=%.2f "
-                  "voxels/row<=%.2f slope<=%.2f",
-                  G->g.type, G->fp_columns ? "columns" : "general", G->fp_need_q, G->fp_nq, G->fp_nk, G->fp_rg, G->fp_waves, G->fp_cw, G->fp_wv, G->bp_tiled ? "tiled" : "general", G->bp_nc, G->bp_nv, BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h,
-                  G->max_cols_per_voxel, G->max_rows_per_voxel, G->max_voxels_per_row, G->max_minor_slope);
+    char fwd[160], back[96];
+    const bool siddon = G->g.model == SF_MODEL_SIDDON;
+    if (siddon && G->sd_columns)
+        std::snprintf(fwd, sizeof fwd, "columns(rg=%d,slab=%d)", G->fp_rg, G->slab_width);
+    else if (!siddon && G->fp_columns)
+        std::snprintf(fwd, sizeof fwd, "columns(nq=%d/%d,nkp=%d,rg=%d,cw=%d,slab=%d)", G->fp_need_q, G->fp_nq, G->fp_nkp,
+                      G->fp_rg, G->fp_cw, G->slab_width);
+    else
+        std::snprintf(fwd, sizeof fwd, "general");
+    if (G->bp_tiled && siddon)
+        std::snprintf(back, sizeof back, "tiled(nc=%d,zc=%d,window=%dx%d)", G->bp_nc, BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h);
+    else if (G->bp_tiled)
+        std::snprintf(back, sizeof back, "tiled(nc=%d,nv=%d,zc=%d,window=%dx%d)", G->bp_nc, G->bp_nv, BP_SHAPES[G->bp_shape].zc,
+                      G->bp_need_w, G->bp_need_h);
+    else
+        std::snprintf(back, sizeof back, "general");
+    const char *modules = G->g.type != SF_MODULAR ? "" : (G->geoms.empty() ? " (tilted modules: one thread per ray / per voxel)" : " (upright modules)");
+    std::snprintf(buf, (size_t)cap, "type=%d model=%s A=%s AT=%s scratch=%zu%s cols/voxel<=%.2f rows/voxel<=%.2f voxels/row<=%.2f%s%s",
+                  G->g.type, siddon ? "siddon" : "sf", fwd, back, G->scratch_bytes, modules, G->max_cols_per_voxel,
+                  G->max_rows_per_voxel, G->max_voxels_per_row, G->note.empty() ? "" : " note=", G->note.c_str());
     return LEAP_OK;
 }
 
@@ -783,18 +756,14 @@ static int check_call(const leap_geometry *G, const void *in, const void *out, i
 
 extern "C" int leap_project(const leap_geometry *G, const float *d_vol, float *d_sino, int32_t batch, void *hip_stream)
 {
-    int rc = check_call(G, d_vol, d_sino, batch);
+    const int rc = check_call(G, d_vol, d_sino, batch);
     if (rc != LEAP_OK) return rc;
-    const size_t nvol = (size_t)G->g.nx * G->g.ny * G->g.nz, nsino = (size_t)G->g.nviews * G->g.nrows * G->g.ncols;
-    (void)nvol; (void)nsino;
     return leap_launch_project_batch(G, d_vol, d_sino, batch, (hipStream_t)hip_stream);
 }
 
 extern "C" int leap_backproject(const leap_geometry *G, const float *d_sino, float *d_vol, int32_t batch, void *hip_stream)
 {
-    int rc = check_call(G, d_sino, d_vol, batch);
+    const int rc = check_call(G, d_sino, d_vol, batch);
     if (rc != LEAP_OK) return rc;
-    const size_t nvol = (size_t)G->g.nx * G->g.ny * G->g.nz, nsino = (size_t)G->g.nviews * G->g.nrows * G->g.ncols;
-    (void)nvol; (void)nsino;
     return leap_launch_backproject_batch(G, d_sino, d_vol, batch, (hipStream_t)hip_stream);
 }

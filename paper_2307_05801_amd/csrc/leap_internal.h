@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -28,11 +29,26 @@ struct leap_geometry {
     float bp_wh = 0.f;
     bool bp_tiled = false;
     int bp_need_w = 0, bp_need_h = 0;   // largest staged window any (view, tile, chunk) asks for
-    // column-wise forward projection: candidate slots per slab, voxels per detector row, row groups per wave
-    int fp_nq = 0, fp_nk = 0, fp_rg = 0, fp_need_q = 0, fp_waves = 4, fp_cw = 4, fp_wv = 1, fp_vb = 128, fp_tb = 1;
+    // column-wise forward projection (footprint and Siddon models): the volume goes through a z-fastest scratch copy
+    // slab by slab (sf_project_columns.h)
+    int fp_nq = 0, fp_need_q = 0;       // candidate slots per slab: instance / needed
+    int fp_nkp = 0;                     // voxels a pair of adjacent detector rows can overlap
+    int fp_rg = 0;                      // row groups per wave (footprints: groups of 128 rows; Siddon: of 64)
+    int fp_cw = 4, fp_vb = 128, fp_tb = 1;   // detector columns per wave; block order: views per run, tiles per chunk
     bool fp_columns = false;
-    float *d_volz = nullptr;            // z-fastest padded copy of one volume (scratch)
-    int nzp = 0;
+    float *d_volz = nullptr;            // the scratch: scratch_items copies of one slab
+    size_t scratch_bytes = 0;           // bytes allocated at d_volz
+    int slab_width = 0;                 // voxel layers across the marching axis per slab when one volume is projected
+    int dbg_slab = 0, dbg_items = 0;    // debugging overrides of the slab width and the items per launch (0: none)
+    int nzp = 0;                        // floats per padded z-column
+    std::vector<unsigned char> major;   // footprints: [view][bundle of fp_cw columns] 1 if the bundle advances fastest along x
+    unsigned char *d_major = nullptr;
+    std::string note;                   // what went differently from the plan at creation (shown by leap_geometry_describe)
+    // calls on one handle share its scratch: a call on another stream than the last first waits for that one's kernels
+    mutable std::mutex scratch_mutex;
+    mutable hipEvent_t scratch_event = nullptr;
+    mutable hipStream_t scratch_stream = nullptr;
+    mutable bool scratch_used = false;
     // Siddon model: per-(view, detector column) ray constants, host copy and device copy
     std::vector<SdRayCol> raycols;
     SdRayCol *d_raycols = nullptr;
@@ -44,7 +60,6 @@ struct leap_geometry {
     std::vector<SfGeom> geoms;
     SfGeom *d_geoms = nullptr;
     void *d_colcs = nullptr;            // cylinder, tiled back projection: (cos, sin) of every column's fan angle, then the (tile, view) table
-    int volz_items = 1;                 // scratch copies of the volume (items of a batch per forward launch)
     bool sd_columns = false;            // wave-per-column forward kernel (needs the scratch copy and slope <= 1)
 };
 
@@ -61,6 +76,9 @@ int leap_hip_fail(hipError_t e, const char *what);
 constexpr size_t LEAP_STATIC_SCRATCH_BYTES = (size_t)72 << 20;
 // Looks up the array's address on `device` (which must be current) once; called from leap_geometry_create.
 int leap_static_scratch_init(int device);
+
+// Slab width and batch items per launch that a scratch of `floats` floats affords (leap_geometry.cpp).
+bool leap_plan_scratch(const leap_geometry *G, size_t floats, int batch, int &width, int &items);
 
 // kernel launchers (leap_kernels.hip); one batch item per call
 int leap_launch_project(const leap_geometry *geom, const float *d_vol, float *d_sino, hipStream_t stream);

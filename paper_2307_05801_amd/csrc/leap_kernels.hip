@@ -139,42 +139,48 @@ static inline unsigned cdiv(unsigned a, unsigned b) { return (a + b - 1) / b; }
 
 constexpr int SD_WAVES = 4;   // adjacent detector columns per workgroup of the Siddon forward kernel
 
+// Where the column-wise forward kernels find their z-fastest copy of a slab: the handle's own scratch, or the library's
+// fixed array (leap_project_static_scratch).
+struct FwdScratch {
+    float *volz;
+    size_t item_floats;     // floats per copy (one per item of a batch in flight): (columns of a slab + 1) * nzp
+    int width;              // voxel layers across the marching axis per slab
+    int items;              // copies
+};
+
 template <int RG>
-static void launch_sd_columns(const leap_geometry *G, const float *volz, float *d_sino, hipStream_t stream, int items)
+static void launch_sd_columns(const leap_geometry *G, const FwdScratch &S, const SfSlab &slab, float *d_sino, hipStream_t stream, int items)
 {
     const SfGeom &g = G->g;
     const int col_tiles = (int)cdiv(g.ncols, SD_WAVES), bands = (int)cdiv(g.nrows, RG * 64);
     const int vb = G->fp_vb, tb = G->fp_tb;
     const int views_pad = (int)cdiv(g.nviews, vb) * vb;
     const int tiles_per_xcd_pad = (int)cdiv(cdiv(col_tiles, 8), tb) * tb;
-    const unsigned zero_col = (unsigned)g.nx * (unsigned)g.ny * (unsigned)G->nzp;
+    const unsigned zero_col = (unsigned)(S.item_floats - (size_t)G->nzp);      // the copy's last column stays zero
     dim3 grid((unsigned)(8 * tiles_per_xcd_pad * views_pad * bands), (unsigned)items, 1);
     if (g.type == SF_MODULAR)
         hipLaunchKernelGGL((sd_project_columns<RG, SD_WAVES, true>), grid, dim3(SD_WAVES * 64, 1, 1), 0, stream, g, G->d_raycols,
-                           volz, d_sino, G->nzp, zero_col, col_tiles, bands, vb, tb, views_pad, tiles_per_xcd_pad,
-                           (const SfGeom *)G->d_geoms);
+                           S.volz, d_sino, G->nzp, S.item_floats, zero_col, col_tiles, bands, vb, tb, views_pad, tiles_per_xcd_pad,
+                           slab, (const SfGeom *)G->d_geoms);
     else
         hipLaunchKernelGGL((sd_project_columns<RG, SD_WAVES, false>), grid, dim3(SD_WAVES * 64, 1, 1), 0, stream, g, G->d_raycols,
-                           volz, d_sino, G->nzp, zero_col, col_tiles, bands, vb, tb, views_pad, tiles_per_xcd_pad,
-                           (const SfGeom *)nullptr);
+                           S.volz, d_sino, G->nzp, S.item_floats, zero_col, col_tiles, bands, vb, tb, views_pad, tiles_per_xcd_pad,
+                           slab, (const SfGeom *)nullptr);
 }
 
-// The column-wise Siddon kernel on `items` consecutive volumes of a batch, each in its own z-fastest copy inside `volz`
-// (whose pads and spare column are zero).
-static int launch_sd_items(const leap_geometry *G, const float *d_vol, float *d_sino, int items, hipStream_t stream, float *volz)
+static bool launch_sd_slab(const leap_geometry *G, const FwdScratch &S, const SfSlab &slab, float *d_sino, hipStream_t stream, int items)
 {
-    const SfGeom &g = G->g;
-    dim3 tgrid(cdiv(g.nx, 32), cdiv(g.nz, 32), (unsigned)(g.ny * items));
-    hipLaunchKernelGGL(sf_volume_to_columns, tgrid, dim3(32, 8, 1), 0, stream, d_vol, volz, g.nx, g.ny, g.nz, G->nzp);
     switch (G->fp_rg) {
-    case 1: launch_sd_columns<1>(G, volz, d_sino, stream, items); break;
-    case 2: launch_sd_columns<2>(G, volz, d_sino, stream, items); break;
-    case 4: launch_sd_columns<4>(G, volz, d_sino, stream, items); break;
-    default: launch_sd_columns<8>(G, volz, d_sino, stream, items); break;
+    case 1: launch_sd_columns<1>(G, S, slab, d_sino, stream, items); return true;
+    case 2: launch_sd_columns<2>(G, S, slab, d_sino, stream, items); return true;
+    case 4: launch_sd_columns<4>(G, S, slab, d_sino, stream, items); return true;
+    case 8: launch_sd_columns<8>(G, S, slab, d_sino, stream, items); return true;
+    default: return false;
     }
-    LEAP_HIP_CHECK(hipGetLastError());
-    return LEAP_OK;
 }
+
+static int run_forward_columns(const leap_geometry *G, const FwdScratch &S, const float *d_vol, float *d_sino, int batch,
+                               hipStream_t stream);
 
 static int launch_sd_project(const leap_geometry *G, const float *d_vol, float *d_sino, hipStream_t stream)
 {
@@ -185,7 +191,7 @@ static int launch_sd_project(const leap_geometry *G, const float *d_vol, float *
         LEAP_HIP_CHECK(hipGetLastError());
         return LEAP_OK;
     }
-    if (G->sd_columns) return launch_sd_items(G, d_vol, d_sino, 1, stream, G->d_volz);
+    if (G->sd_columns) return leap_launch_project_batch(G, d_vol, d_sino, 1, stream);
     dim3 grid(cdiv(g.ncols, 64), cdiv(g.nrows, 4), g.nviews);
     if (grid.y > 65535u) {
         leap_set_error("detector has too many rows for one launch");
@@ -261,85 +267,92 @@ static int launch_sd_backproject(const leap_geometry *G, const float *d_sino, fl
     return LEAP_OK;
 }
 
-template <int NQ, int NK, int RG, int CW, int GT>
-static void launch_fp_columns(const leap_geometry *G, const float *volz, float *d_sino, hipStream_t stream, int items)
+template <int NKP, int RG, int CW, int GT>
+static void launch_fp_columns(const leap_geometry *G, const FwdScratch &S, const SfSlab &slab, float *d_sino, hipStream_t stream, int items)
 {
-    constexpr int W = 4;          // waves per workgroup (8 and 16 measured slower)
     const SfGeom &g = G->g;
-    const int col_tiles = (int)cdiv(g.ncols, W * CW), bands = (int)cdiv(g.nrows, RG * 64);
+    const int col_tiles = (int)cdiv(g.ncols, FP_WAVES * CW), bands = (int)cdiv(g.nrows, RG * 128);
     // XCD-aware block order (see the kernel): pad views to blocks of vb and each XCD's tiles to chunks of tb
     const int vb = G->fp_vb, tb = G->fp_tb;
     const int vgroups_pad = (int)cdiv(g.nviews, vb) * vb;
     const int tiles_per_xcd_pad = (int)cdiv(cdiv(col_tiles, 8), tb) * tb;
+    int nq_log2 = 2;
+    while ((1 << nq_log2) < G->fp_nq) ++nq_log2;
     dim3 grid((unsigned)(8 * tiles_per_xcd_pad * vgroups_pad * bands), (unsigned)items, 1);
-    hipLaunchKernelGGL((sf_project_columns<NQ, NK, RG, W, CW, 1, GT>), grid, dim3(W * 64, 1, 1), 0, stream, g, G->d_views,
-                       volz, d_sino, G->nzp, col_tiles, bands, vb, tb, vgroups_pad, tiles_per_xcd_pad,
-                       (const SfGeom *)G->d_geoms);
+    hipLaunchKernelGGL((sf_project_columns<NKP, RG, CW, GT>), grid, dim3(FP_WAVES * 64, 1, 1), 0, stream, g, G->d_views, S.volz,
+                       d_sino, G->d_major, G->nzp, S.item_floats, nq_log2, col_tiles, bands, vb, tb, vgroups_pad, tiles_per_xcd_pad,
+                       slab, (const SfGeom *)G->d_geoms);
 }
 
-template <int NQ, int NK, int RG>
-static bool launch_fp_w(const leap_geometry *G, const float *volz, float *d_sino, hipStream_t stream, int items)
+template <int NKP, int RG>
+static bool launch_fp_w(const leap_geometry *G, const FwdScratch &S, const SfSlab &slab, float *d_sino, hipStream_t stream, int items)
 {
-    if (G->g.type == SF_CONE_CURVED) {     // bundles of 4 or 2 columns
-        if (G->fp_cw == 4) launch_fp_columns<NQ, NK, RG, 4, 1>(G, volz, d_sino, stream, items);
-        else if (G->fp_cw == 2) launch_fp_columns<NQ, NK, RG, 2, 1>(G, volz, d_sino, stream, items);
-        else return false;
-        return true;
-    }
-    if (G->g.type == SF_MODULAR) {
-        if (G->fp_cw == 4) launch_fp_columns<NQ, NK, RG, 4, 2>(G, volz, d_sino, stream, items);
-        else if (G->fp_cw == 2) launch_fp_columns<NQ, NK, RG, 2, 2>(G, volz, d_sino, stream, items);
-        else return false;
-        return true;
-    }
-    switch (G->fp_cw) {
-    case 1: launch_fp_columns<NQ, NK, RG, 1, 0>(G, volz, d_sino, stream, items); return true;
-    case 2: launch_fp_columns<NQ, NK, RG, 2, 0>(G, volz, d_sino, stream, items); return true;
-    case 4: launch_fp_columns<NQ, NK, RG, 4, 0>(G, volz, d_sino, stream, items); return true;
+    const int gt = G->g.type == SF_CONE_CURVED ? 1 : (G->g.type == SF_MODULAR ? 2 : 0);
+    switch (gt * 10 + G->fp_cw) {
+    case 1: launch_fp_columns<NKP, RG, 1, 0>(G, S, slab, d_sino, stream, items); return true;
+    case 2: launch_fp_columns<NKP, RG, 2, 0>(G, S, slab, d_sino, stream, items); return true;
+    case 4: launch_fp_columns<NKP, RG, 4, 0>(G, S, slab, d_sino, stream, items); return true;
+    case 12: launch_fp_columns<NKP, RG, 2, 1>(G, S, slab, d_sino, stream, items); return true;
+    case 14: launch_fp_columns<NKP, RG, 4, 1>(G, S, slab, d_sino, stream, items); return true;
+    case 22: launch_fp_columns<NKP, RG, 2, 2>(G, S, slab, d_sino, stream, items); return true;
+    case 24: launch_fp_columns<NKP, RG, 4, 2>(G, S, slab, d_sino, stream, items); return true;
     default: return false;
     }
 }
 
-template <int NQ, int NK>
-static bool launch_fp_rg(const leap_geometry *G, const float *volz, float *d_sino, hipStream_t stream, int items)
+template <int NKP>
+static bool launch_fp_rg(const leap_geometry *G, const FwdScratch &S, const SfSlab &slab, float *d_sino, hipStream_t stream, int items)
 {
     switch (G->fp_rg) {
-    case 1: return launch_fp_w<NQ, NK, 1>(G, volz, d_sino, stream, items);
-    case 2: return launch_fp_w<NQ, NK, 2>(G, volz, d_sino, stream, items);
-    case 4: return launch_fp_w<NQ, NK, 4>(G, volz, d_sino, stream, items);
-    case 8: return launch_fp_w<NQ, NK, 8>(G, volz, d_sino, stream, items);
+    case 1: return launch_fp_w<NKP, 1>(G, S, slab, d_sino, stream, items);
+    case 2: return launch_fp_w<NKP, 2>(G, S, slab, d_sino, stream, items);
+    case 4: return launch_fp_w<NKP, 4>(G, S, slab, d_sino, stream, items);
     default: return false;
     }
 }
 
-template <int NQ>
-static bool launch_fp_nk(const leap_geometry *G, const float *volz, float *d_sino, hipStream_t stream, int items)
+static bool launch_fp_slab(const leap_geometry *G, const FwdScratch &S, const SfSlab &slab, float *d_sino, hipStream_t stream, int items)
 {
-    switch (G->fp_nk) {
-    case 2: return launch_fp_rg<NQ, 2>(G, volz, d_sino, stream, items);
-    case 3: return launch_fp_rg<NQ, 3>(G, volz, d_sino, stream, items);
-    case 4: return launch_fp_rg<NQ, 4>(G, volz, d_sino, stream, items);
+    switch (G->fp_nkp) {
+    case 2: return launch_fp_rg<2>(G, S, slab, d_sino, stream, items);
+    case 3: return launch_fp_rg<3>(G, S, slab, d_sino, stream, items);
+    case 4: return launch_fp_rg<4>(G, S, slab, d_sino, stream, items);
+    case 5: return launch_fp_rg<5>(G, S, slab, d_sino, stream, items);
+    case 6: return launch_fp_rg<6>(G, S, slab, d_sino, stream, items);
+    case 7: return launch_fp_rg<7>(G, S, slab, d_sino, stream, items);
     default: return false;
     }
 }
 
-// The column-wise footprint kernel on `items` consecutive volumes of a batch, each in its own z-fastest copy inside
-// `volz` (whose pads are zero).
-static int launch_fp_items(const leap_geometry *G, const float *d_vol, float *d_sino, int items, hipStream_t stream, float *volz)
+// The column-wise forward projection (footprint or Siddon weights) of a batch: up to S.items volumes at a time, each
+// walked slab by slab -- first the slabs across x for the rays that advance fastest along x, then the slabs across y
+// for the others.  Per slab: copy it z-fastest into the scratch, then every ray adds the slab's share to its sample.
+static int run_forward_columns(const leap_geometry *G, const FwdScratch &S, const float *d_vol, float *d_sino, int batch,
+                               hipStream_t stream)
 {
     const SfGeom &g = G->g;
-    dim3 tgrid(cdiv(g.nx, 32), cdiv(g.nz, 32), (unsigned)(g.ny * items));
-    hipLaunchKernelGGL(sf_volume_to_columns, tgrid, dim3(32, 8, 1), 0, stream, d_vol, volz, g.nx, g.ny, g.nz, G->nzp);
-    bool ok = false;
-    switch (G->fp_nq) {
-    case 4: ok = launch_fp_nk<4>(G, volz, d_sino, stream, items); break;
-    case 8: ok = launch_fp_nk<8>(G, volz, d_sino, stream, items); break;
-    case 16: ok = launch_fp_nk<16>(G, volz, d_sino, stream, items); break;
-    default: break;
-    }
-    if (!ok) {
-        leap_set_error("internal: no column-wise forward instance for this footprint");
-        return LEAP_UNSUPPORTED;
+    const size_t nvol = (size_t)g.nx * g.ny * g.nz, nsino = (size_t)g.nviews * g.nrows * g.ncols;
+    const bool siddon = g.model == SF_MODEL_SIDDON;
+    for (int b = 0; b < batch; b += S.items) {
+        const int items = batch - b < S.items ? batch - b : S.items;
+        const float *vol = d_vol + (size_t)b * nvol;
+        float *sino = d_sino + (size_t)b * nsino;
+        for (int xmajor = 1; xmajor >= 0; --xmajor) {
+            const int n_major = xmajor ? g.nx : g.ny;
+            for (int n0 = 0; n0 < n_major; n0 += S.width) {
+                const int n1 = n0 + S.width < n_major ? n0 + S.width : n_major;
+                const SfSlab slab = {n0, n1, xmajor, n0 == 0 ? 1 : 0, S.width};
+                const int i0 = xmajor ? n0 : 0, ni = xmajor ? S.width : g.nx, nj = xmajor ? g.ny : n1 - n0;
+                dim3 tgrid(cdiv(xmajor ? n1 - n0 : g.nx, 32), cdiv(g.nz, 32), (unsigned)(nj * items));
+                hipLaunchKernelGGL(sf_volume_to_columns, tgrid, dim3(32, 8, 1), 0, stream, vol, S.volz, g.nx, g.ny, g.nz, G->nzp, i0,
+                                   xmajor ? 0 : n0, ni, nj, S.item_floats);
+                const bool ok = siddon ? launch_sd_slab(G, S, slab, sino, stream, items) : launch_fp_slab(G, S, slab, sino, stream, items);
+                if (!ok) {
+                    leap_set_error("internal: no column-wise forward instance for this geometry");
+                    return LEAP_UNSUPPORTED;
+                }
+            }
+        }
     }
     LEAP_HIP_CHECK(hipGetLastError());
     return LEAP_OK;
@@ -352,16 +365,22 @@ int leap_launch_project_batch(const leap_geometry *G, const float *d_vol, float 
     const bool footprint_fast = g.model != SF_MODEL_SIDDON && G->fp_columns;
     const bool siddon_fast = g.model == SF_MODEL_SIDDON && G->sd_columns;
     if (footprint_fast || siddon_fast) {
-        // small volumes: several items per launch fill the chip (a batch of training volumes), each in its own scratch copy
-        int per = G->volz_items < 1 ? 1 : G->volz_items;
-        if (per > 65535 / g.ny) per = 65535 / g.ny;
-        if (per < 1) per = 1;
-        for (int b = 0; b < batch; b += per) {
-            const int items = batch - b < per ? batch - b : per;
-            const int rc = footprint_fast ? launch_fp_items(G, d_vol + b * nvol, d_sino + b * nsino, items, stream, G->d_volz)
-                                          : launch_sd_items(G, d_vol + b * nvol, d_sino + b * nsino, items, stream, G->d_volz);
-            if (rc != LEAP_OK) return rc;
+        // Calls on one handle share its scratch.  They are ordered on the device: a call that arrives on another stream
+        // than the last one first waits for that one's kernels.
+        std::lock_guard<std::mutex> lock(G->scratch_mutex);
+        if (G->scratch_used && G->scratch_stream != stream) LEAP_HIP_CHECK(hipStreamWaitEvent(stream, G->scratch_event, 0));
+        FwdScratch S;
+        S.volz = G->d_volz;
+        if (!leap_plan_scratch(G, G->scratch_bytes / sizeof(float), batch, S.width, S.items)) {
+            leap_set_error("internal: the handle's scratch holds no slab");
+            return LEAP_UNSUPPORTED;
         }
+        S.item_floats = ((size_t)S.width * (size_t)(g.nx > g.ny ? g.nx : g.ny) + 1) * (size_t)G->nzp;
+        const int rc = run_forward_columns(G, S, d_vol, d_sino, batch, stream);
+        if (rc != LEAP_OK) return rc;
+        LEAP_HIP_CHECK(hipEventRecord(G->scratch_event, stream));
+        G->scratch_stream = stream;
+        G->scratch_used = true;
         return LEAP_OK;
     }
     for (int b = 0; b < batch; ++b) {
@@ -375,7 +394,7 @@ int leap_launch_project(const leap_geometry *G, const float *d_vol, float *d_sin
 {
     const SfGeom &g = G->g;
     if (g.model == SF_MODEL_SIDDON) return launch_sd_project(G, d_vol, d_sino, stream);
-    if (G->fp_columns) return launch_fp_items(G, d_vol, d_sino, 1, stream, G->d_volz);
+    if (G->fp_columns) return leap_launch_project_batch(G, d_vol, d_sino, 1, stream);
     dim3 block(64, 4, 1);
     dim3 grid(cdiv(g.ncols, 64), cdiv(cdiv(g.nrows, GEN_RC), 4), g.nviews);
     if (grid.y > 65535u) {
@@ -524,17 +543,6 @@ int leap_static_scratch_init(int device)
     return LEAP_OK;
 }
 
-// Zeroes what the column-wise kernels expect to be zero around the voxels that sf_volume_to_columns writes: FP_PAD
-// floats before and after each of the ncolumns z-columns and the whole spare column that follows them (a fill kernel,
-// not a memset, so that a caller may capture the call in a graph).
-__global__ __launch_bounds__(256) void sf_clear_column_pads(float *__restrict__ volz, unsigned ncolumns, int nz, int nzp)
-{
-    const unsigned t = blockIdx.x * 256u + threadIdx.x;
-    const unsigned col = t / (2u * FP_PAD), e = t % (2u * FP_PAD);
-    if (col < ncolumns) volz[(size_t)col * nzp + (e < FP_PAD ? e : nz + e)] = 0.0f;
-    if (t < (unsigned)nzp) volz[(size_t)ncolumns * nzp + t] = 0.0f;
-}
-
 extern "C" int leap_project_static_scratch(const leap_geometry *G, const float *d_vol, float *d_sino, int32_t batch, void *hip_stream)
 {
     if (!G || !d_vol || !d_sino) {
@@ -562,11 +570,12 @@ extern "C" int leap_project_static_scratch(const leap_geometry *G, const float *
         }
         return LEAP_OK;
     }
-    const size_t item_bytes = sizeof(float) * ((size_t)g.nx * g.ny + 1) * (size_t)G->nzp;
-    if (item_bytes > LEAP_STATIC_SCRATCH_BYTES) {
+    const int n_side = g.nx > g.ny ? g.nx : g.ny;
+    FwdScratch S;
+    if (!leap_plan_scratch(G, LEAP_STATIC_SCRATCH_BYTES / sizeof(float), batch, S.width, S.items)) {
         char msg[200];
-        std::snprintf(msg, sizeof msg, "volume too large for the static scratch: its z-fastest copy needs %zu bytes, the array holds %zu",
-                      item_bytes, (size_t)LEAP_STATIC_SCRATCH_BYTES);
+        std::snprintf(msg, sizeof msg, "volume too large for the static scratch: four voxel layers of its z-fastest copy need %.0f bytes, "
+                      "the array holds %zu", 4.0 * G->nzp * (4.0 * n_side + 1.0), (size_t)LEAP_STATIC_SCRATCH_BYTES);
         leap_set_error(msg);
         return LEAP_UNSUPPORTED;
     }
@@ -575,24 +584,15 @@ extern "C" int leap_project_static_scratch(const leap_geometry *G, const float *
         leap_set_error("static scratch address unknown for the handle's device");
         return LEAP_HIP_ERROR;
     }
-    int per = (int)(LEAP_STATIC_SCRATCH_BYTES / item_bytes);
-    if (per > 16) per = 16;
-    if (per > 65535 / g.ny) per = 65535 / g.ny;
-    if (per < 1) per = 1;
-    if (per > batch) per = batch;
-    const size_t nvol = (size_t)g.nx * g.ny * g.nz, nsino = (size_t)g.nviews * g.nrows * g.ncols;
+    S.volz = volz;
+    S.item_floats = ((size_t)S.width * n_side + 1) * (size_t)G->nzp;
+    const int width = S.width, per = S.items;
     // the array keeps what the last call (of any handle) left in it: restore the zeros around this geometry's columns
-    const unsigned ncolumns = (unsigned)g.nx * (unsigned)g.ny;
+    const unsigned ncolumns = (unsigned)width * (unsigned)n_side;
     const unsigned nthreads = ncolumns * 2u * FP_PAD > (unsigned)G->nzp ? ncolumns * 2u * FP_PAD : (unsigned)G->nzp;
     for (int it = 0; it < per; ++it)
-        hipLaunchKernelGGL(sf_clear_column_pads, dim3(cdiv(nthreads, 256)), dim3(256), 0, stream,
-                           volz + (size_t)it * ((size_t)ncolumns + 1) * G->nzp, ncolumns, g.nz, G->nzp);
+        hipLaunchKernelGGL(sf_clear_column_pads, dim3(cdiv(nthreads, 256)), dim3(256), 0, stream, volz + (size_t)it * S.item_floats,
+                           ncolumns, g.nz, G->nzp);
     LEAP_HIP_CHECK(hipGetLastError());
-    for (int b = 0; b < batch; b += per) {
-        const int items = batch - b < per ? batch - b : per;
-        const int rc = footprint_fast ? launch_fp_items(G, d_vol + b * nvol, d_sino + b * nsino, items, stream, volz)
-                                      : launch_sd_items(G, d_vol + b * nvol, d_sino + b * nsino, items, stream, volz);
-        if (rc != LEAP_OK) return rc;
-    }
-    return LEAP_OK;
+    return run_forward_columns(G, S, d_vol, d_sino, batch, stream);
 }

@@ -1,7 +1,9 @@
 // Forward projection (A) of the Siddon model: ray-driven gather, one wavefront per detector column.
 //
-// Uses the z-fastest padded copy of the volume that the footprint kernel uses (sf_project_columns.h), plus one
-// all-zero column at its end that stands in for every in-plane cell outside the volume.
+// Uses the z-fastest padded scratch copy of one slab of the volume, as the footprint kernel does (sf_project_columns.h:
+// slabs across x serve the rays that advance fastest along x, slabs across y the others; every ray adds the slab's share
+// to its sample, the first slab of its kind overwrites), plus one all-zero column at the copy's end that stands in for
+// every in-plane cell outside the volume.
 //
 // Work split.  One 64-lane wavefront owns one detector column of one view and a band of RG * 64 detector rows: lane l
 // owns rows band0 + 64 g + l, g < RG.  All those rays share their in-plane line, so which voxel columns they cross in
@@ -22,12 +24,13 @@
 template <int RG, int SD_WAVES, bool MOD>
 __global__ __launch_bounds__(SD_WAVES * 64) void sd_project_columns(SfGeom gk, const SdRayCol *__restrict__ rays,
                                                                     const float *__restrict__ volz, float *__restrict__ sino,
-                                                                    int nzp, unsigned zero_col, int col_tiles, int bands,
-                                                                    int vb, int tb, int views_pad, int tiles_per_xcd_pad,
+                                                                    int nzp, size_t item_stride, unsigned zero_col, int col_tiles,
+                                                                    int bands, int vb, int tb, int views_pad,
+                                                                    int tiles_per_xcd_pad, SfSlab slab,
                                                                     const SfGeom *__restrict__ geoms)
 {
     // blockIdx.y: item of a batch (its scratch copy and its sinogram)
-    volz += (size_t)blockIdx.y * ((size_t)gk.nx * gk.ny + 1) * nzp;
+    volz += (size_t)blockIdx.y * item_stride;
     sino += (size_t)blockIdx.y * gk.nviews * gk.nrows * gk.ncols;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -52,7 +55,8 @@ __global__ __launch_bounds__(SD_WAVES * 64) void sd_project_columns(SfGeom gk, c
     const int band0 = band * (RG * 64);
 
     const SdRayCol R = rays[(size_t)a * g.ncols + c];
-    const int n_major = R.xmajor ? g.nx : g.ny;
+    if (R.xmajor != slab.xmajor) return;             // this column's rays read the other kind of slab
+    const int n_major = slab.n1;
     const int n_minor = R.xmajor ? g.ny : g.nx;
     const int kmax = nzp - 2;
 
@@ -71,15 +75,15 @@ __global__ __launch_bounds__(SD_WAVES * 64) void sd_project_columns(SfGeom gk, c
         acc[gq] = 0.0f;
     }
 
-    for (int nb = 0; nb < n_major; nb += 64) {
+    for (int nb = slab.n0; nb < n_major; nb += 64) {
         // ---- lane-parallel: the in-plane part of slab nb + lane
         const int n = nb + lane;
         const SdSplit s = sd_slab_split(R, n);
         const bool in_n = n < n_major;
         const bool a_ok = in_n && s.qa >= 0 && s.qa < n_minor;
         const bool b_ok = in_n && s.qa != s.qb && s.qb >= 0 && s.qb < n_minor;
-        const unsigned base_a = a_ok ? (unsigned)(R.xmajor ? s.qa * g.nx + n : n * g.nx + s.qa) * (unsigned)nzp : zero_col;
-        const unsigned base_b = b_ok ? (unsigned)(R.xmajor ? s.qb * g.nx + n : n * g.nx + s.qb) * (unsigned)nzp : zero_col;
+        const unsigned base_a = a_ok ? sf_slab_column(slab, g.nx, R.xmajor ? n : s.qa, R.xmajor ? s.qa : n) * (unsigned)nzp : zero_col;
+        const unsigned base_b = b_ok ? sf_slab_column(slab, g.nx, R.xmajor ? n : s.qb, R.xmajor ? s.qb : n) * (unsigned)nzp : zero_col;
         const double h = fma((double)n, R.dh, R.h0);
         const int h_lo = __double2loint(h), h_hi = __double2hiint(h);
         const float f = s.f, omf = 1.0f - s.f;
@@ -133,7 +137,10 @@ __global__ __launch_bounds__(SD_WAVES * 64) void sd_project_columns(SfGeom gk, c
 #pragma unroll
     for (int gq = 0; gq < RG; ++gq) {
         const int r = band0 + 64 * gq + lane;
-        if (r < g.nrows) ya[(size_t)r * g.ncols] = sd_ray_length(R, vr[gq]) * acc[gq];
+        if (r < g.nrows) {
+            const float part = sd_ray_length(R, vr[gq]) * acc[gq];
+            ya[(size_t)r * g.ncols] = slab.first ? part : ya[(size_t)r * g.ncols] + part;
+        }
     }
 }
 

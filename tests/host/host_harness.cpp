@@ -27,6 +27,8 @@ hipError_t hipMemset(void *p, int v, size_t n) { std::memset(p, v, n); return hi
 hipError_t hipFree(void *p) { std::free(p); return hipSuccess; }
 hipError_t hipDeviceSynchronize() { return hipSuccess; }
 hipError_t hipGetLastError() { return hipSuccess; }
+hipError_t hipEventCreateWithFlags(hipEvent_t *e, unsigned) { *e = nullptr; return hipSuccess; }
+hipError_t hipEventDestroy(hipEvent_t) { return hipSuccess; }
 const char *hipGetErrorString(hipError_t) { return "stub"; }
 }
 
@@ -207,27 +209,49 @@ extern "C" int host_curved_column_deviation(const leap_geometry *G, double *out)
     return 0;
 }
 
-// ---- column-wise forward projection: its arithmetic, serially ---------------------------------------------------
-// Returns -1 when the handle does not use the column kernel, else the number of (view, bundle, slab) cases in which the
-// candidate slots do not cover the candidate range (must be 0).
-extern "C" long host_project_columns(const leap_geometry *G, const float *vol, float *sino)
+// ---- column-wise forward projection: the kernel's own per-lane functions, stepped serially ------------------------------
+// One (view, bundle of CW detector columns) at a time, the way a wavefront of sf_project_columns works through it: the
+// host's marching axis for the bundle, candidate slots per slab, sf_candidate_record for every candidate, then for every
+// pair of adjacent rows sf_place_row, a window of P voxels read from the z-fastest copy (zero outside the padded
+// column, as the kernel's buffer loads return) and sf_pair_sums.  The whole volume stands in for one slab.
+template <int CW, int P>
+static void host_pairs_of_candidate(const SfGeom &g, const float *col, int nzp, double mu, double zkp, const float (&fa)[CW],
+                                    std::vector<float> &acc)
 {
-    const SfGeom &g = G->g;
-    if (!G->fp_columns) return -1;
-    const int NQ = G->fp_nq, NK = G->fp_nk, CW = G->fp_cw, nzp = g.nz + 2 * FP_PAD, kmax = g.nz + FP_PAD;
-    std::vector<float> volz((size_t)g.nx * g.ny * nzp, 0.f);
-    for (int k = 0; k < g.nz; ++k)
-        for (int j = 0; j < g.ny; ++j)
-            for (int i = 0; i < g.nx; ++i) volz[((size_t)j * g.nx + i) * nzp + FP_PAD + k] = vol[((size_t)k * g.ny + j) * g.nx + i];
+    const float step = (float)mu;
+    for (int r = 0; r < g.nrows; r += 2) {
+        float fr1;
+        unsigned hi;
+        sf_place_row((double)r - g.row_offd, mu, zkp, fr1, hi);
+        const int kf = (int)(hi - FP_KAP_HI);
+        float x[P];
+        for (int t = 0; t < P; ++t) x[t] = (kf + t >= 0 && kf + t < nzp) ? col[kf + t] : 0.0f;
+        float sa, sb;
+        sf_pair_sums<P>(x, fr1, step, sa, sb);
+        for (int cw = 0; cw < CW; ++cw) {
+            acc[(size_t)r * CW + cw] = fmaf(fa[cw], sa, acc[(size_t)r * CW + cw]);
+            if (r + 1 < g.nrows) acc[(size_t)(r + 1) * CW + cw] = fmaf(fa[cw], sb, acc[(size_t)(r + 1) * CW + cw]);
+        }
+    }
+}
+
+template <int CW>
+static long host_project_bundles(const leap_geometry *G, const std::vector<float> (&volz)[2], int nzp, float *sino)
+{
+    const int NQ = G->fp_nq, NKP = G->fp_nkp;
+    const int nbundles = (G->g.ncols + CW - 1) / CW;
     long uncovered = 0;
 #pragma omp parallel for collapse(2) reduction(+ : uncovered)
     for (int a = 0; a < G->g.nviews; ++a)
-        for (int c0 = 0; c0 < G->g.ncols; c0 += CW) {
+        for (int b = 0; b < nbundles; ++b) {
+            const int c0 = b * CW;
             const SfGeom &g = G->geoms.empty() ? G->g : G->geoms[a];      // modular: the view's own parameter block
-            const double zkp = -g.zlo0d * g.iTzd + (double)FP_PAD, mu_scale = g.ikvd * g.iTzd;
+            const double zkp = sf_kappa_const(g);
             const SfView v = G->views[a];
-            const SfRayLines L = sf_ray_lines(g, v, c0, CW);
-            const int n_major = L.xmajor ? g.nx : g.ny, n_minor = L.xmajor ? g.ny : g.nx;
+            const int xmajor = G->major[(size_t)a * nbundles + b];
+            const SfRayLines L = sf_ray_lines(g, v, c0, CW, xmajor);
+            const int n_major = xmajor ? g.nx : g.ny, n_minor = xmajor ? g.ny : g.nx;
+            const SfSlab slab = {0, n_major, xmajor, 1, n_major};
             std::vector<float> acc((size_t)g.nrows * CW, 0.f);
             for (int n = 0; n < n_major; ++n) {
                 int qf, ql;
@@ -236,35 +260,19 @@ extern "C" long host_project_columns(const leap_geometry *G, const float *vol, f
                 for (int s = 0; s < NQ; ++s) {
                     const int q = qf + s;
                     if (q < 0 || q >= n_minor || q > ql) continue;
-                    const int i = L.xmajor ? n : q, j = L.xmajor ? q : n;
-                    const SfColumn f = sf_column(g, v, i, j);
-                    const float rows_per_voxel = (float)(g.kvd * f.inv * g.Tzd);
-                    float fa[8];
-                    bool any = false;
-                    float e = sf_pixel_edge(f, c0), g0 = sf_trap_integral(f, e);
-                    for (int cw = 0; cw < CW; ++cw) {
-                        e += 1.0f;
-                        const float g1 = sf_trap_integral(f, e);
-                        const float fu = (c0 + cw < g.ncols) ? fmaxf(g1 - g0, 0.f) : 0.f;
-                        fa[cw] = fu * rows_per_voxel;
-                        any = any || fu > 0.f;
-                        g0 = g1;
-                    }
-                    if (!any) continue;
-                    const double mu = f.den * mu_scale;
-                    const float step = (float)mu;
-                    const float *col = &volz[((size_t)j * g.nx + i) * nzp];
-                    for (int r = 0; r < g.nrows; ++r) {
-                        const double kap = fma((double)r - g.row_offd, mu, zkp);
-                        const float fr = (float)(kap - std::floor(kap));
-                        const int kf = std::max(0, std::min((int)kap, kmax));
-                        float rem = step, sum = 0.f, w = fminf(1.f - fr, step);
-                        for (int t = 0; t < NK; ++t) {
-                            sum = fmaf(w, col[kf + t], sum);
-                            rem -= w;
-                            w = (t == NK - 2) ? rem : fminf(rem, 1.f);
-                        }
-                        for (int cw = 0; cw < CW; ++cw) acc[(size_t)r * CW + cw] = fmaf(fa[cw], sum, acc[(size_t)r * CW + cw]);
+                    const int i = xmajor ? n : q, j = xmajor ? q : n;
+                    float fa[CW];
+                    double mu;
+                    if (!sf_candidate_record<CW, -1>(g, v, i, j, c0, true, fa, mu)) continue;
+                    const float *col = &volz[xmajor][(size_t)sf_slab_column(slab, g.nx, i, j) * nzp];
+                    const int P = (NKP > 4 && (float)mu <= 1.4999f) ? 4 : NKP;
+                    switch (P) {
+                    case 2: host_pairs_of_candidate<CW, 2>(g, col, nzp, mu, zkp, fa, acc); break;
+                    case 3: host_pairs_of_candidate<CW, 3>(g, col, nzp, mu, zkp, fa, acc); break;
+                    case 4: host_pairs_of_candidate<CW, 4>(g, col, nzp, mu, zkp, fa, acc); break;
+                    case 5: host_pairs_of_candidate<CW, 5>(g, col, nzp, mu, zkp, fa, acc); break;
+                    case 6: host_pairs_of_candidate<CW, 6>(g, col, nzp, mu, zkp, fa, acc); break;
+                    default: host_pairs_of_candidate<CW, 7>(g, col, nzp, mu, zkp, fa, acc); break;
                     }
                 }
             }
@@ -275,6 +283,30 @@ extern "C" long host_project_columns(const leap_geometry *G, const float *vol, f
             }
         }
     return uncovered;
+}
+
+// Returns -1 when the handle does not use the column kernel, else the number of (view, bundle, slab) cases in which the
+// candidate slots do not cover the candidate range (must be 0).
+extern "C" long host_project_columns(const leap_geometry *G, const float *vol, float *sino)
+{
+    const SfGeom &g = G->g;
+    if (!G->fp_columns) return -1;
+    const int nzp = g.nz + 2 * FP_PAD;
+    // the z-fastest copy in both slab layouts (a slab across x is laid out differently from one across y)
+    std::vector<float> volz[2];
+    for (int xmajor = 0; xmajor < 2; ++xmajor) {
+        const SfSlab slab = {0, xmajor ? g.nx : g.ny, xmajor, 1, xmajor ? g.nx : g.ny};
+        volz[xmajor].assign((size_t)g.nx * g.ny * nzp, 0.f);
+        for (int k = 0; k < g.nz; ++k)
+            for (int j = 0; j < g.ny; ++j)
+                for (int i = 0; i < g.nx; ++i)
+                    volz[xmajor][(size_t)sf_slab_column(slab, g.nx, i, j) * nzp + FP_PAD + k] = vol[((size_t)k * g.ny + j) * g.nx + i];
+    }
+    switch (G->fp_cw) {
+    case 1: return host_project_bundles<1>(G, volz, nzp, sino);
+    case 2: return host_project_bundles<2>(G, volz, nzp, sino);
+    default: return host_project_bundles<4>(G, volz, nzp, sino);
+    }
 }
 
 // ---- Siddon column-wise forward projection: its arithmetic, serially, with every read of the padded copy checked ----

