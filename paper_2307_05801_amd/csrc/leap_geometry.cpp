@@ -199,7 +199,8 @@ static void select_footprint_tiled(leap_geometry *G)
     G->bp_nv = std::max(2, (int)std::ceil(G->max_rows_per_voxel - 1e-6) + 1);
     G->bp_wh = (float)(0.5 * G->max_cols_per_voxel);
     const float hx = 0.5f * (float)(BP_T - 1) * G->g.T;
-    long first_shape = d->nz >= 128 ? 0 : 1;       // 64-voxel chunks only pay off on tall volumes
+    // 64-voxel chunks only pay off on tall volumes, and only the two-row instances keep 64 sums in registers without spilling
+    long first_shape = d->nz >= 128 && G->bp_nv == 2 ? 0 : BP_FIRST_SHORT_SHAPE;
     if (debug_option("bp_shape", first_shape)) first_shape = ((first_shape % BP_NSHAPES) + BP_NSHAPES) % BP_NSHAPES;
     for (int sh = (int)first_shape; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
         staged_window_need(G, BP_SHAPES[sh].zc,
@@ -220,15 +221,24 @@ static void select_footprint_tiled(leap_geometry *G)
     }
 }
 
-// Row groups per wave of the column-wise forward kernels: the largest of 1, 2, 4, (8) that the detector fills.
-static int row_groups(int nrows, int rows_per_group, int most)
+// Row groups per wave of the column-wise forward kernels.  A wave pays a fixed share per candidate voxel column (its
+// parameters, the transaxial record) worth about a group and a half, then one share per group whether or not the group
+// holds rows of the detector; the detector needs ceil(groups / rg) bands of waves.
+static int row_groups(int nrows, int rows_per_group, const int *choices, int nchoices)
 {
     const int groups = (nrows + rows_per_group - 1) / rows_per_group;
-    int rg = 1;
-    while (rg * 2 <= most && rg * 2 <= groups) rg *= 2;
+    int best = choices[0];
+    double best_cost = 1e300;
+    for (int n = 0; n < nchoices; ++n) {
+        const int rg = choices[n], bands = (groups + rg - 1) / rg;
+        const double cost = bands * (1.6 + rg);
+        if (cost < best_cost - 1e-9) { best_cost = cost; best = rg; }
+    }
     long v;
-    if (debug_option("rg", v) && (v == 1 || v == 2 || v == 4 || (v == 8 && most >= 8))) rg = (int)v;
-    return rg;
+    if (debug_option("rg", v))
+        for (int n = 0; n < nchoices; ++n)
+            if (choices[n] == v) best = (int)v;
+    return best;
 }
 
 static void block_order_options(leap_geometry *G)
@@ -278,7 +288,8 @@ static void select_footprint_columns(leap_geometry *G)
     G->fp_need_q = need;
     G->fp_nq = need <= 4 ? 4 : (need <= 8 ? 8 : 16);
     G->fp_nkp = std::min(FP_MAX_P, std::max(2, (int)std::ceil(2.0 * vpr - 1e-6) + 1));
-    G->fp_rg = row_groups(d->nrows, 128, 4);
+    static const int pair_groups[] = {1, 2, 3, 4};
+    G->fp_rg = row_groups(d->nrows, 128, pair_groups, 4);
     G->fp_columns = need <= 16;
     block_order_options(G);
     if (!G->fp_columns) return;
@@ -298,7 +309,8 @@ static void select_siddon_fast_kernels(leap_geometry *G)
     // wave-per-column forward projection: no ray may cross more than one z-face per slab
     if (d->nrows >= 32) {
         G->sd_columns = true;
-        G->fp_rg = row_groups(d->nrows, 64, 8);
+        static const int single_groups[] = {1, 2, 4, 8};
+        G->fp_rg = row_groups(d->nrows, 64, single_groups, 4);
         block_order_options(G);
     }
 
@@ -308,8 +320,8 @@ static void select_siddon_fast_kernels(leap_geometry *G)
         (double)d->nrows * d->ncols < 1073741824.0) {      // the staging loads use 32-bit byte offsets within a view
         G->bp_nc = std::max(2, (int)std::floor(G->max_cols_per_voxel + 0.01) + 1);
         const float hx = 0.5f * (float)BP_T * G->g.T;
-        long first_shape = 1;                          // the 64-voxel shape does not fit: the sums live in LDS
-        if (debug_option("bp_shape", first_shape)) first_shape = std::max(1L, first_shape % BP_NSHAPES);
+        long first_shape = BP_FIRST_SHORT_SHAPE;       // the 64-voxel shapes do not fit: the sums live in LDS
+        if (debug_option("bp_shape", first_shape)) first_shape = std::max((long)BP_FIRST_SHORT_SHAPE, first_shape % BP_NSHAPES);
         for (int sh = (int)first_shape; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
             staged_window_need(G, BP_SHAPES[sh].zc,
                                [&](const SfGeom &ga, const SfView &v, float xc, float yc, float z0, float z1) {

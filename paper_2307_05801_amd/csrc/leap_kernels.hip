@@ -306,6 +306,7 @@ static bool launch_fp_rg(const leap_geometry *G, const FwdScratch &S, const SfSl
     switch (G->fp_rg) {
     case 1: return launch_fp_w<NKP, 1>(G, S, slab, d_sino, stream, items);
     case 2: return launch_fp_w<NKP, 2>(G, S, slab, d_sino, stream, items);
+    case 3: return launch_fp_w<NKP, 3>(G, S, slab, d_sino, stream, items);
     case 4: return launch_fp_w<NKP, 4>(G, S, slab, d_sino, stream, items);
     default: return false;
     }
@@ -432,7 +433,13 @@ template <int NC, int NV>
 static bool launch_bp_shape(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream, int items)
 {
     switch (G->bp_shape) {
-    case 0: launch_bp_tiled<NC, NV, 0>(G, d_sino, d_vol, stream, items); return true;
+    case 0:      // 64 voxels per thread: instances for two-row footprints only (taller ones would spill registers)
+        if constexpr (NV == 2) {
+            launch_bp_tiled<NC, NV, 0>(G, d_sino, d_vol, stream, items);
+            return true;
+        } else {
+            return false;
+        }
     case 1: launch_bp_tiled<NC, NV, 1>(G, d_sino, d_vol, stream, items); return true;
     case 2: launch_bp_tiled<NC, NV, 2>(G, d_sino, d_vol, stream, items); return true;
     case 3: launch_bp_tiled<NC, NV, 3>(G, d_sino, d_vol, stream, items); return true;

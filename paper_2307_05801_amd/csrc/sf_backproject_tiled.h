@@ -27,6 +27,7 @@ struct SfBpShape {
 };
 constexpr SfBpShape BP_SHAPES[] = {{64, 32, 76}, {32, 32, 44}, {32, 32, 56}, {16, 32, 44}, {16, 64, 48}};
 constexpr int BP_NSHAPES = 5;
+constexpr int BP_FIRST_SHORT_SHAPE = 1;      // first shape with fewer than 64 voxels per thread
 
 // Window of the detector that one (view, tile, z-chunk) can touch.  Evaluated identically on the host
 // (limit check) and in the kernel; everything here is uniform over the workgroup.
@@ -266,7 +267,12 @@ __global__ __launch_bounds__(256, (GT == 1 && NV > 2 && BP_ZC > 32) ? 3 : 4) voi
         const SfRowsOfVoxels ax = sf_rows_of_voxels(gv, f, zlo_k0);
         unsigned ofs = (unsigned)((ax.rb - win.r0) * BP_PS + (cf - win.c0));
 
-        if constexpr (NV == 2) {
+        // Where no voxel of the wave is taller than a detector row in this view, consecutive voxels share rows and the
+        // cheaper running scheme applies; tiles far from the source qualify even when the nearest voxels of the volume do
+        // not (the instance is built for the tallest footprint).  The choice is uniform over the wave, so it costs one
+        // ballot per view.
+        const bool shared_rows = NV == 2 || __builtin_amdgcn_ballot_w64(ax.av > 1.0f) == 0;
+        if (shared_rows) {
             // A voxel is at most one row tall, so consecutive voxels share a row: keep the u-combined samples of the
             // current and the next row in registers and fetch one new row per voxel (half the LDS traffic).
             auto row_sum = [&](const float *q) {
@@ -300,7 +306,7 @@ __global__ __launch_bounds__(256, (GT == 1 && NV > 2 && BP_ZC > 32) ? 3 : 4) voi
                 if ((kk & 3) == 3)
                     asm volatile("" : "+v"(pb), "+v"(acc[kk - 3]), "+v"(acc[kk - 2]), "+v"(acc[kk - 1]), "+v"(acc[kk]));
             }
-        } else {
+        } else if constexpr (NV > 2) {
         float lo = ax.phi0;
 #pragma unroll
         for (int kk = 0; kk < BP_ZC; ++kk) {
@@ -327,7 +333,6 @@ __global__ __launch_bounds__(256, (GT == 1 && NV > 2 && BP_ZC > 32) ? 3 : 4) voi
             if ((kk & 3) == 3)
                 asm volatile("" : "+v"(ofs), "+v"(acc[kk - 3]), "+v"(acc[kk - 2]), "+v"(acc[kk - 1]), "+v"(acc[kk]));
         }
-
         }
 
         if (a + 1 < g.nviews)
