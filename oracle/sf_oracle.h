@@ -35,13 +35,18 @@
  * length) in step 1, and the magnification in step 3 is SDD over the in-plane distance of the voxel centre from the
  * source, SDD / hypot(SOD-l, t).  Step 4 uses D = P - S as before.
  *
- * Modular geometry (SFO_MODULAR; the paper's flexible geometry with a pose per view), UPRIGHT modules only: the column
- * axis is horizontal, the row axis is +z.  The paper gives no footprint construction for it; the reading here is the
- * cone-beam construction carried out in each view's own frame: e_u = the module's column axis, e_s = the horizontal
- * unit vector orthogonal to it on the source's side, source at (l, t, z) = (lS, tS, zS), detector plane at
- * l = lS - sdd_a with its centre at (tC, zC).  Step 1: u = tS + sdd_a (t - tS)/(lS - l) - tC; step 3: magnification
- * sdd_a/(lS - l) about the source height, [v-,v+] = zS + m (z_k -+ Tz/2 - zS) - zC; step 4: D = pixel - source.
- * A tilted module has no such reading (its oracle calls return an error); the Siddon oracle covers those.
+ * Modular geometry (SFO_MODULAR; the paper's flexible geometry with a pose per view).  The paper gives no footprint
+ * construction for it.  UPRIGHT modules (column axis horizontal, row axis +z): the cone-beam construction carried out in
+ * each view's own frame: e_u = the module's column axis, e_s = the horizontal unit vector orthogonal to it on the
+ * source's side, source at (l, t, z) = (lS, tS, zS), detector plane at l = lS - sdd_a with its centre at (tC, zC).
+ * Step 1: u = tS + sdd_a (t - tS)/(lS - l) - tC; step 3: magnification sdd_a/(lS - l) about the source height,
+ * [v-,v+] = zS + m (z_k -+ Tz/2 - zS) - zC; step 4: D = pixel - source.
+ * TILTED modules (any other orthonormal axes): the same separable footprint on the module's own (u, v) axes.  Step 1: the
+ * knots are the u coordinates of the central projections (from the source onto the module's plane) of the voxel's four
+ * in-plane corners, taken at the height of the voxel's centre; step 3: [v-,v+] spans the v coordinates of the central
+ * projections of the centres of the voxel's lower and upper face; steps 2 and 4 unchanged.  For an upright module
+ * these are the expressions above, so the readings meet as the tilt goes to zero.  The whole volume must lie in front of
+ * the source (else the calls return -1).
  *
  * Footprints partly off the detector are truncated; rays that miss the volume give 0.
  * For parallel-beam w * pu * pv equals the volume of (pixel beam  intersect  voxel) exactly.

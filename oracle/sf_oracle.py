@@ -79,8 +79,6 @@ def _scan(cfg):
     poses = None
     if cfg.geom == 4:
         poses = np.ascontiguousarray(cfg.poses, dtype=np.float64).reshape(cfg.nviews, 12)
-        assert np.abs(poses[:, 8]).max() < 1e-12 and np.abs(poses[:, 9:12] - [0.0, 0.0, 1.0]).max() < 1e-12, \
-            "footprint oracle: upright modules only (column axis horizontal, row axis +z)"
         pp = poses.ctypes.data_as(C.POINTER(C.c_double))
     else:
         pp = C.POINTER(C.c_double)()

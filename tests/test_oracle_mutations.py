@@ -121,12 +121,33 @@ MODULAR_SF_MUTATIONS = [
      "f->lS = S[0] * f->cphi + S[1] * f->sphi;", "f->lS = sqrt(S[0] * S[0] + S[1] * S[1]);"),
 ]
 
+TILTED_SF_MUTATIONS = [
+    ("tilted module: row coordinate measured along z instead of the module's row axis",
+     "*v = q[0] * p->ev[0] + q[1] * p->ev[1] + q[2] * p->ev[2];\n    return 0;", "*v = q[2];\n    return 0;"),
+    ("tilted module: column coordinate ignores the column axis' vertical part",
+     "*u = q[0] * p->eu[0] + q[1] * p->eu[1] + q[2] * p->eu[2];\n    *v", "*u = q[0] * p->eu[0] + q[1] * p->eu[1];\n    *v"),
+    ("tilted module: one component of the plane's normal with the wrong sign",
+     "p->n[1] = p->eu[2] * p->ev[0] - p->eu[0] * p->ev[2];", "p->n[1] = p->eu[0] * p->ev[2] - p->eu[2] * p->ev[0];"),
+    ("tilted module: corners projected from the upper face instead of the centre's height",
+     "bad |= module_project(&p, x - h, y - h, z, &tau[0], &v);",
+     "bad |= module_project(&p, x - h, y - h, z + 0.5 * s->Tz, &tau[0], &v);"),
+    ("tilted module: amplitude of a ray to an upright module's pixel",
+     "d[q] = p.C[q] + u * p.eu[q] + v * p.ev[q] - p.S[q];", "d[q] = p.C[q] + u * p.eu[q] + v * (q == 2) - p.S[q];"),
+    ("tilted module: upper face a whole voxel above the centre",
+     "bad |= module_project(&p, x, y, z + 0.5 * s->Tz, &u, &vb);", "bad |= module_project(&p, x, y, z + 1.0 * s->Tz, &u, &vb);"),
+    ("tilted module: sample index transposed in A",
+     "int64_t pixel = (int64_t)r * s->ncols + c;", "int64_t pixel = (int64_t)c * s->nrows + r;"),
+    ("tilted module: plane hit slightly short of the plane",
+     "double lam = p->gap / along;\n    double q[3]", "double lam = p->gap / (along + 0.01);\n    double q[3]"),
+]
+
 CASES = ([("sf_oracle.c", "test_oracle_pins.py") + m for m in MUTATIONS]
          + [("siddon_oracle.c", "test_siddon_pins.py") + m for m in SIDDON_MUTATIONS]
          + [("sf_oracle.c", "test_curved_pins.py") + m for m in CURVED_SF_MUTATIONS]
          + [("siddon_oracle.c", "test_curved_pins.py") + m for m in CURVED_SIDDON_MUTATIONS]
          + [("siddon_oracle.c", "test_modular_pins.py") + m for m in MODULAR_SIDDON_MUTATIONS]
-         + [("sf_oracle.c", "test_modular_pins.py") + m for m in MODULAR_SF_MUTATIONS])
+         + [("sf_oracle.c", "test_modular_pins.py") + m for m in MODULAR_SF_MUTATIONS]
+         + [("sf_oracle.c", "test_modular_pins.py") + m for m in TILTED_SF_MUTATIONS])
 
 
 @pytest.mark.parametrize("source,pins,what,old,new", CASES, ids=[c[0][:-9] + ": " + c[2] for c in CASES])
