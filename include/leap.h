@@ -56,8 +56,14 @@ extern "C" {
  * every view has its own pose, 12 doubles in `poses`: source position S, detector centre C, unit vector along the
  * column index, unit vector along the row index (orthogonal to each other); pixel (r, c) sits at
  * C + u_c ucol + v_r vrow.  sod, sdd and angles_rad are not read.  LEAP_MODEL_SIDDON takes any pose.
- * LEAP_MODEL_SF needs upright modules (ucol horizontal, vrow = +z): the cone-beam footprint construction is carried
- * out in each view's own frame; for a tilted module leap_geometry_create returns LEAP_UNSUPPORTED. */
+ * LEAP_MODEL_SF on upright modules (ucol horizontal, vrow = +z): the cone-beam footprint construction is carried out
+ * in each view's own frame.  On any other module (the paper gives no construction) the footprint stays separable on
+ * the module's own axes: the trapezoid's knots are the column coordinates of the central projections, from the source
+ * onto the module's plane, of the voxel's four in-plane corners at the height of its centre; the axial interval lies
+ * between the row coordinates of the central projections of the centres of its lower and upper face; the amplitude is
+ * T |D| / max(|Dx|, |Dy|) with D = pixel - source.  A scan with one such module runs on one thread per ray / per voxel
+ * in double precision.  It needs the whole volume in front of every source (on the module's side of the plane through
+ * the source parallel to the module) and no pixel whose ray runs along z, else LEAP_BAD_GEOMETRY. */
 enum { LEAP_PARALLEL = 0, LEAP_FAN = 1, LEAP_CONE = 2, LEAP_CONE_CURVED = 3, LEAP_MODULAR = 4 };
 
 /* Projector models ("CT Projection Models and Geometries").  LEAP_MODEL_SF: separable footprints.
@@ -68,9 +74,10 @@ enum { LEAP_MODEL_SF = 0, LEAP_MODEL_SIDDON = 1 };
 enum {
     LEAP_OK = 0,
     LEAP_INVALID_ARG = -1,   /* null pointer, non-positive size or count, unknown type or model, FAN with nrows != 1 or nz != 1 */
-    LEAP_BAD_GEOMETRY = -2,  /* cone/fan: source not strictly outside the volume's bounding circle, sdd <= 0, curved fan wider than +-1.5 rad */
+    LEAP_BAD_GEOMETRY = -2,  /* cone/fan: source not strictly outside the volume's bounding circle, sdd <= 0, curved fan wider than +-1.5 rad;
+                                modular: a source inside the volume, a module with no footprints (see LEAP_MODULAR) */
     LEAP_HIP_ERROR = -3,     /* a HIP runtime call failed (the message is kept, see leap_last_error) */
-    LEAP_UNSUPPORTED = -4    /* sizes beyond what the index arithmetic of the kernels covers; a tilted module with LEAP_MODEL_SF;
+    LEAP_UNSUPPORTED = -4    /* sizes beyond what the index arithmetic of the kernels covers;
                                 a volume beyond the fixed array of leap_project_static_scratch */
 };
 

@@ -435,6 +435,7 @@ static void free_handle(leap_geometry *G)
     if (G->d_raycols) (void)hipFree(G->d_raycols);
     if (G->d_poses) (void)hipFree(G->d_poses);
     if (G->d_geoms) (void)hipFree(G->d_geoms);
+    if (G->d_mfviews) (void)hipFree(G->d_mfviews);
     if (G->d_colcs) (void)hipFree(G->d_colcs);
     if (G->scratch_event) (void)hipEventDestroy(G->scratch_event);
     delete G;
@@ -498,6 +499,8 @@ static int finish_handle(leap_geometry *G, leap_geometry **out)
     if (e == hipSuccess && !G->raycols.empty()) e = upload((void **)&G->d_raycols, G->raycols.data(), sizeof(SdRayCol) * G->raycols.size());
     if (e == hipSuccess && !G->geoms.empty()) e = upload((void **)&G->d_geoms, G->geoms.data(), sizeof(SfGeom) * G->geoms.size());
     if (e == hipSuccess && !G->poses.empty()) e = upload((void **)&G->d_poses, G->poses.data(), sizeof(MdPose) * G->poses.size());
+    if (e == hipSuccess && !G->mfviews.empty())
+        e = upload((void **)&G->d_mfviews, G->mfviews.data(), sizeof(MfView) * G->mfviews.size());
     if (e == hipSuccess && d->type == LEAP_CONE_CURVED && d->model == LEAP_MODEL_SF && G->bp_tiled) upload_curved_tables(G);
     if (e != hipSuccess) {
         free_handle(G);
@@ -535,33 +538,28 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
     }
     // Upright modules (column axis horizontal, row axis +z, detector behind the volume as seen from the source, source
     // clear of the volume's bounding circle in the module's frame) are circular cone-beam views of a translated scene:
-    // the footprint construction needs them, the Siddon model uses them for its fast kernels.
-    bool upright = true;
-    const char *why_not = "";
-    int why_status = LEAP_OK;
-    for (int a = 0; a < d->nviews && upright; ++a) {
+    // both models have fast kernels for scans made of them.  A scan with any other module goes through the general
+    // kernels of its model.
+    bool tilted = false, upright = true;
+    for (int a = 0; a < d->nviews; ++a) {
         const double *p = d->poses + 12 * (size_t)a;
         if (std::fabs(p[8]) > 1e-9 || std::fabs(p[9]) > 1e-9 || std::fabs(p[10]) > 1e-9 || std::fabs(p[11] - 1.0) > 1e-9) {
+            tilted = true;
             upright = false;
-            why_not = "the footprint model needs upright modules (column axis horizontal, row axis +z); "
-                      "use LEAP_MODEL_SIDDON for tilted ones";
-            why_status = LEAP_UNSUPPORTED;
-            break;
         }
+    }
+    for (int a = 0; a < d->nviews && !tilted && upright; ++a) {
+        const double *p = d->poses + 12 * (size_t)a;
         const double c = p[7], s = -p[6];
         const double lS = p[0] * c + p[1] * s, lD = p[3] * c + p[4] * s, tS = -p[0] * s + p[1] * c;
         // the volume as this view sees it: moved by -tS along the column axis
         const double mx = std::fabs(d->center_x - tS * p[6]) + half[0], my = std::fabs(d->center_y - tS * p[7]) + half[1];
         const double reach_a = std::sqrt(mx * mx + my * my);
-        if (!(lS - lD > 0.0) || !(lS > reach_a) || !(d->pixel_u < 0.25 * (lS - lD))) {
-            upright = false;
-            why_not = "module does not face its source across the volume";
-            why_status = LEAP_BAD_GEOMETRY;
-        }
+        if (!(lS - lD > 0.0) || !(lS > reach_a) || !(d->pixel_u < 0.25 * (lS - lD))) upright = false;
     }
-    if (d->model == LEAP_MODEL_SF && !upright) {
-        leap_set_error(why_not);
-        return why_status;
+    if (d->model == LEAP_MODEL_SF && !upright && !tilted) {
+        leap_set_error("module does not face its source across the volume");
+        return LEAP_BAD_GEOMETRY;
     }
     leap_geometry *G = new (std::nothrow) leap_geometry;
     if (!G) return invalid("out of host memory");
@@ -620,6 +618,19 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
     if (upright) {
         if (d->model == LEAP_MODEL_SIDDON) build_ray_table(G);
         select_fast_kernels(G);
+    } else if (d->model == LEAP_MODEL_SF) {
+        G->mfviews.resize(d->nviews);
+        for (int a = 0; a < d->nviews; ++a) {
+            const MdPose &P = G->poses[a];
+            MfView &V = G->mfviews[a];
+            for (int q = 0; q < 3; ++q) { V.S[q] = P.S[q]; V.C[q] = P.C[q]; V.eu[q] = P.ucol[q]; V.ev[q] = P.vrow[q]; }
+            if (!mf_prepare_view(g, V)) {
+                leap_set_error("view " + std::to_string(a) + " has no footprints: the whole volume must lie in front of the "
+                               "source (on the module's side) and no pixel's ray may run along z");
+                free_handle(G);
+                return LEAP_BAD_GEOMETRY;
+            }
+        }
     }
     return finish_handle(G, out);
 }

@@ -11,6 +11,7 @@
 #include "sf_types.h"
 #include "sd_ray.h"
 #include "md_siddon.h"
+#include "md_footprint.h"
 
 struct leap_geometry {
     leap_geometry_desc desc;            // caller's parameters (angles_rad re-pointed at `angles`)
@@ -59,6 +60,9 @@ struct leap_geometry {
     // footprint model on upright modules: every view is a cone-beam view with its own parameter block
     std::vector<SfGeom> geoms;
     SfGeom *d_geoms = nullptr;
+    // footprint model on tilted modules: per-view table of the general kernels (md_footprint.h)
+    std::vector<MfView> mfviews;
+    MfView *d_mfviews = nullptr;
     void *d_colcs = nullptr;            // cylinder, tiled back projection: (cos, sin) of every column's fan angle, then the (tile, view) table
     bool sd_columns = false;            // wave-per-column forward kernel (needs the scratch copy and slope <= 1)
 };

@@ -88,6 +88,28 @@ __global__ __launch_bounds__(256) void sf_project_general_modular(const SfGeom *
         if (r0 + rr < g.nrows) y[(size_t)(r0 + rr) * g.ncols] = out[rr];
 }
 
+// Modular geometry, footprint model on tilted modules: one thread per ray / per voxel (md_footprint.h).
+// grids as for the general Siddon kernels below.
+__global__ __launch_bounds__(256) void mf_project_general(SfGeom g, const MfView *__restrict__ views,
+                                                          const float *__restrict__ vol, float *__restrict__ sino)
+{
+    const int c = blockIdx.x * 64 + threadIdx.x;
+    const int r = blockIdx.y * 4 + threadIdx.y;
+    const int a = blockIdx.z;
+    if (c >= g.ncols || r >= g.nrows) return;
+    sino[((size_t)a * g.nrows + r) * g.ncols + c] = mf_project_ray(g, views[a], vol, r, c);
+}
+
+__global__ __launch_bounds__(256) void mf_backproject_general(SfGeom g, const MfView *__restrict__ views,
+                                                              const float *__restrict__ sino, float *__restrict__ vol)
+{
+    const int i = blockIdx.x * 64 + threadIdx.x;
+    const int j = blockIdx.y * 4 + threadIdx.y;
+    const int k = blockIdx.z;
+    if (i >= g.nx || j >= g.ny) return;
+    vol[((size_t)k * g.ny + j) * g.nx + i] = mf_backproject_voxel(g, views, sino, i, j, k);
+}
+
 // Siddon model, general kernels: one thread per ray / per voxel.
 // grid: x = ceil(ncols/64), y = ceil(nrows/4), z = nviews; block 64x4.
 __global__ __launch_bounds__(256) void sd_project_general(SfGeom g, const SdRayCol *__restrict__ rays,
@@ -396,6 +418,12 @@ int leap_launch_project(const leap_geometry *G, const float *d_vol, float *d_sin
     const SfGeom &g = G->g;
     if (g.model == SF_MODEL_SIDDON) return launch_sd_project(G, d_vol, d_sino, stream);
     if (G->fp_columns) return leap_launch_project_batch(G, d_vol, d_sino, 1, stream);
+    if (G->d_mfviews) {                     // sizes were checked against the grid limits at creation
+        dim3 grid(cdiv(g.ncols, 64), cdiv(g.nrows, 4), g.nviews);
+        hipLaunchKernelGGL(mf_project_general, grid, dim3(64, 4, 1), 0, stream, g, G->d_mfviews, d_vol, d_sino);
+        LEAP_HIP_CHECK(hipGetLastError());
+        return LEAP_OK;
+    }
     dim3 block(64, 4, 1);
     dim3 grid(cdiv(g.ncols, 64), cdiv(cdiv(g.nrows, GEN_RC), 4), g.nviews);
     if (grid.y > 65535u) {
@@ -501,6 +529,12 @@ int leap_launch_backproject(const leap_geometry *G, const float *d_sino, float *
     const SfGeom &g = G->g;
     if (g.model == SF_MODEL_SIDDON) return launch_sd_backproject(G, d_sino, d_vol, stream);
     if (G->bp_tiled) return launch_bp_items(G, d_sino, d_vol, 1, stream);
+    if (G->d_mfviews) {
+        dim3 grid(cdiv(g.nx, 64), cdiv(g.ny, 4), g.nz);
+        hipLaunchKernelGGL(mf_backproject_general, grid, dim3(64, 4, 1), 0, stream, g, G->d_mfviews, d_sino, d_vol);
+        LEAP_HIP_CHECK(hipGetLastError());
+        return LEAP_OK;
+    }
     dim3 block(64, 4, 1);
     dim3 grid(cdiv(g.nx, 64), cdiv(g.ny, 4), cdiv(g.nz, GEN_ZC));
     if (grid.y > 65535u || grid.z > 65535u) {

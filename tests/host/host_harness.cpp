@@ -47,6 +47,14 @@ int leap_launch_project(const leap_geometry *G, const float *vol, float *sino, h
                     sino[((size_t)a * g.nrows + r) * g.ncols + c] = md_project_ray(g, G->d_poses[a], vol, r, c);
         return LEAP_OK;
     }
+    if (G->d_mfviews) {
+#pragma omp parallel for collapse(2)
+        for (int a = 0; a < g.nviews; ++a)
+            for (int r = 0; r < g.nrows; ++r)
+                for (int c = 0; c < g.ncols; ++c)
+                    sino[((size_t)a * g.nrows + r) * g.ncols + c] = mf_project_ray(g, G->d_mfviews[a], vol, r, c);
+        return LEAP_OK;
+    }
     if (g.model == SF_MODEL_SIDDON) {
 #pragma omp parallel for collapse(2)
         for (int a = 0; a < g.nviews; ++a)
@@ -86,6 +94,13 @@ int leap_launch_backproject(const leap_geometry *G, const float *sino, float *vo
         for (int k = 0; k < g.nz; ++k)
             for (int j = 0; j < g.ny; ++j)
                 for (int i = 0; i < g.nx; ++i) vol[((size_t)k * g.ny + j) * g.nx + i] = md_backproject_voxel(g, G->d_poses, sino, i, j, k);
+        return LEAP_OK;
+    }
+    if (G->d_mfviews) {
+#pragma omp parallel for collapse(2)
+        for (int k = 0; k < g.nz; ++k)
+            for (int j = 0; j < g.ny; ++j)
+                for (int i = 0; i < g.nx; ++i) vol[((size_t)k * g.ny + j) * g.nx + i] = mf_backproject_voxel(g, G->d_mfviews, sino, i, j, k);
         return LEAP_OK;
     }
     if (g.model == SF_MODEL_SIDDON) {

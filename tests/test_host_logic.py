@@ -317,6 +317,62 @@ def test_modular_siddon_bodies_match_oracle_on_cpu(host, oracle_mod, name):
         assert rel_l2(ax, sd.project(cone, x)) <= TOL
 
 
+TILTED_FOOTPRINT_CASES = {
+    "tilted_modules": MODULAR_CASES["tilted_modules"],
+    "tilted_tall_voxels": lambda: perturbed_poses(
+        reduced(config(3), 16, nviews=7).replace(nx=23, ny=19, nz=9, voxel_z=3.1, nrows=33, ncols=29), 8, shift_mm=15.0,
+        tilt_rad=0.35),
+    "looking_down_obliquely": lambda: CTConfig(
+        "down", 4, nviews=2, arc_deg=360.0, nrows=20, ncols=24, pixel_v=1.5, pixel_u=1.4, nx=18, ny=16, nz=12,
+        voxel_xy=1.0, voxel_z=1.3, shift_u=0.2, shift_v=-0.3,
+        poses=((30.0, -4.0, 40.0, -22.0, 3.0, -30.0, 0.0, 1.0, 0.0, 0.8, 0.0, -0.6),
+               (6.0, 34.0, 38.0, -2.0, -25.0, -28.0, 0.8, 0.6, 0.0, -0.36, 0.48, -0.8))),
+    "mixed_upright_and_tilted": lambda: _mixed_scan(),
+}
+
+
+def _mixed_scan():
+    base = reduced(config(3), 16, nviews=8).replace(nx=21, ny=26, nz=17, nrows=25, ncols=30)
+    t = perturbed_poses(base, 5, shift_mm=10.0, tilt_rad=0.2)
+    u = perturbed_poses(base, 5, shift_mm=10.0, tilt_rad=0.2, upright=True)
+    return t.replace(poses=tuple(t.poses[a] if a % 2 else u.poses[a] for a in range(t.nviews)))
+
+
+@pytest.mark.parametrize("name", list(TILTED_FOOTPRINT_CASES))
+def test_tilted_footprint_bodies_match_oracle_on_cpu(host, oracle_mod, name):
+    """The one-thread-per-ray / per-voxel bodies of the footprint model on tilted modules, stepped on the CPU."""
+    cfg = TILTED_FOOTPRINT_CASES[name]()
+    x = uniform_volume(cfg, 5)[0]
+    y = uniform_sinogram(cfg, 6)[0]
+    h = handle(host, cfg, B.LEAP_MODEL_SF)
+    desc = B.leap_geometry_describe(h, host)
+    assert "tilted modules" in desc and "A=general" in desc and "AT=general" in desc, desc
+    ax = np.zeros(cfg.sino_shape, np.float32)
+    aty = np.zeros(cfg.vol_shape, np.float32)
+    B.leap_project(h, x.ctypes.data, ax.ctypes.data, 1, 0, host)
+    B.leap_backproject(h, y.ctypes.data, aty.ctypes.data, 1, 0, host)
+    B.leap_geometry_destroy(h, host)
+    ref_a, ref_t = oracle_mod.project(cfg, x), oracle_mod.backproject(cfg, y)
+    assert np.abs(ref_a).max() > 0 and np.abs(ref_t).max() > 0
+    assert rel_l2(ax, ref_a) <= 1e-6 and rel_l2(aty, ref_t) <= 1e-6
+    assert np.abs(ax - ref_a).max() <= 2e-6 * np.abs(ref_a).max()
+    assert np.abs(aty - ref_t).max() <= 2e-6 * np.abs(ref_t).max()
+
+
+def test_tilted_scans_without_footprints_are_refused(host):
+    """A source beside the volume with the module on the far side of only part of it, and a module below a source that
+    looks straight down: LEAP_BAD_GEOMETRY with a message, as the oracle refuses them."""
+    base = dict(nviews=1, arc_deg=360.0, nrows=20, ncols=24, pixel_v=1.5, pixel_u=1.4, nx=18, ny=16, nz=12, voxel_xy=1.0,
+                voxel_z=1.3)
+    grazing = (10.5, 0.0, 0.0, -30.0, 0.0, 0.0, 0.0, 1.0, 0.0, 0.6, 0.0, 0.8)       # the plane's normal tilts: corners behind
+    below = (0.3, -0.2, 40.0, 0.0, 0.0, -30.0, 1.0, 0.0, 0.0, 0.0, 1.0, 0.0)
+    for pose in (grazing, below):
+        cfg = CTConfig("bad", 4, poses=(pose,), **base)
+        with pytest.raises(B.LeapError) as err:
+            handle(host, cfg, B.LEAP_MODEL_SF)
+        assert err.value.status == B.LEAP_BAD_GEOMETRY and "no footprints" in str(err.value)
+
+
 UPRIGHT_CASES = {
     "cone_as_modular": lambda: modular_from(reduced(config(3), 16, nviews=10).replace(shift_u=0.3, shift_v=-0.4)),
     "shifted_upright_modules": lambda: perturbed_poses(
@@ -374,7 +430,7 @@ def test_modular_argument_checks(host):
     cfg = MODULAR_CASES["looking_down"]()
     d, keep = B.desc_from_config(cfg, B.LEAP_MODEL_SF)
     hnd = C.c_void_p()
-    assert host.leap_geometry_create(C.byref(d), C.byref(hnd)) == B.LEAP_UNSUPPORTED      # footprints need upright modules
+    assert host.leap_geometry_create(C.byref(d), C.byref(hnd)) == B.LEAP_BAD_GEOMETRY     # a pixel's ray runs along z: no footprint
     d, keep = B.desc_from_config(cfg, B.LEAP_MODEL_SIDDON)
     d.poses = C.POINTER(C.c_double)()
     assert host.leap_geometry_create(C.byref(d), C.byref(hnd)) == B.LEAP_INVALID_ARG
