@@ -141,6 +141,8 @@ def main() -> int:
     ap.add_argument("--detector", choices=["flat", "curved"], default="flat",
                     help="cone-beam cases only: flat panel (the headline) or cylindrical detector of the same pixel pitch")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="CPU time budget of the oracle baseline; 0 skips it")
+    ap.add_argument("--no-transfer-leg", action="store_true",
+                    help="skip the extra leg that times the host-memory entry points (upload + run + download)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed region, run one device-to-device copy of the volume (a plain copy kernel of "
                          "known size) so that a rocprofv3 --pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
@@ -277,6 +279,27 @@ def main() -> int:
         "roofline": roofline,
         "operators": per_op,
     }
+    if not args.no_transfer_leg:
+        # the same operators with their arrays in (pinned) host memory: upload, run, download, the three overlapped over
+        # the items of a batch.  Reported beside the resident figures, never as `value`.
+        hx = torch.from_numpy(x_np).pin_memory()
+        hy = torch.empty((batch,) + cfg.sino_shape, dtype=torch.float32).pin_memory()
+        hxb = torch.empty_like(hx).pin_memory()
+        geo.project_host(hx, hy)                 # first call: the handle allocates its staging and device buffers
+        geo.backproject_host(hy, hxb)
+        t0 = time.perf_counter()
+        geo.project_host(hx, hy)
+        t1 = time.perf_counter()
+        geo.backproject_host(hy, hxb)
+        t2 = time.perf_counter()
+        out["with_transfer"] = {
+            "A_ms": 1e3 * (t1 - t0), "AT_ms": 1e3 * (t2 - t1), "host_memory": "pinned",
+            "bytes_moved_per_operator": alg_bytes,
+            "updates_per_s": updates / (t2 - t0),
+            "note": "leap_project_host + leap_backproject_host, one call each: input uploaded, output downloaded, "
+                    "PCIe-inclusive; not the headline value",
+        }
+        del hx, hy, hxb
     if args.calibration_copy:
         xb.copy_(x)
         torch.cuda.synchronize()

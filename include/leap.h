@@ -132,6 +132,19 @@ int leap_backproject(const leap_geometry *geom, const float *d_sino, float *d_vo
  * The array keeps the last call's contents; each call restores the zeros it relies on. */
 int leap_project_static_scratch(const leap_geometry *geom, const float *d_vol, float *d_sino, int32_t batch, void *hip_stream);
 
+/* The pair on arrays in HOST memory ("Core CUDA Implementation": data may live on the CPU, the library moves it;
+ * "Performance and Memory Usage" quotes times with and without that transfer).  h_vol, h_sino: host memory, layouts
+ * as above, pageable or pinned, not overlapping.  Synchronous: the result is in place when the call returns.  The
+ * items of a batch run through a three-stage pipeline: item b+1 is uploaded while item b is projected and item b-1
+ * is downloaded, on three streams of the library's own (default priority).  Pageable memory is staged through four
+ * pinned buffers of 32 MiB, so that the CPU's copy of one chunk overlaps the DMA of the previous one; pinned memory
+ * (hipHostMalloc) goes to the DMA engines directly.  The first such call on a handle allocates, on the handle, two
+ * device arrays per direction (one for batch 1) of max(volume, sinogram) size, the pinned buffers, streams and
+ * events; leap_geometry_destroy frees them.  Calls on one handle are serialised.  The handle's device must be current.
+ * Returns LEAP_HIP_ERROR if an allocation or a copy fails. */
+int leap_project_host(const leap_geometry *geom, const float *h_vol, float *h_sino, int32_t batch);
+int leap_backproject_host(const leap_geometry *geom, const float *h_sino, float *h_vol, int32_t batch);
+
 /* ---- iterative reconstruction on top of the pair ------------------------------------------------------------
  * "CT Projection Models and Geometries" motivates the matched transpose with the least-squares cost
  * 1/2 ||A x - y||^2, whose gradient is A^T (A x - y), and with iterations that stay stable over a thousand or
@@ -169,7 +182,7 @@ const char *leap_last_error(void);
  * there.  Comma-separated key=value pairs: general=1 (no fast kernels), cw=1|2|4 (detector columns per wavefront),
  * rg=1|2|4|8 (row groups per wavefront), vb=N / tb=N (views per run / tiles per chunk of the block order), bp_shape=0..4
  * (first back-projection tile shape tried), slab=N (voxel layers per scratch slab), items=N (batch items per launch),
- * scratch_mib=N (scratch budget). */
+ * scratch_mib=N (scratch budget), stage_kib=N (size of a pinned staging buffer of the host-memory entry points). */
 int leap_geometry_describe(const leap_geometry *geom, char *buf, int32_t cap);
 
 #ifdef __cplusplus

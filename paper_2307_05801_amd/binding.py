@@ -18,6 +18,7 @@ MODELS = {"sf": LEAP_MODEL_SF, "siddon": LEAP_MODEL_SIDDON}
 LEAP_OK, LEAP_INVALID_ARG, LEAP_BAD_GEOMETRY, LEAP_HIP_ERROR, LEAP_UNSUPPORTED = 0, -1, -2, -3, -4
 
 EXPORTS = ("leap_geometry_create", "leap_geometry_destroy", "leap_project", "leap_backproject", "leap_project_static_scratch",
+           "leap_project_host", "leap_backproject_host",
            "leap_status_string", "leap_last_error", "leap_geometry_describe",
            "leap_recon_workspace_floats", "leap_sirt", "leap_least_squares_descent")
 
@@ -57,6 +58,9 @@ def declare(lib, solvers: bool = True) -> None:
     for fn in (lib.leap_project, lib.leap_backproject) + ((lib.leap_project_static_scratch,) if solvers else ()):
         fn.restype = C.c_int
         fn.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+    for fn in (lib.leap_project_host, lib.leap_backproject_host):
+        fn.restype = C.c_int
+        fn.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
     if solvers:
         lib.leap_recon_workspace_floats.restype = C.c_int
         lib.leap_recon_workspace_floats.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
@@ -158,6 +162,17 @@ def leap_project_static_scratch(handle: int, d_vol: int, d_sino: int, batch: int
     lib = lib or load_library()
     _check(lib, lib.leap_project_static_scratch(C.c_void_p(handle), C.c_void_p(d_vol), C.c_void_p(d_sino), batch,
                                                 C.c_void_p(stream)))
+
+
+def leap_project_host(handle: int, h_vol: int, h_sino: int, batch: int, lib=None) -> None:
+    """h_vol, h_sino: HOST addresses (numpy `.ctypes.data`, a pinned tensor's data_ptr()); returns when h_sino is written."""
+    lib = lib or load_library()
+    _check(lib, lib.leap_project_host(C.c_void_p(handle), C.c_void_p(h_vol), C.c_void_p(h_sino), batch))
+
+
+def leap_backproject_host(handle: int, h_sino: int, h_vol: int, batch: int, lib=None) -> None:
+    lib = lib or load_library()
+    _check(lib, lib.leap_backproject_host(C.c_void_p(handle), C.c_void_p(h_sino), C.c_void_p(h_vol), batch))
 
 
 def leap_backproject(handle: int, d_sino: int, d_vol: int, batch: int, stream: int = 0, lib=None) -> None:

@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libleap_hip.so")
-SOURCES = ["leap_geometry.cpp", "leap_kernels.hip", "leap_recon.hip"]
+SOURCES = ["leap_geometry.cpp", "leap_host.cpp", "leap_kernels.hip", "leap_recon.hip"]
 
 
 def hipcc() -> str:

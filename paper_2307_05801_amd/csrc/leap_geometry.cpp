@@ -429,6 +429,7 @@ static void allocate_forward_scratch(leap_geometry *G)
 static void free_handle(leap_geometry *G)
 {
     if (!G) return;
+    leap_host_stage_free(G);
     if (G->d_views) (void)hipFree(G->d_views);
     if (G->d_volz) (void)hipFree(G->d_volz);
     if (G->d_major) (void)hipFree(G->d_major);
@@ -492,6 +493,8 @@ static int finish_handle(leap_geometry *G, leap_geometry **out)
         if (e == hipSuccess) e = hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice);
         return e;
     };
+    long kib;
+    if (debug_option("stage_kib", kib) && kib >= 4) G->stage_chunk = (size_t)kib << 10;
     hipError_t e = hipGetDevice(&G->device);
     if (e == hipSuccess) (void)leap_static_scratch_init(G->device);   // set-up for leap_project_static_scratch; it reports a failure itself
     if (e == hipSuccess && !G->views.empty()) e = upload((void **)&G->d_views, G->views.data(), sizeof(SfView) * G->views.size());

@@ -13,6 +13,8 @@
 #include "md_siddon.h"
 #include "md_footprint.h"
 
+struct LeapHostStage;                  // streams, events, staging and device buffers of the host-memory entry points (leap_host.cpp)
+
 struct leap_geometry {
     leap_geometry_desc desc;            // caller's parameters (angles_rad re-pointed at `angles`)
     std::vector<double> angles;
@@ -64,6 +66,10 @@ struct leap_geometry {
     std::vector<MfView> mfviews;
     MfView *d_mfviews = nullptr;
     void *d_colcs = nullptr;            // cylinder, tiled back projection: (cos, sin) of every column's fan angle, then the (tile, view) table
+    // leap_project_host / leap_backproject_host: created by the first such call, freed with the handle
+    mutable LeapHostStage *host_stage = nullptr;
+    mutable std::mutex host_mutex;
+    size_t stage_chunk = (size_t)32 << 20;   // bytes per pinned staging buffer
     bool sd_columns = false;            // wave-per-column forward kernel (needs the scratch copy and slope <= 1)
 };
 
@@ -83,6 +89,9 @@ int leap_static_scratch_init(int device);
 
 // Slab width and batch items per launch that a scratch of `floats` floats affords (leap_geometry.cpp).
 bool leap_plan_scratch(const leap_geometry *G, size_t floats, int batch, int &width, int &items);
+
+// Frees what the host-memory entry points created on the handle (leap_host.cpp).
+void leap_host_stage_free(leap_geometry *G);
 
 // kernel launchers (leap_kernels.hip); one batch item per call
 int leap_launch_project(const leap_geometry *geom, const float *d_vol, float *d_sino, hipStream_t stream);

@@ -94,6 +94,50 @@ class Geometry:
         return out
 
 
+    # ---- the same operators on arrays in host memory (numpy arrays or CPU tensors, pinned or not) --------
+
+    def _host_array(self, a, shape, what: str):
+        """(address, batch, keep-alive) of a C-contiguous float32 host array ending in `shape`."""
+        if isinstance(a, torch.Tensor):
+            if a.device.type != "cpu" or a.dtype != torch.float32 or not a.is_contiguous():
+                raise ValueError(f"{what} must be a contiguous float32 CPU tensor or numpy array")
+            addr, dims = a.data_ptr(), tuple(a.shape)
+        else:
+            import numpy as np
+            if not isinstance(a, np.ndarray) or a.dtype != np.float32 or not a.flags["C_CONTIGUOUS"]:
+                raise ValueError(f"{what} must be a C-contiguous float32 numpy array or CPU tensor")
+            addr, dims = a.ctypes.data, tuple(a.shape)
+        if dims[-3:] != tuple(shape):
+            raise ValueError(f"{what} must end in shape {tuple(shape)}, got {dims}")
+        batch = 1
+        for n in dims[:-3]:
+            batch *= n
+        if batch < 1:
+            raise ValueError("empty batch")
+        return addr, batch
+
+    def project_host(self, vol, out):
+        """out = A vol with both arrays in host memory; the library uploads, projects and downloads, overlapping the
+        three over the items of a batch.  Returns `out`."""
+        a_in, batch = self._host_array(vol, self.vol_shape, "volume")
+        a_out, batch_out = self._host_array(out, self.sino_shape, "output sinogram")
+        if batch != batch_out:
+            raise ValueError("output batch mismatch")
+        with torch.cuda.device(self.device):
+            B.leap_project_host(self.handle, a_in, a_out, batch)
+        return out
+
+    def backproject_host(self, sino, out):
+        """out = A^T sino with both arrays in host memory.  Returns `out`."""
+        a_in, batch = self._host_array(sino, self.sino_shape, "sinogram")
+        a_out, batch_out = self._host_array(out, self.vol_shape, "output volume")
+        if batch != batch_out:
+            raise ValueError("output batch mismatch")
+        with torch.cuda.device(self.device):
+            B.leap_backproject_host(self.handle, a_in, a_out, batch)
+        return out
+
+
 class _ProjectFn(torch.autograd.Function):
     @staticmethod
     def forward(ctx, vol, geom):

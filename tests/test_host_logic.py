@@ -33,7 +33,8 @@ def host():
             tmp = f"{LIB}.{os.getpid()}.tmp"
             cmd = ["g++", "-O2", "-fopenmp", "-std=c++17", "-fPIC", "-shared", "-D__HIP_PLATFORM_AMD__",
                    "-I/opt/rocm/include", "-o", tmp, SRC,
-                   os.path.join(ROOT, "paper_2307_05801_amd", "csrc", "leap_geometry.cpp")]
+                   os.path.join(ROOT, "paper_2307_05801_amd", "csrc", "leap_geometry.cpp"),
+                   os.path.join(ROOT, "paper_2307_05801_amd", "csrc", "leap_host.cpp")]
             subprocess.run(cmd, check=True, capture_output=True)
             os.replace(tmp, LIB)
     lib = C.CDLL(LIB)
@@ -440,3 +441,31 @@ def test_modular_argument_checks(host):
     inside = cfg.replace(poses=((0.3, -0.2, 1.0, 0.0, 0.0, -30.0, 1.0, 0.0, 0.0, 0.0, 1.0, 0.0),) * 2)
     d, keep = B.desc_from_config(inside, B.LEAP_MODEL_SIDDON)
     assert host.leap_geometry_create(C.byref(d), C.byref(hnd)) == B.LEAP_BAD_GEOMETRY
+
+
+def test_host_memory_pipeline_rotates_buffers_and_chunks_correctly(host, monkeypatch):
+    """leap_project_host / leap_backproject_host against the device-pointer calls, with every asynchronous HIP call
+    of the pipeline carried out at once (the harness' stubs): 5 items through the two-deep buffer rotation, staging
+    buffers of 4 KiB so that every array takes many chunks with a ragged last one, both directions on one handle."""
+    monkeypatch.setenv("LEAP_DEBUG", "stage_kib=4")
+    cfg = reduced(config(3), 32, nviews=5).replace(nx=19, ny=17, nz=11, nrows=13, ncols=23)
+    batch = 5
+    x = np.stack([uniform_volume(cfg, 20 + b)[0] for b in range(batch)])
+    y = np.stack([uniform_sinogram(cfg, 40 + b)[0] for b in range(batch)])
+    h = handle(host, cfg)
+    ax_ref = np.zeros((batch,) + cfg.sino_shape, np.float32)
+    aty_ref = np.zeros((batch,) + cfg.vol_shape, np.float32)
+    B.leap_project(h, x.ctypes.data, ax_ref.ctypes.data, batch, 0, host)
+    B.leap_backproject(h, y.ctypes.data, aty_ref.ctypes.data, batch, 0, host)
+    ax = np.full_like(ax_ref, np.nan)
+    aty = np.full_like(aty_ref, np.nan)
+    B.leap_project_host(h, x.ctypes.data, ax.ctypes.data, batch, host)
+    B.leap_backproject_host(h, y.ctypes.data, aty.ctypes.data, batch, host)      # arrays of the other sizes on the same handle
+    one = np.full(cfg.sino_shape, np.nan, np.float32)
+    B.leap_project_host(h, x[3].ctypes.data, one.ctypes.data, 1, host)
+    with pytest.raises(B.LeapError):
+        B.leap_project_host(h, x.ctypes.data, x.ctypes.data, 1, host)
+    with pytest.raises(B.LeapError):
+        B.leap_project_host(h, x.ctypes.data, ax.ctypes.data, 0, host)
+    B.leap_geometry_destroy(h, host)
+    assert np.array_equal(ax, ax_ref) and np.array_equal(aty, aty_ref) and np.array_equal(one, ax_ref[3])
