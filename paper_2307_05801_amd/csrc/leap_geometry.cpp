@@ -334,6 +334,75 @@ static void select_siddon_fast_kernels(leap_geometry *G)
     }
 }
 
+// Is the convex polygon {rect} cut by the half-planes a u + b v + c >= 0 non-empty?  (Sutherland-Hodgman; a polygon
+// that shrinks to a point or a segment still counts.)
+static bool rectangle_meets(double u0, double u1, double v0, double v1, const double (*planes)[3], int nplanes)
+{
+    std::vector<std::pair<double, double>> poly = {{u0, v0}, {u1, v0}, {u1, v1}, {u0, v1}}, next;
+    for (int p = 0; p < nplanes && !poly.empty(); ++p) {
+        next.clear();
+        const double a = planes[p][0], b = planes[p][1], c = planes[p][2];
+        for (size_t q = 0; q < poly.size(); ++q) {
+            const auto &A = poly[q], &B = poly[(q + 1) % poly.size()];
+            const double fa = a * A.first + b * A.second + c, fb = a * B.first + b * B.second + c;
+            if (fa >= 0.0) next.push_back(A);
+            if ((fa >= 0.0) != (fb >= 0.0)) {
+                const double t = fa / (fa - fb);
+                next.push_back({A.first + t * (B.first - A.first), A.second + t * (B.second - A.second)});
+            }
+        }
+        poly.swap(next);
+    }
+    return !poly.empty();
+}
+
+// Siddon model on tilted modules: can the per-lane slab kernels serve the scan?  They need every ray to rise by less
+// than one axial cell per slab along its faster in-plane axis (kappa |Dz| <= limit * max(|Dx|, |Dy|), kappa = T / Tz;
+// D is affine in the detector coordinates, so the rays that break it fill a convex polygon of the detector per sign of
+// Dz), and every source more than a voxel away from the volume's box.
+static bool tilted_rays_stay_flat(const leap_geometry *G, double limit)
+{
+    const leap_geometry_desc *d = &G->desc;
+    const SfGeom &g = G->g;
+    const double kappa = d->voxel_xy / d->voxel_z;
+    const double u0 = (0.0 - g.col_offd) * g.pu_d, u1 = ((double)(d->ncols - 1) - g.col_offd) * g.pu_d;
+    const double v0 = g.v0d, v1 = g.v0d + (double)(d->nrows - 1) * g.pvd;
+    const double half[3] = {0.5 * d->nx * d->voxel_xy + d->voxel_xy, 0.5 * d->ny * d->voxel_xy + d->voxel_xy,
+                            0.5 * d->nz * d->voxel_z + d->voxel_z};
+    const double ctr[3] = {d->center_x, d->center_y, d->center_z};
+    for (const MdPose &P : G->poses) {
+        bool clear = false;
+        for (int q = 0; q < 3; ++q) clear = clear || std::fabs(P.S[q] - ctr[q]) > half[q];
+        if (!clear) return false;
+        for (int sign = -1; sign <= 1; sign += 2) {
+            double planes[4][3];
+            for (int h = 0; h < 4; ++h) {
+                const int axis = h >> 1;                       // 0: x, 1: y
+                const double w = (h & 1) ? limit : -limit;     // sign kappa Dz -+ limit D_axis >= 0
+                planes[h][0] = sign * kappa * P.ucol[2] + w * P.ucol[axis];
+                planes[h][1] = sign * kappa * P.vrow[2] + w * P.vrow[axis];
+                planes[h][2] = sign * kappa * (P.C[2] - P.S[2]) + w * (P.C[axis] - P.S[axis]);
+            }
+            if (rectangle_meets(u0, u1, v0, v1, planes, 4)) return false;
+        }
+    }
+    return true;
+}
+
+// Siddon model, scans with tilted modules: the per-lane forward kernel on the slab scratch.
+static void select_tilted_siddon_kernels(leap_geometry *G)
+{
+    const leap_geometry_desc *d = &G->desc;
+    long v;
+    if (debug_option("general", v) && v == 1) return;
+    if (d->nrows < 32 || !tilted_rays_stay_flat(G, 0.999)) return;
+    G->md_tilted = true;
+    G->sd_columns = true;
+    static const int single_groups[] = {1, 2, 4};
+    G->fp_rg = row_groups(d->nrows, 64, single_groups, 3);
+    block_order_options(G);
+}
+
 // Picks the kernels of a validated scan (circular scanners, or modular scans made of upright modules).
 static void select_fast_kernels(leap_geometry *G)
 {
@@ -621,7 +690,10 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
     if (upright) {
         if (d->model == LEAP_MODEL_SIDDON) build_ray_table(G);
         select_fast_kernels(G);
-    } else if (d->model == LEAP_MODEL_SF) {
+    } else if (d->model == LEAP_MODEL_SIDDON) {
+        select_tilted_siddon_kernels(G);
+    }
+    if (!upright && d->model == LEAP_MODEL_SF) {
         G->mfviews.resize(d->nviews);
         for (int a = 0; a < d->nviews; ++a) {
             const MdPose &P = G->poses[a];
@@ -765,7 +837,7 @@ extern "C" int leap_geometry_describe(const leap_geometry *G, char *buf, int32_t
                       G->bp_need_w, G->bp_need_h);
     else
         std::snprintf(back, sizeof back, "general");
-    const char *modules = G->g.type != SF_MODULAR ? "" : (G->geoms.empty() ? " (tilted modules: one thread per ray / per voxel)" : " (upright modules)");
+    const char *modules = G->g.type != SF_MODULAR ? "" : (G->geoms.empty() ? " (tilted modules)" : " (upright modules)");
     std::snprintf(buf, (size_t)cap, "type=%d model=%s A=%s AT=%s scratch=%zu%s cols/voxel<=%.2f rows/voxel<=%.2f voxels/row<=%.2f%s%s",
                   G->g.type, siddon ? "siddon" : "sf", fwd, back, G->scratch_bytes, modules, G->max_cols_per_voxel,
                   G->max_rows_per_voxel, G->max_voxels_per_row, G->note.empty() ? "" : " note=", G->note.c_str());

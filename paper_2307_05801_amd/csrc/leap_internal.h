@@ -70,6 +70,7 @@ struct leap_geometry {
     mutable LeapHostStage *host_stage = nullptr;
     mutable std::mutex host_mutex;
     size_t stage_chunk = (size_t)32 << 20;   // bytes per pinned staging buffer
+    bool md_tilted = false;             // Siddon model on tilted modules: the per-lane variants of the two fast kernels
     bool sd_columns = false;            // wave-per-column forward kernel (needs the scratch copy and slope <= 1)
 };
 

@@ -9,6 +9,7 @@
 #include "sf_backproject_tiled.h"
 #include "sf_project_columns.h"
 #include "sd_project_columns.h"
+#include "md_project_columns.h"
 #include "sd_backproject_tiled.h"
 
 // ------------------------------------------------------------------------------------------------
@@ -180,7 +181,12 @@ static void launch_sd_columns(const leap_geometry *G, const FwdScratch &S, const
     const int tiles_per_xcd_pad = (int)cdiv(cdiv(col_tiles, 8), tb) * tb;
     const unsigned zero_col = (unsigned)(S.item_floats - (size_t)G->nzp);      // the copy's last column stays zero
     dim3 grid((unsigned)(8 * tiles_per_xcd_pad * views_pad * bands), (unsigned)items, 1);
-    if (g.type == SF_MODULAR)
+    if (G->md_tilted) {
+        if constexpr (RG <= 4)        // (the selection offers the per-lane kernel 1, 2 or 4 row groups)
+            hipLaunchKernelGGL((md_project_columns<RG, SD_WAVES>), grid, dim3(SD_WAVES * 64, 1, 1), 0, stream, g,
+                               (const MdPose *)G->d_poses, S.volz, d_sino, G->nzp, S.item_floats, zero_col, col_tiles, bands, vb, tb,
+                               views_pad, tiles_per_xcd_pad, slab);
+    } else if (g.type == SF_MODULAR)
         hipLaunchKernelGGL((sd_project_columns<RG, SD_WAVES, true>), grid, dim3(SD_WAVES * 64, 1, 1), 0, stream, g, G->d_raycols,
                            S.volz, d_sino, G->nzp, S.item_floats, zero_col, col_tiles, bands, vb, tb, views_pad, tiles_per_xcd_pad,
                            slab, (const SfGeom *)G->d_geoms);

@@ -17,6 +17,7 @@
 #define SF_NO_KERNELS
 #include "../../paper_2307_05801_amd/csrc/sf_backproject_tiled.h"
 #include "../../paper_2307_05801_amd/csrc/sf_project_columns.h"
+#include "../../paper_2307_05801_amd/csrc/md_project_columns.h"
 
 // ---- stubs of the HIP runtime calls made by leap_geometry.cpp: "device" memory is host memory ---------------
 extern "C" {
@@ -391,5 +392,52 @@ extern "C" long host_sd_project_columns(const leap_geometry *G, const float *vol
                 sino[((size_t)a * g.nrows + r) * g.ncols + c] = sd_ray_length(R, vr) * acc;
             }
         }
+    return bad;
+}
+
+// ---- Siddon model on tilted modules: the per-lane forward kernel, slab by slab, with the kernel's own functions ---------
+// Returns -1 when the handle does not use that kernel, else the number of samples that came out non-finite (the slab
+// copies sit between guard bands of NaN, so a gather outside a copy shows).
+extern "C" long host_md_project_columns(const leap_geometry *G, const float *vol, float *sino, int width)
+{
+    const SfGeom &g = G->g;
+    if (!G->md_tilted) return -1;
+    const int nzp = g.nz + 2 * FP_PAD;
+    const size_t guard = 4096;
+    std::vector<float> acc((size_t)g.nviews * g.nrows * g.ncols, 0.f);
+    for (int xmajor = 1; xmajor >= 0; --xmajor) {
+        const int n_major = xmajor ? g.nx : g.ny, n_side = xmajor ? g.ny : g.nx;
+        for (int n0 = 0; n0 < n_major; n0 += width) {
+            const int n1 = std::min(n0 + width, n_major);
+            const SfSlab slab = {n0, n1, xmajor, n0 == 0 ? 1 : 0, width};
+            const size_t columns = (size_t)width * n_side;
+            std::vector<float> buf(2 * guard + (columns + 1) * nzp, NAN);
+            float *volz = buf.data() + guard;
+            std::fill(volz, volz + (columns + 1) * nzp, 0.f);
+            for (int n = n0; n < n1; ++n)
+                for (int q = 0; q < n_side; ++q) {
+                    const int i = xmajor ? n : q, j = xmajor ? q : n;
+                    float *col = volz + (size_t)sf_slab_column(slab, g.nx, i, j) * nzp + FP_PAD;
+                    for (int k = 0; k < g.nz; ++k) col[k] = vol[((size_t)k * g.ny + j) * g.nx + i];
+                }
+            const unsigned zero_col = (unsigned)(columns * nzp);
+#pragma omp parallel for collapse(2)
+            for (int a = 0; a < g.nviews; ++a)
+                for (int r = 0; r < g.nrows; ++r)
+                    for (int c = 0; c < g.ncols; ++c) {
+                        const MdSlabRay M = md_slab_ray(g, G->poses[a], r, c);
+                        const MdAxial A = md_axial(M);
+                        const bool mine = M.R.xmajor == xmajor;
+                        float t = 0.f;
+                        for (int n = n0; n < n1; ++n) t = md_slab_step(g, M, A, n, slab, volz, nzp, zero_col, mine, t);
+                        if (mine) acc[((size_t)a * g.nrows + r) * g.ncols + c] += M.len * t;
+                    }
+        }
+    }
+    long bad = 0;
+    for (size_t q = 0; q < acc.size(); ++q) {
+        sino[q] = acc[q];
+        bad += !std::isfinite(acc[q]);
+    }
     return bad;
 }
