@@ -76,7 +76,7 @@ def siddon_flops_per_update(cfg) -> tuple:
     2 ln(2)/pi... taken as 0.44 over a full turn, |m_z| as a quarter of the cone's half angle slope), and there are
     nrows*ncols rays per view against ny*nz voxel columns per slab.  Returns (flops per update, nonzeros per update)."""
     rays_per_column = (cfg.nrows * cfg.ncols) / float(cfg.ny * cfg.nz)
-    mz = 0.0 if cfg.geom != 2 else 0.25 * (0.5 * cfg.nrows * cfg.pixel_v / cfg.sdd) * cfg.voxel_xy / cfg.voxel_z
+    mz = 0.0 if cfg.geom not in (2, 4) else 0.25 * (0.5 * cfg.nrows * cfg.pixel_v / cfg.sdd) * cfg.voxel_xy / cfg.voxel_z
     per_slab = 1.0 + 0.44 + mz
     return rays_per_column * (10.0 + 3.0 * per_slab), rays_per_column * per_slab
 
@@ -140,6 +140,9 @@ def main() -> int:
                     help="projector model: sf = separable footprint (the headline), siddon = thin rays")
     ap.add_argument("--detector", choices=["flat", "curved"], default="flat",
                     help="cone-beam cases only: flat panel (the headline) or cylindrical detector of the same pixel pitch")
+    ap.add_argument("--tilted-modules", type=float, default=0.0, metavar="RAD",
+                    help="cone-beam cases only: the same scan as a modular geometry whose every source and detector is moved "
+                         "by up to 5 mm and whose every module is turned by up to RAD about each of its axes (seeded)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="CPU time budget of the oracle baseline; 0 skips it")
     ap.add_argument("--no-transfer-leg", action="store_true",
                     help="skip the extra leg that times the host-memory entry points (upload + run + download)")
@@ -164,6 +167,12 @@ def main() -> int:
             print("bench.py: --detector curved needs a cone-beam case", file=sys.stderr)
             return 2
         cfg = cfg.replace(geom=3, name=cfg.name + "_curved")
+    if args.tilted_modules > 0.0:
+        if cfg.geom != 2:
+            print("bench.py: --tilted-modules needs a flat-panel cone-beam case", file=sys.stderr)
+            return 2
+        from synthetic import perturbed_poses
+        cfg = perturbed_poses(cfg, 3, shift_mm=5.0, tilt_rad=args.tilted_modules)
     batch = cfg.batch
     x_np = np.stack([standard_volume(args.config, cfg, item=b) for b in range(batch)])
     torch.cuda.synchronize()

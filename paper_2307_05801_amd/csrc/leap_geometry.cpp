@@ -12,6 +12,8 @@
 #define SF_NO_KERNELS   // this file needs the kernels' host-side limit functions only
 #include "sf_backproject_tiled.h"
 #include "sf_project_columns.h"
+#include "md_backproject_tiled.h"
+#include <thread>
 #include "sd_backproject_tiled.h"
 
 static thread_local std::string g_last_error;
@@ -389,18 +391,114 @@ static bool tilted_rays_stay_flat(const leap_geometry *G, double limit)
     return true;
 }
 
-// Siddon model, scans with tilted modules: the per-lane forward kernel on the slab scratch.
+// Siddon model on tilted modules, tiled back projection: largest window any (view, tile, z-chunk) asks for (every chunk
+// counts: a tilted module's windows are not extreme at the ends of the volume only).  The corners of all those boxes are
+// the points of one lattice, so each view projects the lattice once and every window takes the extremes of its eight
+// corners; the kernel's own function forms the same corners by increments and may round apart in the last place, which
+// the spare row and column of the fit test absorb.  The views are shared out among a few threads.
+static void tilted_window_need(const leap_geometry *G, const std::vector<MdBpView> &views, int zc, int &need_w, int &need_h)
+{
+    const leap_geometry_desc *d = &G->desc;
+    const SfGeom &g = G->g;
+    const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T, chunks = (d->nz + zc - 1) / zc;
+    const int lx = tiles_x + 1, ly = tiles_y + 1, lz = chunks + 1;
+    const int workers = (int)std::max<size_t>(1, std::min<size_t>(8, views.size() / 8));
+    std::vector<int> w(workers, 0), h(workers, 0);
+    auto scan = [&](int t) {
+        std::vector<float> xi((size_t)lx * ly * lz), eta(xi.size());
+        float ew = 0.0f, eh = 0.0f;             // widest and tallest shadow; a window holds at most that many pixel centres + 1.04
+        for (size_t a = t; a < views.size(); a += workers) {
+            const MdBpView &V = views[a];
+            for (int iz = 0; iz < lz; ++iz)
+                for (int iy = 0; iy < ly; ++iy)
+                    for (int ix = 0; ix < lx; ++ix) {
+                        const float dx = fmaf((float)(ix * BP_T), g.T, V.dlo[0]), dy = fmaf((float)(iy * BP_T), g.T, V.dlo[1]);
+                        const float dz = fmaf((float)(iz * zc), g.Tz, V.dlo[2]);
+                        const float inv = 1.0f / fmaf(dx, V.nrm[0], fmaf(dy, V.nrm[1], dz * V.nrm[2]));
+                        const size_t o = ((size_t)iz * ly + iy) * lx + ix;
+                        xi[o] = fmaf(fmaf(dx, V.euP[0], fmaf(dy, V.euP[1], dz * V.euP[2])), inv, V.xi0);
+                        eta[o] = fmaf(fmaf(dx, V.evP[0], fmaf(dy, V.evP[1], dz * V.evP[2])), inv, V.eta0);
+                    }
+            for (int iz = 0; iz < chunks; ++iz)
+                for (int iy = 0; iy < tiles_y; ++iy)
+                    for (int ix = 0; ix < tiles_x; ++ix) {
+                        float a0 = 3.0e38f, a1 = -3.0e38f, b0 = 3.0e38f, b1 = -3.0e38f;
+                        for (int q = 0; q < 8; ++q) {
+                            const size_t o = ((size_t)(iz + (q >> 2)) * ly + iy + ((q >> 1) & 1)) * lx + ix + (q & 1);
+                            const float u = xi[o], v = eta[o];
+                            a0 = u < a0 ? u : a0; a1 = u > a1 ? u : a1;
+                            b0 = v < b0 ? v : b0; b1 = v > b1 ? v : b1;
+                        }
+                        ew = a1 - a0 > ew ? a1 - a0 : ew;
+                        eh = b1 - b0 > eh ? b1 - b0 : eh;
+                        if (!(a1 - a0 < 1.0e6f && b1 - b0 < 1.0e6f)) ew = eh = 1.0e6f;      // NaN or absurd: no instance fits
+                    }
+        }
+        w[t] = sf_f2i(floorf(ew + 1.04f));
+        h[t] = sf_f2i(floorf(eh + 1.04f));
+    };
+    std::vector<std::thread> pool;
+    for (int t = 1; t < workers; ++t) pool.emplace_back(scan, t);
+    scan(0);
+    for (auto &th : pool) th.join();
+    need_w = *std::max_element(w.begin(), w.end());
+    need_h = *std::max_element(h.begin(), h.end());
+}
+
+// Siddon model, scans with tilted modules: the per-lane variants of the two fast kernels.
 static void select_tilted_siddon_kernels(leap_geometry *G)
 {
     const leap_geometry_desc *d = &G->desc;
     long v;
     if (debug_option("general", v) && v == 1) return;
-    if (d->nrows < 32 || !tilted_rays_stay_flat(G, 0.999)) return;
-    G->md_tilted = true;
-    G->sd_columns = true;
-    static const int single_groups[] = {1, 2, 4};
-    G->fp_rg = row_groups(d->nrows, 64, single_groups, 3);
-    block_order_options(G);
+    if (d->nrows >= 32 && tilted_rays_stay_flat(G, 0.999)) {        // forward projection on the slab scratch
+        G->md_tilted = true;
+        G->sd_columns = true;
+        static const int single_groups[] = {1, 2, 4};
+        G->fp_rg = row_groups(d->nrows, 64, single_groups, 3);
+        block_order_options(G);
+    }
+    // Tiled back projection.  Its rays are marched along the TILE's faster in-plane axis: a ray through a tile whose
+    // centre lies c_maj from the source along that axis has |d_maj| >= c_maj - 8 T and max(|dx|, |dy|) <= c_maj + 8 T, so
+    // a rise of at most 0.8 cells per slab along the ray's own axis stays below one cell along the tile's if
+    // c_maj >= 72 T, which an in-plane distance of 102 T between source and volume guarantees.
+    if (d->nz < 8 || !((double)d->nrows * d->ncols < 1073741824.0) || !tilted_rays_stay_flat(G, 0.8)) return;
+    const double half[3] = {0.5 * d->nx * d->voxel_xy, 0.5 * d->ny * d->voxel_xy, 0.5 * d->nz * d->voxel_z};
+    const double ctr[3] = {d->center_x, d->center_y, d->center_z};
+    for (const MdPose &P : G->poses) {
+        const double ox = std::fmax(std::fabs(P.S[0] - ctr[0]) - half[0], 0.0), oy = std::fmax(std::fabs(P.S[1] - ctr[1]) - half[1], 0.0);
+        if (!(std::hypot(ox, oy) >= 102.0 * d->voxel_xy)) return;
+        const double n[3] = {P.ucol[1] * P.vrow[2] - P.ucol[2] * P.vrow[1], P.ucol[2] * P.vrow[0] - P.ucol[0] * P.vrow[2],
+                             P.ucol[0] * P.vrow[1] - P.ucol[1] * P.vrow[0]};
+        const double gap = (P.C[0] - P.S[0]) * n[0] + (P.C[1] - P.S[1]) * n[1] + (P.C[2] - P.S[2]) * n[2];
+        for (int corner = 0; corner < 8; ++corner) {                // the whole volume in front of the source
+            double along = 0.0;
+            for (int q = 0; q < 3; ++q) along += (ctr[q] + ((corner >> q) & 1 ? half[q] : -half[q]) - P.S[q]) * n[q];
+            if (!(along * gap > 0.0) || !(std::fabs(along) > 1e-3 * std::fabs(gap))) return;
+        }
+    }
+    std::vector<MdBpView> views;
+    views.reserve(G->poses.size());
+    for (const MdPose &P : G->poses) views.push_back(md_bp_view(G->g, P));
+    long first_shape = 0;
+    if (debug_option("bp_shape", first_shape)) first_shape = ((first_shape % MD_BP_NSHAPES) + MD_BP_NSHAPES) % MD_BP_NSHAPES;
+    bool fits = false;
+    for (int sh = (int)first_shape; sh < MD_BP_NSHAPES && !fits; ++sh) {
+        tilted_window_need(G, views, MD_BP_SHAPES[sh].zc, G->bp_need_w, G->bp_need_h);
+        G->bp_shape = sh;
+        fits = G->bp_need_w <= MD_BP_SHAPES[sh].pw - 1 && G->bp_need_h <= MD_BP_SHAPES[sh].ph - 1;
+    }
+    if (!fits) return;
+    hipError_t e = hipMalloc((void **)&G->d_mdbp, sizeof(MdBpView) * views.size());
+    if (e == hipSuccess) e = hipMemcpy(G->d_mdbp, views.data(), sizeof(MdBpView) * views.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        if (G->d_mdbp) (void)hipFree(G->d_mdbp);
+        G->d_mdbp = nullptr;
+        (void)hipGetLastError();
+        G->note = "table allocation failed: back projection runs on the general kernel";
+        return;
+    }
+    G->bp_tiled = true;
 }
 
 // Picks the kernels of a validated scan (circular scanners, or modular scans made of upright modules).
@@ -506,6 +604,7 @@ static void free_handle(leap_geometry *G)
     if (G->d_poses) (void)hipFree(G->d_poses);
     if (G->d_geoms) (void)hipFree(G->d_geoms);
     if (G->d_mfviews) (void)hipFree(G->d_mfviews);
+    if (G->d_mdbp) (void)hipFree(G->d_mdbp);
     if (G->d_colcs) (void)hipFree(G->d_colcs);
     if (G->scratch_event) (void)hipEventDestroy(G->scratch_event);
     delete G;
@@ -830,7 +929,9 @@ extern "C" int leap_geometry_describe(const leap_geometry *G, char *buf, int32_t
                       G->fp_rg, G->fp_cw, G->slab_width);
     else
         std::snprintf(fwd, sizeof fwd, "general");
-    if (G->bp_tiled && siddon)
+    if (G->bp_tiled && G->d_mdbp)
+        std::snprintf(back, sizeof back, "tiled(zc=%d,window=%dx%d)", MD_BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h);
+    else if (G->bp_tiled && siddon)
         std::snprintf(back, sizeof back, "tiled(nc=%d,zc=%d,window=%dx%d)", G->bp_nc, BP_SHAPES[G->bp_shape].zc, G->bp_need_w, G->bp_need_h);
     else if (G->bp_tiled)
         std::snprintf(back, sizeof back, "tiled(nc=%d,nv=%d,zc=%d,window=%dx%d)", G->bp_nc, G->bp_nv, BP_SHAPES[G->bp_shape].zc,

@@ -13,6 +13,7 @@
 #include "md_siddon.h"
 #include "md_footprint.h"
 
+struct MdBpView;                       // per-view table of the tiled Siddon back projection on tilted modules (md_backproject_tiled.h)
 struct LeapHostStage;                  // streams, events, staging and device buffers of the host-memory entry points (leap_host.cpp)
 
 struct leap_geometry {
@@ -70,6 +71,7 @@ struct leap_geometry {
     mutable LeapHostStage *host_stage = nullptr;
     mutable std::mutex host_mutex;
     size_t stage_chunk = (size_t)32 << 20;   // bytes per pinned staging buffer
+    MdBpView *d_mdbp = nullptr;         // Siddon model on tilted modules, tiled back projection: its per-view table
     bool md_tilted = false;             // Siddon model on tilted modules: the per-lane variants of the two fast kernels
     bool sd_columns = false;            // wave-per-column forward kernel (needs the scratch copy and slope <= 1)
 };

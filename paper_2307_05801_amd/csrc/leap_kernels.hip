@@ -11,6 +11,7 @@
 #include "sd_project_columns.h"
 #include "md_project_columns.h"
 #include "sd_backproject_tiled.h"
+#include "md_backproject_tiled.h"
 
 // ------------------------------------------------------------------------------------------------
 // General kernels: plain loop nests over global memory, valid for every validated geometry.
@@ -257,10 +258,31 @@ static bool launch_sd_shape(const leap_geometry *G, const float *d_sino, float *
     }
 }
 
+template <int SH>
+static void launch_md_tiled(const leap_geometry *G, const float *d_sino, float *d_vol, hipStream_t stream, int items)
+{
+    constexpr SfBpShape S = MD_BP_SHAPES[SH];
+    const SfGeom &g = G->g;
+    const unsigned tiles_x = cdiv(g.nx, BP_T), tiles_y = cdiv(g.ny, BP_T);
+    dim3 grid(tiles_x * tiles_y, cdiv(g.nz, S.zc), (unsigned)items);
+    hipLaunchKernelGGL((md_backproject_tiled<S.zc, S.pw, S.ph>), grid, dim3(256, 1, 1), 0, stream, g, (const MdBpView *)G->d_mdbp,
+                       d_sino, d_vol, (int)tiles_x);
+}
+
 // The tiled Siddon back projection on `items` consecutive sinograms of a batch in one launch.
 static int launch_sd_bp_items(const leap_geometry *G, const float *d_sino, float *d_vol, int items, hipStream_t stream)
 {
     bool ok = false;
+    if (G->md_tilted || G->d_mdbp) {
+        switch (G->d_mdbp ? G->bp_shape : -1) {
+        case 0: launch_md_tiled<0>(G, d_sino, d_vol, stream, items); ok = true; break;
+        case 1: launch_md_tiled<1>(G, d_sino, d_vol, stream, items); ok = true; break;
+        case 2: launch_md_tiled<2>(G, d_sino, d_vol, stream, items); ok = true; break;
+        case 3: launch_md_tiled<3>(G, d_sino, d_vol, stream, items); ok = true; break;
+        case 4: launch_md_tiled<4>(G, d_sino, d_vol, stream, items); ok = true; break;
+        default: break;
+        }
+    } else
     switch (G->bp_nc) {
     case 2: ok = launch_sd_shape<2>(G, d_sino, d_vol, stream, items); break;
     case 3: ok = launch_sd_shape<3>(G, d_sino, d_vol, stream, items); break;

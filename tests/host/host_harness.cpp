@@ -18,6 +18,7 @@
 #include "../../paper_2307_05801_amd/csrc/sf_backproject_tiled.h"
 #include "../../paper_2307_05801_amd/csrc/sf_project_columns.h"
 #include "../../paper_2307_05801_amd/csrc/md_project_columns.h"
+#include "../../paper_2307_05801_amd/csrc/md_backproject_tiled.h"
 
 // ---- stubs of the HIP runtime calls made by leap_geometry.cpp: "device" memory is host memory ---------------
 extern "C" {
@@ -440,4 +441,80 @@ extern "C" long host_md_project_columns(const leap_geometry *G, const float *vol
         bad += !std::isfinite(acc[q]);
     }
     return bad;
+}
+
+// ---- Siddon model on tilted modules: the tiled back projection, tile by tile, with the kernel's own functions ------------
+// report[0]: (view, tile, chunk) windows wider or taller than the instance stages; report[1]: reads outside the staged
+// window; report[2]: slots outside the per-thread sums.  Returns -1 when the handle does not use that kernel.
+template <int ZC, int PW, int PH>
+static void host_md_bp_shape(const leap_geometry *G, const float *sino, float *vol, int64_t *report)
+{
+    const SfGeom &g = G->g;
+    constexpr int PS = PW + 1, NSLOT = ZC + 4;
+    const int tiles_x = (g.nx + BP_T - 1) / BP_T, tiles_y = (g.ny + BP_T - 1) / BP_T, chunks = (g.nz + ZC - 1) / ZC;
+    int64_t wide = 0, outside = 0, badslot = 0;
+#pragma omp parallel for collapse(2) reduction(+ : wide, outside, badslot)
+    for (int ch = 0; ch < chunks; ++ch)
+        for (int tile = 0; tile < tiles_x * tiles_y; ++tile) {
+            const int i0 = (tile % tiles_x) * BP_T, j0 = (tile / tiles_x) * BP_T, k0 = ch * ZC;
+            std::vector<float> sums((size_t)NSLOT * 256, 0.f);
+            std::vector<MdBpPixel> px((size_t)PH * PS);
+            for (int a = 0; a < g.nviews; ++a) {
+                const MdBpView &V = G->d_mdbp[a];
+                const SfWindow win = md_bp_window(g, V, i0, j0, k0, ZC);
+                wide += win.need_w > PW || win.need_h > PH;
+                const bool xmajor = md_bp_tile_xmajor(g, V, i0, j0);
+                for (int sc = 0; sc < PW; ++sc) {
+                    const int c = win.c0 + sc;
+                    for (int row = 0; row < PH; ++row) {
+                        const int r = win.r0 + row;
+                        const bool in = c >= 0 && c < g.ncols && r >= 0 && r < g.nrows;
+                        const float y = in ? sino[((size_t)a * g.nrows + r) * g.ncols + c] : 0.f;
+                        px[(size_t)row * PS + sc] = md_bp_pixel(md_bp_slopes(g, V, xmajor, r, c), y);
+                    }
+                }
+                const int H = std::min(win.need_h, PH);
+                for (int tid = 0; tid < 256; ++tid) {
+                    const int i = i0 + (tid & (BP_T - 1)), j = j0 + (tid >> 4);
+                    const int ic = std::min(i, g.nx - 1), jc = std::min(j, g.ny - 1);
+                    const MdBpColumn C = md_bp_column<ZC>(g, V, xmajor, ic, jc, k0);
+                    for (int c = C.cfirst; c <= C.clast; ++c) {
+                        const int wc = c - win.c0;
+                        if (c < 0 || c >= g.ncols || wc < 0 || wc >= PW) continue;
+                        int rs, re;
+                        md_bp_rows(C, c, win.r0, H, rs, re);
+                        for (int row = rs; row < re; ++row) {
+                            if (row < 0 || row >= PH) { ++outside; continue; }
+                            int slot;
+                            float w_low, w_high;
+                            if (!md_bp_row<ZC>(C, px[(size_t)row * PS + wc], slot, w_low, w_high)) continue;
+                            if (slot < 0 || slot + 1 >= NSLOT) { ++badslot; continue; }
+                            sums[(size_t)slot * 256 + tid] += w_low;
+                            sums[(size_t)(slot + 1) * 256 + tid] += w_high;
+                        }
+                    }
+                }
+            }
+            for (int tid = 0; tid < 256; ++tid) {
+                const int i = i0 + (tid & (BP_T - 1)), j = j0 + (tid >> 4);
+                if (i >= g.nx || j >= g.ny) continue;
+                for (int kk = 0; kk < ZC && k0 + kk < g.nz; ++kk)
+                    vol[((size_t)(k0 + kk) * g.ny + j) * g.nx + i] = sums[(size_t)(kk + 2) * 256 + tid];
+            }
+        }
+    report[0] = wide; report[1] = outside; report[2] = badslot;
+}
+
+extern "C" long host_md_backproject_tiled(const leap_geometry *G, const float *sino, float *vol, int64_t *report)
+{
+    if (!G->d_mdbp || !G->bp_tiled) return -1;
+    switch (G->bp_shape) {
+    case 0: host_md_bp_shape<MD_BP_SHAPES[0].zc, MD_BP_SHAPES[0].pw, MD_BP_SHAPES[0].ph>(G, sino, vol, report); break;
+    case 1: host_md_bp_shape<MD_BP_SHAPES[1].zc, MD_BP_SHAPES[1].pw, MD_BP_SHAPES[1].ph>(G, sino, vol, report); break;
+    case 2: host_md_bp_shape<MD_BP_SHAPES[2].zc, MD_BP_SHAPES[2].pw, MD_BP_SHAPES[2].ph>(G, sino, vol, report); break;
+    case 3: host_md_bp_shape<MD_BP_SHAPES[3].zc, MD_BP_SHAPES[3].pw, MD_BP_SHAPES[3].ph>(G, sino, vol, report); break;
+    case 4: host_md_bp_shape<MD_BP_SHAPES[4].zc, MD_BP_SHAPES[4].pw, MD_BP_SHAPES[4].ph>(G, sino, vol, report); break;
+    default: return -1;
+    }
+    return report[0] + report[1] + report[2];
 }
