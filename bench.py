@@ -10,6 +10,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import re
 import os
 import sys
 import time
@@ -227,6 +228,8 @@ def main() -> int:
         fl = algorithmic_flops_per_update(n_u, n_v, cfg.nz)
         nnz_per_update = n_u * n_v
     describe = geo.describe()
+    found = re.search(r"scratch=(\d+)", describe)
+    scratch_bytes = int(found.group(1)) if found else None      # device memory the handle owns beyond its tables
     flops_call = fl * batch * cfg.voxel_views
     alg_bytes = 4.0 * batch * (cfg.nx * cfg.ny * cfg.nz + cfg.nviews * cfg.nrows * cfg.ncols)
     workload = cfg.name if args.model == "sf" else cfg.name + ":" + args.model
@@ -285,6 +288,7 @@ def main() -> int:
         "A_updates_per_s": per_op["A"]["updates_per_s"], "AT_updates_per_s": per_op["AT"]["updates_per_s"],
         "nnz_per_update": nnz_per_update,
         "geometry_create_ms": create_ms,
+        "scratch_bytes": scratch_bytes,
         "roofline": roofline,
         "operators": per_op,
     }

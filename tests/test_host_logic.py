@@ -80,6 +80,11 @@ CASES = {
     "tall_rows_7": (3, lambda: reduced(config(3), 8, nviews=12).replace(pixel_v=12.3, nrows=36, voxel_z=3.4, nz=70, shift_v=-0.4)),
     # rows under half a voxel tall: a pair stays within 2 voxels
     "short_rows_2": (3, lambda: reduced(config(3), 8, nviews=12).replace(pixel_v=2.3, nrows=200, voxel_z=4.0, nz=64)),
+    # the source barely clears the volume's bounding circle (27.6 mm) and nx, ny are no multiples of the tile edge: the
+    # padding voxels of the edge tiles reach past the source plane, where the window functions must stay defined
+    "source_grazing_ragged_volume": (3, lambda: CTConfig("grazing", CONE, nviews=11, arc_deg=360.0, nrows=40, ncols=150,
+                                                         pixel_v=1.5, pixel_u=1.5, nx=37, ny=41, nz=12, voxel_xy=1.0,
+                                                         voxel_z=1.0, sod=28.5, sdd=60.0, shift_u=0.4, start_deg=2.0)),
     "fan": (3, lambda: CTConfig("fan", FAN, nviews=20, arc_deg=360.0, nrows=1, ncols=90, pixel_v=1.0, pixel_u=2.0,
                                 nx=70, ny=64, nz=1, voxel_xy=1.0, voxel_z=1.0, sod=300.0, sdd=500.0, shift_u=0.8)),
 }
