@@ -54,7 +54,7 @@ SF_HD MdSlabRay md_slab_ray(const SfGeom &g, const MdPose &P, int r, int c)
 // Slab n lies wholly in front of the source.
 SF_HD bool md_slab_in_front(const MdSlabRay &M, int n) { return M.forward ? (double)n >= M.xs : (double)(n + 1) <= M.xs; }
 
-// Per-ray constants of the axial split, and one slab's contribution to a ray's sum.
+// Per-ray constants of the axial split.
 struct MdAxial {
     double zadj;         // Z at X = 0 of the lower end of a slab's piece, plus the pad of the scratch copy's z-columns
     float inv_amz;       // 1 / |dZ per slab|
@@ -72,40 +72,23 @@ SF_HD MdAxial md_axial(const MdSlabRay &M)
     return A;
 }
 
-// volz: the z-fastest copy of the slab (columns of nzp floats; column zero_col / nzp is all zero); live: the ray reads
-// this kind of slab.  Returns acc plus the slab's share, in units of X.
+// One slab's contribution to a ray's sum.  volz: the z-fastest copy of the slab (columns of nzp floats; column
+// zero_col / nzp is all zero); live: the ray reads this kind of slab.  Returns acc plus the slab's share, in units of X.
 SF_HD float md_slab_step(const SfGeom &g, const MdSlabRay &M, const MdAxial &A, int n, const SfSlab &slab,
                          const float *__restrict__ volz, int nzp, unsigned zero_col, bool live, float acc)
 {
-    const int n_minor = slab.xmajor ? g.ny : g.nx, kmax = nzp - 2;
+    const int n_minor = slab.xmajor ? g.ny : g.nx;
     const SdSplit s = sd_slab_split(M.R, n);
     live = live && md_slab_in_front(M, n);
     const bool a_ok = live && s.qa >= 0 && s.qa < n_minor;
     const bool b_ok = live && s.qa != s.qb && s.qb >= 0 && s.qb < n_minor;
     const unsigned base_a = a_ok ? sf_slab_column(slab, g.nx, slab.xmajor ? n : s.qa, slab.xmajor ? s.qa : n) * (unsigned)nzp : zero_col;
     const unsigned base_b = b_ok ? sf_slab_column(slab, g.nx, slab.xmajor ? n : s.qb, slab.xmajor ? s.qb : n) * (unsigned)nzp : zero_col;
-    const double zlo = fma((double)n, M.R.dh, A.zadj);
-    // lower axial cell, clamped into the copy (far outside it the ray reads the zero pads), and the fraction above its face
-#if defined(__HIP_DEVICE_COMPILE__)
-    const float fr = (float)__builtin_amdgcn_fract(zlo);
-    int kf = (int)zlo;                                           // the conversion saturates
-    asm("v_med3_i32 %0, %1, 0, %2" : "=v"(kf) : "v"(kf), "s"(kmax));
-#else
-    const float fr = (float)(zlo - floor(zlo));
-    const int kf = (int)fmin(fmax(zlo, 0.0), (double)kmax);
-#endif
-    const float *__restrict__ xa = volz + base_a + (unsigned)kf;
-    const float *__restrict__ xb = volz + base_b + (unsigned)kf;
-    const float s_f = s.f, s_omf = 1.0f - s.f;
-    const float tlow = fminf((1.0f - fr) * A.inv_amz, 1.0f);     // share of the slab spent in the lower axial cell
-    // rising rays are in the lower cell first (while still in in-plane cell a), falling rays last
-    const float p = fminf(A.inc ? s_f : s_omf, tlow), q = tlow - p;
-    const float a_low = A.inc ? p : q, b_low = A.inc ? q : p;
-    float t = acc;
-    t = fmaf(a_low, xa[0], t);
-    t = fmaf(s_f - a_low, xa[1], t);
-    t = fmaf(b_low, xb[0], t);
-    return fmaf(s_omf - b_low, xb[1], t);
+    int kf;
+    float tlow;
+    sd_axial_cell(fma((double)n, M.R.dh, A.zadj), A.inv_amz, nzp - 2, kf, tlow);
+    // (a slab without a crossing has f = 1 and reads the zero column for cell b: the same four terms serve both)
+    return sd_gather_two(volz + base_a + (unsigned)kf, volz + base_b + (unsigned)kf, A.inc, s.f, 1.0f - s.f, tlow, acc);
 }
 
 #if defined(__HIPCC__) && !defined(SF_NO_KERNELS)

@@ -17,6 +17,67 @@
 #include "sd_ray.h"
 #include "sf_project_columns.h"
 
+// ---- the axial part of a slab, shared by the kernel and by the host-side re-enactment of its arithmetic ---------------
+
+// Per ray (lane and row group): the row's v, the constant of its lower-Z map, 1 / |dZ per slab|, and the sign of dZ.
+struct SdAxial {
+    double vr, zadj;
+    float inv_amz;
+    bool inc;
+};
+
+SF_HD SdAxial sd_axial(const SfGeom &g, const SdRayCol &R, int r)
+{
+    SdAxial A;
+    A.vr = sd_row_v(g, r);
+    const double mz = A.vr * R.dh;
+    A.zadj = g.zk0d + (double)FP_PAD + fmin(mz, 0.0);     // Z of the lower end of the slab's piece, plus the copy's pad
+    const float amz = fabsf((float)mz);
+    A.inv_amz = amz > 1e-30f ? 1.0f / amz : 1e30f;
+    A.inc = mz >= 0.0;
+    return A;
+}
+
+// Lower axial cell of the slab's piece as an index into the padded z-column (clamped: far outside the column the ray
+// reads the zero pads), and the share of the slab spent in that cell.  zlo: Z of the piece's lower end, plus the pad.
+SF_HD void sd_axial_cell(double zlo, float inv_amz, int kmax, int &kf, float &tlow)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    const float fr = (float)__builtin_amdgcn_fract(zlo);
+    kf = (int)zlo;                                       // the conversion saturates
+    asm("v_med3_i32 %0, %1, 0, %2" : "=v"(kf) : "v"(kf), "s"(kmax));
+#else
+    const float fr = (float)(zlo - floor(zlo));
+    kf = (int)fmin(fmax(zlo, 0.0), (double)kmax);
+#endif
+    tlow = fminf((1.0f - fr) * inv_amz, 1.0f);
+}
+
+// The same for a ray of the circular scanners.  h: h(X) at the slab's entry face.
+SF_HD void sd_axial_place(const SdAxial &A, double h, int kmax, int &kf, float &tlow)
+{
+    sd_axial_cell(fma(A.vr, h, A.zadj), A.inv_amz, kmax, kf, tlow);
+}
+
+// A slab whose piece stays in one in-plane cell: xa points at the lower axial cell of that cell's z-column.
+SF_HD float sd_gather_one(const float *__restrict__ xa, float tlow, float acc)
+{
+    return fmaf(tlow, xa[0], fmaf(1.0f - tlow, xa[1], acc));
+}
+
+// A slab whose piece changes from in-plane cell a to b at tau = f (omf = 1 - f): rising rays are in the lower axial cell
+// first (while still in cell a), falling rays last.
+SF_HD float sd_gather_two(const float *__restrict__ xa, const float *__restrict__ xb, bool inc, float f, float omf, float tlow, float acc)
+{
+    const float p = fminf(inc ? f : omf, tlow), q = tlow - p;
+    const float a_low = inc ? p : q, b_low = inc ? q : p;
+    float t = acc;
+    t = fmaf(a_low, xa[0], t);
+    t = fmaf(f - a_low, xa[1], t);
+    t = fmaf(b_low, xb[0], t);
+    return fmaf(omf - b_low, xb[1], t);
+}
+
 #if defined(__HIPCC__) && !defined(SF_NO_KERNELS)
 
 // MOD: modular geometry with upright modules: the wave's view brings its own parameter block geoms[a] (the scene
@@ -60,18 +121,11 @@ __global__ __launch_bounds__(SD_WAVES * 64) void sd_project_columns(SfGeom gk, c
     const int n_minor = R.xmajor ? g.ny : g.nx;
     const int kmax = nzp - 2;
 
-    // per lane and row group: the row's v, the constant of its lower-Z map, 1/|dZ per slab|, and the sign of dZ
-    double vr[RG], zadj[RG];
-    float inv_amz[RG], acc[RG];
-    bool inc[RG];
+    SdAxial A[RG];
+    float acc[RG];
 #pragma unroll
     for (int gq = 0; gq < RG; ++gq) {
-        vr[gq] = sd_row_v(g, band0 + 64 * gq + lane);
-        const double mz = vr[gq] * R.dh;
-        zadj[gq] = g.zk0d + (double)FP_PAD + fmin(mz, 0.0);     // Z of the lower end of the slab's piece, plus the pad
-        const float amz = fabsf((float)mz);
-        inv_amz[gq] = amz > 1e-30f ? 1.0f / amz : 1e30f;
-        inc[gq] = mz >= 0.0;
+        A[gq] = sd_axial(g, R, band0 + 64 * gq + lane);
         acc[gq] = 0.0f;
     }
 
@@ -94,40 +148,24 @@ __global__ __launch_bounds__(SD_WAVES * 64) void sd_project_columns(SfGeom gk, c
         for (int e = 0; e < count; ++e) {
             const double s_h = __hiloint2double(__builtin_amdgcn_readlane(h_hi, e), __builtin_amdgcn_readlane(h_lo, e));
             const float s_f = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, f), e));
-            const char *__restrict__ col_a =
-                reinterpret_cast<const char *>(volz + (unsigned)__builtin_amdgcn_readlane((int)base_a, e));
+            const float *__restrict__ col_a = volz + (unsigned)__builtin_amdgcn_readlane((int)base_a, e);
             if ((cross >> e) & 1ull) {
                 const float s_omf = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, omf), e));
-                const char *__restrict__ col_b =
-                    reinterpret_cast<const char *>(volz + (unsigned)__builtin_amdgcn_readlane((int)base_b, e));
+                const float *__restrict__ col_b = volz + (unsigned)__builtin_amdgcn_readlane((int)base_b, e);
 #pragma unroll
                 for (int gq = 0; gq < RG; ++gq) {
-                    const double zlo = fma(vr[gq], s_h, zadj[gq]);
-                    const float fr = (float)__builtin_amdgcn_fract(zlo);
-                    int kf = (int)zlo;
-                    asm("v_med3_i32 %0, %1, 0, %2" : "=v"(kf) : "v"(kf), "s"(kmax));
-                    const float *__restrict__ xa = reinterpret_cast<const float *>(col_a + ((unsigned)kf << 2));
-                    const float *__restrict__ xb = reinterpret_cast<const float *>(col_b + ((unsigned)kf << 2));
-                    const float tlow = fminf((1.0f - fr) * inv_amz[gq], 1.0f);   // share of the slab spent in the lower cell
-                    // rising rays are in the lower cell first (while still in in-plane cell a), falling rays last
-                    const float p = fminf(inc[gq] ? s_f : s_omf, tlow), q = tlow - p;
-                    const float a_low = inc[gq] ? p : q, b_low = inc[gq] ? q : p;
-                    float t = acc[gq];
-                    t = fmaf(a_low, xa[0], t);
-                    t = fmaf(s_f - a_low, xa[1], t);
-                    t = fmaf(b_low, xb[0], t);
-                    acc[gq] = fmaf(s_omf - b_low, xb[1], t);
+                    int kf;
+                    float tlow;
+                    sd_axial_place(A[gq], s_h, kmax, kf, tlow);
+                    acc[gq] = sd_gather_two(col_a + kf, col_b + kf, A[gq].inc, s_f, s_omf, tlow, acc[gq]);
                 }
             } else {
 #pragma unroll
                 for (int gq = 0; gq < RG; ++gq) {
-                    const double zlo = fma(vr[gq], s_h, zadj[gq]);
-                    const float fr = (float)__builtin_amdgcn_fract(zlo);
-                    int kf = (int)zlo;
-                    asm("v_med3_i32 %0, %1, 0, %2" : "=v"(kf) : "v"(kf), "s"(kmax));
-                    const float *__restrict__ xa = reinterpret_cast<const float *>(col_a + ((unsigned)kf << 2));
-                    const float tlow = fminf((1.0f - fr) * inv_amz[gq], 1.0f);
-                    acc[gq] = fmaf(tlow, xa[0], fmaf(1.0f - tlow, xa[1], acc[gq]));
+                    int kf;
+                    float tlow;
+                    sd_axial_place(A[gq], s_h, kmax, kf, tlow);
+                    acc[gq] = sd_gather_one(col_a + kf, tlow, acc[gq]);
                 }
             }
         }
@@ -138,7 +176,7 @@ __global__ __launch_bounds__(SD_WAVES * 64) void sd_project_columns(SfGeom gk, c
     for (int gq = 0; gq < RG; ++gq) {
         const int r = band0 + 64 * gq + lane;
         if (r < g.nrows) {
-            const float part = sd_ray_length(R, vr[gq]) * acc[gq];
+            const float part = sd_ray_length(R, A[gq].vr) * acc[gq];
             ya[(size_t)r * g.ncols] = slab.first ? part : ya[(size_t)r * g.ncols] + part;
         }
     }

@@ -338,7 +338,8 @@ extern "C" long host_project_columns(const leap_geometry *G, const float *vol, f
     }
 }
 
-// ---- Siddon column-wise forward projection: its arithmetic, serially, with every read of the padded copy checked ----
+// ---- Siddon column-wise forward projection: the kernel's own functions, serially, with every read of the padded copy
+// checked ----
 // Returns -1 when the handle does not use that kernel, else the number of reads that would leave the scratch array.
 extern "C" long host_sd_project_columns(const leap_geometry *G, const float *vol, float *sino)
 {
@@ -360,37 +361,21 @@ extern "C" long host_sd_project_columns(const leap_geometry *G, const float *vol
             const SdRayCol R = G->raycols[(size_t)a * g.ncols + c];
             const int n_major = R.xmajor ? g.nx : g.ny, n_minor = R.xmajor ? g.ny : g.nx;
             for (int r = 0; r < g.nrows; ++r) {
-                const double vr = sd_row_v(g, r), mz = vr * R.dh;
-                const double zadj = g.zk0d + (double)FP_PAD + std::fmin(mz, 0.0);
-                const float amz = fabsf((float)mz), inv_amz = amz > 1e-30f ? 1.0f / amz : 1e30f;
-                const bool inc = mz >= 0.0;
+                const SdAxial A = sd_axial(g, R, r);
                 float acc = 0.f;
                 for (int n = 0; n < n_major; ++n) {
                     const SdSplit s = sd_slab_split(R, n);
                     const bool a_ok = s.qa >= 0 && s.qa < n_minor, b_ok = s.qa != s.qb && s.qb >= 0 && s.qb < n_minor;
                     const unsigned base_a = a_ok ? (unsigned)(R.xmajor ? s.qa * g.nx + n : n * g.nx + s.qa) * (unsigned)nzp : zero_col;
                     const unsigned base_b = b_ok ? (unsigned)(R.xmajor ? s.qb * g.nx + n : n * g.nx + s.qb) * (unsigned)nzp : zero_col;
-                    const double h = fma((double)n, R.dh, R.h0);
-                    const float f = s.f, omf = 1.0f - s.f;
-                    const double zlo = fma(vr, h, zadj);
-                    const float fr = (float)(zlo - std::floor(zlo));
-                    const double zt = std::fmin(std::fmax(std::trunc(zlo), -2147483648.0), 2147483647.0);
-                    const int kf = std::max(0, std::min((int)zt, kmax));
-                    if ((size_t)base_a + kf + 1 >= total || (size_t)base_b + kf + 1 >= total) { ++bad; continue; }
+                    int kf;
+                    float tlow;
+                    sd_axial_place(A, fma((double)n, R.dh, R.h0), kmax, kf, tlow);
+                    if (kf < 0 || (size_t)base_a + kf + 1 >= total || (size_t)base_b + kf + 1 >= total) { ++bad; continue; }
                     const float *xa = &volz[(size_t)base_a + kf], *xb = &volz[(size_t)base_b + kf];
-                    const float tlow = fminf((1.0f - fr) * inv_amz, 1.0f);
-                    if (s.qa != s.qb) {
-                        const float p = fminf(inc ? f : omf, tlow), q = tlow - p;
-                        const float a_low = inc ? p : q, b_low = inc ? q : p;
-                        acc = fmaf(a_low, xa[0], acc);
-                        acc = fmaf(f - a_low, xa[1], acc);
-                        acc = fmaf(b_low, xb[0], acc);
-                        acc = fmaf(omf - b_low, xb[1], acc);
-                    } else {
-                        acc = fmaf(tlow, xa[0], fmaf(1.0f - tlow, xa[1], acc));
-                    }
+                    acc = s.qa != s.qb ? sd_gather_two(xa, xb, A.inc, s.f, 1.0f - s.f, tlow, acc) : sd_gather_one(xa, tlow, acc);
                 }
-                sino[((size_t)a * g.nrows + r) * g.ncols + c] = sd_ray_length(R, vr) * acc;
+                sino[((size_t)a * g.nrows + r) * g.ncols + c] = sd_ray_length(R, A.vr) * acc;
             }
         }
     return bad;
