@@ -264,6 +264,42 @@ def test_c3_full_size_samples_match_oracle(c3_siddon, oracle_mod):
     assert abs(lhs - rhs) <= TOL * abs(lhs)
 
 
+def test_c3_tilted_modules_full_size_samples_match_oracle(torch_mod, oracle_mod):
+    """The 512^3 x 720 scan with every module moved by up to 5 mm and turned by up to 0.05 rad about each of its axes
+    (what `bench.py --tilted-modules 0.05` times), on the per-lane slab kernel and the tiled kernel with per-sample
+    slopes: two whole views, random rays and random voxels recomputed by the oracle; adjoint identity."""
+    import torch
+    from paper_2307_05801_amd import Geometry
+    cfg = perturbed_poses(config(3), 3, shift_mm=5.0, tilt_rad=0.05)
+    sd = oracle_mod.siddon
+    print("[gpu] tilted siddon full-size C3: inputs", flush=True)
+    x = standard_volume(3, cfg)
+    noise = np.random.default_rng([1003, 7]).random(cfg.sino_shape, dtype=np.float32)
+    geo = Geometry(cfg, model="siddon")
+    desc = geo.describe()
+    print("[gpu] tilted siddon full-size C3: " + desc, flush=True)
+    assert "A=columns" in desc and "AT=tiled" in desc and "tilted" in desc, desc
+    ax = geo.project(torch.from_numpy(x).cuda()).cpu().numpy()
+    print("[gpu] tilted siddon full-size C3: backproject", flush=True)
+    atn = geo.backproject(torch.from_numpy(noise).cuda()).cpu().numpy()
+    geo.close()
+    views = [89, 404]
+    ref = sd.project(cfg.with_views(views), x)
+    for n, a in enumerate(views):
+        assert rel_l2(ax[a], ref[n]) <= TOL
+    rng = np.random.default_rng(47)
+    rays = rng.integers(0, cfg.nviews * cfg.nrows * cfg.ncols, 600)
+    assert rel_l2(ax.ravel()[rays], sd.project_rays(cfg, x, rays)) <= TOL
+    n = cfg.nx * cfg.ny * cfg.nz
+    vox = np.unique(np.concatenate([rng.integers(0, n, 4000), np.array([0, cfg.nx - 1, n - 1, n - cfg.nx, n // 2 + 255])]))
+    got, want = atn.ravel()[vox], sd.backproject_voxels(cfg, noise, vox)
+    assert rel_l2(got, want) <= TOL
+    assert np.abs(got - want).max() <= 5e-5 * np.abs(want).max()
+    lhs = float((ax.astype(np.float64) * noise).sum())
+    rhs = float((atn.astype(np.float64) * x).sum())
+    assert abs(lhs - rhs) <= TOL * abs(lhs)
+
+
 MODULAR_CASES = [
     ("cone_as_modular", lambda: modular_from(reduced(config(3), 8, nviews=12).replace(shift_u=0.123))),
     ("tilted_modules", lambda: perturbed_poses(reduced(config(3), 8, nviews=16).replace(nx=67, ny=70, nz=45, nrows=61, ncols=77),
