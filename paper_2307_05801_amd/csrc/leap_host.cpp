@@ -20,20 +20,26 @@ constexpr int COPY_THREADS = 4;                     // CPU threads sharing one c
 
 void parallel_copy(void *dst, const void *src, size_t bytes)
 {
-    if (bytes < ((size_t)4 << 20)) {
+    if (bytes < ((size_t)1 << 20)) {                // not worth a thread
         std::memcpy(dst, src, bytes);
         return;
     }
     const size_t part = ((bytes / COPY_THREADS) + 4095) & ~(size_t)4095;
     std::thread helpers[COPY_THREADS - 1];
     int started = 0;
-    for (int t = 1; t < COPY_THREADS; ++t) {
-        const size_t off = (size_t)t * part;
-        if (off >= bytes) break;
-        const size_t len = std::min(part, bytes - off);
-        helpers[started++] = std::thread([=] { std::memcpy((char *)dst + off, (const char *)src + off, len); });
+    size_t handed = std::min(part, bytes);          // the calling thread copies [0, part) itself
+    for (int t = 1; t < COPY_THREADS && handed < bytes; ++t) {
+        const size_t off = handed, len = std::min(part, bytes - off);
+        try {
+            helpers[started] = std::thread([=] { std::memcpy((char *)dst + off, (const char *)src + off, len); });
+        } catch (...) {
+            break;                                  // no thread to be had: the caller copies the rest below
+        }
+        ++started;
+        handed += len;
     }
     std::memcpy(dst, src, std::min(part, bytes));
+    if (handed < bytes) std::memcpy((char *)dst + handed, (const char *)src + handed, bytes - handed);
     for (int t = 0; t < started; ++t) helpers[t].join();
 }
 

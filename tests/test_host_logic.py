@@ -561,3 +561,23 @@ def test_tilted_siddon_tiled_back_projection_matches_oracle_on_cpu(host, oracle_
     ref = oracle_mod.siddon.backproject(cfg, y)
     assert rel_l2(out, ref) <= TOL, desc
     assert np.abs(out - ref).max() <= 2e-5 * np.abs(ref).max()
+
+
+def test_host_memory_pipeline_with_threaded_staging_copies(host, monkeypatch):
+    """Staging buffers of 1 MiB: every chunk's copy to or from pinned memory is shared out among the helper threads, and
+    arrays of 2.4 and 1.6 MB take a ragged last chunk."""
+    monkeypatch.setenv("LEAP_DEBUG", "stage_kib=1024")
+    cfg = reduced(config(3), 8, nviews=6).replace(nx=96, ny=96, nz=64, nrows=96, ncols=112)
+    batch = 3
+    x = np.stack([uniform_volume(cfg, 60 + b)[0] for b in range(batch)])
+    h = handle(host, cfg)
+    ref = np.zeros((batch,) + cfg.sino_shape, np.float32)
+    B.leap_project(h, x.ctypes.data, ref.ctypes.data, batch, 0, host)
+    ax = np.full_like(ref, np.nan)
+    B.leap_project_host(h, x.ctypes.data, ax.ctypes.data, batch, host)
+    back_ref = np.zeros((batch,) + cfg.vol_shape, np.float32)
+    B.leap_backproject(h, ref.ctypes.data, back_ref.ctypes.data, batch, 0, host)
+    back = np.full_like(back_ref, np.nan)
+    B.leap_backproject_host(h, ref.ctypes.data, back.ctypes.data, batch, host)
+    B.leap_geometry_destroy(h, host)
+    assert np.array_equal(ax, ref) and np.array_equal(back, back_ref)
