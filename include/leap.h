@@ -61,7 +61,7 @@ extern "C" {
  * the module's own axes: the trapezoid's knots are the column coordinates of the central projections, from the source
  * onto the module's plane, of the voxel's four in-plane corners at the height of its centre; the axial interval lies
  * between the row coordinates of the central projections of the centres of its lower and upper face; the amplitude is
- * T |D| / max(|Dx|, |Dy|) with D = pixel - source.  A scan with one such module runs on one thread per ray / per voxel
+ * T |D| / max(|Dx|, |Dy|) with D = pixel - source.  A scan with one such module runs on one thread per few rays / per voxel
  * in double precision.  It needs the whole volume in front of every source (on the module's side of the plane through
  * the source parallel to the module) and no pixel whose ray runs along z, else LEAP_BAD_GEOMETRY. */
 enum { LEAP_PARALLEL = 0, LEAP_FAN = 1, LEAP_CONE = 2, LEAP_CONE_CURVED = 3, LEAP_MODULAR = 4 };

@@ -90,16 +90,26 @@ __global__ __launch_bounds__(256) void sf_project_general_modular(const SfGeom *
         if (r0 + rr < g.nrows) y[(size_t)(r0 + rr) * g.ncols] = out[rr];
 }
 
-// Modular geometry, footprint model on tilted modules: one thread per ray / per voxel (md_footprint.h).
-// grids as for the general Siddon kernels below.
+// Modular geometry, footprint model on tilted modules (md_footprint.h): one thread per MF_RC rows of a detector column /
+// per voxel.  Forward grid: x = ceil(ncols/64), y = ceil(ceil(nrows/MF_RC)/4), z = nviews; back grid as for the general
+// Siddon kernel below.
+#ifndef MF_RC_VALUE
+#define MF_RC_VALUE 8
+#endif
+constexpr int MF_RC = MF_RC_VALUE;
 __global__ __launch_bounds__(256) void mf_project_general(SfGeom g, const MfView *__restrict__ views,
                                                           const float *__restrict__ vol, float *__restrict__ sino)
 {
     const int c = blockIdx.x * 64 + threadIdx.x;
-    const int r = blockIdx.y * 4 + threadIdx.y;
+    const int r0 = (blockIdx.y * 4 + threadIdx.y) * MF_RC;
     const int a = blockIdx.z;
-    if (c >= g.ncols || r >= g.nrows) return;
-    sino[((size_t)a * g.nrows + r) * g.ncols + c] = mf_project_ray(g, views[a], vol, r, c);
+    if (c >= g.ncols || r0 >= g.nrows) return;
+    float out[MF_RC];
+    mf_project_rows<MF_RC>(g, views[a], vol, r0, c, out);
+    float *__restrict__ y = sino + ((size_t)a * g.nrows) * g.ncols + c;
+#pragma unroll
+    for (int rr = 0; rr < MF_RC; ++rr)
+        if (r0 + rr < g.nrows) y[(size_t)(r0 + rr) * g.ncols] = out[rr];
 }
 
 __global__ __launch_bounds__(256) void mf_backproject_general(SfGeom g, const MfView *__restrict__ views,
@@ -447,7 +457,7 @@ int leap_launch_project(const leap_geometry *G, const float *d_vol, float *d_sin
     if (g.model == SF_MODEL_SIDDON) return launch_sd_project(G, d_vol, d_sino, stream);
     if (G->fp_columns) return leap_launch_project_batch(G, d_vol, d_sino, 1, stream);
     if (G->d_mfviews) {                     // sizes were checked against the grid limits at creation
-        dim3 grid(cdiv(g.ncols, 64), cdiv(g.nrows, 4), g.nviews);
+        dim3 grid(cdiv(g.ncols, 64), cdiv(cdiv(g.nrows, MF_RC), 4), g.nviews);
         hipLaunchKernelGGL(mf_project_general, grid, dim3(64, 4, 1), 0, stream, g, G->d_mfviews, d_vol, d_sino);
         LEAP_HIP_CHECK(hipGetLastError());
         return LEAP_OK;

@@ -64,9 +64,12 @@ int leap_launch_project(const leap_geometry *G, const float *vol, float *sino, h
     if (G->d_mfviews) {
 #pragma omp parallel for collapse(2)
         for (int a = 0; a < g.nviews; ++a)
-            for (int r = 0; r < g.nrows; ++r)
-                for (int c = 0; c < g.ncols; ++c)
-                    sino[((size_t)a * g.nrows + r) * g.ncols + c] = mf_project_ray(g, G->d_mfviews[a], vol, r, c);
+            for (int r0 = 0; r0 < g.nrows; r0 += RC)
+                for (int c = 0; c < g.ncols; ++c) {
+                    float out[RC];
+                    mf_project_rows<RC>(g, G->d_mfviews[a], vol, r0, c, out);
+                    for (int rr = 0; rr < RC && r0 + rr < g.nrows; ++rr) sino[((size_t)a * g.nrows + r0 + rr) * g.ncols + c] = out[rr];
+                }
         return LEAP_OK;
     }
     if (g.model == SF_MODEL_SIDDON) {
