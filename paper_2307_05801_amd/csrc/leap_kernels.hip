@@ -290,6 +290,7 @@ static int launch_sd_bp_items(const leap_geometry *G, const float *d_sino, float
         case 2: launch_md_tiled<2>(G, d_sino, d_vol, stream, items); ok = true; break;
         case 3: launch_md_tiled<3>(G, d_sino, d_vol, stream, items); ok = true; break;
         case 4: launch_md_tiled<4>(G, d_sino, d_vol, stream, items); ok = true; break;
+        case 5: launch_md_tiled<5>(G, d_sino, d_vol, stream, items); ok = true; break;
         default: break;
         }
     } else

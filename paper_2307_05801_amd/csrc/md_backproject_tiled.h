@@ -29,10 +29,10 @@
 #include "sf_backproject_tiled.h"
 
 // Shapes this kernel is instantiated for (voxels along z per thread, staged window columns x rows), in the order they
-// are tried.  LDS per workgroup: 28 bytes per staged sample plus (zc + 4) KiB of sums; the first shape leaves room for
-// three workgroups per compute unit, the next two for two.
-constexpr SfBpShape MD_BP_SHAPES[] = {{16, 32, 35}, {32, 32, 44}, {16, 32, 44}, {32, 32, 56}, {16, 64, 48}};
-constexpr int MD_BP_NSHAPES = 5;
+// are tried.  LDS per workgroup: 28 bytes per staged sample (row stride pw + 1) plus (zc + 4) KiB of sums; the first shape
+// leaves room for four workgroups per compute unit, the second for three, the next two for two.
+constexpr SfBpShape MD_BP_SHAPES[] = {{16, 32, 21}, {16, 32, 35}, {32, 32, 44}, {16, 32, 44}, {32, 32, 56}, {16, 64, 48}};
+constexpr int MD_BP_NSHAPES = 6;
 constexpr double MD_BP_ZBIAS = 1048576.0;      // added to axial positions so that truncation is floor for every row of a window
 
 // One entry per view, built in double on the host.

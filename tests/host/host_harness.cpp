@@ -502,6 +502,7 @@ extern "C" long host_md_backproject_tiled(const leap_geometry *G, const float *s
     case 2: host_md_bp_shape<MD_BP_SHAPES[2].zc, MD_BP_SHAPES[2].pw, MD_BP_SHAPES[2].ph>(G, sino, vol, report); break;
     case 3: host_md_bp_shape<MD_BP_SHAPES[3].zc, MD_BP_SHAPES[3].pw, MD_BP_SHAPES[3].ph>(G, sino, vol, report); break;
     case 4: host_md_bp_shape<MD_BP_SHAPES[4].zc, MD_BP_SHAPES[4].pw, MD_BP_SHAPES[4].ph>(G, sino, vol, report); break;
+    case 5: host_md_bp_shape<MD_BP_SHAPES[5].zc, MD_BP_SHAPES[5].pw, MD_BP_SHAPES[5].ph>(G, sino, vol, report); break;
     default: return -1;
     }
     return report[0] + report[1] + report[2];
