@@ -63,7 +63,8 @@ extern "C" {
  * between the row coordinates of the central projections of the centres of its lower and upper face; the amplitude is
  * T |D| / max(|Dx|, |Dy|) with D = pixel - source.  A scan with one such module runs on one thread per few rays / per voxel
  * in double precision.  It needs the whole volume in front of every source (on the module's side of the plane through
- * the source parallel to the module) and no pixel whose ray runs along z, else LEAP_BAD_GEOMETRY. */
+ * the source parallel to the module) and no pixel whose ray runs along z, else LEAP_BAD_GEOMETRY; a source so close to
+ * the volume that the nearest voxel's footprint spans more than 64 pixels is LEAP_UNSUPPORTED. */
 enum { LEAP_PARALLEL = 0, LEAP_FAN = 1, LEAP_CONE = 2, LEAP_CONE_CURVED = 3, LEAP_MODULAR = 4 };
 
 /* Projector models ("CT Projection Models and Geometries").  LEAP_MODEL_SF: separable footprints.
@@ -77,7 +78,7 @@ enum {
     LEAP_BAD_GEOMETRY = -2,  /* cone/fan: source not strictly outside the volume's bounding circle, sdd <= 0, curved fan wider than +-1.5 rad;
                                 modular: a source inside the volume, a module with no footprints (see LEAP_MODULAR) */
     LEAP_HIP_ERROR = -3,     /* a HIP runtime call failed (the message is kept, see leap_last_error) */
-    LEAP_UNSUPPORTED = -4    /* sizes beyond what the index arithmetic of the kernels covers;
+    LEAP_UNSUPPORTED = -4    /* sizes beyond what the index arithmetic of the kernels covers; footprints of more than 64 pixels on a tilted module;
                                 a volume beyond the fixed array of leap_project_static_scratch */
 };
 

@@ -804,6 +804,15 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
                 free_handle(G);
                 return LEAP_BAD_GEOMETRY;
             }
+            // the forward kernel looks for a pixel's voxels within the footprint's reach around its ray: a source so close
+            // to the volume that the nearest voxel's footprint spans dozens of pixels makes that search the whole volume
+            if (V.pad_u * V.ipu > 32.0 || V.pad_v * V.ipv > 32.0) {
+                leap_set_error("view " + std::to_string(a) + ": the source is so close to the volume that a voxel's footprint on "
+                               "this tilted module spans more than 64 pixels; not supported by the footprint kernels for "
+                               "tilted modules");
+                free_handle(G);
+                return LEAP_UNSUPPORTED;
+            }
         }
     }
     return finish_handle(G, out);

@@ -325,9 +325,11 @@ __global__ __launch_bounds__(256) void md_backproject_tiled(SfGeom g, const MdBp
         const bool xmajor = md_bp_tile_xmajor(g, V, i0, j0);
         const MdBpColumn C = md_bp_column<ZC>(g, V, xmajor, ic, jc, k0);
         const int H = cur.need_h < PH ? cur.need_h : PH;
-        for (int c = C.cfirst; c <= C.clast; ++c) {
+        // (the loop runs over the window's columns at most, whatever the shadow's extent came out as)
+        const int cbeg = C.cfirst > cur.c0 ? C.cfirst : cur.c0, cend = C.clast < cur.c0 + PW - 1 ? C.clast : cur.c0 + PW - 1;
+        for (int c = cbeg; c <= cend; ++c) {
             const int wc = c - cur.c0;
-            if (c < 0 || c >= g.ncols || wc < 0 || wc >= PW) continue;
+            if (c < 0 || c >= g.ncols) continue;
             int rs, re;
             md_bp_rows(C, c, cur.r0, H, rs, re);
             for (int row = rs; row < re; ++row) {

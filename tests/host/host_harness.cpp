@@ -466,9 +466,10 @@ static void host_md_bp_shape(const leap_geometry *G, const float *sino, float *v
                     const int i = i0 + (tid & (BP_T - 1)), j = j0 + (tid >> 4);
                     const int ic = std::min(i, g.nx - 1), jc = std::min(j, g.ny - 1);
                     const MdBpColumn C = md_bp_column<ZC>(g, V, xmajor, ic, jc, k0);
-                    for (int c = C.cfirst; c <= C.clast; ++c) {
+                    const int cbeg = std::max(C.cfirst, win.c0), cend = std::min(C.clast, win.c0 + PW - 1);
+                    for (int c = cbeg; c <= cend; ++c) {
                         const int wc = c - win.c0;
-                        if (c < 0 || c >= g.ncols || wc < 0 || wc >= PW) continue;
+                        if (c < 0 || c >= g.ncols) continue;
                         int rs, re;
                         md_bp_rows(C, c, win.r0, H, rs, re);
                         for (int row = rs; row < re; ++row) {

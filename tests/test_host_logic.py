@@ -381,6 +381,12 @@ def test_tilted_scans_without_footprints_are_refused(host):
         with pytest.raises(B.LeapError) as err:
             handle(host, cfg, B.LEAP_MODEL_SF)
         assert err.value.status == B.LEAP_BAD_GEOMETRY and "no footprints" in str(err.value)
+    # a source 0.2 mm in front of the volume's face: the nearest voxels' footprints span hundreds of pixels
+    roll = np.sqrt(1 - 0.01)
+    close = (9.2, 0.0, 0.0, -300.0, 0.0, 0.0, 0.0, roll, -0.1, 0.0, 0.1, roll)        # rolled about its normal (the x axis)
+    with pytest.raises(B.LeapError) as err:
+        handle(host, CTConfig("close", 4, poses=(close,), **base), B.LEAP_MODEL_SF)
+    assert err.value.status == B.LEAP_UNSUPPORTED and "64 pixels" in str(err.value)
 
 
 UPRIGHT_CASES = {
