@@ -55,7 +55,9 @@ extern "C" {
  * LEAP_MODULAR: the flexible geometry of the same section (sources and detectors at any position and orientation):
  * every view has its own pose, 12 doubles in `poses`: source position S, detector centre C, unit vector along the
  * column index, unit vector along the row index (orthogonal to each other); pixel (r, c) sits at
- * C + u_c ucol + v_r vrow.  sod, sdd and angles_rad are not read.  LEAP_MODEL_SIDDON takes any pose.
+ * C + u_c ucol + v_r vrow.  sod, sdd and angles_rad are not read.  LEAP_MODEL_SIDDON takes any pose (one limit: a scan
+ * of more than 5e11 voxel-pixel pairs in views whose volume reaches behind the plane through the source parallel to the
+ * module is LEAP_UNSUPPORTED; the back projection of such views has no bound on a voxel's pixel search).
  * LEAP_MODEL_SF on upright modules (ucol horizontal, vrow = +z): the cone-beam footprint construction is carried out
  * in each view's own frame.  On any other module (the paper gives no construction) the footprint stays separable on
  * the module's own axes: the trapezoid's knots are the column coordinates of the central projections, from the source

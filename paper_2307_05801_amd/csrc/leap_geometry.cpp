@@ -791,6 +791,31 @@ static int create_modular(const leap_geometry_desc *d, leap_geometry **out)
         select_fast_kernels(G);
     } else if (d->model == LEAP_MODEL_SIDDON) {
         select_tilted_siddon_kernels(G);
+        // The general back projection bounds a voxel's pixel search by its projected corners; a voxel that reaches behind
+        // a source's plane (the plane through the source parallel to its module) has no such bound and tests every pixel
+        // of that view.  On large scans that is not a slow call but one that never ends: refuse it.
+        if (!G->bp_tiled) {
+            double behind = 0.0;
+            for (const MdPose &P : G->poses) {
+                const double n[3] = {P.ucol[1] * P.vrow[2] - P.ucol[2] * P.vrow[1], P.ucol[2] * P.vrow[0] - P.ucol[0] * P.vrow[2],
+                                     P.ucol[0] * P.vrow[1] - P.ucol[1] * P.vrow[0]};
+                const double gap = (P.C[0] - P.S[0]) * n[0] + (P.C[1] - P.S[1]) * n[1] + (P.C[2] - P.S[2]) * n[2];
+                bool all_in_front = true;
+                for (int corner = 0; corner < 8; ++corner) {
+                    double along = 0.0;
+                    for (int q = 0; q < 3; ++q) along += (ctr[q] + ((corner >> q) & 1 ? half[q] : -half[q]) - P.S[q]) * n[q];
+                    all_in_front = all_in_front && along * gap > 0.0;
+                }
+                behind += all_in_front ? 0.0 : 1.0;
+            }
+            if (behind * d->nrows * d->ncols * ((double)d->nx * d->ny * d->nz) > 5.0e11) {
+                leap_set_error("in " + std::to_string((long)behind) + " views the volume reaches behind the source's plane (the plane "
+                               "through the source parallel to its module); on a scan of this size the back projection of such "
+                               "views is not supported");
+                free_handle(G);
+                return LEAP_UNSUPPORTED;
+            }
+        }
     }
     if (!upright && d->model == LEAP_MODEL_SF) {
         G->mfviews.resize(d->nviews);

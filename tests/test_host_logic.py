@@ -587,3 +587,24 @@ def test_host_memory_pipeline_with_threaded_staging_copies(host, monkeypatch):
     B.leap_backproject_host(h, ref.ctypes.data, back.ctypes.data, batch, host)
     B.leap_geometry_destroy(h, host)
     assert np.array_equal(ax, ref) and np.array_equal(back, back_ref)
+
+
+def test_large_scans_behind_a_source_plane_are_refused_for_the_siddon_model(host):
+    """A module turned 60 degrees away from the line source - volume and rolled a little: the plane through the source
+    parallel to the module cuts the volume, so the general back projection would test every pixel for the voxels behind
+    it.  Tiny scans run that way (the oracle agrees); at 256^3 x 256^2 the handle is refused."""
+    c, s_ = np.cos(np.pi / 3), np.sin(np.pi / 3)
+    n = np.array([c, s_, 0.0])
+    eu = np.array([-s_, c, 0.0]) * np.sqrt(1 - 0.01) + np.array([0.0, 0.0, -0.1])
+    ev = np.cross(n, eu)
+    S = np.array([200.0, 0.0, 0.0])
+    pose = tuple(np.concatenate([S, S - 300.0 * n, eu / np.linalg.norm(eu), ev / np.linalg.norm(ev)]))
+    big = CTConfig("cut", 4, nviews=4, arc_deg=360.0, nrows=256, ncols=256, pixel_v=1.0, pixel_u=1.0, nx=256, ny=256, nz=256,
+                   voxel_xy=1.0, voxel_z=1.0, poses=(pose,) * 4)
+    with pytest.raises(B.LeapError) as err:
+        handle(host, big, B.LEAP_MODEL_SIDDON)
+    assert err.value.status == B.LEAP_UNSUPPORTED and "behind the source's plane" in str(err.value)
+    small = big.replace(nrows=24, ncols=24, nx=20, ny=20, nz=20, voxel_xy=12.8, voxel_z=12.8, pixel_u=10.0, pixel_v=10.0)
+    h = handle(host, small, B.LEAP_MODEL_SIDDON)
+    assert "AT=general" in B.leap_geometry_describe(h, host)
+    B.leap_geometry_destroy(h, host)
