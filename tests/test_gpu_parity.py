@@ -288,6 +288,33 @@ def test_streams_are_honoured(torch_mod):
     geo.close()
 
 
+def test_two_streams_share_one_handle(torch_mod):
+    """Calls on one handle share its forward scratch; the library orders them on the device.  Two streams project two
+    different volumes through one handle back to back, without any synchronisation in between, several times over:
+    every result equals the one a lone call gives."""
+    from paper_2307_05801_amd import Geometry
+    torch = torch_mod
+    cfg = reduced(config(3), 4, nviews=90)
+    geo = Geometry(cfg)
+    assert "A=columns" in geo.describe()
+    x1 = torch.from_numpy(uniform_volume(cfg, 1)[0]).cuda()
+    x2 = torch.from_numpy(uniform_volume(cfg, 2)[0]).cuda()
+    ref1, ref2 = geo.project(x1), geo.project(x2)
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    for _ in range(4):
+        with torch.cuda.stream(s1):
+            y1 = geo.project(x1)
+        with torch.cuda.stream(s2):
+            y2 = geo.project(x2)
+        outs.append((y1, y2))
+    s1.synchronize(); s2.synchronize()
+    for y1, y2 in outs:
+        assert torch.equal(y1, ref1) and torch.equal(y2, ref2)
+    geo.close()
+
+
 def test_training_step_of_case_4(torch_mod, oracle_mod):
     """Batch of volumes: y = A x, residual against a photon-noise measurement, gradient g = A^T r."""
     from paper_2307_05801_amd import Geometry
