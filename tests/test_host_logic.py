@@ -608,3 +608,32 @@ def test_large_scans_behind_a_source_plane_are_refused_for_the_siddon_model(host
     h = handle(host, small, B.LEAP_MODEL_SIDDON)
     assert "AT=general" in B.leap_geometry_describe(h, host)
     B.leap_geometry_destroy(h, host)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_flatness_decision_of_tilted_siddon_scans_matches_brute_force(host, seed):
+    """The per-lane slab kernel is chosen iff no ray rises by more than 0.999 axial cells per slab along its faster in-plane
+    axis.  The library decides that by clipping the detector's rectangle with four half-planes per view; here every pixel
+    (and a 4 x finer grid between the pixel centres) is simply tried."""
+    rng = np.random.default_rng([seed, 77])
+    base = far_scanner(nviews=6, voxel_z=float(rng.uniform(0.5, 2.0)), nz=int(rng.integers(10, 40)))
+    cfg = perturbed_poses(base, seed, shift_mm=float(rng.uniform(0, 30)), tilt_rad=float(rng.uniform(0.05, 1.3)))
+    lift = float(rng.uniform(0.0, 260.0))            # sources raised above the volume: their rays dive
+    cfg = cfg.replace(poses=tuple(tuple(np.asarray(p) + np.array([0, 0, lift * (a % 2)] + [0] * 9)) for a, p in enumerate(cfg.poses)))
+    h = handle(host, cfg, B.LEAP_MODEL_SIDDON)
+    fast = "A=columns" in B.leap_geometry_describe(h, host)
+    B.leap_geometry_destroy(h, host)
+    kappa = cfg.voxel_xy / cfg.voxel_z
+    u = (np.linspace(0, cfg.ncols - 1, 4 * cfg.ncols - 3) - (cfg.ncols - 1) / 2 + cfg.shift_u) * cfg.pixel_u
+    v = (np.linspace(0, cfg.nrows - 1, 4 * cfg.nrows - 3) - (cfg.nrows - 1) / 2 + cfg.shift_v) * cfg.pixel_v
+    uu, vv = np.meshgrid(u, v)
+    worst = 0.0
+    for p in cfg.poses:
+        p = np.asarray(p)
+        D = (p[3:6] - p[0:3]) + uu[..., None] * p[6:9] + vv[..., None] * p[9:12]
+        with np.errstate(divide="ignore"):
+            worst = max(worst, float((kappa * np.abs(D[..., 2]) / np.maximum(np.abs(D[..., 0]), np.abs(D[..., 1]))).max()))
+    if worst > 1.0:
+        assert not fast, worst
+    elif worst < 0.99:
+        assert fast, worst          # (these scanners keep every source far more than a voxel from the volume)
