@@ -2,7 +2,7 @@
 in about a second)."""
 import numpy as np
 
-from synthetic import CTConfig
+from synthetic import CTConfig, perturbed_poses
 from synthetic.configs import CONE, PARALLEL
 
 
@@ -33,3 +33,14 @@ def random_config(seed: int) -> CTConfig:
     return CTConfig(f"random_{seed}", geom, nviews=nviews, arc_deg=360.0, nrows=nrows, ncols=ncols, pixel_v=pixel_v,
                     pixel_u=pixel_u, nx=nx, ny=ny, nz=nz, voxel_xy=voxel_xy, voxel_z=voxel_z, sod=sod, sdd=sdd,
                     shift_v=shift_v, shift_u=shift_u, center_x=cx, center_y=cy, center_z=cz, angles_override=angles)
+
+
+def random_tilted_scan(seed: int) -> CTConfig:
+    """A modular scan with tilted modules (up to 0.5 rad about every axis) whose sources keep more than a hundred voxels
+    from the volume: random shifts, voxel aspect ratios and sizes."""
+    rng = np.random.default_rng([seed, 91])
+    base = CTConfig("far", CONE, nviews=5, arc_deg=360.0, nrows=48, ncols=56, pixel_v=1.5, pixel_u=1.5,
+                    nx=int(rng.integers(17, 40)), ny=int(rng.integers(17, 40)), nz=int(rng.integers(9, 34)), voxel_xy=1.0,
+                    voxel_z=float(rng.uniform(0.6, 1.8)), sod=160.0, sdd=240.0, shift_u=float(rng.uniform(-2, 2)),
+                    shift_v=float(rng.uniform(-2, 2)), center_x=1.0, center_y=-2.0, center_z=0.5, start_deg=3.0)
+    return perturbed_poses(base, 100 + seed, shift_mm=float(rng.uniform(0, 12)), tilt_rad=float(rng.uniform(0.02, 0.5)))

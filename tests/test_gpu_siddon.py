@@ -300,6 +300,28 @@ def test_c3_tilted_modules_full_size_samples_match_oracle(torch_mod, oracle_mod)
     assert abs(lhs - rhs) <= TOL * abs(lhs)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_tilted_scans(torch_mod, oracle_mod, seed):
+    """Random tilts, shifts, voxel aspect ratios and sizes on the per-lane kernels (window shapes from 32 x 21 to 64 x 48)."""
+    from paper_2307_05801_amd import Geometry
+    from random_geometries import random_tilted_scan
+    cfg = random_tilted_scan(seed)
+    sd = oracle_mod.siddon
+    x, y = uniform_volume(cfg, 5)[0], uniform_sinogram(cfg, 6)[0]
+    geo = Geometry(cfg, model="siddon")
+    desc = geo.describe()
+    print(f"[gpu] random tilted scan {seed}: {desc}", flush=True)
+    assert "A=columns" in desc and "AT=tiled" in desc, desc
+    ax = geo.project(torch_mod.from_numpy(x).cuda()).cpu().numpy()
+    aty = geo.backproject(torch_mod.from_numpy(y).cuda()).cpu().numpy()
+    geo.close()
+    ref_a, ref_t = sd.project(cfg, x), sd.backproject(cfg, y)
+    e_a, e_t = rel_l2(ax, ref_a), rel_l2(aty, ref_t)
+    print(f"seed {seed}: A {e_a:.2e}  A^T {e_t:.2e}")
+    assert e_a <= TOL and e_t <= TOL
+    assert np.abs(ax - ref_a).max() <= 2e-5 * np.abs(ref_a).max() and np.abs(aty - ref_t).max() <= 2e-5 * np.abs(ref_t).max()
+
+
 MODULAR_CASES = [
     ("cone_as_modular", lambda: modular_from(reduced(config(3), 8, nviews=12).replace(shift_u=0.123))),
     ("tilted_modules", lambda: perturbed_poses(reduced(config(3), 8, nviews=16).replace(nx=67, ny=70, nz=45, nrows=61, ncols=77),

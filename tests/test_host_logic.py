@@ -643,10 +643,8 @@ def test_flatness_decision_of_tilted_siddon_scans_matches_brute_force(host, seed
 def test_tilted_siddon_kernels_on_random_scans_match_oracle_on_cpu(host, oracle_mod, seed):
     """Random tilts (up to 0.5 rad about every axis), shifts, voxel aspect ratios and sizes: wherever the library picks the
     per-lane kernels, their re-enactments stay inside their buffers and agree with the oracle."""
-    rng = np.random.default_rng([seed, 91])
-    base = far_scanner(nviews=5, nz=int(rng.integers(9, 34)), voxel_z=float(rng.uniform(0.6, 1.8)), nx=int(rng.integers(17, 40)),
-                       ny=int(rng.integers(17, 40)), shift_u=float(rng.uniform(-2, 2)), shift_v=float(rng.uniform(-2, 2)))
-    cfg = perturbed_poses(base, 100 + seed, shift_mm=float(rng.uniform(0, 12)), tilt_rad=float(rng.uniform(0.02, 0.5)))
+    from random_geometries import random_tilted_scan
+    cfg = random_tilted_scan(seed)
     x, y = uniform_volume(cfg, 5)[0], uniform_sinogram(cfg, 6)[0]
     h = handle(host, cfg, B.LEAP_MODEL_SIDDON)
     desc = B.leap_geometry_describe(h, host)
