@@ -445,6 +445,20 @@ def test_modular_geometry_with_tilted_modules(torch_mod, oracle_mod, name, make)
     assert abs(lhs - rhs) <= TOL * abs(lhs)
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_random_tilted_scans_with_footprints(torch_mod, oracle_mod, seed):
+    from random_geometries import random_tilted_scan
+    cfg = random_tilted_scan(seed)
+    x, y = uniform_volume(cfg, 5)[0], uniform_sinogram(cfg, 6)[0]
+    ax = gpu_project(torch_mod, cfg, x)
+    aty = gpu_backproject(torch_mod, cfg, y)
+    ref_a, ref_t = oracle_mod.project(cfg, x), oracle_mod.backproject(cfg, y)
+    e_a, e_t = rel_l2(ax, ref_a), rel_l2(aty, ref_t)
+    print(f"seed {seed}: A {e_a:.2e}  A^T {e_t:.2e}")
+    assert e_a <= TOL and e_t <= TOL
+    assert np.abs(ax - ref_a).max() <= 2e-5 * np.abs(ref_a).max() and np.abs(aty - ref_t).max() <= 2e-5 * np.abs(ref_t).max()
+
+
 def test_tilted_scan_without_footprints_is_refused(torch_mod):
     from paper_2307_05801_amd import Geometry, binding as B
     below = (0.3, -0.2, 40.0, 0.0, 0.0, -30.0, 0.8, 0.6, 0.0, -0.6, 0.8, 0.0)
