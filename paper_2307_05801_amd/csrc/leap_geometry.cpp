@@ -173,21 +173,34 @@ static void staged_window_need(const leap_geometry *G, int zc, WindowFn window, 
     const leap_geometry_desc *d = &G->desc;
     const int tiles_x = (d->nx + BP_T - 1) / BP_T, tiles_y = (d->ny + BP_T - 1) / BP_T;
     const int chunks = (d->nz + zc - 1) / zc;
-    need_w = need_h = 0;
-    for (int a = 0; a < d->nviews; ++a) {
-        const SfGeom &ga = view_geom(G, a);
-        for (int ty = 0; ty < tiles_y; ++ty)
-            for (int tx = 0; tx < tiles_x; ++tx) {
-                const float xc = (float)(ga.x0d + ((double)(tx * BP_T) + 0.5 * (BP_T - 1)) * ga.Td);
-                const float yc = (float)(ga.y0d + ((double)(ty * BP_T) + 0.5 * (BP_T - 1)) * ga.Td);
-                for (int ch = 0; ch < chunks; ch += (chunks > 1 ? chunks - 1 : 1)) {   // extremes: first and last chunk
-                    const float z0 = (float)(ga.zlo0d + (double)(ch * zc) * ga.Tzd), z1 = z0 + (float)zc * ga.Tz;
-                    const SfWindow w = window(ga, G->views[a], xc, yc, z0, z1);
-                    need_w = w.need_w > need_w ? w.need_w : need_w;
-                    need_h = w.need_h > need_h ? w.need_h : need_h;
+    // the views are shared out among a few threads (a thousand views of a few thousand tiles each)
+    const int workers = (int)std::max(1, std::min(8, d->nviews / 32));
+    std::vector<int> w(workers, 0), h(workers, 0);
+    auto scan = [&](int t) {
+        int wt = 0, ht = 0;                   // kept local: the workers' slots of w and h share a cache line
+        for (int a = t; a < d->nviews; a += workers) {
+            const SfGeom &ga = view_geom(G, a);
+            for (int ty = 0; ty < tiles_y; ++ty)
+                for (int tx = 0; tx < tiles_x; ++tx) {
+                    const float xc = (float)(ga.x0d + ((double)(tx * BP_T) + 0.5 * (BP_T - 1)) * ga.Td);
+                    const float yc = (float)(ga.y0d + ((double)(ty * BP_T) + 0.5 * (BP_T - 1)) * ga.Td);
+                    for (int ch = 0; ch < chunks; ch += (chunks > 1 ? chunks - 1 : 1)) {   // extremes: first and last chunk
+                        const float z0 = (float)(ga.zlo0d + (double)(ch * zc) * ga.Tzd), z1 = z0 + (float)zc * ga.Tz;
+                        const SfWindow win = window(ga, G->views[a], xc, yc, z0, z1);
+                        wt = win.need_w > wt ? win.need_w : wt;
+                        ht = win.need_h > ht ? win.need_h : ht;
+                    }
                 }
-            }
-    }
+        }
+        w[t] = wt;
+        h[t] = ht;
+    };
+    std::vector<std::thread> pool;
+    for (int t = 1; t < workers; ++t) pool.emplace_back(scan, t);
+    scan(0);
+    for (auto &th : pool) th.join();
+    need_w = *std::max_element(w.begin(), w.end());
+    need_h = *std::max_element(h.begin(), h.end());
 }
 
 // Footprint model, tiled back projection: pick the template instance and verify its staged window.
