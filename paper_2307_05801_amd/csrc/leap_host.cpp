@@ -83,6 +83,17 @@ void leap_host_stage_free(leap_geometry *G)
     G->host_stage = nullptr;
 }
 
+static int stage_create(LeapHostStage *H)
+{
+    LEAP_HIP_CHECK(hipStreamCreateWithFlags(&H->s_up, hipStreamNonBlocking));
+    LEAP_HIP_CHECK(hipStreamCreateWithFlags(&H->s_run, hipStreamNonBlocking));
+    LEAP_HIP_CHECK(hipStreamCreateWithFlags(&H->s_down, hipStreamNonBlocking));
+    for (int q = 0; q < 2; ++q)
+        for (hipEvent_t *e : {&H->up_slot[q], &H->down_slot[q], &H->uploaded[q], &H->ran[q], &H->downloaded[q]})
+            LEAP_HIP_CHECK(hipEventCreateWithFlags(e, hipEventDisableTiming));
+    return LEAP_OK;
+}
+
 static int stage_prepare(const leap_geometry *G, size_t in_floats, size_t out_floats, int slots)
 {
     if (!G->host_stage) {
@@ -92,12 +103,11 @@ static int stage_prepare(const leap_geometry *G, size_t in_floats, size_t out_fl
             return LEAP_INVALID_ARG;
         }
         G->host_stage = H;
-        LEAP_HIP_CHECK(hipStreamCreateWithFlags(&H->s_up, hipStreamNonBlocking));
-        LEAP_HIP_CHECK(hipStreamCreateWithFlags(&H->s_run, hipStreamNonBlocking));
-        LEAP_HIP_CHECK(hipStreamCreateWithFlags(&H->s_down, hipStreamNonBlocking));
-        for (int q = 0; q < 2; ++q)
-            for (hipEvent_t *e : {&H->up_slot[q], &H->down_slot[q], &H->uploaded[q], &H->ran[q], &H->downloaded[q]})
-                LEAP_HIP_CHECK(hipEventCreateWithFlags(e, hipEventDisableTiming));
+        const int rc = stage_create(H);
+        if (rc != LEAP_OK) {                        // no half-built stage is kept for the next call to trip over
+            leap_host_stage_free(const_cast<leap_geometry *>(G));
+            return rc;
+        }
     }
     LeapHostStage *H = G->host_stage;
     for (int q = 0; q < 2; ++q) {
@@ -188,23 +198,12 @@ struct Transfer {
     }
 };
 
-int run_host_pipeline(const leap_geometry *G, const float *h_in, float *h_out, int batch, bool forward)
+// The steps of the pipeline; returns at the first failure with work possibly still in flight on the three streams.
+int pipeline_steps(const leap_geometry *G, LeapHostStage *H, const float *h_in, float *h_out, size_t nin, size_t nout,
+                   int batch, bool forward)
 {
-    const SfGeom &g = G->g;
-    const size_t nvol = (size_t)g.nx * g.ny * g.nz, nsino = (size_t)g.nviews * g.nrows * g.ncols;
-    const size_t nin = forward ? nvol : nsino, nout = forward ? nsino : nvol;
-    int device = -1;
-    LEAP_HIP_CHECK(hipGetDevice(&device));
-    if (device != G->device) {
-        leap_set_error("the handle was created on another device than the current one");
-        return LEAP_INVALID_ARG;
-    }
-    std::lock_guard<std::mutex> lock(G->host_mutex);
-    int rc = stage_prepare(G, nin, nout, batch > 1 ? 2 : 1);
-    if (rc != LEAP_OK) return rc;
-    LeapHostStage *H = G->host_stage;
     const bool in_pinned = is_pinned(h_in), out_pinned = is_pinned(h_out);
-
+    int rc = LEAP_OK;
     // step s: upload item s, run item s-1, download item s-2
     Transfer upload, download;
     upload.H = download.H = H;
@@ -254,6 +253,25 @@ int run_host_pipeline(const leap_geometry *G, const float *h_in, float *h_out, i
             rc = download.finish();
         }
     }
+    return rc;
+}
+
+int run_host_pipeline(const leap_geometry *G, const float *h_in, float *h_out, int batch, bool forward)
+{
+    const SfGeom &g = G->g;
+    const size_t nvol = (size_t)g.nx * g.ny * g.nz, nsino = (size_t)g.nviews * g.nrows * g.ncols;
+    const size_t nin = forward ? nvol : nsino, nout = forward ? nsino : nvol;
+    int device = -1;
+    LEAP_HIP_CHECK(hipGetDevice(&device));
+    if (device != G->device) {
+        leap_set_error("the handle was created on another device than the current one");
+        return LEAP_INVALID_ARG;
+    }
+    std::lock_guard<std::mutex> lock(G->host_mutex);
+    int rc = stage_prepare(G, nin, nout, batch > 1 ? 2 : 1);
+    if (rc != LEAP_OK) return rc;
+    LeapHostStage *H = G->host_stage;
+    rc = pipeline_steps(G, H, h_in, h_out, nin, nout, batch, forward);
     // the call returns with the outputs in place; after a failure the streams are still drained before the buffers
     // can be touched again
     const hipError_t e1 = hipStreamSynchronize(H->s_up), e2 = hipStreamSynchronize(H->s_run), e3 = hipStreamSynchronize(H->s_down);
