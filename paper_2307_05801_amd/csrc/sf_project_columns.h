@@ -153,20 +153,44 @@ constexpr int sf_single_of_pair(int P) { return P / 2 + 1; }
 // [fr + step, fr + 2 step).  With a_t = clamp(fr + step - t), b_t = clamp(fr + 2 step - t) and d_t = x_t - x_0 (t >= 1):
 //   S_A = step x_0 + sum a_t d_t,    S_B = 2 step x_0 + sum b_t d_t - S_A
 // (voxel 0 gets what the others leave of each row; additions with the clamp modifier are the cheapest way to an overlap).
+// What sf_pair_sums needs of a candidate besides the voxels: step and the offsets of the clamps, ka[t-1] = step - (t+1)
+// for 1 <= t < NK (NK = sf_single_of_pair(P)) and kb[t-1] = 2 step - (t+1) for 1 <= t < P.  The same for every row
+// of the detector, so the forward kernel works them out once per candidate, lane-parallel.
 template <int P>
-SF_HD void sf_pair_sums(const float (&x)[P], float fr1, float step, float &sa, float &sb)
+struct SfPairConsts {
+    float step;
+    float ka[sf_single_of_pair(P) > 1 ? sf_single_of_pair(P) - 1 : 1];
+    float kb[P > 1 ? P - 1 : 1];
+};
+
+template <int P>
+SF_HD SfPairConsts<P> sf_pair_consts(float step)
 {
     constexpr int NK = sf_single_of_pair(P);
+    SfPairConsts<P> k;
+    k.step = step;
     const float step2 = step + step;
+#pragma unroll
+    for (int t = 1; t < NK && t < P; ++t) k.ka[t - 1] = step - (float)(t + 1);
+#pragma unroll
+    for (int t = 1; t < P; ++t) k.kb[t - 1] = step2 - (float)(t + 1);
+    return k;
+}
+
+template <int P>
+SF_HD void sf_pair_sums(const float (&x)[P], float fr1, const SfPairConsts<P> &k, float &sa, float &sb)
+{
+    constexpr int NK = sf_single_of_pair(P);
     float d[P];
 #pragma unroll
     for (int t = 1; t < P; ++t) d[t] = x[t] - x[0];
-    float a = step * x[0];
+    const float a0 = k.step * x[0];
+    float a = a0;
 #pragma unroll
-    for (int t = 1; t < NK && t < P; ++t) a = fmaf(sf_clamp(fr1 + (step - (float)(t + 1)), 0.0f, 1.0f), d[t], a);
-    float b = step2 * x[0];
+    for (int t = 1; t < NK && t < P; ++t) a = fmaf(sf_clamp(fr1 + k.ka[t - 1], 0.0f, 1.0f), d[t], a);
+    float b = a0 + a0;                              // 2 step x_0, exactly
 #pragma unroll
-    for (int t = 1; t < P; ++t) b = fmaf(sf_clamp(fr1 + (step2 - (float)(t + 1)), 0.0f, 1.0f), d[t], b);
+    for (int t = 1; t < P; ++t) b = fmaf(sf_clamp(fr1 + k.kb[t - 1], 0.0f, 1.0f), d[t], b);
     sa = a;
     sb = b - a;
 }
@@ -305,6 +329,17 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom gk, c
 
     const int slot = lane & ((1 << nq_log2) - 1), nrel = lane >> nq_log2, sb_slabs = 64 >> nq_log2;
 
+    // What a candidate's visit needs as plain vector operands (the CW column factors, step and the clamp offsets of the
+    // four-voxel body) goes through LDS: every lane writes its candidate's record, the wave reads the record of the
+    // candidate it visits back at a uniform address, which the LDS serves as a broadcast without touching the vector
+    // ALU (a v_readlane costs as much issue time as two and a half FMAs; the kernel is bound by that issue time).
+    // Only what must sit in scalar registers still comes by v_readlane: the column's offset (buffer descriptor) and mu
+    // (scalar operand of the placement FMAs).
+    constexpr int PB = NKP > 4 ? 4 : NKP;           // the body most candidates take
+    constexpr int FP_REC = 3;                       // float4s per record
+    __shared__ float4 recs[FP_WAVES][64][FP_REC];
+    float4 (*rec)[FP_REC] = recs[wave];
+
     for (int nb = slab.n0; nb < slab.n1; nb += sb_slabs) {
         // ---- lane-parallel: one candidate voxel column per lane
         const int n = nb + nrel;
@@ -320,14 +355,48 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom gk, c
         const unsigned colbase = sf_slab_column(slab, g.nx, ic, jc) * (unsigned)nzp;   // start of the padded column
         const int mu_lo = __double2loint(mu), mu_hi = __double2hiint(mu);
         const float muf = (float)mu;
+        {
+            const SfPairConsts<PB> k = sf_pair_consts<PB>(muf);
+            float w[4 * FP_REC];
+#pragma unroll
+            for (int t = 0; t < 4 * FP_REC; ++t) w[t] = 0.0f;
+#pragma unroll
+            for (int cw = 0; cw < CW; ++cw) w[cw] = fa[cw];
+            w[4] = k.step;
+#pragma unroll
+            for (int t = 0; t < sf_single_of_pair(PB) - 1; ++t) w[5 + t] = k.ka[t];
+#pragma unroll
+            for (int t = 0; t < PB - 1; ++t) w[8 + t] = k.kb[t];
+            // (the wave has consumed every value it read from the previous block's records)
+#pragma unroll
+            for (int t = 0; t < FP_REC; ++t) rec[lane][t] = make_float4(w[4 * t], w[4 * t + 1], w[4 * t + 2], w[4 * t + 3]);
+            // the records are read by the other lanes of this wave only: order the LDS accesses, no barrier
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
 
         unsigned long long mask = __ballot(any);
+        unsigned long long touch[CW];                              // candidates that touch detector column cw
+#pragma unroll
+        for (int cw = 0; cw < CW; ++cw) touch[cw] = __ballot(fa[cw] != 0.0f);
+        // most candidates of a scan with NKP > 4 still fit four voxels per pair: one 16-byte load per pair
+        const unsigned long long wide = NKP > 4 ? __ballot(!(muf <= 1.4999f)) : 0ull;
         // ---- wave-uniform walk over the candidates that matter
-        auto pairs = [&](auto pc, int e, float (&sa)[RG], float (&sb)[RG]) {
+        auto pairs = [&](auto pc, int e, const float (&r)[4 * FP_REC], float (&sa)[RG], float (&sb)[RG]) {
             constexpr int P = decltype(pc)::value;
             const unsigned s_base = (unsigned)__builtin_amdgcn_readlane((int)colbase, e);
             const double s_mu = __hiloint2double(__builtin_amdgcn_readlane(mu_hi, e), __builtin_amdgcn_readlane(mu_lo, e));
-            const float step = (float)s_mu;
+            SfPairConsts<P> k;
+            if constexpr (P == PB) {
+                k.step = r[4];
+#pragma unroll
+                for (int t = 0; t < sf_single_of_pair(P) - 1; ++t) k.ka[t] = r[5 + t];
+#pragma unroll
+                for (int t = 0; t < P - 1; ++t) k.kb[t] = r[8 + t];
+            } else {
+                k = sf_pair_consts<P>(r[4]);
+            }
             // buffer resource of this candidate's padded z-column: loads beyond it return zero
             const __amdgpu_buffer_rsrc_t col = __builtin_amdgcn_make_buffer_rsrc((void *)(volz + s_base), 0, (int)col_bytes, 0x00020000);
             float fr1[RG];
@@ -345,32 +414,32 @@ __global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom gk, c
                 for (int t = 0; t < P; ++t)      // the compiler merges these into loads of up to 16 bytes
                     xv[gq][t] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(col, (int)ko[gq] + 4 * t, 0, 0));
 #pragma unroll
-            for (int gq = 0; gq < RG; ++gq) sf_pair_sums<P>(xv[gq], fr1[gq], step, sa[gq], sb[gq]);
+            for (int gq = 0; gq < RG; ++gq) sf_pair_sums<P>(xv[gq], fr1[gq], k, sa[gq], sb[gq]);
         };
         while (mask) {
             const int e = __builtin_ctzll(mask);
             mask &= mask - 1;
+            float r[4 * FP_REC];
+#pragma unroll
+            for (int t = 0; t < FP_REC; ++t) {
+                const float4 q4 = rec[e][t];
+                r[4 * t] = q4.x; r[4 * t + 1] = q4.y; r[4 * t + 2] = q4.z; r[4 * t + 3] = q4.w;
+            }
             float sa[RG], sb[RG];
             if constexpr (NKP > 4) {
-                // most candidates of such a scan still fit four voxels per pair: one 16-byte load per pair
-                const float s_step = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, muf), e));
-                if (s_step <= 1.4999f) pairs(std::integral_constant<int, 4>{}, e, sa, sb);
-                else pairs(std::integral_constant<int, NKP>{}, e, sa, sb);
+                if (!((wide >> e) & 1ull)) pairs(std::integral_constant<int, 4>{}, e, r, sa, sb);
+                else pairs(std::integral_constant<int, NKP>{}, e, r, sa, sb);
             } else {
-                pairs(std::integral_constant<int, NKP>{}, e, sa, sb);
+                pairs(std::integral_constant<int, NKP>{}, e, r, sa, sb);
             }
-            float s_fa[CW];
-#pragma unroll
-            for (int cw = 0; cw < CW; ++cw)
-                s_fa[cw] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, fa[cw]), e));
             // a candidate usually touches only some of the bundle's columns: skip the others (wave-uniform branches)
 #pragma unroll
             for (int cw = 0; cw < CW; ++cw) {
-                if (s_fa[cw] != 0.0f) {
+                if ((touch[cw] >> e) & 1ull) {
 #pragma unroll
                     for (int gq = 0; gq < RG; ++gq) {
-                        acc[cw][gq][0] = fmaf(s_fa[cw], sa[gq], acc[cw][gq][0]);
-                        acc[cw][gq][1] = fmaf(s_fa[cw], sb[gq], acc[cw][gq][1]);
+                        acc[cw][gq][0] = fmaf(r[cw], sa[gq], acc[cw][gq][0]);
+                        acc[cw][gq][1] = fmaf(r[cw], sb[gq], acc[cw][gq][1]);
                     }
                 }
             }

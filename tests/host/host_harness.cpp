@@ -250,7 +250,7 @@ template <int CW, int P>
 static void host_pairs_of_candidate(const SfGeom &g, const float *col, int nzp, double mu, double zkp, const float (&fa)[CW],
                                     std::vector<float> &acc)
 {
-    const float step = (float)mu;
+    const SfPairConsts<P> k = sf_pair_consts<P>((float)mu);      // per candidate, as the kernel's lanes work them out
     for (int r = 0; r < g.nrows; r += 2) {
         float fr1;
         unsigned hi;
@@ -259,7 +259,7 @@ static void host_pairs_of_candidate(const SfGeom &g, const float *col, int nzp, 
         float x[P];
         for (int t = 0; t < P; ++t) x[t] = (kf + t >= 0 && kf + t < nzp) ? col[kf + t] : 0.0f;
         float sa, sb;
-        sf_pair_sums<P>(x, fr1, step, sa, sb);
+        sf_pair_sums<P>(x, fr1, k, sa, sb);
         for (int cw = 0; cw < CW; ++cw) {
             acc[(size_t)r * CW + cw] = fmaf(fa[cw], sa, acc[(size_t)r * CW + cw]);
             if (r + 1 < g.nrows) acc[(size_t)(r + 1) * CW + cw] = fmaf(fa[cw], sb, acc[(size_t)(r + 1) * CW + cw]);
