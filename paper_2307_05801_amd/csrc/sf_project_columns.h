@@ -263,10 +263,12 @@ constexpr int FP_WAVES = 4;      // waves per workgroup: adjacent column bundles
 
 // NKP: voxels a pair of adjacent rows can overlap (2 .. FP_MAX_P); RG: groups of 128 rows per wave; CW: adjacent detector
 // columns per wave; GT: 0 flat or parallel, 1 cylindrical detector, 2 modular geometry with upright modules.
+// (The cylinder's record phase needs more registers: its instances are held to the waves per SIMD they reach without
+// the records' staging, four up to two row groups, three beyond.)
 // nq_log2: log2 of the candidate slots per slab (a power of two <= 64).  major[a * nbundles + b]: 1 if bundle b of view
 // a advances fastest along x (decided once, on the host, so that both agree on which slabs a bundle reads).
 template <int NKP, int RG, int CW, int GT>
-__global__ __launch_bounds__(FP_WAVES * 64) void sf_project_columns(SfGeom gk, const SfView *__restrict__ views,
+__global__ __launch_bounds__(FP_WAVES * 64, GT == 1 ? (RG <= 2 ? 4 : 3) : 1) void sf_project_columns(SfGeom gk, const SfView *__restrict__ views,
                                                                     const float *__restrict__ volz, float *__restrict__ sino,
                                                                     const unsigned char *__restrict__ major, int nzp,
                                                                     size_t item_stride, int nq_log2, int col_tiles, int bands,
