@@ -272,22 +272,26 @@ __global__ __launch_bounds__(256, (GT == 1 && NV > 2 && BP_ZC > 32) ? 3 : 4) voi
         // not (the instance is built for the tallest footprint).  The choice is uniform over the wave, so it costs one
         // ballot per view.
         const bool shared_rows = NV == 2 || __builtin_amdgcn_ballot_w64(ax.av > 1.0f) == 0;
+        // Where every voxel of the wave is between one and two rows tall, a voxel covers the rest of its first row, then
+        // up to one whole row, then part of a third, and the next voxel starts one or two rows further: the
+        // u-combined sum of that row is carried over (one select), the two rows after it are fetched fresh.
+        const bool one_to_two_rows = NV == 3 && !shared_rows && __builtin_amdgcn_ballot_w64(!(ax.av > 1.0f && ax.av <= 2.0f)) == 0;
+        auto row_sum = [&](const float *q) {
+            float s = fu[0] * q[0];
+#pragma unroll
+            for (int m = 1; m < NC; ++m) s = fmaf(fu[m], q[m], s);
+            return s;
+        };
+        // The voxel's first row is carried as a byte offset into the patch array (both buffers), so that every LDS read is
+        // that register plus an immediate and a row crossing costs one select and one add.
+        const char *const lds0 = reinterpret_cast<const char *>(&patch[0][0]);
+        unsigned pb = (unsigned)((a & 1) * (BP_PH * BP_PS) + (int)ofs) * 4u;
+        auto at = [&](unsigned byte_ofs) { return reinterpret_cast<const float *>(lds0 + byte_ofs); };
         if (shared_rows) {
             // A voxel is at most one row tall, so consecutive voxels share a row: keep the u-combined samples of the
             // current and the next row in registers and fetch one new row per voxel (half the LDS traffic).
-            auto row_sum = [&](const float *q) {
-                float s = fu[0] * q[0];
-#pragma unroll
-                for (int m = 1; m < NC; ++m) s = fmaf(fu[m], q[m], s);
-                return s;
-            };
             // f: where the voxel's lower face lies inside its first row, in [0,1); the face moves up by av per voxel.
-            // The voxel's first row is carried as a byte offset into the patch array (both buffers), so that every
-            // LDS read is that register plus an immediate and a row crossing costs one select and one add.
             float f = ax.phi0;
-            const char *const lds0 = reinterpret_cast<const char *>(&patch[0][0]);
-            unsigned pb = (unsigned)((a & 1) * (BP_PH * BP_PS) + (int)ofs) * 4u;
-            auto at = [&](unsigned byte_ofs) { return reinterpret_cast<const float *>(lds0 + byte_ofs); };
             float s_cur = row_sum(at(pb)), s_next = row_sum(at(pb + 4u * BP_PS));
 #pragma unroll
             for (int kk = 0; kk < BP_ZC; ++kk) {
@@ -302,6 +306,27 @@ __global__ __launch_bounds__(256, (GT == 1 && NV > 2 && BP_ZC > 32) ? 3 : 4) voi
                     s_cur = cross ? s_next : s_cur;
                     s_next = s_new;
                     f = cross ? w1 : t;                           // t - 1 where a row was crossed
+                }
+                if ((kk & 3) == 3)
+                    asm volatile("" : "+v"(pb), "+v"(acc[kk - 3]), "+v"(acc[kk - 2]), "+v"(acc[kk - 1]), "+v"(acc[kk]));
+            }
+        } else if (NV == 3 && one_to_two_rows) {
+            float f = ax.phi0;
+            float s0 = row_sum(at(pb)), s1 = row_sum(at(pb + 4u * BP_PS)), s2 = row_sum(at(pb + 8u * BP_PS));
+#pragma unroll
+            for (int kk = 0; kk < BP_ZC; ++kk) {
+                const float t = f + ax.av;                        // upper face from the first row's lower edge: in (1, 3)
+                const float w2 = sf_clamp(t - 2.0f, 0.0f, 1.0f);  // part in the third row
+                const float w0 = 1.0f - f;                        // the rest of the first row
+                const float w1 = (ax.av - w0) - w2;
+                acc[kk] = fmaf(w2, s2, fmaf(w1, s1, fmaf(w0, s0, acc[kk])));
+                if (kk + 1 < BP_ZC) {
+                    const bool two = t >= 2.0f;                   // the next voxel starts two rows further
+                    pb += two ? 8u * BP_PS : 4u * BP_PS;
+                    s0 = two ? s2 : s1;
+                    s1 = row_sum(at(pb + 4u * BP_PS));
+                    s2 = row_sum(at(pb + 8u * BP_PS));
+                    f = two ? w2 : t - 1.0f;                      // t - 2 where two rows were crossed
                 }
                 if ((kk & 3) == 3)
                     asm volatile("" : "+v"(pb), "+v"(acc[kk - 3]), "+v"(acc[kk - 2]), "+v"(acc[kk - 1]), "+v"(acc[kk]));
