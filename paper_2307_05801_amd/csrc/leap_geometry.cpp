@@ -211,13 +211,27 @@ static void select_footprint_tiled(leap_geometry *G)
         G->max_rows_per_voxel > 3.0 || !((double)d->nrows * d->ncols < 1073741824.0))     // 32-bit byte offsets within a view
         return;
     G->bp_nc = std::max(2, (int)std::ceil(G->max_cols_per_voxel) + 1);
-    G->bp_nv = std::max(2, (int)std::ceil(G->max_rows_per_voxel - 1e-6) + 1);
+    // rows a voxel can touch; the three-row instance runs schemes that need every voxel at most two rows tall, so a
+    // bound that close to two rows takes the four-row instance
+    const double mr = G->max_rows_per_voxel;
+    G->bp_nv = mr <= 1.0 + 1e-6 ? 2 : (mr <= 1.999 ? 3 : std::max(4, (int)std::ceil(mr - 1e-6) + 1));
     G->bp_wh = (float)(0.5 * G->max_cols_per_voxel);
     const float hx = 0.5f * (float)(BP_T - 1) * G->g.T;
-    // 64-voxel chunks only pay off on tall volumes, and only the two-row instances keep 64 sums in registers without spilling
-    long first_shape = d->nz >= 128 && G->bp_nv == 2 ? 0 : BP_FIRST_SHORT_SHAPE;
-    if (debug_option("bp_shape", first_shape)) first_shape = ((first_shape % BP_NSHAPES) + BP_NSHAPES) % BP_NSHAPES;
-    for (int sh = (int)first_shape; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
+    // 64-voxel chunks only pay off on tall volumes; the two-row instances keep 64 sums in registers in either 64-voxel
+    // shape, the three-row instances in the tall one only
+    int order[BP_NSHAPES], norder = 0;
+    if (d->nz >= 128 && G->bp_nv == 2) order[norder++] = 0;
+    if (d->nz >= 128 && G->bp_nv <= 3) order[norder++] = BP_TALL_SHAPE;
+    for (int sh = BP_FIRST_SHORT_SHAPE; sh <= BP_LAST_SHORT_SHAPE; ++sh) order[norder++] = sh;
+    long forced;
+    if (debug_option("bp_shape", forced)) {        // start at a given shape, then the short ones after it
+        forced = ((forced % BP_NSHAPES) + BP_NSHAPES) % BP_NSHAPES;
+        norder = 0;
+        order[norder++] = (int)forced;
+        for (int sh = std::max((int)forced + 1, BP_FIRST_SHORT_SHAPE); sh <= BP_LAST_SHORT_SHAPE; ++sh) order[norder++] = sh;
+    }
+    for (int n = 0; n < norder && !G->bp_tiled; ++n) {
+        const int sh = order[n];
         staged_window_need(G, BP_SHAPES[sh].zc,
                            [&](const SfGeom &ga, const SfView &v, float xc, float yc, float z0, float z1) {
                                return sf_bp_window(ga, v, xc, yc, hx, z0, z1, G->bp_wh, G->bp_nc, G->bp_nv);
@@ -336,8 +350,9 @@ static void select_siddon_fast_kernels(leap_geometry *G)
         G->bp_nc = std::max(2, (int)std::floor(G->max_cols_per_voxel + 0.01) + 1);
         const float hx = 0.5f * (float)BP_T * G->g.T;
         long first_shape = BP_FIRST_SHORT_SHAPE;       // the 64-voxel shapes do not fit: the sums live in LDS
-        if (debug_option("bp_shape", first_shape)) first_shape = std::max((long)BP_FIRST_SHORT_SHAPE, first_shape % BP_NSHAPES);
-        for (int sh = (int)first_shape; sh < BP_NSHAPES && !G->bp_tiled; ++sh) {
+        if (debug_option("bp_shape", first_shape))
+            first_shape = std::min((long)BP_LAST_SHORT_SHAPE, std::max((long)BP_FIRST_SHORT_SHAPE, first_shape % BP_NSHAPES));
+        for (int sh = (int)first_shape; sh <= BP_LAST_SHORT_SHAPE && !G->bp_tiled; ++sh) {
             staged_window_need(G, BP_SHAPES[sh].zc,
                                [&](const SfGeom &ga, const SfView &v, float xc, float yc, float z0, float z1) {
                                    return sd_bp_window(ga, v, xc, yc, hx, z0, z1);

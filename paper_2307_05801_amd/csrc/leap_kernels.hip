@@ -511,6 +511,13 @@ static bool launch_bp_shape(const leap_geometry *G, const float *d_sino, float *
     case 2: launch_bp_tiled<NC, NV, 2>(G, d_sino, d_vol, stream, items); return true;
     case 3: launch_bp_tiled<NC, NV, 3>(G, d_sino, d_vol, stream, items); return true;
     case 4: launch_bp_tiled<NC, NV, 4>(G, d_sino, d_vol, stream, items); return true;
+    case BP_TALL_SHAPE:      // 64 voxels per thread under a taller window: two- and three-row instances
+        if constexpr (NV <= 3) {
+            launch_bp_tiled<NC, NV, BP_TALL_SHAPE>(G, d_sino, d_vol, stream, items);
+            return true;
+        } else {
+            return false;
+        }
     default: return false;
     }
 }

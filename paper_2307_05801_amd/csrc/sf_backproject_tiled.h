@@ -25,9 +25,13 @@ constexpr int BP_T = 16;        // tile edge in voxels (x and y)
 struct SfBpShape {
     int zc, pw, ph;
 };
-constexpr SfBpShape BP_SHAPES[] = {{64, 32, 76}, {32, 32, 44}, {32, 32, 56}, {16, 32, 44}, {16, 64, 48}};
-constexpr int BP_NSHAPES = 5;
+// The last one keeps 64 voxels per thread for footprints up to two rows tall (a voxel up to about 1.3 rows at 512 rows
+// and more); it is instantiated for NV <= 3 only, shape 0 for NV == 2 only (taller footprints would spill registers).
+constexpr SfBpShape BP_SHAPES[] = {{64, 32, 76}, {32, 32, 44}, {32, 32, 56}, {16, 32, 44}, {16, 64, 48}, {64, 32, 96}};
+constexpr int BP_NSHAPES = 6;
 constexpr int BP_FIRST_SHORT_SHAPE = 1;      // first shape with fewer than 64 voxels per thread
+constexpr int BP_LAST_SHORT_SHAPE = 4;       // last one
+constexpr int BP_TALL_SHAPE = 5;
 
 // Window of the detector that one (view, tile, z-chunk) can touch.  Evaluated identically on the host
 // (limit check) and in the kernel; everything here is uniform over the workgroup.
@@ -121,7 +125,8 @@ __device__ __forceinline__ void bp_load_view(const SfGeom &g, const SfView v, co
 #pragma unroll
     for (int s = 0; s < NSTAGE; ++s) {
         const int r = w.r0 + sr + RSTEP * s;
-        const bool in = cin && (unsigned)r < (unsigned)g.nrows && (sr + RSTEP * s) < PH;
+        // (rows from need_h on are never read: whole steps beyond it are left out, here and in bp_store_view)
+        const bool in = cin && (unsigned)r < (unsigned)g.nrows && (sr + RSTEP * s) < PH && RSTEP * s < w.need_h;
         stage[s] = in ? *reinterpret_cast<const float *>(yb + off) : 0.0f;
         off += step;
     }
@@ -148,7 +153,9 @@ __device__ __forceinline__ void bp_store_view(const SfGeom &g, const SfView v, i
 #pragma unroll
     for (int s = 0; s < NSTAGE; ++s) {
         const int row = sr + RSTEP * s;
-        if (row < PH) buf[row * PS + sc] = stage[s] * sf_amp_at(g, v, ac, vv);
+        if (RSTEP * s < w.need_h) {        // uniform over the workgroup
+            if (row < PH) buf[row * PS + sc] = stage[s] * sf_amp_at(g, v, ac, vv);
+        }
         vv += dv;
     }
 }
@@ -271,11 +278,11 @@ __global__ __launch_bounds__(256, (GT == 1 && NV > 2 && BP_ZC > 32) ? 3 : 4) voi
         // cheaper running scheme applies; tiles far from the source qualify even when the nearest voxels of the volume do
         // not (the instance is built for the tallest footprint).  The choice is uniform over the wave, so it costs one
         // ballot per view.
-        const bool shared_rows = NV == 2 || __builtin_amdgcn_ballot_w64(ax.av > 1.0f) == 0;
-        // Where every voxel of the wave is between one and two rows tall, a voxel covers the rest of its first row, then
-        // up to one whole row, then part of a third, and the next voxel starts one or two rows further: the
-        // u-combined sum of that row is carried over (one select), the two rows after it are fetched fresh.
-        const bool one_to_two_rows = NV == 3 && !shared_rows && __builtin_amdgcn_ballot_w64(!(ax.av > 1.0f && ax.av <= 2.0f)) == 0;
+        // NV == 3 is chosen on the host only when no voxel is taller than two rows (with a margin): every lane takes one
+        // of the two running schemes below, whichever fits its voxel column in this view.  Tiles far from the source hold
+        // short voxels even when the nearest voxels of the volume are tall; a wave that holds both kinds (rare: the line
+        // where a voxel is exactly one row tall crosses its 16 x 4 columns) runs the two schemes one after the other.
+        const bool shared_rows = NV == 2 || (NV == 3 ? ax.av <= 1.0f : __builtin_amdgcn_ballot_w64(ax.av > 1.0f) == 0);
         auto row_sum = [&](const float *q) {
             float s = fu[0] * q[0];
 #pragma unroll
@@ -310,7 +317,10 @@ __global__ __launch_bounds__(256, (GT == 1 && NV > 2 && BP_ZC > 32) ? 3 : 4) voi
                 if ((kk & 3) == 3)
                     asm volatile("" : "+v"(pb), "+v"(acc[kk - 3]), "+v"(acc[kk - 2]), "+v"(acc[kk - 1]), "+v"(acc[kk]));
             }
-        } else if (NV == 3 && one_to_two_rows) {
+        } else if constexpr (NV == 3) {
+            // Between one and two rows tall: a voxel covers the rest of its first row, then up to one whole row, then
+            // part of a third, and the next voxel starts one or two rows further: the u-combined sum of that row is
+            // carried over (one select), the two rows after it are fetched fresh.
             float f = ax.phi0;
             float s0 = row_sum(at(pb)), s1 = row_sum(at(pb + 4u * BP_PS)), s2 = row_sum(at(pb + 8u * BP_PS));
 #pragma unroll
@@ -331,7 +341,7 @@ __global__ __launch_bounds__(256, (GT == 1 && NV > 2 && BP_ZC > 32) ? 3 : 4) voi
                 if ((kk & 3) == 3)
                     asm volatile("" : "+v"(pb), "+v"(acc[kk - 3]), "+v"(acc[kk - 2]), "+v"(acc[kk - 1]), "+v"(acc[kk]));
             }
-        } else if constexpr (NV > 2) {
+        } else if constexpr (NV > 3) {
         float lo = ax.phi0;
 #pragma unroll
         for (int kk = 0; kk < BP_ZC; ++kk) {
