@@ -34,25 +34,25 @@ MEASURED_TRAFFIC = {
                            "fetch_bytes": 3.74159e7 * 2048, "write_bytes": 9.93274e6 * 1024,
                            "source": "profiles/sf_project_columns_c3_cone_512.md"},
     ("c3_cone_512", "AT"): {"instance": "AT=tiled(nc=3,nv=2,zc=64,window=24x63)", "launches": 1,
-                            "fetch_bytes": 8.48028e6 * 2048, "write_bytes": 524288 * 1024,
+                            "fetch_bytes": 6.36848e6 * 2048, "write_bytes": 524288 * 1024,
                             "source": "profiles/sf_backproject_tiled_c3_cone_512.md"},
     ("c2_parallel3d_256", "A"): {"instance": "A=columns(nq=8/8,nkp=3,rg=2,cw=4,slab=256)", "launches": 2,
                                  "fetch_bytes": 1.72456e6 * 2048, "write_bytes": 72767 * 1024,
                                  "source": "profiles/sf_pair_c2_parallel_256.md"},
     ("c2_parallel3d_256", "AT"): {"instance": "AT=tiled(nc=3,nv=2,zc=64,window=25x67)", "launches": 1,
-                                  "fetch_bytes": 182401 * 2048, "write_bytes": 65536 * 1024,
+                                  "fetch_bytes": 178849 * 2048, "write_bytes": 65536 * 1024,
                                   "source": "profiles/sf_pair_c2_parallel_256.md"},
     ("c4_cone_limited_batch8_256", "A"): {"instance": "A=columns(nq=8/8,nkp=3,rg=3,cw=4,slab=256)", "launches": 10,
                                           "fetch_bytes": 4.58747e6 * 2048, "write_bytes": 1.85073e6 * 1024,
                                           "source": "profiles/sf_pair_c4_training_batch.md"},
     ("c4_cone_limited_batch8_256", "AT"): {"instance": "AT=tiled(nc=4,nv=3,zc=16,window=49x46)", "launches": 1,
-                                           "fetch_bytes": 3.17815e6 * 2048, "write_bytes": 524288 * 1024,
+                                           "fetch_bytes": 1.65103e6 * 2048, "write_bytes": 524288 * 1024,
                                            "source": "profiles/sf_pair_c4_training_batch.md"},
     ("c5_cone_1024", "A"): {"instance": "A=columns(nq=11/16,nkp=4,rg=4,cw=4,slab=124)", "launches": 18,
                             "fetch_bytes": 9.98654e8 * 2048, "write_bytes": 9.88812e7 * 1024,
                             "source": "profiles/sf_pair_c5_cone_1024.md"},
-    ("c5_cone_1024", "AT"): {"instance": "AT=tiled(nc=3,nv=3,zc=32,window=31x47)", "launches": 1,
-                             "fetch_bytes": 1.18738e9 * 2048, "write_bytes": 4.1943e6 * 1024,
+    ("c5_cone_1024", "AT"): {"instance": "AT=tiled(nc=3,nv=3,zc=64,window=31x86)", "launches": 1,
+                             "fetch_bytes": 7.15103e8 * 2048, "write_bytes": 4.1943e6 * 1024,
                              "source": "profiles/sf_pair_c5_cone_1024.md"},
     ("c3_cone_512:siddon", "A"): {"instance": "A=columns(rg=8,slab=124)", "launches": 10,
                                   "fetch_bytes": 8.21501e7 * 2048, "write_bytes": 9.42225e6 * 1024,
