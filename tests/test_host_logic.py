@@ -205,6 +205,21 @@ def test_scratch_override_and_general_kernels_need_none(host, monkeypatch):
     assert "A=general" in desc and scratch_bytes(desc) == 0, desc
 
 
+def test_row_schemes_of_the_tiled_back_projection_follow_the_voxel_height(host):
+    """The three-row instance of the tiled back projection runs schemes that need every voxel at most two detector rows
+    tall: a bound on the height within a thousandth of two rows takes the four-row instance, and volumes of 128 layers
+    and more keep 64 voxels per thread for footprints up to two rows tall when their window fits."""
+    base = reduced(config(2), 4, nviews=8)                 # parallel beam: a voxel is voxel_z / pixel_v rows tall
+    for voxel_z, nz, token in ((0.99, 40, "nv=2,"), (1.0, 40, "nv=2,"), (1.25, 40, "nv=3,"), (1.99, 40, "nv=3,"),
+                               (1.9995, 40, "nv=4,"), (2.4, 40, "nv=4,"),
+                               (1.0, 160, "nv=2,zc=64"), (1.2, 160, "nv=3,zc=64"), (1.9, 160, "nv=3,zc=16")):
+        cfg = base.replace(voxel_z=voxel_z, pixel_v=1.0, nz=nz, nrows=int(voxel_z * nz) + 12)
+        h = handle(host, cfg)
+        desc = B.leap_geometry_describe(h, host)
+        B.leap_geometry_destroy(h, host)
+        assert "AT=tiled" in desc and token in desc, (voxel_z, nz, desc)
+
+
 def window_report(host, cfg):
     h = handle(host, cfg)
     rep = (C.c_int64 * 8)()
