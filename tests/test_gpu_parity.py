@@ -66,6 +66,8 @@ SMALL_CASES = [
     ("c4_div4", 4, lambda: reduced(config(4), 4, nviews=15)),
     ("c5_div16_shifted", 5, lambda: reduced(config(5), 16, nviews=36)),
     ("c5_div8_tall_voxels", 5, lambda: reduced(config(5), 8, nviews=10).replace(voxel_z=1.7, nz=40, pixel_v=2.1, nrows=70)),
+    # voxels 1.6 to 2.4 rows tall: the four-row instance of the tiled back projection (general gather)
+    ("c5_div8_taller_voxels", 5, lambda: reduced(config(5), 8, nviews=10).replace(voxel_z=2.6, nz=28, pixel_v=2.1, nrows=70)),
     ("fan", 3, lambda: CTConfig("fan_200", FAN, nviews=50, arc_deg=360.0, nrows=1, ncols=150, pixel_v=1.0,
                                 pixel_u=2.0, nx=130, ny=120, nz=1, voxel_xy=1.0, voxel_z=1.0, sod=500.0,
                                 sdd=900.0, shift_u=0.8, center_x=2.0)),
