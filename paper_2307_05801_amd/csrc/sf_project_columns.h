@@ -15,8 +15,9 @@
 // the same for the 64 lanes, and the axial part (a row's overlaps with the voxels of a voxel column) is the same for
 // the CW pixel columns: it is computed once and applied CW times.  The wave therefore computes the transaxial part
 // lane-parallel: per block of 64 / nq slabs along the marching axis, lane (slab, slot) evaluates one candidate voxel
-// column; a ballot picks the candidates with F_u > 0 and the wave then walks them one by one, broadcasting their few
-// parameters through v_readlane, while each lane accumulates its own rows' axial overlaps.
+// column; a ballot picks the candidates with F_u > 0 and the wave then walks them one by one, reading a candidate's
+// record back from LDS at a wave-uniform address (and the two numbers that must be scalar through v_readlane), while
+// each lane accumulates its own rows' axial overlaps.
 //
 // Two adjacent rows per lane, one load.  The vector cache serves a wave-wide load at four lanes per clock whether a
 // lane asks for 4 or for 16 bytes (measured), and two adjacent rows overlap in the voxels they need.  One load of P
@@ -259,7 +260,7 @@ __global__ __launch_bounds__(256) void sf_clear_column_pads(float *__restrict__ 
     if (t < (unsigned)nzp) volz[(size_t)ncolumns * nzp + t] = 0.0f;
 }
 
-constexpr int FP_WAVES = 4;      // waves per workgroup: adjacent column bundles of one view (no LDS, no barrier)
+constexpr int FP_WAVES = 4;      // waves per workgroup: adjacent column bundles of one view (each wave its own LDS, no barrier)
 
 // NKP: voxels a pair of adjacent rows can overlap (2 .. FP_MAX_P); RG: groups of 128 rows per wave; CW: adjacent detector
 // columns per wave; GT: 0 flat or parallel, 1 cylindrical detector, 2 modular geometry with upright modules.
