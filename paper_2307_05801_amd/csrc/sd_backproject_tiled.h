@@ -120,6 +120,9 @@ SF_HD SdBpScene sd_bp_scene(const SfGeom &g, int i0, int j0, int k0)
 
 // NCS: detector columns whose centre can fall inside one voxel's in-plane footprint.  MOD: modular geometry with
 // upright modules, one parameter block geoms[a] per view (g holds the sizes).
+constexpr double SD_BP_MAGIC = 1572864.0;        // 1.5 * 2^20
+constexpr unsigned SD_BP_HI = 0x41380000u;       // its high word
+
 template <int NCS, int ZC, int PW, int PH, bool MOD>
 __global__ __launch_bounds__(256) void sd_backproject_tiled(SfGeom g, const SfView *__restrict__ views,
                                                             const SdRayCol *__restrict__ rays, const float *__restrict__ sino,
@@ -209,13 +212,17 @@ __global__ __launch_bounds__(256) void sd_backproject_tiled(SfGeom g, const SfVi
                 const int rs = run ? rz : 0, re = run ? H : rz;
                 if (rs >= re) continue;
                 const double h = run ? hmin : hmax;
-                long long q = (long long)floor(fma(sd_row_v(gv, win.r0 + rs), h, zrel0) * 4294967296.0);
-                const long long dq = (long long)rint(gv.pvd * h * 4294967296.0);
+                // The fixed-point number lives in a double: with 1.5 * 2^20 added, a double's unit in the last place is
+                // 2^-32, so its low word is the fraction and its high word SD_BP_HI plus the slot, and advancing it is one
+                // double addition (exact: both terms are multiples of 2^-32) instead of a 64-bit integer add in two halves.
+                double q = floor(fma(sd_row_v(gv, win.r0 + rs), h, zrel0) * 4294967296.0) * 2.3283064365386963e-10 + SD_BP_MAGIC;
+                const double dq = rint(gv.pvd * h * 4294967296.0) * 2.3283064365386963e-10;
                 unsigned ofs = (unsigned)(rs * PS + wc);
                 for (int row = rs; row < re; ++row) {
-                    int slot = (int)(q >> 32);
+                    const unsigned long long qbits = __builtin_bit_cast(unsigned long long, q);
+                    int slot = (int)((unsigned)(qbits >> 32) - SD_BP_HI);
                     slot = slot < 0 ? 0 : (slot > ZC + 2 ? ZC + 2 : slot);
-                    const float up = (float)(~(unsigned)q) + 1.0f;     // (1 - fraction) * 2^32, at least 1
+                    const float up = (float)(~(unsigned)qbits) + 1.0f;  // (1 - fraction) * 2^32, at least 1
                     const float wl = fminf(up * (scale * ri[row]), dt);
                     const float y = buf[ofs];
                     float *__restrict__ cell = sums + (slot * 256 + tid);
