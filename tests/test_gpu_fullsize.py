@@ -120,6 +120,55 @@ def test_c5_subset_of_views_large_offsets(oracle_mod):
     assert abs(lhs - rhs) <= TOL * abs(lhs)
 
 
+def test_volume_of_more_than_2_31_voxels(oracle_mod):
+    """1296 x 1296 x 1290 voxels (2.17e9: element indices beyond 2^31, 8.7 GB) seen from six views by the fast kernels:
+    sampled rays and voxels against the oracle, with the last voxel and the last ray among them, and the adjoint identity
+    over the whole arrays."""
+    import torch
+    from synthetic import CTConfig
+    from synthetic.configs import CONE
+    from paper_2307_05801_amd import Geometry
+    cfg = CTConfig("beyond_2_31", CONE, nviews=6, arc_deg=360.0, nrows=640, ncols=640, pixel_v=0.6, pixel_u=0.6,
+                   nx=1296, ny=1296, nz=1290, voxel_xy=0.2, voxel_z=0.2, sod=800.0, sdd=1200.0, shift_u=0.3, shift_v=-0.2,
+                   start_deg=11.0)
+    n = cfg.nx * cfg.ny * cfg.nz
+    assert n > 2 ** 31
+    print("[gpu] beyond 2^31: inputs", flush=True)
+    rng = np.random.default_rng([2031, 3])
+    x = np.empty(cfg.vol_shape, dtype=np.float32)
+    for k in range(0, cfg.nz, 64):                      # in slices: no second 8.7 GB array on the way
+        x[k:k + 64] = rng.random(x[k:k + 64].shape, dtype=np.float32)
+    y = uniform_sinogram(cfg, 2031)[0]
+    geo = Geometry(cfg)
+    desc = geo.describe()
+    print(f"[gpu] beyond 2^31: {desc}", flush=True)
+    assert "A=columns" in desc and "AT=tiled" in desc, desc
+    print("[gpu] beyond 2^31: project", flush=True)
+    xt = torch.from_numpy(x).cuda()
+    ax = geo.project(xt)
+    torch.cuda.synchronize()
+    del xt
+    print("[gpu] beyond 2^31: backproject", flush=True)
+    aty_t = geo.backproject(torch.from_numpy(y).cuda())
+    torch.cuda.synchronize()
+    ax, aty = ax.cpu().numpy(), aty_t.cpu().numpy()
+    del aty_t
+    geo.close()
+    print("[gpu] beyond 2^31: samples", flush=True)
+    rs = np.random.default_rng(45)
+    nrays = cfg.nviews * cfg.nrows * cfg.ncols
+    rays = np.unique(np.concatenate([rs.integers(0, nrays, 300), np.array([0, nrays - 1])]))
+    assert rel_l2(ax.ravel()[rays], oracle_mod.project_rays(cfg, x, rays)) <= TOL
+    vox = np.unique(np.concatenate([rs.integers(0, n, 12000), rs.integers(2 ** 31, n, 4000),
+                                    np.array([0, 2 ** 31 - 1, 2 ** 31, n - 1])]))
+    assert rel_l2(aty.ravel()[vox], oracle_mod.backproject_voxels(cfg, y, vox)) <= TOL
+    lhs = float((ax.astype(np.float64) * y).sum())
+    rhs = 0.0
+    for k in range(0, cfg.nz, 64):
+        rhs += float(np.dot(aty[k:k + 64].astype(np.float64).ravel(), x[k:k + 64].astype(np.float64).ravel()))
+    assert abs(lhs - rhs) <= TOL * abs(lhs)
+
+
 def test_c5_full_size_all_views(oracle_mod):
     """The largest case whole: 1024^3 volume, 1440 views, 1024x1024 detector shifted by 2.5 pixels (4 GiB volume,
     5.6 GiB sinogram).  Inputs are uniform noise (rasterising 50 ellipsoids on 10^9 voxels takes minutes on the CPU);
