@@ -120,10 +120,11 @@ def test_c5_subset_of_views_large_offsets(oracle_mod):
     assert abs(lhs - rhs) <= TOL * abs(lhs)
 
 
-def test_volume_of_more_than_2_31_voxels(oracle_mod):
-    """1296 x 1296 x 1290 voxels (2.17e9: element indices beyond 2^31, 8.7 GB) seen from six views by the fast kernels:
-    sampled rays and voxels against the oracle, with the last voxel and the last ray among them, and the adjoint identity
-    over the whole arrays."""
+@pytest.mark.parametrize("model", ["sf", "siddon"])
+def test_volume_of_more_than_2_31_voxels(oracle_mod, model):
+    """1296 x 1296 x 1290 voxels (2.17e9: element indices beyond 2^31, 8.7 GB) seen from six views by the fast kernels of
+    either model: sampled rays and voxels against the oracle, with the last voxel and the last ray among them, and the
+    adjoint identity over the whole arrays."""
     import torch
     from synthetic import CTConfig
     from synthetic.configs import CONE
@@ -139,7 +140,8 @@ def test_volume_of_more_than_2_31_voxels(oracle_mod):
     for k in range(0, cfg.nz, 64):                      # in slices: no second 8.7 GB array on the way
         x[k:k + 64] = rng.random(x[k:k + 64].shape, dtype=np.float32)
     y = uniform_sinogram(cfg, 2031)[0]
-    geo = Geometry(cfg)
+    ora = oracle_mod if model == "sf" else oracle_mod.siddon
+    geo = Geometry(cfg, model=model)
     desc = geo.describe()
     print(f"[gpu] beyond 2^31: {desc}", flush=True)
     assert "A=columns" in desc and "AT=tiled" in desc, desc
@@ -158,10 +160,10 @@ def test_volume_of_more_than_2_31_voxels(oracle_mod):
     rs = np.random.default_rng(45)
     nrays = cfg.nviews * cfg.nrows * cfg.ncols
     rays = np.unique(np.concatenate([rs.integers(0, nrays, 300), np.array([0, nrays - 1])]))
-    assert rel_l2(ax.ravel()[rays], oracle_mod.project_rays(cfg, x, rays)) <= TOL
+    assert rel_l2(ax.ravel()[rays], ora.project_rays(cfg, x, rays)) <= TOL
     vox = np.unique(np.concatenate([rs.integers(0, n, 12000), rs.integers(2 ** 31, n, 4000),
                                     np.array([0, 2 ** 31 - 1, 2 ** 31, n - 1])]))
-    assert rel_l2(aty.ravel()[vox], oracle_mod.backproject_voxels(cfg, y, vox)) <= TOL
+    assert rel_l2(aty.ravel()[vox], ora.backproject_voxels(cfg, y, vox)) <= TOL
     lhs = float((ax.astype(np.float64) * y).sum())
     rhs = 0.0
     for k in range(0, cfg.nz, 64):
