@@ -171,6 +171,54 @@ def test_volume_of_more_than_2_31_voxels(oracle_mod, model):
     assert abs(lhs - rhs) <= TOL * abs(lhs)
 
 
+@pytest.mark.parametrize("model", ["sf", "siddon"])
+def test_sinogram_of_more_than_2_31_samples(oracle_mod, model):
+    """1440 views of 1250 x 1250 pixels (2.25e9 samples: element indices beyond 2^31, 9 GB) of a 256^3 volume, through the
+    fast kernels of either model: sampled rays (the last one among them) and voxels against the oracle, adjoint identity."""
+    import torch
+    from synthetic import CTConfig
+    from synthetic.configs import CONE
+    from paper_2307_05801_amd import Geometry
+    cfg = CTConfig("sino_beyond_2_31", CONE, nviews=1440, arc_deg=360.0, nrows=1250, ncols=1250, pixel_v=0.35, pixel_u=0.35,
+                   nx=256, ny=256, nz=256, voxel_xy=0.3, voxel_z=0.3, sod=800.0, sdd=1200.0, shift_u=-0.4, shift_v=0.3,
+                   start_deg=2.0)
+    nsino = cfg.nviews * cfg.nrows * cfg.ncols
+    assert nsino > 2 ** 31
+    ora = oracle_mod if model == "sf" else oracle_mod.siddon
+    print("[gpu] sinogram beyond 2^31: inputs", flush=True)
+    x = standard_volume(3, cfg)
+    rng = np.random.default_rng([2032, 2])
+    y = np.empty(cfg.sino_shape, dtype=np.float32)
+    for a in range(0, cfg.nviews, 90):
+        y[a:a + 90] = rng.random(y[a:a + 90].shape, dtype=np.float32)
+    geo = Geometry(cfg, model=model)
+    desc = geo.describe()
+    print(f"[gpu] sinogram beyond 2^31: {desc}", flush=True)
+    assert "A=columns" in desc and "AT=tiled" in desc, desc
+    ax_t = geo.project(torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    ax = ax_t.cpu().numpy()
+    del ax_t
+    print("[gpu] sinogram beyond 2^31: backproject", flush=True)
+    yt = torch.from_numpy(y).cuda()
+    aty = geo.backproject(yt).cpu().numpy()
+    del yt
+    geo.close()
+    print("[gpu] sinogram beyond 2^31: samples", flush=True)
+    rs = np.random.default_rng(47)
+    rays = np.unique(np.concatenate([rs.integers(0, nsino, 300), rs.integers(2 ** 31, nsino, 100),
+                                     np.array([0, 2 ** 31 - 1, 2 ** 31, nsino - 1])]))
+    assert rel_l2(ax.ravel()[rays], ora.project_rays(cfg, x, rays)) <= TOL
+    n = cfg.nx * cfg.ny * cfg.nz
+    vox = np.unique(np.concatenate([rs.integers(0, n, 3000), np.array([0, n - 1])]))
+    assert rel_l2(aty.ravel()[vox], ora.backproject_voxels(cfg, y, vox)) <= TOL
+    lhs = 0.0
+    for a in range(0, cfg.nviews, 90):
+        lhs += float(np.dot(ax[a:a + 90].astype(np.float64).ravel(), y[a:a + 90].astype(np.float64).ravel()))
+    rhs = float((aty.astype(np.float64) * x).sum())
+    assert abs(lhs - rhs) <= TOL * abs(lhs)
+
+
 def test_c5_full_size_all_views(oracle_mod):
     """The largest case whole: 1024^3 volume, 1440 views, 1024x1024 detector shifted by 2.5 pixels (4 GiB volume,
     5.6 GiB sinogram).  Inputs are uniform noise (rasterising 50 ellipsoids on 10^9 voxels takes minutes on the CPU);
