@@ -205,6 +205,23 @@ def test_scratch_override_and_general_kernels_need_none(host, monkeypatch):
     assert "A=general" in desc and scratch_bytes(desc) == 0, desc
 
 
+@pytest.mark.parametrize("case,model,tokens", [
+    (2, B.LEAP_MODEL_SF, ("A=columns(", "cw=4", "AT=tiled(nc=3,nv=2,zc=64")),
+    (3, B.LEAP_MODEL_SF, ("A=columns(", "rg=4,cw=4", "AT=tiled(nc=3,nv=2,zc=64")),
+    (4, B.LEAP_MODEL_SF, ("A=columns(", "rg=3,cw=4", "AT=tiled(nc=4,nv=3,zc=16")),
+    (5, B.LEAP_MODEL_SF, ("A=columns(", "rg=4,cw=4", "AT=tiled(nc=3,nv=3,zc=64")),
+    (3, B.LEAP_MODEL_SIDDON, ("A=columns(rg=8", "AT=tiled(nc=2,zc=32")),
+])
+def test_benchmark_cases_take_the_instances_the_measurements_name(host, case, model, tokens):
+    """The kernel instances the measured figures belong to: a change of the selection rules that moves a benchmark case
+    to another instance (or to the general kernels) shows up here, on the CPU."""
+    h = handle(host, config(case), model)
+    desc = B.leap_geometry_describe(h, host)
+    B.leap_geometry_destroy(h, host)
+    for token in tokens:
+        assert token in desc, desc
+
+
 def test_row_schemes_of_the_tiled_back_projection_follow_the_voxel_height(host):
     """The three-row instance of the tiled back projection runs schemes that need every voxel at most two detector rows
     tall: a bound on the height within a thousandth of two rows takes the four-row instance, and volumes of 128 layers
