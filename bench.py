@@ -58,7 +58,7 @@ MEASURED_TRAFFIC = {
                                   "fetch_bytes": 8.21501e7 * 2048, "write_bytes": 9.42225e6 * 1024,
                                   "source": "profiles/sd_project_columns_c3_cone_512.md"},
     ("c3_cone_512:siddon", "AT"): {"instance": "AT=tiled(nc=2,zc=32,window=21x32)", "launches": 1,
-                                   "fetch_bytes": 3.67343e7 * 2048, "write_bytes": 524288 * 1024,
+                                   "fetch_bytes": 2.19946e7 * 2048, "write_bytes": 524288 * 1024,
                                    "source": "profiles/sd_backproject_tiled_c3_cone_512.md"},
 }
 

@@ -68,7 +68,8 @@ __device__ __forceinline__ void sd_load_view(const SfGeom &g, const SfView v, co
 #pragma unroll
     for (int s = 0; s < NSTAGE; ++s) {
         const int r = w.r0 + sr + RSTEP * s;
-        const bool in = cin && (unsigned)r < (unsigned)g.nrows && (sr + RSTEP * s) < PH;
+        // (the walk stops at row need_h: whole steps beyond it are left out, here and in sd_store_view)
+        const bool in = cin && (unsigned)r < (unsigned)g.nrows && (sr + RSTEP * s) < PH && RSTEP * s < w.need_h;
         stage[s] = in ? *reinterpret_cast<const float *>(yb + off) : 0.0f;
         off += step;
     }
@@ -88,7 +89,7 @@ __device__ __forceinline__ void sd_store_view(const SfGeom &g, const SdRayCol *_
 #pragma unroll
     for (int s = 0; s < NSTAGE; ++s) {
         const int row = sr + RSTEP * s;
-        if (row < PH) {
+        if (row < PH && RSTEP * s < w.need_h) {        // the second test is uniform over the workgroup
             const float vr = (float)sd_row_v(g, w.r0 + row);
             const float t = vscale * vr;
             buf[row * PS + sc] = stage[s] * sf_sqrt(fmaf(t, t, lxy * lxy));
