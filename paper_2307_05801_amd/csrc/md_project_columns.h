@@ -23,7 +23,7 @@ struct MdSlabRay {
     SdRayCol R;          // m, b, inv_m, xmajor as for the circular scanners; h0 = Z at X = 0, dh = mz (so v_r = 1, zk0 = 0)
     double xs;           // major index coordinate of the source
     float len;           // mm of ray per unit of X
-    bool forward;        // the ray runs towards larger X
+    int n_lo, n_hi;      // slabs that lie wholly in front of the source: n_lo <= n <= n_hi
 };
 
 SF_HD MdSlabRay md_slab_ray(const SfGeom &g, const MdPose &P, int r, int c)
@@ -47,12 +47,17 @@ SF_HD MdSlabRay md_slab_ray(const SfGeom &g, const MdPose &P, int r, int c)
     M.R.lxy = 0.0f; M.R.vscale = 0.0f;
     M.R.xmajor = xmajor ? 1 : 0;
     M.len = (float)(g.Td * sqrt(D[0] * D[0] + D[1] * D[1] + D[2] * D[2]) * fabs(inv));
-    M.forward = dmaj > 0.0;
+    // towards larger X the slabs from ceil(xs) on, towards smaller X those up to floor(xs) - 1 (bounds kept within int)
+    const double far = 1073741824.0;
+    const double xc = fmin(fmax(M.xs, -far), far);
+    const bool forward = dmaj > 0.0;
+    M.n_lo = forward ? (int)ceil(xc) : -1073741824;
+    M.n_hi = forward ? 1073741824 : (int)floor(xc) - 1;
     return M;
 }
 
 // Slab n lies wholly in front of the source.
-SF_HD bool md_slab_in_front(const MdSlabRay &M, int n) { return M.forward ? (double)n >= M.xs : (double)(n + 1) <= M.xs; }
+SF_HD bool md_slab_in_front(const MdSlabRay &M, int n) { return n >= M.n_lo && n <= M.n_hi; }
 
 // Per-ray constants of the axial split.
 struct MdAxial {

@@ -38,8 +38,13 @@ SF_HD SdSplit sd_slab_split(const SdRayCol &R, int n)
     SdSplit s;
     const double yin = fma(R.m, (double)n, R.b);
     const double yout = yin + R.m;
+#if defined(__HIP_DEVICE_COMPILE__)
+    // (the device's conversion saturates: rays that miss the volume by far get an index far outside it either way)
+    const double fa = floor(yin), fb = floor(yout);
+#else
     // rays that miss the volume by far: keep the conversion to int defined
     const double fa = fmin(fmax(floor(yin), -1.0e9), 1.0e9), fb = fmin(fmax(floor(yout), -1.0e9), 1.0e9);
+#endif
     s.qa = (int)fa;
     s.qb = (int)fb;
     if (s.qa == s.qb) {
