@@ -232,17 +232,20 @@ template <int ZC>
 SF_HD bool md_bp_row(const MdBpColumn &C, const MdBpPixel &p, int &slot, float &w_low, float &w_high)
 {
     const float y0 = (float)fma(C.ln, p.m, C.bq);                // minor position at X = n, relative to the cell
-    const float ta = -y0 * p.inv_m, tb = (1.0f - y0) * p.inv_m;
-    const float t0 = fminf(fmaxf(fminf(ta, tb), 0.0f), 1.0f), t1 = fminf(fmaxf(fmaxf(ta, tb), 0.0f), 1.0f);
+    // (clamping is monotone: the clamped crossing times of the cell's two faces, then their order; the clamp rides on
+    // the multiplication)
+    const float ta = sf_clamp(-y0 * p.inv_m, 0.0f, 1.0f), tb = sf_clamp((1.0f - y0) * p.inv_m, 0.0f, 1.0f);
+    const float t0 = fminf(ta, tb), t1 = fmaxf(ta, tb);
     const float dt = t1 - t0;
     if (!(dt > 0.0f)) return false;
     const double zin = fma(C.ln, p.mz, C.bz);                    // Z at X = n in slots, plus MD_BP_ZBIAS (positive)
 #if defined(__HIP_DEVICE_COMPILE__)
     const float fz = (float)__builtin_amdgcn_fract(zin);
+    const int kz = (int)zin - (int)MD_BP_ZBIAS;                  // (the device's conversion saturates; the slot is clamped below)
 #else
     const float fz = (float)(zin - floor(zin));
-#endif
     const int kz = (int)fmin(fmax(zin, 0.0), 2.0 * MD_BP_ZBIAS) - (int)MD_BP_ZBIAS;
+#endif
     const float lo = fmaf(p.inv_mz >= 0.0f ? t0 : t1, (float)p.mz, fz);      // lower end of the piece, relative to cell kz
     const float kl = floorf(lo);
     const int s = kz + (int)kl;
