@@ -25,8 +25,9 @@ constexpr int BP_T = 16;        // tile edge in voxels (x and y)
 struct SfBpShape {
     int zc, pw, ph;
 };
-// The last one keeps 64 voxels per thread for footprints up to two rows tall (a voxel up to about 1.3 rows at 512 rows
-// and more); it is instantiated for NV <= 3 only, shape 0 for NV == 2 only (taller footprints would spill registers).
+// The last one keeps 64 voxels per thread for footprints up to two rows tall (its 96 rows hold what 64 voxels of up to
+// about 1.3 rows each project to); it is instantiated for NV <= 3 only, shape 0 for NV == 2 only (the general gather of
+// taller footprints would spill registers).
 constexpr SfBpShape BP_SHAPES[] = {{64, 32, 76}, {32, 32, 44}, {32, 32, 56}, {16, 32, 44}, {16, 64, 48}, {64, 32, 96}};
 constexpr int BP_NSHAPES = 6;
 constexpr int BP_FIRST_SHORT_SHAPE = 1;      // first shape with fewer than 64 voxels per thread
